@@ -1,0 +1,147 @@
+/*
+ * libwildcat -- C ABI of the WildCat hot path for AMD MI355X (gfx950).
+ *
+ * WildCat ("WildCat: Near-Linear Attention in Theory and Practice") replaces
+ * softmax attention over n keys by weighted softmax attention over a coreset
+ * of r keys:
+ *
+ *   CompressKV (Alg. 2, with Alg. 1 "RPNys" inside) picks r pivot keys by
+ *   randomly pivoted Nystrom on the kernel exp(beta <k,k'> / tau^2) of the
+ *   recentred keys, and folds ALL n values into r rows with the Nystrom
+ *   weights W = h(K_S,K_S)^-1 h(K_S,K):  V_S = W V,  w = W 1.
+ *
+ *   WtdAttn (Alg. 3) then evaluates, for every query q_i,
+ *       A_is = exp(beta <q_i, k_s>),   O_i = (A V_S)_i / (A w)_i  if (A w)_i > 0 else 0,
+ *   clipped column-wise to the value range [v_min, v_max] of Alg. 4.
+ *
+ * Conventions
+ *   - Every tensor is dense, row-major, last index fastest:
+ *       Q   [batch, q_heads,  m, d]        K [batch, kv_heads, n, d]
+ *       V   [batch, kv_heads, n, dv]       out [batch, q_heads, m, dv]
+ *     A "problem" is one (batch, kv_head) pair; P = batch * kv_heads.  Query
+ *     head h attends to kv head h / (q_heads / kv_heads).
+ *   - Unless marked HOST, every pointer is a DEVICE pointer on the current HIP
+ *     device.  The caller owns every buffer, including the workspace; the
+ *     library allocates and frees nothing and keeps no state between calls.
+ *   - All work is enqueued on opts->stream (NULL = the null stream).  No entry
+ *     point synchronises with the host; results are valid once the stream has
+ *     reached the end of the enqueued work.
+ *   - Every function returning int returns WILDCAT_OK (0) or a negative
+ *     wildcat_status.  Arguments are validated on the host before anything is
+ *     launched; on error nothing has been enqueued.  No exception crosses the
+ *     boundary.  Non-finite inputs give unspecified (but memory-safe) results.
+ *   - Calls that share a workspace or output buffers must be ordered by the
+ *     caller (same stream, or events).
+ */
+#ifndef WILDCAT_H
+#define WILDCAT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { WILDCAT_F32 = 0, WILDCAT_BF16 = 1 } wildcat_dtype;
+
+typedef enum {
+  WILDCAT_OK = 0,
+  WILDCAT_EINVAL = -1,      /* null pointer, bad shape / dtype / option            */
+  WILDCAT_EWORKSPACE = -2,  /* workspace missing, misaligned or too small          */
+  WILDCAT_EHIP = -3,        /* a HIP runtime call or kernel launch failed          */
+  WILDCAT_EUNSUPPORTED = -4 /* valid request that this build does not implement    */
+} wildcat_status;
+
+/* Options.  A zero-filled struct selects the paper's defaults. */
+typedef struct {
+  int32_t batch;     /* 0 -> 1                                                      */
+  int32_t q_heads;   /* 0 -> kv_heads                                               */
+  int32_t kv_heads;  /* 0 -> 1; q_heads must be a multiple (grouped-query attention)*/
+  int64_t m;         /* queries per head; 0 -> n                                    */
+  int32_t dv;        /* value width; 0 -> d                                         */
+  int32_t dtype;     /* wildcat_dtype: storage type of Q, K, V, K_S and out         */
+  double beta;       /* softmax scale of eq. (1); 0 -> 1/sqrt(d)                    */
+  double rank_tol;   /* an entry of the residual diagonal p that drops to           */
+                     /* <= rank_tol * its initial value is set to 0 (the key is     */
+                     /* numerically in the span of the coreset).  0 -> 1e-10;       */
+                     /* negative -> bare clamp max(p, 0).  See Alg. 1, last two     */
+                     /* lines of the loop ("for numerical stability").              */
+  const double *r_q; /* [P] query radius R_Q per problem (input of Alg. 2).         */
+                     /* Required by wildcat_compress_kv; fill it with               */
+                     /* wildcat_query_radius or pass your own bound.                */
+  const double *uniforms; /* [P, r] pivot uniforms in [0,1), one per RPNys step,    */
+                     /* or NULL: then u[p, i] is element p*r+i of the stream        */
+                     /* wildcat_draw_uniforms(seed, ...) documents.                 */
+  int32_t bins;      /* B of Alg. 2.  0 or 1 (no binning) is what this build runs;  */
+                     /* B > 1 returns WILDCAT_EUNSUPPORTED.                         */
+  int32_t reserved0;
+  void *stream;      /* hipStream_t                                                 */
+  void *workspace;   /* device scratch, 256-byte aligned, of at least               */
+  size_t workspace_bytes; /* wildcat_workspace_bytes(...) bytes                     */
+} wildcat_opts;
+
+/* The compressed cache: output of CompressKV, input of WtdAttn.  All buffers are
+ * caller-allocated device memory. */
+typedef struct {
+  int32_t *idx;   /* [P, r]  pivot index into the n keys, in selection order; -1 in */
+                  /*         unused slots (rank exhausted before r pivots)          */
+  int32_t *r_eff; /* [P]     number of pivots drawn                                 */
+  void *k_s;      /* [P, r, d]  storage dtype: original (un-recentred) key rows     */
+  float *v_s;     /* [P, r, dv] W V                                                 */
+  float *w;       /* [P, r]     W 1                                                 */
+  float *v_min;   /* [P, dv]    column minima of V (Alg. 4, first line)             */
+  float *v_max;   /* [P, dv]    column maxima of V                                  */
+  double *tau;    /* [P]        temperature used (eq. (kernel-temperature))         */
+} wildcat_coreset;
+
+/* Library version as major*10000 + minor*100 + patch. */
+int wildcat_version(void);
+
+/* Static text for a wildcat_status (never NULL). */
+const char *wildcat_strerror(int status);
+
+/* HOST.  Bytes of workspace wildcat_compress_kv needs for keys of length n, width
+ * d, rank r under *opts (batch, kv_heads, dv, dtype are read; opts may be NULL).
+ * Returns 0 for invalid arguments.  wildcat_query_radius and wildcat_wtd_attn need
+ * no workspace. */
+size_t wildcat_workspace_bytes(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts);
+
+/* HOST.  Fills host_out[0..count) with the library's pivot uniforms for `seed`:
+ *   u_t = (mix64(seed + (t+1) * 0x9E3779B97F4A7C15) >> 11) * 2^-53,   t = 0, 1, ...
+ * mix64 = the SplitMix64 output function.  The paper leaves the sampler of Alg. 1
+ * ("s ~ p / sum p") open; this is the stream a bare seed stands for. */
+int wildcat_draw_uniforms(uint64_t seed, int64_t count, double *host_out);
+
+/* R_Q of Alg. 4: r_q_out[p] = max over the query rows of every query head that
+ * shares kv head p of ||q||_2.  Q is [batch, q_heads, m, d] in opts->dtype.
+ * r_q_out: device [P] doubles. */
+int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts,
+                         double *r_q_out);
+
+/* CompressKV (Alg. 2, one bin) together with the value range of Alg. 4:
+ *   kbar = row mean of K;  R_K = max_l ||k_l - kbar||;  tau from eq.
+ *   (kernel-temperature) with opts->r_q;  RPNys (Alg. 1) on the recentred keys
+ *   with kernel exp(beta <.,.> / tau^2), the pivot of step i drawn by inverse CDF
+ *   from uniform u[p, i]:  s = min{ l : sum_{l'<=l} p_l' > u * sum p };
+ *   out->k_s = K[idx], out->v_s = W V, out->w = W 1, out->v_min/v_max, out->tau.
+ * K [batch, kv_heads, n, d], V [batch, kv_heads, n, dv] in opts->dtype.
+ * Requires 1 <= r <= n, d >= 1, opts != NULL with r_q and workspace set.
+ * If the residual mass reaches zero after r_eff < r pivots, the remaining slots get
+ * idx = -1 and zero key, value and weight (they then add nothing in WtdAttn). */
+int wildcat_compress_kv(const void *K, const void *V, int64_t n, int32_t d, int32_t r,
+                        uint64_t seed, const wildcat_opts *opts, wildcat_coreset *out);
+
+/* WtdAttn (Alg. 3): out[b, h, i, :] = clip( (A V_S)_i / (A w)_i  if (A w)_i > 0 else 0,
+ * v_min, v_max ), A_is = exp(beta <q_i, k_s>), against the coreset of kv head
+ * h / (q_heads / kv_heads).  Q [batch, q_heads, m, d], out [batch, q_heads, m, dv] in
+ * opts->dtype; cs->idx, cs->r_eff and cs->tau are not read, so any (k_s, v_s, w,
+ * v_min, v_max) may be supplied -- e.g. all n keys with unit weights, which is exact
+ * attention. */
+int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *out, int64_t m,
+                     int32_t d, int32_t r, const wildcat_opts *opts);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WILDCAT_H */

@@ -118,7 +118,13 @@ def temperature(beta, R_Q, R_K, n):
         tau = sqrt(rho R_K / R_Q)
 
     Returns (tau, rho, b_0).
+
+    Reading: if R_Q or R_K is zero the formula divides by zero, but then every
+    kernel value exp(beta <q, k>) the method looks at is 1 whatever tau is;
+    tau = +inf is returned and the caller runs Alg. 1 with exponent scale 0.
     """
+    if not (R_Q > 0.0 and R_K > 0.0):
+        return math.inf, math.inf, math.inf
     b0 = math.log(n) / (beta * R_Q * R_K) + 2.0
     rho = b0 / (2.0 * lambert_w0(b0 / (2.0 * RHO0)))
     tau = math.sqrt(rho * R_K / R_Q)
@@ -270,7 +276,7 @@ def compress_kv(K, V, R_Q, beta, r, u, rank_tol=1e-10, keep_p_trace=False):
     Kc = K - kbar
     R_K = float(np.sqrt(np.einsum("ld,ld->l", Kc, Kc).max()))
     tau, _, _ = temperature(beta, R_Q, R_K, n)
-    beta_tau = beta / (tau * tau)
+    beta_tau = beta / (tau * tau) if math.isfinite(tau) else 0.0
     rp = rpnys(Kc, beta_tau, r, u, rank_tol=rank_tol, keep_p_trace=keep_p_trace)
     k = len(rp.S)
     idx = np.full(r, -1, dtype=np.int64)

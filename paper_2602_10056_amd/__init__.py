@@ -1,0 +1,227 @@
+"""Python binding of libwildcat (argument marshalling only).
+
+Every step of CompressKV and WtdAttn runs in the HIP kernels of ``libwildcat.so``; this module turns
+torch tensors into raw device pointers, fills the C structs of ``include/wildcat.h`` and allocates
+outputs and the workspace with torch.  There is no CPU fallback: if the shared library is missing or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwildcat.so")
+
+WILDCAT_F32, WILDCAT_BF16 = 0, 1
+EXPORTS = ("wildcat_version", "wildcat_strerror", "wildcat_workspace_bytes", "wildcat_draw_uniforms",
+           "wildcat_query_radius", "wildcat_compress_kv", "wildcat_wtd_attn")
+
+
+class WildcatError(RuntimeError):
+    pass
+
+
+class _Opts(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("q_heads", ctypes.c_int32), ("kv_heads", ctypes.c_int32),
+        ("m", ctypes.c_int64), ("dv", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("beta", ctypes.c_double), ("rank_tol", ctypes.c_double),
+        ("r_q", ctypes.c_void_p), ("uniforms", ctypes.c_void_p),
+        ("bins", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+class _Coreset(ctypes.Structure):
+    _fields_ = [
+        ("idx", ctypes.c_void_p), ("r_eff", ctypes.c_void_p), ("k_s", ctypes.c_void_p),
+        ("v_s", ctypes.c_void_p), ("w", ctypes.c_void_p), ("v_min", ctypes.c_void_p),
+        ("v_max", ctypes.c_void_p), ("tau", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def load_library(force: bool = False):
+    """Loads libwildcat.so (built in-tree by ``__graft_entry__.build()``) and declares its signatures."""
+    global _lib
+    if _lib is not None and not force:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise WildcatError(f"{LIB_PATH} not found: build it first (python __graft_entry__.py)")
+    lib = ctypes.CDLL(LIB_PATH)
+    for name in EXPORTS:
+        if not hasattr(lib, name):
+            raise WildcatError(f"libwildcat.so does not export {name}")
+    lib.wildcat_version.restype = ctypes.c_int
+    lib.wildcat_strerror.restype = ctypes.c_char_p
+    lib.wildcat_strerror.argtypes = [ctypes.c_int]
+    lib.wildcat_workspace_bytes.restype = ctypes.c_size_t
+    lib.wildcat_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
+    lib.wildcat_draw_uniforms.restype = ctypes.c_int
+    lib.wildcat_draw_uniforms.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_void_p]
+    lib.wildcat_query_radius.restype = ctypes.c_int
+    lib.wildcat_query_radius.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(_Opts),
+                                         ctypes.c_void_p]
+    lib.wildcat_compress_kv.restype = ctypes.c_int
+    lib.wildcat_compress_kv.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.c_uint64, ctypes.POINTER(_Opts),
+                                        ctypes.POINTER(_Coreset)]
+    lib.wildcat_wtd_attn.restype = ctypes.c_int
+    lib.wildcat_wtd_attn.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Coreset), ctypes.c_void_p, ctypes.c_int64,
+                                     ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
+    _lib = lib
+    return lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise WildcatError(f"{what} failed: {load_library().wildcat_strerror(rc).decode()} ({rc})")
+
+
+def version():
+    return load_library().wildcat_version()
+
+
+def draw_uniforms(seed: int, count: int):
+    """The library's host-side uniform stream for `seed` (numpy float64 [count])."""
+    import numpy as np
+    out = np.empty(count, dtype=np.float64)
+    _check(load_library().wildcat_draw_uniforms(seed, count, out.ctypes.data), "wildcat_draw_uniforms")
+    return out
+
+
+@dataclass
+class Coreset:
+    """Device buffers of the compressed cache (see wildcat_coreset in include/wildcat.h)."""
+    idx: "torch.Tensor"     # [B, Hkv, r] int32
+    r_eff: "torch.Tensor"   # [B, Hkv] int32
+    k_s: "torch.Tensor"     # [B, Hkv, r, d] storage dtype
+    v_s: "torch.Tensor"     # [B, Hkv, r, dv] float32
+    w: "torch.Tensor"       # [B, Hkv, r] float32
+    v_min: "torch.Tensor"   # [B, Hkv, dv] float32
+    v_max: "torch.Tensor"   # [B, Hkv, dv] float32
+    tau: "torch.Tensor"     # [B, Hkv] float64
+
+    def c_struct(self):
+        return _Coreset(self.idx.data_ptr(), self.r_eff.data_ptr() if self.r_eff is not None else None,
+                        self.k_s.data_ptr(), self.v_s.data_ptr(), self.w.data_ptr(), self.v_min.data_ptr(),
+                        self.v_max.data_ptr(), self.tau.data_ptr() if self.tau is not None else None)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return WILDCAT_F32
+    if t.dtype == torch.bfloat16:
+        return WILDCAT_BF16
+    raise WildcatError(f"unsupported storage dtype {t.dtype}")
+
+
+def _need(t, name, ndim):
+    if not t.is_cuda or not t.is_contiguous() or t.dim() != ndim:
+        raise WildcatError(f"{name} must be a contiguous CUDA tensor with {ndim} dims")
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _opts(batch, q_heads, kv_heads, m, dv, dtype, beta, rank_tol=0.0, r_q=None, uniforms=None, workspace=None):
+    o = _Opts()
+    o.batch, o.q_heads, o.kv_heads, o.m, o.dv, o.dtype = batch, q_heads, kv_heads, m, dv, dtype
+    o.beta = 0.0 if beta is None else float(beta)
+    o.rank_tol = float(rank_tol)
+    o.r_q = r_q.data_ptr() if r_q is not None else None
+    o.uniforms = uniforms.data_ptr() if uniforms is not None else None
+    o.stream = _stream()
+    if workspace is not None:
+        o.workspace, o.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    return o
+
+
+def workspace_bytes(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16):
+    o = _Opts()
+    o.batch, o.kv_heads, o.dv, o.dtype = batch, kv_heads, dv, dtype
+    return load_library().wildcat_workspace_bytes(n, d, r, ctypes.byref(o))
+
+
+def query_radius(Q, kv_heads=None):
+    """R_Q of Alg. 4 per (batch, kv_head): float64 tensor [B, Hkv].  Q: [B, Hq, m, d]."""
+    import torch
+    _need(Q, "Q", 4)
+    B, Hq, m, d = Q.shape
+    kv_heads = kv_heads or Hq
+    out = torch.empty((B, kv_heads), dtype=torch.float64, device=Q.device)
+    o = _opts(B, Hq, kv_heads, m, 0, _dtype_code(Q), None)
+    _check(load_library().wildcat_query_radius(Q.data_ptr(), m, d, ctypes.byref(o), out.data_ptr()),
+           "wildcat_query_radius")
+    return out
+
+
+def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None):
+    """CompressKV (Alg. 2).  K: [B, Hkv, n, d], V: [B, Hkv, n, dv]; r_q: float64 [B, Hkv] on the device;
+    uniforms: optional float64 [B*Hkv, r] on the device (else drawn from `seed`).  Returns a Coreset."""
+    import torch
+    _need(K, "K", 4)
+    _need(V, "V", 4)
+    B, H, n, d = K.shape
+    dv = V.shape[3]
+    if V.shape[:3] != K.shape[:3] or V.dtype != K.dtype:
+        raise WildcatError("K and V must agree in batch, heads, length and dtype")
+    if r_q.dtype != torch.float64 or r_q.numel() != B * H or not r_q.is_cuda:
+        raise WildcatError("r_q must be a float64 CUDA tensor with batch*kv_heads entries")
+    if uniforms is not None and (uniforms.dtype != torch.float64 or uniforms.numel() != B * H * r
+                                 or not uniforms.is_cuda or not uniforms.is_contiguous()):
+        raise WildcatError("uniforms must be a contiguous float64 CUDA tensor with batch*kv_heads*r entries")
+    code = _dtype_code(K)
+    dev = K.device
+    need = workspace_bytes(n, d, r, B, H, dv, code)
+    if need == 0:
+        raise WildcatError("wildcat_workspace_bytes rejected the shape")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    cs = Coreset(
+        idx=torch.empty((B, H, r), dtype=torch.int32, device=dev),
+        r_eff=torch.empty((B, H), dtype=torch.int32, device=dev),
+        k_s=torch.empty((B, H, r, d), dtype=K.dtype, device=dev),
+        v_s=torch.empty((B, H, r, dv), dtype=torch.float32, device=dev),
+        w=torch.empty((B, H, r), dtype=torch.float32, device=dev),
+        v_min=torch.empty((B, H, dv), dtype=torch.float32, device=dev),
+        v_max=torch.empty((B, H, dv), dtype=torch.float32, device=dev),
+        tau=torch.empty((B, H), dtype=torch.float64, device=dev),
+    )
+    o = _opts(B, H, H, n, dv, code, beta, rank_tol, r_q.contiguous(), uniforms, workspace)
+    c = cs.c_struct()
+    _check(load_library().wildcat_compress_kv(K.data_ptr(), V.data_ptr(), n, d, r, seed, ctypes.byref(o),
+                                              ctypes.byref(c)), "wildcat_compress_kv")
+    return cs
+
+
+def wtd_attn(Q, cs: Coreset, beta=None, out=None):
+    """WtdAttn (Alg. 3).  Q: [B, Hq, m, d]; returns [B, Hq, m, dv] in Q's dtype."""
+    import torch
+    _need(Q, "Q", 4)
+    B, Hq, m, d = Q.shape
+    Hkv, r, dv = cs.k_s.shape[1], cs.k_s.shape[2], cs.v_s.shape[3]
+    if cs.k_s.dtype != Q.dtype or cs.k_s.shape[0] != B or cs.k_s.shape[3] != d:
+        raise WildcatError("coreset does not match Q")
+    if out is None:
+        out = torch.empty((B, Hq, m, dv), dtype=Q.dtype, device=Q.device)
+    o = _opts(B, Hq, Hkv, m, dv, _dtype_code(Q), beta)
+    c = cs.c_struct()
+    _check(load_library().wildcat_wtd_attn(Q.data_ptr(), ctypes.byref(c), out.data_ptr(), m, d, r, ctypes.byref(o)),
+           "wildcat_wtd_attn")
+    return out
+
+
+def wildcat(Q, K, V, r, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, return_coreset=False):
+    """WildCat (Alg. 4): query radius, CompressKV, WtdAttn."""
+    r_q = query_radius(Q, K.shape[1])
+    cs = compress_kv(K, V, r, r_q, seed=seed, uniforms=uniforms, beta=beta, rank_tol=rank_tol, workspace=workspace)
+    out = wtd_attn(Q, cs, beta=beta)
+    return (out, cs) if return_coreset else out

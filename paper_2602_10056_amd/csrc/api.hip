@@ -1,0 +1,118 @@
+// Host-side pieces of the C ABI that launch nothing: option resolution, the workspace plan,
+// the documented uniform stream and error strings.
+#include <cmath>
+
+#include "common.h"
+
+namespace wildcat {
+
+int resolve_shape(int64_t n, int64_t m_arg, int32_t d, int32_t r, const wildcat_opts *o, Shape *s) {
+  wildcat_opts z = {};
+  if (!o) o = &z;
+  s->batch = o->batch > 0 ? o->batch : 1;
+  s->kv_heads = o->kv_heads > 0 ? o->kv_heads : 1;
+  s->q_heads = o->q_heads > 0 ? o->q_heads : s->kv_heads;
+  if (o->batch < 0 || o->kv_heads < 0 || o->q_heads < 0) return WILDCAT_EINVAL;
+  if (s->q_heads % s->kv_heads) return WILDCAT_EINVAL;
+  s->group = s->q_heads / s->kv_heads;
+  if ((int64_t)s->batch * s->kv_heads > (1 << 20)) return WILDCAT_EINVAL;
+  s->P = s->batch * s->kv_heads;
+  if (n < 1 || n > (int64_t)1 << 30 || d < 1 || r < 1 || r > n) return WILDCAT_EINVAL;
+  if (o->dv < 0 || o->m < 0 || m_arg < 0) return WILDCAT_EINVAL;
+  s->n = n;
+  s->m = m_arg > 0 ? m_arg : (o->m > 0 ? o->m : n);
+  if (s->m > (int64_t)1 << 30) return WILDCAT_EINVAL;
+  s->d = d;
+  s->dv = o->dv > 0 ? o->dv : d;
+  s->r = r;
+  if (o->dtype != WILDCAT_F32 && o->dtype != WILDCAT_BF16) return WILDCAT_EINVAL;
+  s->dtype = o->dtype;
+  if (!(o->beta >= 0.0) || !std::isfinite(o->beta)) return WILDCAT_EINVAL;
+  s->beta = o->beta > 0.0 ? o->beta : 1.0 / std::sqrt((double)d);
+  if (!std::isfinite(o->rank_tol) || o->rank_tol >= 1.0) return WILDCAT_EINVAL;
+  s->rank_tol = o->rank_tol == 0.0 ? 1e-10 : (o->rank_tol < 0.0 ? 0.0 : o->rank_tol);
+  if (o->bins < 0) return WILDCAT_EINVAL;
+  if (o->bins > 1) return WILDCAT_EUNSUPPORTED;
+  if (d > kMaxWidth || s->dv > kMaxWidth) return WILDCAT_EUNSUPPORTED;
+  s->stream = (hipStream_t)o->stream;
+  return WILDCAT_OK;
+}
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+Plan make_plan(const Shape &s) {
+  Plan p = {};
+  // Two keys per thread (16-byte history loads) once that still leaves >= 2 workgroups per compute unit.
+  p.kpt = ((int64_t)s.P * s.n >= (int64_t)2 * kThreads * 512) ? 2 : 1;
+  p.slab = kThreads * p.kpt;
+  p.nblk = (int)((s.n + p.slab - 1) / p.slab);
+  p.npad = (int64_t)p.nblk * p.slab;
+  p.dpad = (s.d + kChunk - 1) / kChunk * kChunk;
+  int64_t nb0 = (s.n + 1023) / 1024;
+  p.nb0 = (int)(nb0 > 256 ? 256 : nb0);
+  // Gram pass: about 1024 workgroups in total, each a whole number of slabs.
+  int rtiles = (s.r + 63) / 64;
+  int want = 1024 / (s.P * rtiles);
+  if (want < 1) want = 1;
+  if (want > p.nblk) want = p.nblk;
+  p.slabs_per_chunk = (p.nblk + want - 1) / want;
+  p.nchunk = (p.nblk + p.slabs_per_chunk - 1) / p.slabs_per_chunk;
+
+  const size_t es = s.dtype == WILDCAT_BF16 ? 2 : 4;
+  const size_t P = (size_t)s.P, n = (size_t)p.npad, r = (size_t)s.r, dv1 = (size_t)s.dv + 1;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  p.off_kbar = take(P * p.dpad * 8);
+  p.off_kp = take(P * n * p.dpad * es);
+  p.off_d0 = take(P * n * 8);
+  p.off_p = take(2 * P * n * 8);
+  p.off_bsum = take(2 * P * p.nblk * 8);
+  p.off_scal = take(P * 8 * 8);
+  p.off_F = take(P * n * r * 8);
+  p.off_L = take(P * r * r * 8);
+  p.off_U = take(P * r * r * 8);
+  p.off_gpart = take(P * p.nchunk * r * dv1 * 8);
+  p.off_g = take(P * r * dv1 * 8);
+  p.off_mpart = take(P * p.nb0 * (size_t)p.dpad * 8);
+  p.off_vminpart = take(P * p.nb0 * (size_t)s.dv * 4);
+  p.off_vmaxpart = take(P * p.nb0 * (size_t)s.dv * 4);
+  p.off_u = take(P * r * 8);
+  p.total = off;
+  return p;
+}
+
+}  // namespace wildcat
+
+using namespace wildcat;
+
+extern "C" int wildcat_version(void) { return 100; }
+
+extern "C" const char *wildcat_strerror(int status) {
+  switch (status) {
+    case WILDCAT_OK: return "ok";
+    case WILDCAT_EINVAL: return "invalid argument";
+    case WILDCAT_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case WILDCAT_EHIP: return "HIP runtime call or kernel launch failed";
+    case WILDCAT_EUNSUPPORTED: return "request not supported by this build";
+    default: return "unknown status";
+  }
+}
+
+extern "C" size_t wildcat_workspace_bytes(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts) {
+  Shape s;
+  if (resolve_shape(n, 0, d, r, opts, &s) != WILDCAT_OK || r > kMaxRank) return 0;
+  return make_plan(s).total;
+}
+
+static inline uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+extern "C" int wildcat_draw_uniforms(uint64_t seed, int64_t count, double *host_out) {
+  if (count < 0 || (count > 0 && !host_out)) return WILDCAT_EINVAL;
+  for (int64_t t = 0; t < count; ++t)
+    host_out[t] = (double)(mix64(seed + (uint64_t)(t + 1) * 0x9E3779B97F4A7C15ull) >> 11) * 0x1.0p-53;
+  return WILDCAT_OK;
+}

@@ -1,0 +1,117 @@
+// Internal helpers shared by the libwildcat translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "wildcat.h"
+
+namespace wildcat {
+
+constexpr int kThreads = 256;       // workgroup size of every streaming kernel (4 wavefronts of 64)
+constexpr int kWave = 64;
+constexpr int kMaxWidth = 256;      // largest key / value width d, dv
+constexpr int kMaxRank = 4096;      // largest coreset size r
+constexpr int kChunk = 4;           // keys are re-packed as [d/4][n][4] for coalesced per-key access
+
+// ---- resolved options -------------------------------------------------------------------------
+struct Shape {
+  int batch, q_heads, kv_heads, group, P;
+  int64_t n, m;
+  int d, dv, r, dtype;
+  double beta, rank_tol;
+  hipStream_t stream;
+};
+
+// Fills `s` from the raw arguments with the defaults of wildcat_opts; returns a wildcat_status.
+int resolve_shape(int64_t n, int64_t m_arg, int32_t d, int32_t r, const wildcat_opts *o, Shape *s);
+
+// ---- workspace plan of CompressKV --------------------------------------------------------------
+struct Plan {
+  int kpt;          // keys per thread in the step kernel (1 or 2)
+  int slab;         // keys per workgroup = kThreads * kpt
+  int nblk;         // slabs per problem
+  int64_t npad;     // nblk * slab
+  int dpad;         // d rounded up to a multiple of kChunk
+  int nb0;          // row blocks of the column-statistics pass
+  int nchunk;       // n-chunks of the Gram pass (each a whole number of slabs)
+  int slabs_per_chunk;
+  size_t off_kbar, off_kp, off_d0, off_p, off_bsum, off_scal, off_F, off_L, off_U, off_gpart, off_g,
+      off_mpart, off_vminpart, off_vmaxpart, off_u;
+  size_t total;
+};
+Plan make_plan(const Shape &s);
+
+// ---- storage types ---------------------------------------------------------------------------
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+
+__device__ __forceinline__ void from_float(float v, float *dst) { *dst = v; }
+__device__ __forceinline__ void from_float(float v, bf16_t *dst) {   // round to nearest even
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) { dst->bits = (uint16_t)((u >> 16) | 0x40); return; }
+  u += 0x7fffu + ((u >> 16) & 1u);
+  dst->bits = (uint16_t)(u >> 16);
+}
+
+// ---- deterministic workgroup reductions / scans over kThreads threads ------------------------------------
+// All take one value per thread and combine in a fixed order, so results do not depend on timing.
+
+__device__ __forceinline__ double wave_incl_scan(double v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    double o = __shfl_up(v, off, kWave);
+    if (lane >= off) v += o;
+  }
+  return v;
+}
+
+// Inclusive scan across the workgroup; *total receives the sum of all values.  `sm` is >= 4 doubles of LDS.
+__device__ __forceinline__ double block_incl_scan(double v, double *sm, double *total) {
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+  double inc = wave_incl_scan(v);
+  __syncthreads();                       // protect sm from a previous use
+  if (lane == kWave - 1) sm[wv] = inc;
+  __syncthreads();
+  double base = 0.0, tot = 0.0;
+#pragma unroll
+  for (int k = 0; k < kThreads / kWave; ++k) {
+    double x = sm[k];
+    if (k < wv) base += x;
+    tot += x;
+  }
+  *total = tot;
+  return base + inc;
+}
+
+__device__ __forceinline__ double block_sum(double v, double *sm) {
+  double tot;
+  block_incl_scan(v, sm, &tot);
+  return tot;
+}
+
+template <typename T, typename Op>
+__device__ __forceinline__ T block_reduce(T v, T *sm, Op op) {
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) v = op(v, __shfl_xor(v, off, kWave));
+  __syncthreads();
+  if (lane == 0) sm[wv] = v;
+  __syncthreads();
+  T out = sm[0];
+#pragma unroll
+  for (int k = 1; k < kThreads / kWave; ++k) out = op(out, sm[k]);
+  return out;
+}
+
+struct MinOp { template <typename T> __device__ T operator()(T a, T b) const { return a < b ? a : b; } };
+struct MaxOp { template <typename T> __device__ T operator()(T a, T b) const { return a > b ? a : b; } };
+
+// ---- host-side launch check ------------------------------------------------------------------
+inline int hip_ok(hipError_t e) { return e == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP; }
+
+}  // namespace wildcat

@@ -1,0 +1,762 @@
+// CompressKV (Alg. 2, one bin) with the RPNys selection loop (Alg. 1) for gfx950.
+//
+// The selection loop is bound by HBM bandwidth: step i must touch, for every key l, the i numbers
+// already computed for that key.  Everything here is laid out so that this stream is contiguous and
+// read with full-width loads:
+//
+//   * Keys are re-packed once as Kp[problem][d/4][n][4], so a thread that owns one or two adjacent keys
+//     reads 8..32 contiguous bytes per 4-wide chunk of the feature dimension and a wavefront reads a
+//     contiguous run.
+//   * Instead of the kernel rows R and the explicit inverse M of Alg. 1, the loop keeps the partial
+//     Cholesky rows F_i(l) = h_res^{i}(k_s, k_l) / sqrt(h_res^{i}(k_s, k_s)); delta of Alg. 1 equals
+//     -F_i (proof of Thm. 1), so p <- p - delta^2 is p <- p - F_i^2, the lower-triangular L with
+//     L[j][i] = F_i(s_j) satisfies h(K_S,K_S) = L L^T (so M = L^-T L^-1), and W = M R = L^-T F.
+//     Same pivots in exact arithmetic, same bytes per step, better conditioned than updating M.
+//   * F is stored slab-blocked, F[problem][slab][r][slab_keys]: the history of a workgroup's keys is one
+//     contiguous region.
+//   * All pivot-critical arithmetic (inner products, exp, history, p, prefix sums, the comparison
+//     against u * sum p) is fp64, so that the drawn index equals the one a float64 reference draws
+//     from the same uniform.  Sums use a fixed order: results are bit-reproducible run to run.
+//
+// One launch per RPNys step; every workgroup redoes the (cheap) pivot search from the per-slab sums
+// the previous launch left, so no grid-wide synchronisation happens inside a kernel.
+#include <climits>
+#include <cmath>
+
+#include "common.h"
+
+namespace wildcat {
+namespace {
+
+// --------------------------------------------------------------------------------------------
+// Column statistics of K (sums, for the mean of Alg. 2) and V (min / max, Alg. 4), pass 1.
+// grid (nb0, P); thread (rr, cc) walks rows rr, rr+rif, ... of its row block, column cc.
+// --------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_col_stats(const T *__restrict__ K, const T *__restrict__ V,
+                                                        int64_t n, int d, int dv, int dpad, int nb0, int lpr,
+                                                        double *__restrict__ mpart, float *__restrict__ vminpart,
+                                                        float *__restrict__ vmaxpart) {
+  __shared__ double sd[kThreads];
+  __shared__ float smn[kThreads], smx[kThreads];
+  const int t = threadIdx.x, blk = blockIdx.x, pr = blockIdx.y;
+  const int rif = kThreads / lpr, rr = t / lpr, cc = t % lpr;
+  const int64_t rpb = (n + nb0 - 1) / nb0;
+  const int64_t row0 = blk * rpb, row1 = (row0 + rpb < n) ? row0 + rpb : n;
+  const T *Kp = K + (size_t)pr * n * d;
+  const T *Vp = V + (size_t)pr * n * dv;
+  double acc = 0.0;
+  float mn = INFINITY, mx = -INFINITY;
+  for (int64_t row = row0 + rr; row < row1; row += rif) {
+    if (cc < d) acc += (double)to_float(Kp[row * d + cc]);
+    if (cc < dv) {
+      float v = to_float(Vp[row * dv + cc]);
+      mn = fminf(mn, v);
+      mx = fmaxf(mx, v);
+    }
+  }
+  sd[t] = acc; smn[t] = mn; smx[t] = mx;
+  __syncthreads();
+  if (rr == 0) {
+    for (int q = 1; q < rif; ++q) {
+      acc += sd[q * lpr + cc];
+      mn = fminf(mn, smn[q * lpr + cc]);
+      mx = fmaxf(mx, smx[q * lpr + cc]);
+    }
+    if (cc < dpad) mpart[((size_t)pr * nb0 + blk) * dpad + cc] = cc < d ? acc : 0.0;
+    if (cc < dv) {
+      vminpart[((size_t)pr * nb0 + blk) * dv + cc] = mn;
+      vmaxpart[((size_t)pr * nb0 + blk) * dv + cc] = mx;
+    }
+  }
+}
+
+// pass 2: grid P.  kbar = column sums / n; v_min, v_max; clears the R_K^2 accumulator.
+__global__ __launch_bounds__(kThreads) void k_col_final(const double *__restrict__ mpart,
+                                                        const float *__restrict__ vminpart,
+                                                        const float *__restrict__ vmaxpart, int64_t n, int dv,
+                                                        int dpad, int nb0, double *__restrict__ kbar,
+                                                        float *__restrict__ vmin, float *__restrict__ vmax,
+                                                        unsigned long long *__restrict__ scal) {
+  const int t = threadIdx.x, pr = blockIdx.x;
+  if (t < dpad) {
+    double s = 0.0;
+    for (int b = 0; b < nb0; ++b) s += mpart[((size_t)pr * nb0 + b) * dpad + t];
+    kbar[(size_t)pr * dpad + t] = s / (double)n;
+  }
+  if (t < dv) {
+    float mn = INFINITY, mx = -INFINITY;
+    for (int b = 0; b < nb0; ++b) {
+      mn = fminf(mn, vminpart[((size_t)pr * nb0 + b) * dv + t]);
+      mx = fmaxf(mx, vmaxpart[((size_t)pr * nb0 + b) * dv + t]);
+    }
+    vmin[(size_t)pr * dv + t] = mn;
+    vmax[(size_t)pr * dv + t] = mx;
+  }
+  if (t == 0) scal[(size_t)pr * 8] = 0ull;
+}
+
+// --------------------------------------------------------------------------------------------
+// Re-pack keys: Kp[pr][c][l][e] = K[pr][l][4c+e] (zero beyond n or d).  grid (ceil(npad*nc/256), P).
+// --------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_pack(const T *__restrict__ K, int64_t n, int64_t npad, int d,
+                                                   int dpad, T *__restrict__ Kp) {
+  const int pr = blockIdx.y, nc = dpad / kChunk;
+  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (gid >= npad * nc) return;
+  const int64_t l = gid % npad;
+  const int c = (int)(gid / npad);
+  T out[kChunk];
+#pragma unroll
+  for (int e = 0; e < kChunk; ++e) {
+    const int j = c * kChunk + e;
+    T z;
+    from_float(0.0f, &z);
+    out[e] = (l < n && j < d) ? K[((size_t)pr * n + l) * d + j] : z;
+  }
+  T *dst = Kp + (((size_t)pr * nc + c) * npad + l) * kChunk;
+#pragma unroll
+  for (int e = 0; e < kChunk; ++e) dst[e] = out[e];
+}
+
+// Loads the kChunk packed features of KPT adjacent keys as floats.
+template <typename T, int KPT>
+__device__ __forceinline__ void load_chunk(const T *__restrict__ src, float (&x)[KPT][kChunk]);
+
+template <>
+__device__ __forceinline__ void load_chunk<float, 1>(const float *__restrict__ src, float (&x)[1][kChunk]) {
+  const float4 v = *reinterpret_cast<const float4 *>(src);
+  x[0][0] = v.x; x[0][1] = v.y; x[0][2] = v.z; x[0][3] = v.w;
+}
+template <>
+__device__ __forceinline__ void load_chunk<float, 2>(const float *__restrict__ src, float (&x)[2][kChunk]) {
+  const float4 a = reinterpret_cast<const float4 *>(src)[0], b = reinterpret_cast<const float4 *>(src)[1];
+  x[0][0] = a.x; x[0][1] = a.y; x[0][2] = a.z; x[0][3] = a.w;
+  x[1][0] = b.x; x[1][1] = b.y; x[1][2] = b.z; x[1][3] = b.w;
+}
+__device__ __forceinline__ void unpack_bf16x4(uint2 v, float (&x)[kChunk]) {
+  x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xffff0000u);
+  x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+template <>
+__device__ __forceinline__ void load_chunk<bf16_t, 1>(const bf16_t *__restrict__ src, float (&x)[1][kChunk]) {
+  unpack_bf16x4(*reinterpret_cast<const uint2 *>(src), x[0]);
+}
+template <>
+__device__ __forceinline__ void load_chunk<bf16_t, 2>(const bf16_t *__restrict__ src, float (&x)[2][kChunk]) {
+  const uint4 v = *reinterpret_cast<const uint4 *>(src);
+  unpack_bf16x4(make_uint2(v.x, v.y), x[0]);
+  unpack_bf16x4(make_uint2(v.z, v.w), x[1]);
+}
+
+// --------------------------------------------------------------------------------------------
+// sq[l] = ||k_l - kbar||^2 (fp64) and R_K^2 = max_l sq[l] (Alg. 2, first line of the bin loop).
+// grid (nblk, P).  The maximum of non-negative doubles is taken on their bit patterns, which order
+// the same way, with an integer atomic: exact and order-independent.
+// --------------------------------------------------------------------------------------------
+template <typename T, int KPT>
+__global__ __launch_bounds__(kThreads) void k_sqnorm(const T *__restrict__ Kp, const double *__restrict__ kbar,
+                                                     int64_t n, int64_t npad, int dpad, double *__restrict__ sq,
+                                                     unsigned long long *__restrict__ scal) {
+  __shared__ double skb[kMaxWidth];
+  __shared__ double sm[kThreads / kWave];
+  const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y, nc = dpad / kChunk;
+  if (t < dpad) skb[t] = kbar[(size_t)pr * dpad + t];
+  __syncthreads();
+  const int64_t l0 = (int64_t)b * (kThreads * KPT) + t * KPT;
+  double acc[KPT];
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) acc[k] = 0.0;
+  for (int c = 0; c < nc; ++c) {
+    float x[KPT][kChunk];
+    load_chunk<T, KPT>(Kp + (((size_t)pr * nc + c) * npad + l0) * kChunk, x);
+#pragma unroll
+    for (int k = 0; k < KPT; ++k)
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) {
+        const double df = (double)x[k][e] - skb[c * kChunk + e];
+        acc[k] = fma(df, df, acc[k]);
+      }
+  }
+  double mx = 0.0;
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    if (l0 + k >= n) acc[k] = 0.0;
+    sq[(size_t)pr * npad + l0 + k] = acc[k];
+    mx = fmax(mx, acc[k]);
+  }
+  mx = block_reduce<double>(mx, sm, MaxOp());
+  if (t == 0) atomicMax(&scal[(size_t)pr * 8], (unsigned long long)__double_as_longlong(mx));
+}
+
+// --------------------------------------------------------------------------------------------
+// Temperature, eq. (kernel-temperature):  b0 = log n / (beta R_Q R_K) + 2,
+// rho = b0 / (2 W0(b0 / (2 rho0))), tau = sqrt(rho R_K / R_Q); the loop then uses beta / tau^2.
+// W0 by Newton on w + log w = log z (z = b0 / (2 rho0) > 0.3 here).
+// If R_K or R_Q is zero every kernel value is 1 whatever tau is; tau is then reported as +inf and
+// the loop runs with exponent scale 0.
+// --------------------------------------------------------------------------------------------
+__device__ double lambert_w0(double z) {
+  const double lz = log(z);
+  double w = log1p(z);
+  for (int it = 0; it < 64; ++it) {
+    const double wn = w - (w + log(w) - lz) / (1.0 + 1.0 / w);
+    const bool done = fabs(wn - w) <= 4e-16 * fabs(wn);
+    w = wn;
+    if (done) break;
+  }
+  return w;
+}
+
+__global__ void k_tau(int P, int64_t n, double beta, const double *__restrict__ r_q, double *__restrict__ scal,
+                      double *__restrict__ tau_out) {
+  const int pr = blockIdx.x * blockDim.x + threadIdx.x;
+  if (pr >= P) return;
+  const double rk = sqrt(__longlong_as_double(((const long long *)scal)[(size_t)pr * 8]));
+  const double rq = r_q[pr];
+  double tau, beta_tau;
+  if (!(rk > 0.0) || !(rq > 0.0)) {
+    tau = INFINITY;
+    beta_tau = 0.0;
+  } else {
+    const double rho0 = sqrt(1.0 + exp(lambert_w0(2.0 * exp(-2.0)) + 2.0));
+    const double b0 = log((double)n) / (beta * rq * rk) + 2.0;
+    const double rho = b0 / (2.0 * lambert_w0(b0 / (2.0 * rho0)));
+    tau = sqrt(rho * rk / rq);
+    beta_tau = beta / (tau * tau);
+  }
+  scal[(size_t)pr * 8 + 1] = tau;
+  scal[(size_t)pr * 8 + 2] = beta_tau;
+  scal[(size_t)pr * 8 + 3] = rk;
+  tau_out[pr] = tau;
+}
+
+// --------------------------------------------------------------------------------------------
+// Alg. 1, first line: p_l = h_tau(k_l, k_l) = exp(beta_tau ||k_l - kbar||^2); also the per-key floor
+// rank_tol * p_l, the per-slab sums, idx = -1, r_eff = r and (if asked) the uniforms of the seed.
+// grid (nblk, P).  sq_floor holds sq on entry and the floor on exit.
+// --------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+template <int KPT>
+__global__ __launch_bounds__(kThreads) void k_init_p(int64_t n, int64_t npad, int nblk, int r, double rank_tol,
+                                                     const double *__restrict__ scal, double *__restrict__ sq_floor,
+                                                     double *__restrict__ p0, double *__restrict__ bsum0,
+                                                     int32_t *__restrict__ idx, int32_t *__restrict__ r_eff,
+                                                     double *__restrict__ u_gen, unsigned long long seed) {
+  __shared__ double sm[kThreads / kWave];
+  const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
+  const double beta_tau = scal[(size_t)pr * 8 + 2];
+  const int64_t l0 = (int64_t)b * (kThreads * KPT) + t * KPT;
+  double loc = 0.0;
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    const size_t at = (size_t)pr * npad + l0 + k;
+    const double v = (l0 + k < n) ? exp(beta_tau * sq_floor[at]) : 0.0;
+    p0[at] = v;
+    sq_floor[at] = rank_tol * v;
+    loc += v;
+  }
+  const double tot = block_sum(loc, sm);
+  if (t == 0) bsum0[(size_t)pr * nblk + b] = tot;
+  if (b == 0) {
+    for (int i = t; i < r; i += kThreads) {
+      idx[(size_t)pr * r + i] = -1;
+      if (u_gen) {
+        const unsigned long long ctr = (unsigned long long)pr * r + i + 1ull;
+        u_gen[(size_t)pr * r + i] = (double)(mix64(seed + ctr * 0x9E3779B97F4A7C15ull) >> 11) * 0x1.0p-53;
+      }
+    }
+    if (t == 0) r_eff[pr] = r;
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// One RPNys step (body of the loop of Alg. 1) for step index i.  grid (nblk, P).
+// --------------------------------------------------------------------------------------------
+struct StepArgs {
+  const void *Kp;         // [P][dpad/4][npad][4] packed keys
+  const double *kbar;     // [P][dpad]
+  const double *scal;     // [P][8]: 1 = tau, 2 = beta_tau
+  const double *floor;    // [P][npad]
+  const double *u;        // [P][r]
+  double *p;              // [2][P][npad]   residual diagonal, double-buffered by step parity
+  double *bsum;           // [2][P][nblk]   per-slab sums of p, same parity
+  double *F;              // [P][nblk][r][slab]
+  double *L, *U;          // [P][r][r] Cholesky factor of h(K_S,K_S) (row-major lower) and its transpose
+  int32_t *idx, *r_eff;
+  int64_t n, npad;
+  int P, nblk, r, dpad;
+};
+
+template <int KPT>
+struct HistVec;
+template <>
+struct HistVec<1> {
+  double v[1];
+  __device__ __forceinline__ void load(const double *p) { v[0] = *p; }
+};
+template <>
+struct HistVec<2> {
+  double v[2];
+  __device__ __forceinline__ void load(const double *p) {
+    const double2 x = *reinterpret_cast<const double2 *>(p);
+    v[0] = x.x; v[1] = x.y;
+  }
+};
+
+template <typename T, int KPT>
+__global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
+  extern __shared__ double dyn[];
+  double *g = dyn;             // [r]    F_j(s), j < i : row i of L
+  double *ksc = dyn + a.r;     // [dpad] k_s - kbar
+  __shared__ double sm[kThreads / kWave];
+  __shared__ int smi[kThreads / kWave];
+  __shared__ double s_base, s_ps;
+  constexpr int SLAB = kThreads * KPT;
+  const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
+  const int lane = t & (kWave - 1);
+  const int rd = i & 1, wr = rd ^ 1;
+  const double *bs = a.bsum + ((size_t)rd * a.P + pr) * a.nblk;
+  double *bs_next = a.bsum + ((size_t)wr * a.P + pr) * a.nblk;
+  const double *pin = a.p + ((size_t)rd * a.P + pr) * a.npad;
+  double *pout = a.p + ((size_t)wr * a.P + pr) * a.npad;
+  double *Fb = a.F + ((size_t)pr * a.nblk + b) * a.r * SLAB;
+  const int l_loc = t * KPT;
+  const int64_t l_glob = (int64_t)b * SLAB + l_loc;
+
+  // ---- 1. total mass = sum p (from the per-slab sums, in slab order) ----------------------------
+  const int per = (a.nblk + kThreads - 1) / kThreads;
+  const int e0 = t * per < a.nblk ? t * per : a.nblk;
+  const int e1 = e0 + per < a.nblk ? e0 + per : a.nblk;
+  double loc = 0.0;
+  for (int e = e0; e < e1; ++e) loc += bs[e];
+  double mass;
+  double inc = block_incl_scan(loc, sm, &mass);
+  double excl = __shfl_up(inc, 1, kWave);          // exclusive prefix = inclusive prefix of thread t-1
+  if (lane == 0) {
+    excl = 0.0;
+    for (int k = 0; k < t / kWave; ++k) excl += sm[k];
+  }
+
+  if (!(mass > 0.0)) {
+    // Residual mass exhausted: h(K,K) is reproduced exactly by the pivots so far.  Carry the (all-zero)
+    // state into the other parity, leave row i of F zero, record the number of pivots once.
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+      pout[l_glob + k] = 0.0;
+      Fb[(size_t)i * SLAB + l_loc + k] = 0.0;
+    }
+    if (t == 0) bs_next[b] = 0.0;
+    if (b == 0 && t == 0 && a.r_eff[pr] > i) a.r_eff[pr] = i;
+    return;
+  }
+
+  // ---- 2. the slab holding the draw: first slab whose inclusive prefix exceeds u * mass ----------------------
+  double target = a.u[(size_t)pr * a.r + i] * mass;
+  int cand = INT_MAX;
+  double cand_base = 0.0;
+  int last_pos = -1;
+  {
+    double run = excl;
+    for (int e = e0; e < e1; ++e) {
+      const double v = bs[e], nxt = run + v;
+      if (nxt > target && cand == INT_MAX) { cand = e; cand_base = run; }
+      if (v > 0.0) last_pos = e;
+      run = nxt;
+    }
+  }
+  int bstar = block_reduce<int>(cand, smi, MinOp());
+  if (bstar == INT_MAX) {
+    // Rounding left no slab above u * mass (u within an ulp of 1): take the last index of positive mass.
+    bstar = block_reduce<int>(last_pos, smi, MaxOp());
+    target = INFINITY;
+    if (t == 0) s_base = 0.0;
+  } else if (cand == bstar) {
+    s_base = cand_base;
+  }
+  __syncthreads();
+  const double base = s_base;
+  bstar = bstar < 0 ? 0 : (bstar >= a.nblk ? a.nblk - 1 : bstar);   // only non-finite input can get here
+
+  // ---- 3. the index inside that slab ---------------------------------------------------------------
+  const double *ps = pin + (size_t)bstar * SLAB;
+  double pv[KPT];
+  loc = 0.0;
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) { pv[k] = ps[l_loc + k]; loc += pv[k]; }
+  double tot2;
+  inc = block_incl_scan(loc, sm, &tot2);
+  excl = __shfl_up(inc, 1, kWave);
+  if (lane == 0) {
+    excl = 0.0;
+    for (int k = 0; k < t / kWave; ++k) excl += sm[k];
+  }
+  cand = INT_MAX;
+  last_pos = -1;
+  {
+    double run = base + excl;
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+      const double nxt = run + pv[k];
+      if (nxt > target && cand == INT_MAX) cand = l_loc + k;
+      if (pv[k] > 0.0) last_pos = l_loc + k;
+      run = nxt;
+    }
+  }
+  int s_loc = block_reduce<int>(cand, smi, MinOp());
+  if (s_loc == INT_MAX) s_loc = block_reduce<int>(last_pos, smi, MaxOp());
+  if (s_loc < 0) s_loc = 0;                                          // non-finite input only
+  if (s_loc / KPT == t) s_ps = pv[s_loc % KPT];
+  const int64_t s_glob = (int64_t)bstar * SLAB + s_loc;
+
+  // ---- 4. broadcast data of the pivot: its history column g_j = F_j(s) and k_s - kbar ------------------
+  const double *Fs = a.F + ((size_t)pr * a.nblk + bstar) * a.r * SLAB + s_loc;
+  for (int j = t; j < i; j += kThreads) g[j] = Fs[(size_t)j * SLAB];
+  const int nc = a.dpad / kChunk;
+  const T *Kp = reinterpret_cast<const T *>(a.Kp) + (size_t)pr * nc * a.npad * kChunk;
+  double cbp = 0.0;
+  if (t < a.dpad) {
+    const double kb = a.kbar[(size_t)pr * a.dpad + t];
+    const double v = (double)to_float(Kp[((size_t)(t / kChunk) * a.npad + s_glob) * kChunk + (t % kChunk)]) - kb;
+    ksc[t] = v;
+    cbp = kb * v;
+  }
+  const double cb = block_sum(cbp, sm);          // <kbar, k_s - kbar>; also publishes g, ksc, s_ps
+  const double inv = 1.0 / sqrt(s_ps);
+  const double beta_tau = a.scal[(size_t)pr * 8 + 2];
+
+  // ---- 5. history product  acc_l = sum_{j<i} F_j(l) g_j  (the O(n i) stream) ---------------------------
+  double acc[KPT];
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) acc[k] = 0.0;
+  {
+    const double *fp = Fb + l_loc;
+    int j = 0;
+    for (; j + 8 <= i; j += 8) {
+      HistVec<KPT> h[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) h[q].load(fp + (size_t)(j + q) * SLAB);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const double gj = g[j + q];
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) acc[k] = fma(h[q].v[k], gj, acc[k]);
+      }
+    }
+    for (; j < i; ++j) {
+      HistVec<KPT> h;
+      h.load(fp + (size_t)j * SLAB);
+      const double gj = g[j];
+#pragma unroll
+      for (int k = 0; k < KPT; ++k) acc[k] = fma(h.v[k], gj, acc[k]);
+    }
+  }
+
+  // ---- 6. kernel column  c_l = exp(beta_tau <k_l - kbar, k_s - kbar>)  (the O(n d) stream) ----------------
+  double dot[KPT];
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) dot[k] = 0.0;
+  {
+    const T *kp = Kp + (size_t)l_glob * kChunk;
+#pragma unroll 4
+    for (int c = 0; c < nc; ++c) {
+      float x[KPT][kChunk];
+      load_chunk<T, KPT>(kp + (size_t)c * a.npad * kChunk, x);
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) {
+        const double ks = ksc[c * kChunk + e];
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) dot[k] = fma((double)x[k][e], ks, dot[k]);
+      }
+    }
+  }
+
+  // ---- 7. new Cholesky row, residual diagonal, slab sum ------------------------------------------------
+  double psum = 0.0;
+  double fs = 0.0;
+  bool own = false;
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    const int64_t l = l_glob + k;
+    double f = (exp(beta_tau * (dot[k] - cb)) - acc[k]) * inv;
+    double pn = pin[l] - f * f;
+    if (pn <= a.floor[(size_t)pr * a.npad + l]) pn = 0.0;      // also clamps negatives (floor >= 0)
+    if (l == s_glob) { pn = 0.0; fs = f; own = true; }
+    if (l >= a.n) { pn = 0.0; f = 0.0; }
+    Fb[(size_t)i * SLAB + l_loc + k] = f;
+    pout[l] = pn;
+    psum += pn;
+  }
+  const double tot = block_sum(psum, sm);
+  if (t == 0) bs_next[b] = tot;
+
+  // ---- 8. bookkeeping by the slab that owns the pivot -----------------------------------------------------
+  if (b == bstar) {
+    double *Lr = a.L + ((size_t)pr * a.r + i) * a.r;
+    double *Uc = a.U + (size_t)pr * a.r * a.r + i;
+    for (int j = t; j < i; j += kThreads) {
+      Lr[j] = g[j];
+      Uc[(size_t)j * a.r] = g[j];
+    }
+    if (own) {
+      Lr[i] = fs;
+      Uc[(size_t)i * a.r] = fs;
+      a.idx[(size_t)pr * a.r + i] = (int32_t)s_glob;
+    }
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// Gram pass  G = F [V, 1]  (Alg. 2 last line, reordered as in Sec. 2.1: weights times (V, 1_n) first).
+// grid (nchunk, ceil(r/64), P); workgroup tile 64 rows of F x all dv columns; thread (ty, tx) owns rows
+// 4ty..4ty+3 and columns tx + 16 q.  fp64 accumulation; partial sums per n-chunk, reduced in order later.
+// --------------------------------------------------------------------------------------------
+constexpr int kGramRows = 64, kGramKT = 32;
+
+template <typename T, int CW>
+__global__ __launch_bounds__(kThreads) void k_gram(const double *__restrict__ F, const T *__restrict__ V, int64_t n,
+                                                   int nblk, int slab, int r, int dv, int slabs_per_chunk,
+                                                   int nchunk, double *__restrict__ gpart) {
+  __shared__ double Fs[kGramRows][kGramKT + 1];
+  __shared__ float Vs[kGramKT][16 * CW];
+  const int t = threadIdx.x, ch = blockIdx.x, rt = blockIdx.y, pr = blockIdx.z;
+  const int ty = t / 16, tx = t % 16;
+  const int a0 = rt * kGramRows;
+  double acc[4][CW];
+  double rs[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    rs[q] = 0.0;
+#pragma unroll
+    for (int c = 0; c < CW; ++c) acc[q][c] = 0.0;
+  }
+  const int sb0 = ch * slabs_per_chunk;
+  const int sb1 = sb0 + slabs_per_chunk < nblk ? sb0 + slabs_per_chunk : nblk;
+  for (int sb = sb0; sb < sb1; ++sb) {
+    const double *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
+    for (int k0 = 0; k0 < slab; k0 += kGramKT) {
+      const int64_t lbase = (int64_t)sb * slab + k0;
+      if (lbase >= n) break;
+      __syncthreads();
+      {  // F tile: 64 rows x 32 keys; thread loads 8 consecutive keys of one row
+        const int row = t / 4, seg = (t % 4) * 8;
+        const bool ok = a0 + row < r;
+        const double *src = Fslab + (size_t)(a0 + row) * slab + k0 + seg;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+          double2 v = ok ? *reinterpret_cast<const double2 *>(src + e) : make_double2(0.0, 0.0);
+          Fs[row][seg + e] = v.x;
+          Fs[row][seg + e + 1] = v.y;
+        }
+      }
+      for (int e = t; e < kGramKT * dv; e += kThreads) {  // V tile: 32 keys x dv
+        const int kk = e / dv, c = e % dv;
+        const int64_t l = lbase + kk;
+        Vs[kk][c] = l < n ? to_float(V[((size_t)pr * n + l) * dv + c]) : 0.0f;
+      }
+      __syncthreads();
+#pragma unroll 4
+      for (int kk = 0; kk < kGramKT; ++kk) {
+        double fv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) fv[q] = Fs[4 * ty + q][kk];
+        if (tx == 0) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) rs[q] += fv[q];
+        }
+#pragma unroll
+        for (int c = 0; c < CW; ++c) {
+          const double vv = (double)Vs[kk][tx + 16 * c];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[q][c] = fma(fv[q], vv, acc[q][c]);
+        }
+      }
+    }
+  }
+  const int dv1 = dv + 1;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int arow = a0 + 4 * ty + q;
+    if (arow >= r) continue;
+    double *dst = gpart + (((size_t)pr * nchunk + ch) * r + arow) * dv1;
+#pragma unroll
+    for (int c = 0; c < CW; ++c)
+      if (tx + 16 * c < dv) dst[tx + 16 * c] = acc[q][c];
+    if (tx == 0) dst[dv] = rs[q];
+  }
+}
+
+// Gt[pr][c][a] = sum over chunks (in chunk order) of gpart[pr][chunk][a][c].  grid (ceil(r*dv1/256), P).
+__global__ __launch_bounds__(kThreads) void k_gram_reduce(const double *__restrict__ gpart, int r, int dv1,
+                                                          int nchunk, double *__restrict__ Gt) {
+  const int pr = blockIdx.y;
+  const int gid = blockIdx.x * kThreads + threadIdx.x;
+  if (gid >= r * dv1) return;
+  const int c = gid / r, arow = gid % r;
+  double s = 0.0;
+  for (int ch = 0; ch < nchunk; ++ch) s += gpart[(((size_t)pr * nchunk + ch) * r + arow) * dv1 + c];
+  Gt[((size_t)pr * dv1 + c) * r + arow] = s;
+}
+
+// --------------------------------------------------------------------------------------------
+// Core solve  X = L^-T G  (W [V,1] = L^-T F [V,1]): back substitution with U = L^T, one right-hand-side
+// column per 32 lanes, cpw columns per workgroup, the column held in LDS.  grid (ceil(dv1/cpw), P),
+// block 32*cpw.  Writes V_S (columns < dv) and w (column dv) as fp32; rows >= r_eff are zero.
+// --------------------------------------------------------------------------------------------
+__global__ void k_solve(const double *__restrict__ U, const double *__restrict__ Gt, const int32_t *__restrict__ r_eff,
+                        int r, int dv, int cpw, float *__restrict__ v_s, float *__restrict__ w) {
+  extern __shared__ double dyn[];
+  const int pr = blockIdx.y, grp = threadIdx.x / 32, q = threadIdx.x % 32;
+  const int c = blockIdx.x * cpw + grp;
+  const int dv1 = dv + 1;
+  const int re = r_eff[pr];
+  if (c >= dv1) return;                       // whole 32-lane groups leave together; no workgroup barrier below
+  double *x = dyn + (size_t)grp * r;
+  const double *Up = U + (size_t)pr * r * r;
+  const double *gcol = Gt + ((size_t)pr * dv1 + c) * r;
+  for (int j = re - 1; j >= 0; --j) {
+    const double *urow = Up + (size_t)j * r;
+    double part = 0.0;
+    for (int k = j + 1 + q; k < re; k += 32) part = fma(urow[k], x[k], part);
+#pragma unroll
+    for (int off = 16; off > 0; off >>= 1) part += __shfl_xor(part, off, 32);
+    const double xj = (gcol[j] - part) / urow[j];
+    if (q == 0) x[j] = xj;
+    __builtin_amdgcn_wave_barrier();
+  }
+  for (int j = q; j < r; j += 32) {
+    const float val = j < re ? (float)x[j] : 0.0f;
+    if (c < dv) v_s[((size_t)pr * r + j) * dv + c] = val;
+    else w[(size_t)pr * r + j] = val;
+  }
+}
+
+// K_S = original key rows at the pivots (Alg. 2: recentred pivots plus the mean), zero in unused slots.
+template <typename T>
+__global__ void k_gather(const T *__restrict__ K, const int32_t *__restrict__ idx, int64_t n, int d, int r,
+                         T *__restrict__ k_s) {
+  const int i = blockIdx.x, pr = blockIdx.y;
+  const int s = idx[(size_t)pr * r + i];
+  for (int j = threadIdx.x; j < d; j += blockDim.x) {
+    T z;
+    from_float(0.0f, &z);
+    k_s[((size_t)pr * r + i) * d + j] = s >= 0 ? K[((size_t)pr * n + s) * d + j] : z;
+  }
+}
+
+#define LAUNCH_CHECK()                                   \
+  do {                                                   \
+    if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP; \
+  } while (0)
+
+template <typename T, int KPT>
+int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const wildcat_opts *o, uint64_t seed,
+                 wildcat_coreset *out) {
+  char *ws = (char *)o->workspace;
+  double *kbar = (double *)(ws + pl.off_kbar);
+  T *Kp = (T *)(ws + pl.off_kp);
+  double *d0 = (double *)(ws + pl.off_d0);
+  double *p = (double *)(ws + pl.off_p);
+  double *bsum = (double *)(ws + pl.off_bsum);
+  double *scal = (double *)(ws + pl.off_scal);
+  double *F = (double *)(ws + pl.off_F);
+  double *L = (double *)(ws + pl.off_L);
+  double *U = (double *)(ws + pl.off_U);
+  double *gpart = (double *)(ws + pl.off_gpart);
+  double *Gt = (double *)(ws + pl.off_g);
+  double *mpart = (double *)(ws + pl.off_mpart);
+  float *vminpart = (float *)(ws + pl.off_vminpart);
+  float *vmaxpart = (float *)(ws + pl.off_vmaxpart);
+  double *u_gen = (double *)(ws + pl.off_u);
+  hipStream_t st = s.stream;
+  const int P = s.P;
+
+  int lpr = 1;
+  while (lpr < s.d || lpr < s.dv || lpr < pl.dpad) lpr <<= 1;
+  hipLaunchKernelGGL((k_col_stats<T>), dim3(pl.nb0, P), dim3(kThreads), 0, st, K, V, s.n, s.d, s.dv, pl.dpad, pl.nb0,
+                     lpr, mpart, vminpart, vmaxpart);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_col_final, dim3(P), dim3(kThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
+                     pl.nb0, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
+  LAUNCH_CHECK();
+  const int nc = pl.dpad / kChunk;
+  const int64_t packs = (pl.npad * nc + kThreads - 1) / kThreads;
+  hipLaunchKernelGGL((k_pack<T>), dim3((unsigned)packs, P), dim3(kThreads), 0, st, K, s.n, pl.npad, s.d, pl.dpad, Kp);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL((k_sqnorm<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, Kp, kbar, s.n, pl.npad, pl.dpad, d0,
+                     (unsigned long long *)scal);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_tau, dim3((P + 63) / 64), dim3(64), 0, st, P, s.n, s.beta, o->r_q, scal, out->tau);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL((k_init_p<KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, s.n, pl.npad, pl.nblk, s.r, s.rank_tol,
+                     scal, d0, p, bsum, out->idx, out->r_eff, o->uniforms ? (double *)nullptr : u_gen,
+                     (unsigned long long)seed);
+  LAUNCH_CHECK();
+
+  StepArgs a;
+  a.Kp = Kp; a.kbar = kbar; a.scal = scal; a.floor = d0; a.u = o->uniforms ? o->uniforms : u_gen;
+  a.p = p; a.bsum = bsum; a.F = F; a.L = L; a.U = U; a.idx = out->idx; a.r_eff = out->r_eff;
+  a.n = s.n; a.npad = pl.npad; a.P = P; a.nblk = pl.nblk; a.r = s.r; a.dpad = pl.dpad;
+  const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
+  for (int i = 0; i < s.r; ++i) {
+    hipLaunchKernelGGL((k_step<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), step_lds, st, a, i);
+    LAUNCH_CHECK();
+  }
+
+  const int rtiles = (s.r + kGramRows - 1) / kGramRows;
+  const dim3 ggrid(pl.nchunk, rtiles, P);
+  if (s.dv <= 64)
+    hipLaunchKernelGGL((k_gram<T, 4>), ggrid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
+                       pl.slabs_per_chunk, pl.nchunk, gpart);
+  else if (s.dv <= 128)
+    hipLaunchKernelGGL((k_gram<T, 8>), ggrid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
+                       pl.slabs_per_chunk, pl.nchunk, gpart);
+  else
+    hipLaunchKernelGGL((k_gram<T, 16>), ggrid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
+                       pl.slabs_per_chunk, pl.nchunk, gpart);
+  LAUNCH_CHECK();
+  const int dv1 = s.dv + 1;
+  hipLaunchKernelGGL(k_gram_reduce, dim3((s.r * dv1 + kThreads - 1) / kThreads, P), dim3(kThreads), 0, st, gpart, s.r,
+                     dv1, pl.nchunk, Gt);
+  LAUNCH_CHECK();
+  int cpw = 8;
+  while (cpw > 1 && (size_t)cpw * s.r * sizeof(double) > 64 * 1024) cpw >>= 1;
+  hipLaunchKernelGGL(k_solve, dim3((dv1 + cpw - 1) / cpw, P), dim3(32 * cpw), (size_t)cpw * s.r * sizeof(double), st, U,
+                     Gt, out->r_eff, s.r, s.dv, cpw, out->v_s, out->w);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL((k_gather<T>), dim3(s.r, P), dim3(64), 0, st, K, out->idx, s.n, s.d, s.r, (T *)out->k_s);
+  LAUNCH_CHECK();
+  return WILDCAT_OK;
+}
+
+}  // namespace
+}  // namespace wildcat
+
+using namespace wildcat;
+
+extern "C" int wildcat_compress_kv(const void *K, const void *V, int64_t n, int32_t d, int32_t r, uint64_t seed,
+                                   const wildcat_opts *opts, wildcat_coreset *out) {
+  if (!K || !V || !opts || !out) return WILDCAT_EINVAL;
+  Shape s;
+  int rc = resolve_shape(n, 0, d, r, opts, &s);
+  if (rc != WILDCAT_OK) return rc;
+  if (r > kMaxRank) return WILDCAT_EUNSUPPORTED;
+  if (!opts->r_q) return WILDCAT_EINVAL;
+  if (!out->idx || !out->r_eff || !out->k_s || !out->v_s || !out->w || !out->v_min || !out->v_max || !out->tau)
+    return WILDCAT_EINVAL;
+  const Plan pl = make_plan(s);
+  if (!opts->workspace || ((uintptr_t)opts->workspace & 255) || opts->workspace_bytes < pl.total)
+    return WILDCAT_EWORKSPACE;
+  if (s.dtype == WILDCAT_BF16) {
+    return pl.kpt == 2 ? run_compress<bf16_t, 2>(s, pl, (const bf16_t *)K, (const bf16_t *)V, opts, seed, out)
+                       : run_compress<bf16_t, 1>(s, pl, (const bf16_t *)K, (const bf16_t *)V, opts, seed, out);
+  }
+  return pl.kpt == 2 ? run_compress<float, 2>(s, pl, (const float *)K, (const float *)V, opts, seed, out)
+                     : run_compress<float, 1>(s, pl, (const float *)K, (const float *)V, opts, seed, out);
+}

@@ -1,0 +1,242 @@
+"""Parity of the HIP path (through the C ABI) with the float64 CPU oracle on the same seeded inputs.
+
+Bars: pivot indices bit-exact; tau to 1e-12; fp32 outputs within 1e-5, bf16 outputs within 2e-2, both as
+max-norm error relative to the max-norm of the oracle's result per head (the paper measures errors in the
+max norm); V_S and w (fp32 masters of fp64 results) within 1e-5 of their own max-norm.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2602_10056_amd as wc                      # noqa: E402
+from oracle import wildcat_oracle as wo                # noqa: E402
+from paper_2602_10056_amd import workloads as wl       # noqa: E402
+
+TOL_OUT = {"f32": 1e-5, "bf16": 2e-2}
+TOL_COMPRESSED = 1e-5
+
+
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    wc.load_library()
+    return torch.device("cuda:0")
+
+
+def to_dev(x32, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(x32))
+    return t.to(dev()).to(torch.bfloat16 if dtype == "bf16" else torch.float32).contiguous()
+
+
+def relmax(a, b):
+    return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-300))
+
+
+def run_gpu(w, r=None, **kw):
+    s = w["shape"]
+    Q, K, V = (to_dev(w[k], s.dtype) for k in ("Q", "K", "V"))
+    u = torch.from_numpy(w["u"]).to(dev())
+    out, cs = wc.wildcat(Q, K, V, r=r or s.r, uniforms=u, return_coreset=True, **kw)
+    torch.cuda.synchronize()
+    return out, cs
+
+
+def check_against_oracle(w, out, cs, heads=None, r=None, rank_tol=1e-10):
+    """Compares every (batch, kv head) in `heads` (default all) against the oracle."""
+    s = w["shape"]
+    r = r or s.r
+    o = out.float().cpu().numpy()
+    idx = cs.idx.cpu().numpy()
+    worst = {"out": 0.0, "w": 0.0, "v_s": 0.0, "margin": 1.0}
+    for b in range(s.batch):
+        for h in (heads if heads is not None else range(s.kv_heads)):
+            p = b * s.kv_heads + h
+            Qg = w["Q"][b, h * s.group:(h + 1) * s.group].astype(np.float64)
+            ref, ocs, (vmin, vmax, RQ) = wo.wildcat(Qg, w["K"][b, h].astype(np.float64),
+                                                    w["V"][b, h].astype(np.float64), s.beta, r, w["u"][p][:r],
+                                                    rank_tol=rank_tol, return_coreset=True)
+            assert cs.tau[b, h].item() == pytest.approx(ocs.tau, rel=1e-12)
+            np.testing.assert_array_equal(idx[b, h], ocs.idx, err_msg=f"pivots differ, problem {p}; oracle "
+                                          f"min tie margin {ocs.rp.margin.min():.2e}")
+            assert cs.r_eff[b, h].item() == ocs.r_eff
+            np.testing.assert_array_equal(cs.k_s[b, h].float().cpu().numpy(), ocs.K_S)
+            np.testing.assert_array_equal(cs.v_min[b, h].cpu().numpy(), vmin.astype(np.float32))
+            np.testing.assert_array_equal(cs.v_max[b, h].cpu().numpy(), vmax.astype(np.float32))
+            ew = relmax(cs.w[b, h].cpu().numpy().astype(np.float64), ocs.w)
+            ev = relmax(cs.v_s[b, h].cpu().numpy().astype(np.float64), ocs.V_S)
+            assert ew <= TOL_COMPRESSED and ev <= TOL_COMPRESSED, (ew, ev)
+            for gq in range(s.group):
+                eo = relmax(o[b, h * s.group + gq].astype(np.float64), ref[gq])
+                assert eo <= TOL_OUT[s.dtype], f"head {h * s.group + gq}: {eo:.3e}"
+                worst["out"] = max(worst["out"], eo)
+            worst["w"], worst["v_s"] = max(worst["w"], ew), max(worst["v_s"], ev)
+            worst["margin"] = min(worst["margin"], float(ocs.rp.margin.min()))
+    return worst
+
+
+# ---------------------------------------------------------------------------------- whole path
+def test_config1_fp32_full():
+    w = wl.make(1)
+    out, cs = run_gpu(w)
+    print(check_against_oracle(w, out, cs))
+
+
+@pytest.mark.parametrize("cfg,ov", [
+    (2, dict(batch=2, q_heads=3, kv_heads=3, n=2048, r=128)),      # several problems, kpt = 1 slabs
+    (2, dict(batch=1, q_heads=2, kv_heads=2, n=1000, r=96)),       # ragged n (not a slab multiple), ragged r
+    (3, dict(q_heads=2, kv_heads=2, n=4096, r=256)),
+    (4, dict(q_heads=8, kv_heads=2, n=4096, r=192)),               # grouped queries, r not a multiple of 64
+    (5, dict(q_heads=2, kv_heads=2, n=8192, r=256)),               # heavy-tailed norms, huge dynamic range of p
+])
+def test_shrunk_configs(cfg, ov):
+    w = wl.make(cfg, **ov)
+    out, cs = run_gpu(w)
+    print(cfg, check_against_oracle(w, out, cs))
+
+
+def test_two_keys_per_thread_path_and_many_slabs():
+    """Large enough that the step kernel takes two keys per thread (16-byte history loads)."""
+    w = wl.make(2, batch=2, q_heads=8, kv_heads=8, n=16384, r=64)
+    assert wc.workspace_bytes(16384, 64, 64, 2, 8) > 0
+    out, cs = run_gpu(w)
+    print(check_against_oracle(w, out, cs, heads=[0, 5]))
+
+
+def test_runs_are_bit_reproducible():
+    w = wl.make(3, q_heads=2, kv_heads=2, n=4096, r=128)
+    o1, c1 = run_gpu(w)
+    o2, c2 = run_gpu(w)
+    for a, b in ((o1, o2), (c1.idx, c2.idx), (c1.w, c2.w), (c1.v_s, c2.v_s), (c1.tau, c2.tau)):
+        assert torch.equal(a, b)
+
+
+def test_seed_path_draws_the_documented_uniforms():
+    w = wl.make(1)
+    s = w["shape"]
+    Q, K, V = (to_dev(w[k], s.dtype) for k in ("Q", "K", "V"))
+    for seed in (0, 77):
+        out_seed, cs_seed = wc.wildcat(Q, K, V, r=s.r, seed=seed, return_coreset=True)
+        u = torch.from_numpy(wo.splitmix_uniforms(seed, s.r)).to(dev()).reshape(1, s.r)
+        out_u, cs_u = wc.wildcat(Q, K, V, r=s.r, uniforms=u, return_coreset=True)
+        assert torch.equal(cs_seed.idx, cs_u.idx) and torch.equal(out_seed, out_u)
+    assert not torch.equal(cs_seed.idx, wc.wildcat(Q, K, V, r=s.r, seed=1, return_coreset=True)[1].idx)
+
+
+# ---------------------------------------------------------------------------------- WtdAttn alone
+@pytest.mark.parametrize("dtype,n,m,d,dv", [("f32", 300, 77, 64, 64), ("bf16", 1000, 333, 64, 64),
+                                            ("bf16", 513, 129, 128, 128), ("bf16", 96, 40, 64, 128),
+                                            ("bf16", 200, 50, 64, 256), ("bf16", 70, 33, 48, 80),
+                                            ("f32", 130, 20, 40, 72)])
+def test_wtd_attn_all_keys_unit_weights_is_exact_attention(dtype, n, m, d, dv):
+    """The coreset = all keys with unit weights turns Alg. 3 into eq. (1): checks the kernel against the
+    textbook definition, ragged m and r included, and m != n, d_v != d."""
+    rng = np.random.default_rng(n + m)
+    Q = wl.round_to_storage(rng.standard_normal((1, 2, m, d)), dtype)
+    K = wl.round_to_storage(rng.standard_normal((1, 2, n, d)), dtype)
+    V = wl.round_to_storage(rng.standard_normal((1, 2, n, dv)), dtype)
+    beta = 1.0 / np.sqrt(d)
+    cs = wc.Coreset(idx=torch.zeros((1, 2, n), dtype=torch.int32, device=dev()), r_eff=None,
+                    k_s=to_dev(K, dtype), v_s=to_dev(V, "f32"), w=torch.ones((1, 2, n), device=dev()),
+                    v_min=to_dev(V.min(axis=2), "f32"), v_max=to_dev(V.max(axis=2), "f32"), tau=None)
+    out = wc.wtd_attn(to_dev(Q, dtype), cs).float().cpu().numpy()
+    for h in range(2):
+        ref = wo.exact_attention(Q[0, h].astype(np.float64), K[0, h].astype(np.float64), V[0, h].astype(np.float64),
+                                 beta)
+        assert relmax(out[0, h], ref) <= TOL_OUT[dtype]
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64), ("bf16", 128)])
+def test_wtd_attn_guard_clip_and_oracle_coreset(dtype, d):
+    """Fed an arbitrary coreset with negative weights: rows whose normaliser is not positive give
+    clip(0, v_min, v_max); everything stays inside the value range; matches the oracle's Alg. 3."""
+    rng = np.random.default_rng(5 + d)
+    m, r = 200, 100
+    Q = wl.round_to_storage(rng.standard_normal((1, 1, m, d)), dtype)
+    KS = wl.round_to_storage(rng.standard_normal((1, 1, r, d)), dtype)
+    VS = rng.standard_normal((1, 1, r, d)).astype(np.float32) * 3
+    wts = rng.standard_normal((1, 1, r)).astype(np.float32)
+    wts[0, 0, ::2] -= 0.7                                         # mixed signs: many rows with A w <= 0
+    vmin = np.full((1, 1, d), -0.5, np.float32); vmin[0, 0, 1] = 0.25
+    vmax = np.full((1, 1, d), 1.0, np.float32)
+    cs = wc.Coreset(idx=torch.zeros((1, 1, r), dtype=torch.int32, device=dev()), r_eff=None, k_s=to_dev(KS, dtype),
+                    v_s=to_dev(VS, "f32"), w=to_dev(wts, "f32"), v_min=to_dev(vmin, "f32"), v_max=to_dev(vmax, "f32"),
+                    tau=None)
+    beta = 1.0 / np.sqrt(d)
+    out = wc.wtd_attn(to_dev(Q, dtype), cs).float().cpu().numpy()[0, 0]
+    ref = wo.wtd_attn(Q[0, 0].astype(np.float64), KS[0, 0].astype(np.float64), VS[0, 0].astype(np.float64),
+                      wts[0, 0].astype(np.float64), vmin[0, 0], vmax[0, 0], beta)
+    A = np.exp(beta * Q[0, 0].astype(np.float64) @ KS[0, 0].astype(np.float64).T)
+    den = A @ wts[0, 0].astype(np.float64)
+    safe = np.abs(den) > 1e-2 * np.abs(A).sum(1)                  # rows whose sign test is not a coin flip
+    bad = safe & (den <= 0)
+    assert bad.sum() > 5 and (safe & (den > 0)).sum() > 5
+    np.testing.assert_array_equal(out[bad], np.tile(np.clip(0.0, vmin[0, 0], vmax[0, 0]), (bad.sum(), 1)))
+    assert np.all(out >= vmin[0, 0]) and np.all(out <= vmax[0, 0])
+    # where the normaliser is well away from zero the clipped values agree with the oracle
+    good = np.abs(den) > 0.2 * np.abs(A).sum(1)
+    assert np.abs(out[good] - ref[good]).max() <= (3e-2 if dtype == "bf16" else 1e-4)
+
+
+def test_query_radius_grouped():
+    rng = np.random.default_rng(3)
+    Q = wl.round_to_storage(rng.standard_normal((2, 6, 700, 64)) * rng.uniform(0.5, 2, (2, 6, 1, 1)), "bf16")
+    got = wc.query_radius(to_dev(Q, "bf16"), kv_heads=2).cpu().numpy()
+    nrm = np.sqrt((Q.astype(np.float64) ** 2).sum(-1)).reshape(2, 2, 3 * 700).max(-1)
+    np.testing.assert_allclose(got, nrm, rtol=1e-14)
+
+
+# ---------------------------------------------------------------------------------- degenerate inputs
+def test_rank_exhaustion_with_duplicate_keys():
+    """Keys drawn from q distinct vectors: the kernel matrix has rank q; the loop stops after q pivots, the
+    remaining slots are empty and the result equals exact attention."""
+    rng = np.random.default_rng(11)
+    n, d, q, r = 600, 64, 9, 16
+    proto = wl.round_to_storage(rng.standard_normal((q, d)), "f32")
+    lab = np.concatenate([np.arange(q), rng.integers(0, q, n - q)])
+    rng.shuffle(lab)
+    K = proto[lab][None, None]
+    V = wl.round_to_storage(rng.standard_normal((1, 1, n, d)), "f32")
+    Q = wl.round_to_storage(rng.standard_normal((1, 1, 128, d)), "f32")
+    u = rng.random((1, r))
+    w = {"shape": wl.shape(1, n=n, r=r), "Q": Q, "K": K, "V": V, "u": u}
+    out, cs = wc.wildcat(to_dev(Q, "f32"), to_dev(K, "f32"), to_dev(V, "f32"), r=r,
+                         uniforms=torch.from_numpy(u).to(dev()), return_coreset=True)
+    assert cs.r_eff.item() == q
+    idx = cs.idx.cpu().numpy()[0, 0]
+    assert sorted(lab[idx[:q]].tolist()) == list(range(q)) and np.all(idx[q:] == -1)
+    assert torch.all(cs.w[0, 0, q:] == 0) and torch.all(cs.v_s[0, 0, q:] == 0) and torch.all(cs.k_s[0, 0, q:] == 0)
+    check_against_oracle(w, out, cs)
+    ref = wo.exact_attention(Q[0, 0].astype(np.float64), K[0, 0].astype(np.float64), V[0, 0].astype(np.float64),
+                             1 / np.sqrt(d))
+    assert relmax(out.cpu().numpy()[0, 0], ref) <= 1e-5
+
+
+def test_r_equals_n_and_tiny_problem():
+    rng = np.random.default_rng(12)
+    n, d = 24, 64
+    Q, K, V = (wl.round_to_storage(rng.standard_normal((1, 1, n, d)) * sc, "f32") for sc in (1.0, 2.0, 1.0))
+    u = rng.random((1, n))
+    w = {"shape": wl.shape(1, n=n, r=n), "Q": Q, "K": K, "V": V, "u": u}
+    out, cs = run_gpu(w)
+    check_against_oracle(w, out, cs)
+    assert sorted(cs.idx.cpu().numpy()[0, 0].tolist()) == list(range(n))
+    ref = wo.exact_attention(Q[0, 0].astype(np.float64), K[0, 0].astype(np.float64), V[0, 0].astype(np.float64),
+                             1 / np.sqrt(d))
+    assert relmax(out.cpu().numpy()[0, 0], ref) <= 1e-5
+
+
+def test_identical_keys_zero_radius():
+    """All keys equal: R_K = 0, every kernel value is 1, one pivot carries all n weights."""
+    rng = np.random.default_rng(13)
+    n, d = 300, 64
+    K = np.tile(wl.round_to_storage(rng.standard_normal((1, 1, 1, d)), "f32"), (1, 1, n, 1))
+    V = wl.round_to_storage(rng.standard_normal((1, 1, n, d)), "f32")
+    Q = wl.round_to_storage(rng.standard_normal((1, 1, 64, d)), "f32")
+    u = torch.from_numpy(rng.random((1, 4))).to(dev())
+    out, cs = wc.wildcat(to_dev(Q, "f32"), to_dev(K, "f32"), to_dev(V, "f32"), r=4, uniforms=u, return_coreset=True)
+    assert cs.r_eff.item() == 1 and torch.isinf(cs.tau).all()
+    assert cs.w[0, 0, 0].item() == pytest.approx(n, rel=1e-6)
+    np.testing.assert_allclose(out.cpu().numpy()[0, 0], np.tile(V[0, 0].astype(np.float64).mean(0), (64, 1)),
+                               rtol=1e-4, atol=1e-6)

@@ -1,0 +1,91 @@
+"""Host-side checks of libwildcat that need no GPU: the library loads, exports every symbol the header
+declares, validates arguments before launching anything, and its uniform stream is the documented one."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2602_10056_amd as wc
+from oracle import wildcat_oracle as wo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(wc.LIB_PATH), reason="libwildcat.so not built")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "wildcat.h")).read()
+    declared = set(re.findall(r"^(?:int|size_t|const char \*)\s*(wildcat_[a-z_0-9]+)\(", header, flags=re.M))
+    assert declared == set(wc.EXPORTS)
+    lib = wc.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert wc.version() >= 100
+
+
+def test_struct_layout_matches_header_order():
+    header = open(os.path.join(ROOT, "include", "wildcat.h")).read()
+    body = header[header.index("typedef struct {", header.index("Options.")):header.index("} wildcat_opts;")]
+    names = re.findall(r"\b(\w+);\s*(?:/\*|$)", body, flags=re.M)
+    assert names == [f[0] for f in wc._Opts._fields_]
+    body = header[header.index("typedef struct {", header.index("compressed cache")):header.index("} wildcat_coreset;")]
+    names = re.findall(r"\*(\w+);", body)
+    assert names == [f[0] for f in wc._Coreset._fields_]
+
+
+def test_strerror():
+    lib = wc.load_library()
+    texts = {lib.wildcat_strerror(c).decode() for c in (0, -1, -2, -3, -4, -99)}
+    assert len(texts) == 6 and all(texts)
+
+
+def test_uniform_stream_equals_the_documented_generator():
+    for seed in (0, 1234567, 2 ** 63 + 5):
+        np.testing.assert_array_equal(wc.draw_uniforms(seed, 257), wo.splitmix_uniforms(seed, 257))
+    assert wc.load_library().wildcat_draw_uniforms(1, -1, None) == -1
+
+
+def test_workspace_bytes():
+    a = wc.workspace_bytes(4096, 64, 128, batch=4, kv_heads=8)
+    b = wc.workspace_bytes(8192, 64, 128, batch=4, kv_heads=8)
+    assert 0 < a < b and a % 256 == 0
+    # dominated by the fp64 history P * n * r * 8
+    assert a >= 32 * 4096 * 128 * 8
+    assert wc.workspace_bytes(100, 64, 101) == 0            # r > n
+    assert wc.workspace_bytes(100, 0, 10) == 0
+    assert wc.workspace_bytes(100, 64, 10, dtype=7) == 0
+    assert wc.workspace_bytes(100000, 64, 5000) == 0        # rank limit of this build
+
+
+def test_entry_points_reject_bad_arguments_before_launching():
+    lib = wc.load_library()
+    o = wc._Opts()
+    c = wc._Coreset()
+    one = ctypes.c_void_p(8)          # never dereferenced: validation fails first
+    assert lib.wildcat_compress_kv(None, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, None, ctypes.byref(c)) == -1
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # no r_q
+    o.r_q = 8
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # null outputs
+    for f, _ in wc._Coreset._fields_:
+        setattr(c, f, 8)
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -2   # no workspace
+    o.workspace, o.workspace_bytes = 256, 16
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -2   # too small
+    o.workspace, o.workspace_bytes = 264, 1 << 40
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -2   # misaligned
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 129, 0, ctypes.byref(o), ctypes.byref(c)) == -1  # r > n
+    o.bins = 4
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -4   # binning
+    o.bins = 0
+    o.q_heads, o.kv_heads = 6, 4
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # 6 % 4
+    o.q_heads, o.kv_heads = 0, 0
+    assert lib.wildcat_compress_kv(one, one, 128, 512, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -4  # d too wide
+    assert lib.wildcat_wtd_attn(None, ctypes.byref(c), one, 16, 64, 16, ctypes.byref(o)) == -1
+    assert lib.wildcat_wtd_attn(one, ctypes.byref(c), one, 0, 64, 16, ctypes.byref(o)) == -1
+    o.dtype = 3
+    assert lib.wildcat_wtd_attn(one, ctypes.byref(c), one, 16, 64, 16, ctypes.byref(o)) == -1
+    assert lib.wildcat_query_radius(one, 0, 64, ctypes.byref(o), one) == -1

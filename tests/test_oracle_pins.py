@@ -332,6 +332,19 @@ def test_compress_kv_shift_invariance_and_definitions():
     np.testing.assert_allclose(oa, ob, atol=1e-8)
 
 
+def test_identical_keys_collapse_to_one_pivot_and_the_value_mean():
+    """R_K = 0: the kernel matrix is all ones (rank 1), one pivot carries weight n and WildCat returns the
+    mean value row, which is what eq. (1) gives for identical keys."""
+    rng = np.random.default_rng(14)
+    K = np.tile(rng.standard_normal((1, 5)).astype(np.float32).astype(np.float64), (40, 1))   # mean is exact
+    V, Q = rng.standard_normal((40, 3)), rng.standard_normal((6, 5))
+    out, cs, _ = wo.wildcat(Q, K, V, 0.4, 4, rng.random(4), return_coreset=True)
+    assert cs.r_eff == 1 and math.isinf(cs.tau) and cs.beta_tau == 0.0
+    assert cs.w[0] == pytest.approx(40.0, rel=1e-12)
+    np.testing.assert_allclose(out, np.tile(V.mean(0), (6, 1)), rtol=1e-12)
+    np.testing.assert_allclose(out, wo.exact_attention(Q, K, V, 0.4), rtol=1e-12)
+
+
 def test_wtd_attn_all_keys_unit_weights_is_exact_attention():
     rng = np.random.default_rng(10)
     Q, K, V = rng.standard_normal((13, 5)), rng.standard_normal((29, 5)), rng.standard_normal((29, 4))

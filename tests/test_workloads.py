@@ -36,7 +36,7 @@ def test_recipes_have_the_documented_structure():
     assert abs(np.log(nrm[16:] / np.sqrt(128)).std() - 0.5) < 0.05             # log-normal norms
     w = wl.make(2, batch=1, q_heads=1, kv_heads=1, n=2048)
     sv = np.linalg.svd(w["K"][0, 0].astype(np.float64), compute_uv=False)
-    assert sv[31] > 5 * sv[32]                                                  # rank 32 plus small noise
+    assert sv[31] > 3 * sv[32]                                                  # rank 32 plus small noise
     w = wl.make(4, q_heads=4, kv_heads=1, n=64)
     assert w["shape"].group == 4
     # rotary rotation preserves row norms
