@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the WildCat hot path on one MI355X.
+
+A "step" is one pass of the whole path -- query radius, CompressKV (prologue, RPNys selection loop,
+Gram pass, core solve, gather) and WtdAttn -- over one batch of synthetic attention inputs that are
+already resident in HBM.  Workload: 32 query heads sharing 8 key/value heads, n = m = 32768, d = 128,
+r = 512, bf16 storage (rotary-rotated Gaussian inputs), the shape the headline metric is quoted on.
+
+Prints ONE JSON line: tokens/s of the whole path, the roofline of the dominant kernel (the RPNys step
+kernel, HBM-bound, timed with HIP events on the launch stream), the WtdAttn MFMA rate, the float64 CPU
+oracle timed on the host cores, and exact attention at the same shape for context.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs (the library records them on its launch stream)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        return ev
+
+    def elapsed_ms(self, a, b):
+        if self.hip.hipEventSynchronize(b) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+        ms = ctypes.c_float()
+        if self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+
+def step_loop_bytes(P, n, d, r, es):
+    """Algorithmic HBM bytes of the r launches of the RPNys step kernel: per launch i and key, the key row
+    (d * es), the i earlier Cholesky entries of that key (8 i), the new entry (8), and p read + written (16)."""
+    return float(P) * n * (r * (d * es + 8 + 16) + 8.0 * r * (r - 1) / 2.0)
+
+
+def cpu_baseline(w, budget_heads):
+    """The float64 oracle, as it stands, on the host cores; whole kv heads of the benchmark workload."""
+    import numpy as np
+    from oracle import wildcat_oracle as wo
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    s = w["shape"]
+    t0 = time.perf_counter()
+    done = 0
+    for h in range(budget_heads):
+        Qg = w["Q"][0, h * s.group:(h + 1) * s.group].astype(np.float64)
+        wo.wildcat(Qg, w["K"][0, h].astype(np.float64), w["V"][0, h].astype(np.float64), s.beta, s.r, w["u"][h])
+        done += 1
+        if time.perf_counter() - t0 > 20.0:
+            break
+    dt = time.perf_counter() - t0
+    tokens_per_s = s.batch * s.n / (dt * s.kv_heads / done)
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{done} of {s.kv_heads} kv heads (each with its {s.group} query heads) of the same workload, "
+                      f"full n={s.n}, r={s.r}; {dt:.1f} s of float64 NumPy; scaled to all heads"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--cfg", type=int, default=4, help="workload catalogue entry (4 = headline shape)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-exact", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives): use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2602_10056_amd as wc
+    from paper_2602_10056_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    wc.load_library()
+    dev = torch.device("cuda:0")
+    w = wl.make(args.cfg)
+    s = w["shape"]
+    tdt = torch.bfloat16 if s.dtype == "bf16" else torch.float32
+    es = 2 if s.dtype == "bf16" else 4
+    Q, K, V = (torch.from_numpy(w[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
+    u = torch.from_numpy(w["u"]).to(dev)
+    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.d, 1 if s.dtype == "bf16" else 0),
+                     dtype=torch.uint8, device=dev)
+    out = torch.empty((s.batch, s.q_heads, s.n, s.d), dtype=tdt, device=dev)
+    hev = HipEvents()
+    loop_ev = [(hev.create(), hev.create()) for _ in range(args.steps)]
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+
+    def one_step(k=None):
+        ev = loop_ev[k] if k is not None else None
+        if k is not None:
+            marks[k][0].record()
+        r_q = wc.query_radius(Q, s.kv_heads)
+        if k is not None:
+            marks[k][1].record()
+        cs = wc.compress_kv(K, V, s.r, r_q, uniforms=u, workspace=ws, loop_events=ev)
+        if k is not None:
+            marks[k][2].record()
+        wc.wtd_attn(Q, cs, out=out)
+        if k is not None:
+            marks[k][3].record()
+        return cs
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        cs = one_step(k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    loop_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in loop_ev]))
+    ph = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(3)] for m in marks]).mean(axis=0)
+    P = s.problems
+    loop_bytes = step_loop_bytes(P, s.n, s.d, s.r, es)
+    achieved = loop_bytes / (loop_ms * 1e-3) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "rpnys_step_traffic.json")
+    if os.path.exists(tfile) and args.cfg == 4:
+        with open(tfile) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    attn_flops = float(s.batch * s.q_heads) * s.n * (4.0 * s.r * s.d + 2.0 * s.r)
+    attn_tflops = attn_flops / (ph[2] * 1e-3) / 1e12
+
+    res = {
+        "metric": "WildCat attention tokens/sec + HBM/MFMA % of peak vs exact attn at n=32K",
+        "value": s.batch * s.n / (dt / args.steps),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": f"{s.name}: batch {s.batch} x {s.q_heads} query heads / {s.kv_heads} kv heads, "
+                               f"n=m={s.n}, d={s.d}, r={s.r}, B=1, {s.dtype} storage; selection loop in fp64, "
+                               f"WtdAttn on bf16 MFMA with fp32 accumulation",
+                   "uniform_seed": s.uniform_seed, "data_seed": s.data_seed},
+        "phases_ms": {"query_radius": float(ph[0]), "compress_kv": float(ph[1]), "rpnys_loop": loop_ms,
+                      "wtd_attn": float(ph[2])},
+        "roofline": {"kernel": "k_step (RPNys selection loop, one launch per step)", "bound": "hbm",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "launches": s.r, "avg_launch_ms": loop_ms / s.r,
+                     "algorithmic_bytes_per_launch": loop_bytes / s.r},
+        "wtd_attn": {"bound": "mfma", "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS},
+    }
+
+    if not args.no_exact:
+        try:
+            import torch.nn.functional as F
+            Kx = K.repeat_interleave(s.group, dim=1)
+            Vx = V.repeat_interleave(s.group, dim=1)
+            for _ in range(2):
+                F.scaled_dot_product_attention(Q, Kx, Vx)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(3):
+                F.scaled_dot_product_attention(Q, Kx, Vx)
+            b.record()
+            torch.cuda.synchronize()
+            ems = a.elapsed_time(b) / 3
+            res["exact_attention"] = {"impl": "torch scaled_dot_product_attention (ROCm)", "ms": ems,
+                                      "tokens_per_s": s.batch * s.n / (ems * 1e-3)}
+            del Kx, Vx
+        except Exception as e:           # context only; never fatal
+            res["exact_attention"] = {"error": str(e)[:200]}
+
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, s.kv_heads)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -77,6 +77,9 @@ typedef struct {
                      /* B > 1 returns WILDCAT_EUNSUPPORTED.                         */
   int32_t reserved0;
   void *stream;      /* hipStream_t                                                 */
+  void *ev_loop_begin; /* optional hipEvent_t pair that wildcat_compress_kv records  */
+  void *ev_loop_end; /* on the stream right before the first and right after the    */
+                     /* last launch of the RPNys selection loop (for profiling)     */
   void *workspace;   /* device scratch, 256-byte aligned, of at least               */
   size_t workspace_bytes; /* wildcat_workspace_bytes(...) bytes                     */
 } wildcat_opts;

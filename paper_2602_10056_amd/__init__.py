@@ -30,7 +30,8 @@ class _Opts(ctypes.Structure):
         ("beta", ctypes.c_double), ("rank_tol", ctypes.c_double),
         ("r_q", ctypes.c_void_p), ("uniforms", ctypes.c_void_p),
         ("bins", ctypes.c_int32), ("reserved0", ctypes.c_int32),
-        ("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p), ("ev_loop_begin", ctypes.c_void_p), ("ev_loop_end", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
     ]
 
 
@@ -163,9 +164,10 @@ def query_radius(Q, kv_heads=None):
     return out
 
 
-def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None):
+def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, loop_events=None):
     """CompressKV (Alg. 2).  K: [B, Hkv, n, d], V: [B, Hkv, n, dv]; r_q: float64 [B, Hkv] on the device;
-    uniforms: optional float64 [B*Hkv, r] on the device (else drawn from `seed`).  Returns a Coreset."""
+    uniforms: optional float64 [B*Hkv, r] on the device (else drawn from `seed`); loop_events: optional pair
+    of raw hipEvent_t handles recorded around the RPNys loop.  Returns a Coreset."""
     import torch
     _need(K, "K", 4)
     _need(V, "V", 4)
@@ -196,6 +198,8 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
         tau=torch.empty((B, H), dtype=torch.float64, device=dev),
     )
     o = _opts(B, H, H, n, dv, code, beta, rank_tol, r_q.contiguous(), uniforms, workspace)
+    if loop_events is not None:
+        o.ev_loop_begin, o.ev_loop_end = loop_events
     c = cs.c_struct()
     _check(load_library().wildcat_compress_kv(K.data_ptr(), V.data_ptr(), n, d, r, seed, ctypes.byref(o),
                                               ctypes.byref(c)), "wildcat_compress_kv")

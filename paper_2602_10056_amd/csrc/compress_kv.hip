@@ -704,10 +704,12 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   a.p = p; a.bsum = bsum; a.F = F; a.L = L; a.U = U; a.idx = out->idx; a.r_eff = out->r_eff;
   a.n = s.n; a.npad = pl.npad; a.P = P; a.nblk = pl.nblk; a.r = s.r; a.dpad = pl.dpad;
   const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
+  if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
   for (int i = 0; i < s.r; ++i) {
     hipLaunchKernelGGL((k_step<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), step_lds, st, a, i);
     LAUNCH_CHECK();
   }
+  if (o->ev_loop_end && hipEventRecord((hipEvent_t)o->ev_loop_end, st) != hipSuccess) return WILDCAT_EHIP;
 
   const int rtiles = (s.r + kGramRows - 1) / kGramRows;
   const dim3 ggrid(pl.nchunk, rtiles, P);
