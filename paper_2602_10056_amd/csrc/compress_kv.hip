@@ -294,18 +294,22 @@ struct StepArgs {
   int P, nblk, r, dpad;
 };
 
+// History loads are streaming: each entry is read once per step and the working set (hundreds of MB)
+// exceeds every cache, so they are issued as non-temporal loads, which measurably raises the sustained
+// HBM read rate on this part.
+typedef double dbl2 __attribute__((ext_vector_type(2)));
 template <int KPT>
 struct HistVec;
 template <>
 struct HistVec<1> {
   double v[1];
-  __device__ __forceinline__ void load(const double *p) { v[0] = *p; }
+  __device__ __forceinline__ void load(const double *p) { v[0] = __builtin_nontemporal_load(p); }
 };
 template <>
 struct HistVec<2> {
   double v[2];
   __device__ __forceinline__ void load(const double *p) {
-    const double2 x = *reinterpret_cast<const double2 *>(p);
+    const dbl2 x = __builtin_nontemporal_load(reinterpret_cast<const dbl2 *>(p));
     v[0] = x.x; v[1] = x.y;
   }
 };
@@ -432,29 +436,40 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
   const double beta_tau = a.scal[(size_t)pr * 8 + 2];
 
   // ---- 5. history product  acc_l = sum_{j<i} F_j(l) g_j  (the O(n i) stream) ---------------------------
+  // Rows are walked upwards on even steps and downwards on odd steps: the rows a step reads last are the
+  // rows the next step reads first, so whatever part of the history the memory-side cache still holds is
+  // reused before it is evicted.  (The order is fixed per step, so results stay reproducible.)
   double acc[KPT];
 #pragma unroll
   for (int k = 0; k < KPT; ++k) acc[k] = 0.0;
   {
-    const double *fp = Fb + l_loc;
+    const bool down = (i & 1) != 0;
+    const ptrdiff_t fstep = down ? -(ptrdiff_t)SLAB : (ptrdiff_t)SLAB;
+    const int gstep = down ? -1 : 1;
+    const double *fp = Fb + l_loc + (down ? (size_t)(i - 1) * SLAB : 0);
+    const double *gp = g + (down ? i - 1 : 0);
     int j = 0;
     for (; j + 8 <= i; j += 8) {
       HistVec<KPT> h[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) h[q].load(fp + (size_t)(j + q) * SLAB);
+      for (int q = 0; q < 8; ++q) h[q].load(fp + q * fstep);
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        const double gj = g[j + q];
+        const double gj = gp[q * gstep];
 #pragma unroll
         for (int k = 0; k < KPT; ++k) acc[k] = fma(h[q].v[k], gj, acc[k]);
       }
+      fp += 8 * fstep;
+      gp += 8 * gstep;
     }
     for (; j < i; ++j) {
       HistVec<KPT> h;
-      h.load(fp + (size_t)j * SLAB);
-      const double gj = g[j];
+      h.load(fp);
+      const double gj = *gp;
 #pragma unroll
       for (int k = 0; k < KPT; ++k) acc[k] = fma(h.v[k], gj, acc[k]);
+      fp += fstep;
+      gp += gstep;
     }
   }
 
