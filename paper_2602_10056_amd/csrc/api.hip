@@ -48,10 +48,10 @@ Plan make_plan(const Shape &s) {
   p.nblk = (int)((s.n + p.slab - 1) / p.slab);
   p.npad = (int64_t)p.nblk * p.slab;
   p.dpad = (s.d + kChunk - 1) / kChunk * kChunk;
-  int64_t nb0 = (s.n + 1023) / 1024;
-  p.nb0 = (int)(nb0 > 256 ? 256 : nb0);
+  int64_t nb0 = (s.n + 127) / 128;
+  p.nb0 = (int)(nb0 > 512 ? 512 : nb0);
   // Gram pass: about 1024 workgroups in total, each a whole number of slabs.
-  int rtiles = (s.r + 63) / 64;
+  int rtiles = (s.r + 127) / 128;
   int want = 1024 / (s.P * rtiles);
   if (want < 1) want = 1;
   if (want > p.nblk) want = p.nblk;
@@ -70,7 +70,6 @@ Plan make_plan(const Shape &s) {
   p.off_scal = take(P * 8 * 8);
   p.off_F = take(P * n * r * 8);
   p.off_L = take(P * r * r * 8);
-  p.off_U = take(P * r * r * 8);
   p.off_gpart = take(P * p.nchunk * r * dv1 * 8);
   p.off_g = take(P * r * dv1 * 8);
   p.off_mpart = take(P * p.nb0 * (size_t)p.dpad * 8);

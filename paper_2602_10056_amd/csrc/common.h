@@ -12,7 +12,7 @@ namespace wildcat {
 constexpr int kThreads = 256;       // workgroup size of every streaming kernel (4 wavefronts of 64)
 constexpr int kWave = 64;
 constexpr int kMaxWidth = 256;      // largest key / value width d, dv
-constexpr int kMaxRank = 4096;      // largest coreset size r
+constexpr int kMaxRank = 2048;      // largest coreset size r (the core solve keeps 8 columns of r doubles in LDS)
 constexpr int kChunk = 4;           // keys are re-packed as [d/4][n][4] for coalesced per-key access
 
 // ---- resolved options -------------------------------------------------------------------------
@@ -37,7 +37,7 @@ struct Plan {
   int nb0;          // row blocks of the column-statistics pass
   int nchunk;       // n-chunks of the Gram pass (each a whole number of slabs)
   int slabs_per_chunk;
-  size_t off_kbar, off_kp, off_d0, off_p, off_bsum, off_scal, off_F, off_L, off_U, off_gpart, off_g,
+  size_t off_kbar, off_kp, off_d0, off_p, off_bsum, off_scal, off_F, off_L, off_gpart, off_g,
       off_mpart, off_vminpart, off_vmaxpart, off_u;
   size_t total;
 };

@@ -288,7 +288,7 @@ struct StepArgs {
   double *p;              // [2][P][npad]   residual diagonal, double-buffered by step parity
   double *bsum;           // [2][P][nblk]   per-slab sums of p, same parity
   double *F;              // [P][nblk][r][slab]
-  double *L, *U;          // [P][r][r] Cholesky factor of h(K_S,K_S) (row-major lower) and its transpose
+  double *L;              // [P][r][r] Cholesky factor of h(K_S,K_S), row-major, lower triangle
   int32_t *idx, *r_eff;
   int64_t n, npad;
   int P, nblk, r, dpad;
@@ -514,14 +514,9 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
   // ---- 8. bookkeeping by the slab that owns the pivot -----------------------------------------------------
   if (b == bstar) {
     double *Lr = a.L + ((size_t)pr * a.r + i) * a.r;
-    double *Uc = a.U + (size_t)pr * a.r * a.r + i;
-    for (int j = t; j < i; j += kThreads) {
-      Lr[j] = g[j];
-      Uc[(size_t)j * a.r] = g[j];
-    }
+    for (int j = t; j < i; j += kThreads) Lr[j] = g[j];
     if (own) {
       Lr[i] = fs;
-      Uc[(size_t)i * a.r] = fs;
       a.idx[(size_t)pr * a.r + i] = (int32_t)s_glob;
     }
   }
@@ -529,24 +524,26 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 
 // --------------------------------------------------------------------------------------------
 // Gram pass  G = F [V, 1]  (Alg. 2 last line, reordered as in Sec. 2.1: weights times (V, 1_n) first).
-// grid (nchunk, ceil(r/64), P); workgroup tile 64 rows of F x all dv columns; thread (ty, tx) owns rows
-// 4ty..4ty+3 and columns tx + 16 q.  fp64 accumulation; partial sums per n-chunk, reduced in order later.
+// grid (nchunk * ncoltiles, ceil(r/128), P); workgroup tile = 128 rows of F x 16*CW value columns; thread
+// (ty, tx) owns rows 8ty..8ty+7 and columns tx + 16 c: 8 x CW fp64 accumulators fed from LDS tiles of
+// 16 keys (F as is, V widened to fp64 once per tile).  Partial sums per n-chunk, reduced in order later.
 // --------------------------------------------------------------------------------------------
-constexpr int kGramRows = 64, kGramKT = 32;
+constexpr int kGramRows = 128, kGramKT = 16;
 
 template <typename T, int CW>
 __global__ __launch_bounds__(kThreads) void k_gram(const double *__restrict__ F, const T *__restrict__ V, int64_t n,
                                                    int nblk, int slab, int r, int dv, int slabs_per_chunk,
-                                                   int nchunk, double *__restrict__ gpart) {
+                                                   int nchunk, int ncoltiles, double *__restrict__ gpart) {
   __shared__ double Fs[kGramRows][kGramKT + 1];
-  __shared__ float Vs[kGramKT][16 * CW];
-  const int t = threadIdx.x, ch = blockIdx.x, rt = blockIdx.y, pr = blockIdx.z;
+  __shared__ double Vs[kGramKT][16 * CW];
+  const int t = threadIdx.x, ch = blockIdx.x / ncoltiles, ct = blockIdx.x % ncoltiles, rt = blockIdx.y,
+            pr = blockIdx.z;
   const int ty = t / 16, tx = t % 16;
-  const int a0 = rt * kGramRows;
-  double acc[4][CW];
-  double rs[4];
+  const int a0 = rt * kGramRows, col0 = ct * 16 * CW;
+  double acc[8][CW];
+  double rs[8];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < 8; ++q) {
     rs[q] = 0.0;
 #pragma unroll
     for (int c = 0; c < CW; ++c) acc[q][c] = 0.0;
@@ -559,51 +556,51 @@ __global__ __launch_bounds__(kThreads) void k_gram(const double *__restrict__ F,
       const int64_t lbase = (int64_t)sb * slab + k0;
       if (lbase >= n) break;
       __syncthreads();
-      {  // F tile: 64 rows x 32 keys; thread loads 8 consecutive keys of one row
-        const int row = t / 4, seg = (t % 4) * 8;
+      {  // F tile: 128 rows x 16 keys; thread loads 8 consecutive keys of one row
+        const int row = t / 2, seg = (t % 2) * 8;
         const bool ok = a0 + row < r;
         const double *src = Fslab + (size_t)(a0 + row) * slab + k0 + seg;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-          double2 v = ok ? *reinterpret_cast<const double2 *>(src + e) : make_double2(0.0, 0.0);
+          const double2 v = ok ? *reinterpret_cast<const double2 *>(src + e) : make_double2(0.0, 0.0);
           Fs[row][seg + e] = v.x;
           Fs[row][seg + e + 1] = v.y;
         }
       }
-      for (int e = t; e < kGramKT * dv; e += kThreads) {  // V tile: 32 keys x dv
-        const int kk = e / dv, c = e % dv;
+      for (int e = t; e < kGramKT * 16 * CW; e += kThreads) {  // V tile: 16 keys x (16 CW) columns, as fp64
+        const int kk = e / (16 * CW), c = e % (16 * CW);
         const int64_t l = lbase + kk;
-        Vs[kk][c] = l < n ? to_float(V[((size_t)pr * n + l) * dv + c]) : 0.0f;
+        Vs[kk][c] = (l < n && col0 + c < dv) ? (double)to_float(V[((size_t)pr * n + l) * dv + col0 + c]) : 0.0;
       }
       __syncthreads();
-#pragma unroll 4
+#pragma unroll 2
       for (int kk = 0; kk < kGramKT; ++kk) {
-        double fv[4];
+        double fv[8], vv[CW];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) fv[q] = Fs[4 * ty + q][kk];
+        for (int q = 0; q < 8; ++q) fv[q] = Fs[8 * ty + q][kk];
+#pragma unroll
+        for (int c = 0; c < CW; ++c) vv[c] = Vs[kk][tx + 16 * c];
         if (tx == 0) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) rs[q] += fv[q];
+          for (int q = 0; q < 8; ++q) rs[q] += fv[q];
         }
 #pragma unroll
-        for (int c = 0; c < CW; ++c) {
-          const double vv = (double)Vs[kk][tx + 16 * c];
+        for (int q = 0; q < 8; ++q)
 #pragma unroll
-          for (int q = 0; q < 4; ++q) acc[q][c] = fma(fv[q], vv, acc[q][c]);
-        }
+          for (int c = 0; c < CW; ++c) acc[q][c] = fma(fv[q], vv[c], acc[q][c]);
       }
     }
   }
   const int dv1 = dv + 1;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int arow = a0 + 4 * ty + q;
+  for (int q = 0; q < 8; ++q) {
+    const int arow = a0 + 8 * ty + q;
     if (arow >= r) continue;
     double *dst = gpart + (((size_t)pr * nchunk + ch) * r + arow) * dv1;
 #pragma unroll
     for (int c = 0; c < CW; ++c)
-      if (tx + 16 * c < dv) dst[tx + 16 * c] = acc[q][c];
-    if (tx == 0) dst[dv] = rs[q];
+      if (col0 + tx + 16 * c < dv) dst[col0 + tx + 16 * c] = acc[q][c];
+    if (tx == 0 && ct == 0) dst[dv] = rs[q];
   }
 }
 
@@ -620,34 +617,78 @@ __global__ __launch_bounds__(kThreads) void k_gram_reduce(const double *__restri
 }
 
 // --------------------------------------------------------------------------------------------
-// Core solve  X = L^-T G  (W [V,1] = L^-T F [V,1]): back substitution with U = L^T, one right-hand-side
-// column per 32 lanes, cpw columns per workgroup, the column held in LDS.  grid (ceil(dv1/cpw), P),
-// block 32*cpw.  Writes V_S (columns < dv) and w (column dv) as fp32; rows >= r_eff are zero.
+// Core solve  X = L^-T G  (W [V,1] = L^-T F [V,1]): back substitution, kSolveCols right-hand-side columns per
+// workgroup, the columns held in LDS.  Rows are taken in panels of 32 from the bottom:
+//   1. the 32 x 32 diagonal block of L goes to LDS; each column is solved inside the panel by its own 32
+//      lanes (lane b keeps entry b in a register, the pivot value travels by a lane broadcast);
+//   2. the panel's solution is eliminated from all rows above with one pass over the panel's rows of L
+//      (contiguous in k, all threads), which amortises the memory latency over 32 substitution steps.
+// grid (ceil(dv1/kSolveCols), P), block 32*kSolveCols.  Writes V_S (columns < dv) and w (column dv) as
+// fp32; rows >= r_eff are zero.  LDS: (kSolveCols * r + 32*33 + kSolveCols*32) doubles.
 // --------------------------------------------------------------------------------------------
-__global__ void k_solve(const double *__restrict__ U, const double *__restrict__ Gt, const int32_t *__restrict__ r_eff,
-                        int r, int dv, int cpw, float *__restrict__ v_s, float *__restrict__ w) {
+constexpr int kSolveCols = 8, kPanel = 32;
+
+__global__ __launch_bounds__(kSolveCols * 32) void k_solve(const double *__restrict__ L,
+                                                           const double *__restrict__ Gt,
+                                                           const int32_t *__restrict__ r_eff, int r, int dv,
+                                                           float *__restrict__ v_s, float *__restrict__ w) {
   extern __shared__ double dyn[];
-  const int pr = blockIdx.y, grp = threadIdx.x / 32, q = threadIdx.x % 32;
-  const int c = blockIdx.x * cpw + grp;
-  const int dv1 = dv + 1;
+  double *gc = dyn;                                   // [kSolveCols][r]
+  double *ld = gc + (size_t)kSolveCols * r;           // [32][33] diagonal block (reciprocals on the diagonal)
+  double *xs = ld + kPanel * (kPanel + 1);            // [kSolveCols][32] panel solution
+  const int pr = blockIdx.y, t = threadIdx.x, grp = t / 32, q = t % 32, nt = kSolveCols * 32;
+  const int dv1 = dv + 1, c0 = blockIdx.x * kSolveCols;
+  const int ncol = min(kSolveCols, dv1 - c0);
   const int re = r_eff[pr];
-  if (c >= dv1) return;                       // whole 32-lane groups leave together; no workgroup barrier below
-  double *x = dyn + (size_t)grp * r;
-  const double *Up = U + (size_t)pr * r * r;
-  const double *gcol = Gt + ((size_t)pr * dv1 + c) * r;
-  for (int j = re - 1; j >= 0; --j) {
-    const double *urow = Up + (size_t)j * r;
-    double part = 0.0;
-    for (int k = j + 1 + q; k < re; k += 32) part = fma(urow[k], x[k], part);
-#pragma unroll
-    for (int off = 16; off > 0; off >>= 1) part += __shfl_xor(part, off, 32);
-    const double xj = (gcol[j] - part) / urow[j];
-    if (q == 0) x[j] = xj;
-    __builtin_amdgcn_wave_barrier();
+  const double *Lp = L + (size_t)pr * r * r;
+  for (int e = t; e < ncol * re; e += nt) {
+    const int c = e / re, k = e % re;
+    gc[(size_t)c * r + k] = Gt[((size_t)pr * dv1 + c0 + c) * r + k];
   }
-  for (int j = q; j < r; j += 32) {
-    const float val = j < re ? (float)x[j] : 0.0f;
-    if (c < dv) v_s[((size_t)pr * r + j) * dv + c] = val;
+  for (int j1 = re; j1 > 0; j1 -= kPanel) {
+    const int j0 = j1 > kPanel ? j1 - kPanel : 0, np = j1 - j0;
+    __syncthreads();
+    for (int e = t; e < np * np; e += nt) {
+      const int a = e / np, bcol = e % np;
+      if (bcol <= a) {
+        const double v = Lp[(size_t)(j0 + a) * r + j0 + bcol];
+        ld[a * (kPanel + 1) + bcol] = bcol == a ? 1.0 / v : v;
+      }
+    }
+    __syncthreads();
+    if (grp < ncol) {                                  // 1. solve inside the panel: x_a = g_a / L_aa, g_b -= L_ab x_a
+      double gb = q < np ? gc[(size_t)grp * r + j0 + q] : 0.0;
+      double xb = 0.0;
+      for (int a = np - 1; a >= 0; --a) {
+        const double xa = __shfl(gb, a, 32) * ld[a * (kPanel + 1) + a];
+        if (q == a) xb = xa;
+        if (q < a) gb = fma(-ld[a * (kPanel + 1) + q], xa, gb);
+      }
+      if (q < np) {
+        gc[(size_t)grp * r + j0 + q] = xb;
+        xs[grp * kPanel + q] = xb;
+      }
+    }
+    __syncthreads();
+    for (int k = t; k < j0; k += nt) {                 // 2. eliminate the panel from the rows above
+      double upd[kSolveCols];
+#pragma unroll
+      for (int c = 0; c < kSolveCols; ++c) upd[c] = 0.0;
+      for (int a = 0; a < np; ++a) {
+        const double lv = Lp[(size_t)(j0 + a) * r + k];
+#pragma unroll
+        for (int c = 0; c < kSolveCols; ++c) upd[c] = fma(lv, xs[c * kPanel + a], upd[c]);
+      }
+#pragma unroll
+      for (int c = 0; c < kSolveCols; ++c)
+        if (c < ncol) gc[(size_t)c * r + k] -= upd[c];
+    }
+  }
+  __syncthreads();
+  for (int e = t; e < ncol * r; e += nt) {
+    const int c = e / r, j = e % r;
+    const float val = j < re ? (float)gc[(size_t)c * r + j] : 0.0f;
+    if (c0 + c < dv) v_s[((size_t)pr * r + j) * dv + c0 + c] = val;
     else w[(size_t)pr * r + j] = val;
   }
 }
@@ -682,7 +723,6 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   double *scal = (double *)(ws + pl.off_scal);
   double *F = (double *)(ws + pl.off_F);
   double *L = (double *)(ws + pl.off_L);
-  double *U = (double *)(ws + pl.off_U);
   double *gpart = (double *)(ws + pl.off_gpart);
   double *Gt = (double *)(ws + pl.off_g);
   double *mpart = (double *)(ws + pl.off_mpart);
@@ -716,7 +756,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
 
   StepArgs a;
   a.Kp = Kp; a.kbar = kbar; a.scal = scal; a.floor = d0; a.u = o->uniforms ? o->uniforms : u_gen;
-  a.p = p; a.bsum = bsum; a.F = F; a.L = L; a.U = U; a.idx = out->idx; a.r_eff = out->r_eff;
+  a.p = p; a.bsum = bsum; a.F = F; a.L = L; a.idx = out->idx; a.r_eff = out->r_eff;
   a.n = s.n; a.npad = pl.npad; a.P = P; a.nblk = pl.nblk; a.r = s.r; a.dpad = pl.dpad;
   const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
   if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
@@ -727,25 +767,25 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   if (o->ev_loop_end && hipEventRecord((hipEvent_t)o->ev_loop_end, st) != hipSuccess) return WILDCAT_EHIP;
 
   const int rtiles = (s.r + kGramRows - 1) / kGramRows;
-  const dim3 ggrid(pl.nchunk, rtiles, P);
-  if (s.dv <= 64)
-    hipLaunchKernelGGL((k_gram<T, 4>), ggrid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
-                       pl.slabs_per_chunk, pl.nchunk, gpart);
-  else if (s.dv <= 128)
-    hipLaunchKernelGGL((k_gram<T, 8>), ggrid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
-                       pl.slabs_per_chunk, pl.nchunk, gpart);
-  else
-    hipLaunchKernelGGL((k_gram<T, 16>), ggrid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
-                       pl.slabs_per_chunk, pl.nchunk, gpart);
+  if (s.dv <= 64) {
+    hipLaunchKernelGGL((k_gram<T, 4>), dim3(pl.nchunk, rtiles, P), dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab,
+                       s.r, s.dv, pl.slabs_per_chunk, pl.nchunk, 1, gpart);
+  } else {
+    const int ncoltiles = (s.dv + 127) / 128;
+    hipLaunchKernelGGL((k_gram<T, 8>), dim3(pl.nchunk * ncoltiles, rtiles, P), dim3(kThreads), 0, st, F, V, s.n,
+                       pl.nblk, pl.slab, s.r, s.dv, pl.slabs_per_chunk, pl.nchunk, ncoltiles, gpart);
+  }
   LAUNCH_CHECK();
   const int dv1 = s.dv + 1;
   hipLaunchKernelGGL(k_gram_reduce, dim3((s.r * dv1 + kThreads - 1) / kThreads, P), dim3(kThreads), 0, st, gpart, s.r,
                      dv1, pl.nchunk, Gt);
   LAUNCH_CHECK();
-  int cpw = 8;
-  while (cpw > 1 && (size_t)cpw * s.r * sizeof(double) > 64 * 1024) cpw >>= 1;
-  hipLaunchKernelGGL(k_solve, dim3((dv1 + cpw - 1) / cpw, P), dim3(32 * cpw), (size_t)cpw * s.r * sizeof(double), st, U,
-                     Gt, out->r_eff, s.r, s.dv, cpw, out->v_s, out->w);
+  const size_t solve_lds = ((size_t)kSolveCols * s.r + kPanel * (kPanel + 1) + kSolveCols * kPanel) * sizeof(double);
+  if (solve_lds > 64 * 1024 &&
+      hipFuncSetAttribute((const void *)k_solve, hipFuncAttributeMaxDynamicSharedMemorySize, (int)solve_lds) != hipSuccess)
+    return WILDCAT_EHIP;
+  hipLaunchKernelGGL(k_solve, dim3((dv1 + kSolveCols - 1) / kSolveCols, P), dim3(kSolveCols * 32), solve_lds, st, L, Gt,
+                     out->r_eff, s.r, s.dv, out->v_s, out->w);
   LAUNCH_CHECK();
   hipLaunchKernelGGL((k_gather<T>), dim3(s.r, P), dim3(64), 0, st, K, out->idx, s.n, s.d, s.r, (T *)out->k_s);
   LAUNCH_CHECK();

@@ -36,6 +36,7 @@ __global__ void k_zero_u64(unsigned long long *x, int count) {
   if (i < count) x[i] = 0ull;
 }
 
+// Generic version: one thread per query row.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_qnorm_max(const T *__restrict__ Q, int64_t m, int d, int q_heads,
                                                         int group, unsigned long long *__restrict__ acc) {
@@ -54,6 +55,49 @@ __global__ __launch_bounds__(kThreads) void k_qnorm_max(const T *__restrict__ Q,
   }
   s = block_reduce<double>(s, sm, MaxOp());
   if (threadIdx.x == 0) atomicMax(&acc[pr], (unsigned long long)__double_as_longlong(s));
+}
+
+// Coalesced version for rows that are a power-of-two number (<= 64) of 16-byte pieces: LPR lanes share a
+// row, each loads one 16-byte piece, squares are summed in fp64 and combined with a butterfly over the
+// LPR lanes.  grid (blocks, batch*q_heads); each workgroup walks rows blockIdx.x*rpb .. with stride.
+__device__ __forceinline__ double sumsq16(const uint4 v, float) {
+  const float x[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+  double s = 0.0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) s = fma((double)x[e], (double)x[e], s);
+  return s;
+}
+__device__ __forceinline__ double sumsq16(const uint4 v, bf16_t) {
+  const unsigned int wds[4] = {v.x, v.y, v.z, v.w};
+  double s = 0.0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const double lo = (double)__uint_as_float(wds[e] << 16), hi = (double)__uint_as_float(wds[e] & 0xffff0000u);
+    s = fma(lo, lo, s);
+    s = fma(hi, hi, s);
+  }
+  return s;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_qnorm_max_vec(const T *__restrict__ Q, int64_t m, int d, int lpr,
+                                                            int q_heads, int group,
+                                                            unsigned long long *__restrict__ acc) {
+  __shared__ double sm[kThreads / kWave];
+  const int bh = blockIdx.y;
+  const int b = bh / q_heads, hq = bh % q_heads;
+  const int pr = b * (q_heads / group) + hq / group;
+  const int rows_per_pass = kThreads / lpr;
+  const int sub = threadIdx.x % lpr, rloc = threadIdx.x / lpr;
+  const uint4 *base = reinterpret_cast<const uint4 *>(Q + (size_t)bh * m * d);
+  double best = 0.0;
+  for (int64_t row = (int64_t)blockIdx.x * rows_per_pass + rloc; row < m; row += (int64_t)gridDim.x * rows_per_pass) {
+    double s = sumsq16(base[row * lpr + sub], T());
+    for (int off = lpr / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
+    best = fmax(best, s);
+  }
+  best = block_reduce<double>(best, sm, MaxOp());
+  if (threadIdx.x == 0) atomicMax(&acc[pr], (unsigned long long)__double_as_longlong(best));
 }
 
 __global__ void k_sqrt_inplace(double *x, int count) {
@@ -352,13 +396,29 @@ extern "C" int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const w
   if (rc != WILDCAT_OK) return rc;
   hipLaunchKernelGGL(k_zero_u64, dim3((s.P + 255) / 256), dim3(256), 0, s.stream, (unsigned long long *)r_q_out, s.P);
   if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP;
-  const dim3 grid((unsigned)((m + kThreads - 1) / kThreads), s.batch * s.q_heads);
-  if (s.dtype == WILDCAT_BF16)
-    hipLaunchKernelGGL((k_qnorm_max<bf16_t>), grid, dim3(kThreads), 0, s.stream, (const bf16_t *)Q, m, d, s.q_heads,
-                       s.group, (unsigned long long *)r_q_out);
-  else
-    hipLaunchKernelGGL((k_qnorm_max<float>), grid, dim3(kThreads), 0, s.stream, (const float *)Q, m, d, s.q_heads,
-                       s.group, (unsigned long long *)r_q_out);
+  const int es = s.dtype == WILDCAT_BF16 ? 2 : 4;
+  const int pieces = (d * es) % 16 == 0 ? d * es / 16 : 0;
+  if (pieces >= 1 && pieces <= kWave && (pieces & (pieces - 1)) == 0) {
+    const int rows_per_pass = kThreads / pieces;
+    int64_t blocks = (m + rows_per_pass - 1) / rows_per_pass;
+    const int64_t cap = (4096 + s.batch * s.q_heads - 1) / (s.batch * s.q_heads);
+    if (blocks > cap) blocks = cap;
+    const dim3 grid((unsigned)blocks, s.batch * s.q_heads);
+    if (s.dtype == WILDCAT_BF16)
+      hipLaunchKernelGGL((k_qnorm_max_vec<bf16_t>), grid, dim3(kThreads), 0, s.stream, (const bf16_t *)Q, m, d, pieces,
+                         s.q_heads, s.group, (unsigned long long *)r_q_out);
+    else
+      hipLaunchKernelGGL((k_qnorm_max_vec<float>), grid, dim3(kThreads), 0, s.stream, (const float *)Q, m, d, pieces,
+                         s.q_heads, s.group, (unsigned long long *)r_q_out);
+  } else {
+    const dim3 grid((unsigned)((m + kThreads - 1) / kThreads), s.batch * s.q_heads);
+    if (s.dtype == WILDCAT_BF16)
+      hipLaunchKernelGGL((k_qnorm_max<bf16_t>), grid, dim3(kThreads), 0, s.stream, (const bf16_t *)Q, m, d, s.q_heads,
+                         s.group, (unsigned long long *)r_q_out);
+    else
+      hipLaunchKernelGGL((k_qnorm_max<float>), grid, dim3(kThreads), 0, s.stream, (const float *)Q, m, d, s.q_heads,
+                         s.group, (unsigned long long *)r_q_out);
+  }
   if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP;
   hipLaunchKernelGGL(k_sqrt_inplace, dim3((s.P + 255) / 256), dim3(256), 0, s.stream, r_q_out, s.P);
   return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;

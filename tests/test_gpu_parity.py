@@ -240,3 +240,46 @@ def test_identical_keys_zero_radius():
     assert cs.w[0, 0, 0].item() == pytest.approx(n, rel=1e-6)
     np.testing.assert_allclose(out.cpu().numpy()[0, 0], np.tile(V[0, 0].astype(np.float64).mean(0), (64, 1)),
                                rtol=1e-4, atol=1e-6)
+
+
+# ---------------------------------------------------------------------------------- full sizes
+def _full_size(cfg, heads, prefix_r=None):
+    """The benchmark's launch configuration (all problems of the workload in one call, real n, d, r); the
+    oracle then checks whole kv heads.  Pivots of a shorter run are a prefix of the longer run under the same
+    uniforms, so the remaining heads are compared on their first `prefix_r` pivots."""
+    w = wl.make(cfg)
+    s = w["shape"]
+    out, cs = run_gpu(w)
+    res = check_against_oracle(w, out, cs, heads=heads)
+    if prefix_r:
+        idx = cs.idx.cpu().numpy()
+        for h in range(s.kv_heads):
+            if h in heads:
+                continue
+            Qg = w["Q"][0, h * s.group:(h + 1) * s.group].astype(np.float64)
+            RQ = float(np.sqrt((Qg ** 2).sum(-1).max()))
+            ocs = wo.compress_kv(w["K"][0, h].astype(np.float64), w["V"][0, h].astype(np.float64), RQ, s.beta,
+                                 prefix_r, w["u"][h][:prefix_r])
+            np.testing.assert_array_equal(idx[0, h, :prefix_r], ocs.idx)
+            assert cs.tau[0, h].item() == pytest.approx(ocs.tau, rel=1e-12)
+    # properties that hold at any size
+    o = out.float()
+    assert torch.isfinite(o).all()
+    vmin = cs.v_min.repeat_interleave(s.group, dim=1)[:, :, None, :]
+    vmax = cs.v_max.repeat_interleave(s.group, dim=1)[:, :, None, :]
+    assert torch.all(o >= vmin) and torch.all(o <= vmax)
+    srt = torch.sort(cs.idx, dim=-1).values
+    assert torch.all(srt[..., 1:] != srt[..., :-1]) and int(cs.idx.min()) >= 0 and int(cs.idx.max()) < s.n
+    return res
+
+
+def test_full_size_config4_bench_configuration():
+    print(_full_size(4, heads=[0, 3, 7], prefix_r=128))
+
+
+def test_full_size_config2():
+    print(_full_size(2, heads=[0, 5], prefix_r=None))
+
+
+def test_full_size_config3():
+    print(_full_size(3, heads=[0, 9], prefix_r=64))
