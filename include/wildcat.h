@@ -96,6 +96,12 @@ typedef struct {
   float *v_min;   /* [P, dv]    column minima of V (Alg. 4, first line)             */
   float *v_max;   /* [P, dv]    column maxima of V                                  */
   double *tau;    /* [P]        temperature used (eq. (kernel-temperature))         */
+  void *v_t;      /* [P, dv, r64] bf16, r64 = r rounded up to a multiple of 64:     */
+                  /*         v_s transposed, rounded to bf16 and zero padded -- the */
+                  /*         MFMA operand form of V_S.  bf16 storage only (NULL for */
+                  /*         fp32).  Written by wildcat_compress_kv; after editing  */
+                  /*         v_s by hand refresh it with wildcat_pack_values.  May  */
+                  /*         be NULL: WtdAttn then converts v_s on the fly (slower) */
 } wildcat_coreset;
 
 /* Library version as major*10000 + minor*100 + patch. */
@@ -138,11 +144,17 @@ int wildcat_compress_kv(const void *K, const void *V, int64_t n, int32_t d, int3
 /* WtdAttn (Alg. 3): out[b, h, i, :] = clip( (A V_S)_i / (A w)_i  if (A w)_i > 0 else 0,
  * v_min, v_max ), A_is = exp(beta <q_i, k_s>), against the coreset of kv head
  * h / (q_heads / kv_heads).  Q [batch, q_heads, m, d], out [batch, q_heads, m, dv] in
- * opts->dtype; cs->idx, cs->r_eff and cs->tau are not read, so any (k_s, v_s, w,
- * v_min, v_max) may be supplied -- e.g. all n keys with unit weights, which is exact
+ * opts->dtype; cs->idx and cs->tau are not read (cs->r_eff, if not NULL, limits the slots
+ * that are read), so any (k_s, v_s, w, v_min, v_max) may be supplied -- e.g. all n keys with unit weights, which is exact
  * attention. */
 int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *out, int64_t m,
                      int32_t d, int32_t r, const wildcat_opts *opts);
+
+/* Rewrites cs->v_t from cs->v_s (both device buffers, see wildcat_coreset) for a coreset
+ * of r rows and value width dv; batch and kv_heads are read from opts, whose dtype must
+ * be WILDCAT_BF16.  For callers who assemble a coreset themselves instead of taking it
+ * from wildcat_compress_kv (Alg. 3 accepts any weighted coreset). */
+int wildcat_pack_values(const wildcat_coreset *cs, int32_t r, int32_t dv, const wildcat_opts *opts);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libwildcat.so")
 
 WILDCAT_F32, WILDCAT_BF16 = 0, 1
 EXPORTS = ("wildcat_version", "wildcat_strerror", "wildcat_workspace_bytes", "wildcat_draw_uniforms",
-           "wildcat_query_radius", "wildcat_compress_kv", "wildcat_wtd_attn")
+           "wildcat_query_radius", "wildcat_compress_kv", "wildcat_wtd_attn", "wildcat_pack_values")
 
 
 class WildcatError(RuntimeError):
@@ -39,7 +39,7 @@ class _Coreset(ctypes.Structure):
     _fields_ = [
         ("idx", ctypes.c_void_p), ("r_eff", ctypes.c_void_p), ("k_s", ctypes.c_void_p),
         ("v_s", ctypes.c_void_p), ("w", ctypes.c_void_p), ("v_min", ctypes.c_void_p),
-        ("v_max", ctypes.c_void_p), ("tau", ctypes.c_void_p),
+        ("v_max", ctypes.c_void_p), ("tau", ctypes.c_void_p), ("v_t", ctypes.c_void_p),
     ]
 
 
@@ -74,6 +74,8 @@ def load_library(force: bool = False):
     lib.wildcat_wtd_attn.restype = ctypes.c_int
     lib.wildcat_wtd_attn.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Coreset), ctypes.c_void_p, ctypes.c_int64,
                                      ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
+    lib.wildcat_pack_values.restype = ctypes.c_int
+    lib.wildcat_pack_values.argtypes = [ctypes.POINTER(_Coreset), ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
     _lib = lib
     return lib
 
@@ -106,11 +108,13 @@ class Coreset:
     v_min: "torch.Tensor"   # [B, Hkv, dv] float32
     v_max: "torch.Tensor"   # [B, Hkv, dv] float32
     tau: "torch.Tensor"     # [B, Hkv] float64
+    v_t: "torch.Tensor" = None   # [B, Hkv, dv, r64] bfloat16 (bf16 storage only): MFMA operand copy of v_s
 
     def c_struct(self):
         return _Coreset(self.idx.data_ptr(), self.r_eff.data_ptr() if self.r_eff is not None else None,
                         self.k_s.data_ptr(), self.v_s.data_ptr(), self.w.data_ptr(), self.v_min.data_ptr(),
-                        self.v_max.data_ptr(), self.tau.data_ptr() if self.tau is not None else None)
+                        self.v_max.data_ptr(), self.tau.data_ptr() if self.tau is not None else None,
+                        self.v_t.data_ptr() if self.v_t is not None else None)
 
 
 def _dtype_code(t):
@@ -196,6 +200,8 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
         v_min=torch.empty((B, H, dv), dtype=torch.float32, device=dev),
         v_max=torch.empty((B, H, dv), dtype=torch.float32, device=dev),
         tau=torch.empty((B, H), dtype=torch.float64, device=dev),
+        v_t=(torch.empty((B, H, dv, (r + 63) // 64 * 64), dtype=torch.bfloat16, device=dev)
+             if code == WILDCAT_BF16 else None),
     )
     o = _opts(B, H, H, n, dv, code, beta, rank_tol, r_q.contiguous(), uniforms, workspace)
     if loop_events is not None:
@@ -203,6 +209,18 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
     c = cs.c_struct()
     _check(load_library().wildcat_compress_kv(K.data_ptr(), V.data_ptr(), n, d, r, seed, ctypes.byref(o),
                                               ctypes.byref(c)), "wildcat_compress_kv")
+    return cs
+
+
+def pack_values(cs: Coreset):
+    """Allocates (if needed) and fills cs.v_t from cs.v_s: for coresets assembled by hand (bf16 storage)."""
+    import torch
+    B, H, r, dv = cs.v_s.shape
+    if cs.v_t is None:
+        cs.v_t = torch.empty((B, H, dv, (r + 63) // 64 * 64), dtype=torch.bfloat16, device=cs.v_s.device)
+    o = _opts(B, H, H, 0, dv, WILDCAT_BF16, None)
+    c = cs.c_struct()
+    _check(load_library().wildcat_pack_values(ctypes.byref(c), r, dv, ctypes.byref(o)), "wildcat_pack_values")
     return cs
 
 

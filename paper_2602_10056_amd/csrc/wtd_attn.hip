@@ -364,6 +364,226 @@ __global__ __launch_bounds__(NW * kWave) void k_wtd_attn_mfma(
   }
 }
 
+
+// --------------------------------------------------------------------------------------------
+// Pipelined bf16 MFMA kernel (needs the transposed bf16 values v_t of the coreset).
+// Workgroup = 8 wavefronts (two per SIMD, so one wave's exp/convert work overlaps the other's MFMAs), each
+// owning 32 queries.  Key tiles of 64 are double-buffered in LDS: the loads of tile t+1 are issued before the
+// math of tile t and stored after it, with one barrier per tile.  Same operand layouts as above.
+//
+// The running maximum is only a reference point for exp(): any reference within 2^8 of the true row maximum
+// keeps every exponential in range, and a change of reference multiplies numerator and normaliser of a row
+// alike.  So the accumulators are rescaled only when a row's maximum has grown by more than 8 (log2 units)
+// since its reference was set -- rare after the first tile -- instead of on every tile.
+// --------------------------------------------------------------------------------------------
+constexpr float kRescaleSlack = 8.0f;
+
+template <int D, int DV>
+__global__ __launch_bounds__(512, 1) void k_wtd_attn_mfma2(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const bf16_t *__restrict__ Vt,
+    const float *__restrict__ w, const float *__restrict__ vmin, const float *__restrict__ vmax,
+    const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int64_t m, int r, int r64, int q_heads, int group,
+    float scale_log2) {
+  constexpr int KSTR = D + 8;        // bf16 per key row in LDS
+  constexpr int VSTR = kKT + 8;      // bf16 per value-column row in LDS
+  constexpr int NT = 512;
+  constexpr int KPIECES = (kKT * D / 8 + NT - 1) / NT;     // 16-byte pieces of the key tile per thread
+  constexpr int VPIECES = (DV * kKT / 8 + NT - 1) / NT;    // 16-byte pieces of the value tile per thread
+  __shared__ __attribute__((aligned(16))) uint16_t lk[2][kKT * KSTR];
+  __shared__ __attribute__((aligned(16))) uint16_t lv[2][DV * VSTR];
+  __shared__ __attribute__((aligned(16))) float lw[2][kKT];
+
+  const int t = threadIdx.x, wv = t / kWave, l = t % kWave, g = l / 32, c32 = l % 32;
+  const int bh = blockIdx.y, b = bh / q_heads, hq = bh % q_heads;
+  const int pr = b * (q_heads / group) + hq / group;
+  const int64_t q0 = (int64_t)blockIdx.x * 256 + wv * 32;
+  const int re = r_eff ? min(r_eff[pr], r) : r;
+  const bf16_t *Kp = Ks + (size_t)pr * r * D;
+  const bf16_t *Vp = Vt + (size_t)pr * DV * r64;
+  const float *wp = w + (size_t)pr * r;
+
+  uint4 kst[KPIECES], vst[VPIECES];
+  float wst = 0.0f;
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int e = 0; e < KPIECES; ++e) {
+      const int idx = t + e * NT, kk = idx / (D / 8), seg = idx % (D / 8);
+      kst[e] = (idx < kKT * D / 8 && k0 + kk < re)
+                   ? *reinterpret_cast<const uint4 *>(Kp + (size_t)(k0 + kk) * D + seg * 8)
+                   : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int e = 0; e < VPIECES; ++e) {
+      const int idx = t + e * NT, col = idx / (kKT / 8), seg = idx % (kKT / 8);
+      vst[e] = idx < DV * kKT / 8 ? *reinterpret_cast<const uint4 *>(Vp + (size_t)col * r64 + k0 + seg * 8)
+                                  : make_uint4(0, 0, 0, 0);
+    }
+    if (t < kKT) wst = k0 + t < re ? wp[k0 + t] : 0.0f;
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int e = 0; e < KPIECES; ++e) {
+      const int idx = t + e * NT, kk = idx / (D / 8), seg = idx % (D / 8);
+      if (idx < kKT * D / 8) *reinterpret_cast<uint4 *>(&lk[buf][kk * KSTR + seg * 8]) = kst[e];
+    }
+#pragma unroll
+    for (int e = 0; e < VPIECES; ++e) {
+      const int idx = t + e * NT, col = idx / (kKT / 8), seg = idx % (kKT / 8);
+      if (idx < DV * kKT / 8) *reinterpret_cast<uint4 *>(&lv[buf][col * VSTR + seg * 8]) = vst[e];
+    }
+    if (t < kKT) lw[buf][t] = wst;
+  };
+
+  fetch(0);
+  // Q fragments: B operand of S^T = K Q^T: query c32, features 16 kb + 8 g .. + 7
+  bf16x8 qf[D / 16];
+  {
+    const int64_t row = q0 + c32 < m ? q0 + c32 : m - 1;
+    const uint4 *src = reinterpret_cast<const uint4 *>(Q + ((size_t)bh * m + row) * D + 8 * g);
+#pragma unroll
+    for (int kb = 0; kb < D / 16; ++kb) {
+      const uint4 v = src[2 * kb];
+      qf[kb] = *reinterpret_cast<const bf16x8 *>(&v);
+    }
+  }
+  floatx16 acc[DV / 32];
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+  float mref = -INFINITY, den = 0.0f;      // reference exponent (log2 domain) and normaliser of query c32
+  stash(0);
+  __syncthreads();
+
+  int buf = 0;
+  for (int k0 = 0; k0 < re; k0 += kKT, buf ^= 1) {
+    const bool more = k0 + kKT < re;
+    if (more) fetch(k0 + kKT);
+    // ---- S^T = K Q^T for the two 32-key halves -----------------------------------------------------------
+    floatx16 st[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) st[mt][v] = 0.0f;
+#pragma unroll
+    for (int kb = 0; kb < D / 16; ++kb) {
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lk[buf][(32 * mt + c32) * KSTR + 16 * kb + 8 * g]);
+        st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kb], st[mt], 0, 0, 0);
+      }
+    }
+    if (k0 + kKT > re) {                                     // ragged last tile: mask the missing keys
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (k0 + 32 * mt + 8 * (v / 4) + 4 * g + (v % 4) >= re) st[mt][v] = -INFINITY;
+    }
+    // ---- row maximum of the raw scores; move the reference only if it is more than the slack behind ------------
+    float mx = st[0][0];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[mt][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * scale_log2;
+    const bool jump = mx > mref + kRescaleSlack;
+    if (__builtin_amdgcn_ballot_w64(jump) != 0) {
+      const float alpha = jump ? __builtin_amdgcn_exp2f(mref - mx) : 1.0f;
+      mref = jump ? mx : mref;
+      den *= alpha;
+#pragma unroll
+      for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] *= alpha;
+    }
+    // ---- P = exp2(S c - mref), normaliser, bf16 operand ---------------------------------------------------------
+    const float nm = -mref;
+    float dl = 0.0f;
+    bf16x8 pf[4];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      floatx16 p;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(st[mt][v], scale_log2, nm));
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 wv4 = *reinterpret_cast<const float4 *>(&lw[buf][32 * mt + 8 * q + 4 * g]);
+        dl = fmaf(p[4 * q + 0], wv4.x, dl);
+        dl = fmaf(p[4 * q + 1], wv4.y, dl);
+        dl = fmaf(p[4 * q + 2], wv4.z, dl);
+        dl = fmaf(p[4 * q + 3], wv4.w, dl);
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const floatx8 ph = {p[8 * h + 0], p[8 * h + 1], p[8 * h + 2], p[8 * h + 3],
+                            p[8 * h + 4], p[8 * h + 5], p[8 * h + 6], p[8 * h + 7]};
+        pf[2 * mt + h] = __builtin_convertvector(ph, bf16x8);
+      }
+    }
+    den += dl;
+    // ---- O^T += V_S^T P^T ------------------------------------------------------------------------------------
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+      for (int i = 0; i < DV / 32; ++i) {
+        const uint16_t *rowp = &lv[buf][(32 * i + c32) * VSTR + 16 * kb + 4 * g];
+        const uint2 lo = *reinterpret_cast<const uint2 *>(rowp);
+        const uint2 hi = *reinterpret_cast<const uint2 *>(rowp + 8);
+        const uint4 av = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&av), pf[kb], acc[i], 0, 0,
+                                                         0);
+      }
+    }
+    if (more) stash(buf ^ 1);
+    __syncthreads();
+  }
+  // ---- epilogue: guard, divide, clip, store -------------------------------------------------------------------
+  den += __shfl_xor(den, 32, kWave);
+  const bool ok = den > 0.0f;
+  const float inv = ok ? 1.0f / den : 0.0f;
+  if (q0 + c32 < m) {
+    bf16_t *orow = out + ((size_t)bh * m + q0 + c32) * DV;
+#pragma unroll
+    for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = 32 * i + 8 * q + 4 * g;
+        const float4 lo = *reinterpret_cast<const float4 *>(vmin + (size_t)pr * DV + col);
+        const float4 hi = *reinterpret_cast<const float4 *>(vmax + (size_t)pr * DV + col);
+        floatx4 o = {acc[i][4 * q + 0] * inv, acc[i][4 * q + 1] * inv, acc[i][4 * q + 2] * inv,
+                     acc[i][4 * q + 3] * inv};
+        if (!ok) o = {0.f, 0.f, 0.f, 0.f};
+        o[0] = fminf(fmaxf(o[0], lo.x), hi.x);
+        o[1] = fminf(fmaxf(o[1], lo.y), hi.y);
+        o[2] = fminf(fmaxf(o[2], lo.z), hi.z);
+        o[3] = fminf(fmaxf(o[3], lo.w), hi.w);
+        const bf16x4 ob = __builtin_convertvector(o, bf16x4);
+        *reinterpret_cast<uint2 *>(orow + col) = *reinterpret_cast<const uint2 *>(&ob);
+      }
+  }
+}
+
+// v_t[pr][c][j] = bf16(v_s[pr][j][c]) for j < r, zero for r <= j < r64.  grid (ceil(r64*dv/256), P).
+__global__ __launch_bounds__(kThreads) void k_pack_values(const float *__restrict__ v_s, int r, int r64, int dv,
+                                                          bf16_t *__restrict__ v_t) {
+  const int pr = blockIdx.y;
+  const int gid = blockIdx.x * kThreads + threadIdx.x;
+  if (gid >= r64 * dv) return;
+  const int c = gid / r64, j = gid % r64;
+  from_float(j < r ? v_s[((size_t)pr * r + j) * dv + c] : 0.0f, &v_t[((size_t)pr * dv + c) * r64 + j]);
+}
+
+template <int D, int DV>
+int launch_mfma2(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
+  const int r64 = (s.r + 63) / 64 * 64;
+  const dim3 grid((unsigned)((s.m + 255) / 256), s.batch * s.q_heads);
+  hipLaunchKernelGGL((k_wtd_attn_mfma2<D, DV>), grid, dim3(512), 0, s.stream, (const bf16_t *)Q,
+                     (const bf16_t *)cs->k_s, (const bf16_t *)cs->v_t, cs->w, cs->v_min, cs->v_max, cs->r_eff,
+                     (bf16_t *)out, s.m, s.r, r64, s.q_heads, s.group, (float)(s.beta * (double)kLog2e));
+  return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
+}
+
 template <int D, int DV>
 int launch_mfma(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
   constexpr int NW = 4;
@@ -432,6 +652,10 @@ extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *
   int rc = resolve_shape(r, m, d, r, opts, &s);
   if (rc != WILDCAT_OK) return rc;
   if (s.dtype == WILDCAT_BF16) {
+    if (cs->v_t) {
+      if (s.d == 64 && s.dv == 64) return launch_mfma2<64, 64>(s, Q, cs, out);
+      if (s.d == 128 && s.dv == 128) return launch_mfma2<128, 128>(s, Q, cs, out);
+    }
     if (s.d == 64 && s.dv == 64) return launch_mfma<64, 64>(s, Q, cs, out);
     if (s.d == 128 && s.dv == 128) return launch_mfma<128, 128>(s, Q, cs, out);
     if (s.d == 64 && s.dv == 128) return launch_mfma<64, 128>(s, Q, cs, out);
@@ -439,4 +663,16 @@ extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *
     return launch_simple<bf16_t>(s, Q, cs, out);
   }
   return launch_simple<float>(s, Q, cs, out);
+}
+
+extern "C" int wildcat_pack_values(const wildcat_coreset *cs, int32_t r, int32_t dv, const wildcat_opts *opts) {
+  if (!cs || !cs->v_s || !cs->v_t || r < 1 || dv < 1) return WILDCAT_EINVAL;
+  Shape s;
+  int rc = resolve_shape(r, 0, dv, r, opts, &s);
+  if (rc != WILDCAT_OK) return rc;
+  if (s.dtype != WILDCAT_BF16) return WILDCAT_EINVAL;
+  const int r64 = (r + 63) / 64 * 64;
+  hipLaunchKernelGGL(k_pack_values, dim3((r64 * dv + kThreads - 1) / kThreads, s.P), dim3(kThreads), 0, s.stream,
+                     cs->v_s, r, r64, dv, (bf16_t *)cs->v_t);
+  return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
 }
