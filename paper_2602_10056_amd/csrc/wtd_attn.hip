@@ -11,6 +11,7 @@
 //                     v_mfma_f32_32x32x16_bf16.  The normaliser sum_s P_s w_s is accumulated in fp32 on
 //                     the vector ALU from the unrounded P (w may be negative and large).
 //   k_wtd_attn_simple any storage type / width, fp32 arithmetic on the vector ALU (the fp32 path).
+#include <climits>
 #include <cmath>
 
 #include "common.h"
@@ -367,9 +368,14 @@ __global__ __launch_bounds__(NW * kWave) void k_wtd_attn_mfma(
 
 // --------------------------------------------------------------------------------------------
 // Pipelined bf16 MFMA kernel (needs the transposed bf16 values v_t of the coreset).
-// Workgroup = 8 wavefronts (two per SIMD, so one wave's exp/convert work overlaps the other's MFMAs), each
-// owning 32 queries.  Key tiles of 64 are double-buffered in LDS: the loads of tile t+1 are issued before the
-// math of tile t and stored after it, with one barrier per tile.  Same operand layouts as above.
+// Workgroup = NW wavefronts, each owning 32 queries; two workgroups (NW = 4) share a compute unit so that one
+// wave's exp/convert work overlaps another's MFMAs.  Key tiles of 64 are double-buffered in LDS and filled
+// with direct global-to-LDS loads (global_load_lds_dwordx4: lane i of a wave writes 16 bytes at base + 16 i),
+// issued for tile t+1 before the math of tile t: no staging registers, one barrier per tile.
+//
+// Direct loads cannot pad rows, so bank conflicts are avoided by permuting the 16-byte pieces of a row:
+// piece p of row q is stored in slot p ^ ((q / rows_per_256B) % pieces_per_row).  Sixteen consecutive rows
+// then put the same logical piece into sixteen different 16-byte bank groups.
 //
 // The running maximum is only a reference point for exp(): any reference within 2^8 of the true row maximum
 // keeps every exponential in range, and a change of reference multiplies numerator and normaliser of a row
@@ -377,190 +383,304 @@ __global__ __launch_bounds__(NW * kWave) void k_wtd_attn_mfma(
 // since its reference was set -- rare after the first tile -- instead of on every tile.
 // --------------------------------------------------------------------------------------------
 constexpr float kRescaleSlack = 8.0f;
+#ifndef WILDCAT_ATTN_NW
+#define WILDCAT_ATTN_NW 4
+#endif
+
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// Kernel arguments and per-wave state of the pipelined kernel, passed by reference to the per-tile function.
+template <int D, int DV>
+struct AttnCtx {
+  const bf16_t *Q, *Ks, *Vt;
+  const float *w, *vmin, *vmax;
+  const int32_t *r_eff;
+  bf16_t *out;
+  int64_t m;
+  int r, r64, q_heads, group, kv_heads, qtiles, total_items, stride;
+  float scale_log2;
+  int wv, l, g, c32, krow_sw, vrow_sw;
+  // per-lane source coordinates of this wave's tile loads (fixed for the whole kernel)
+  int krow[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW], kcol[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW];
+  int voff[DV * (kKT / 8) / 64 / WILDCAT_ATTN_NW];
+  // state
+  int item, pr, re, k0;
+  bf16x8 qf[D / 16];          // Q fragments: B operand of S^T = K Q^T (query c32, features 16 kb + 8 g .. + 7)
+  floatx16 acc[DV / 32];      // O^T accumulators
+  float mref, den;            // reference exponent (log2 domain) and normaliser of query c32
+};
+
+template <int D, int DV, int NW>
+struct AttnGeom {
+  static constexpr int KPPR = D / 8;                     // 16-byte pieces per key row
+  static constexpr int KRP = KPPR >= 16 ? 1 : 16 / KPPR; // key rows per 256 bytes
+  static constexpr int VPPR = kKT / 8;                   // 16-byte pieces per value-column row (= 8)
+  static constexpr int VRP = 16 / VPPR;                  // value rows per 256 bytes (= 2)
+  static constexpr int KLOADS = kKT * KPPR / 64 / NW;    // wave-wide 1 KB loads of the key tile per wave
+  static constexpr int VLOADS = DV * VPPR / 64 / NW;     // ... of the value tile
+  static constexpr int CLOADS = (2 * DV + 63) / 64;      // wave-wide 256-byte loads of the clip vectors
+  static_assert(KLOADS * NW * 64 == kKT * KPPR && VLOADS * NW * 64 == DV * VPPR, "tiles must split evenly");
+  static_assert(DV % 32 == 0 && CLOADS <= NW + 1, "clip vectors are loaded by waves 1..");
+  // One LDS buffer (bytes): key tile | value tile | weights | clip vectors (v_min | v_max)
+  static constexpr int OFF_K = 0;
+  static constexpr int OFF_V = OFF_K + kKT * D * 2;
+  static constexpr int OFF_W = OFF_V + DV * kKT * 2;
+  static constexpr int OFF_C = OFF_W + kKT * 4;
+  static constexpr int BYTES = OFF_C + CLOADS * 256;
+};
 
 template <int D, int DV>
-__global__ __launch_bounds__(512, 1) void k_wtd_attn_mfma2(
-    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const bf16_t *__restrict__ Vt,
-    const float *__restrict__ w, const float *__restrict__ vmin, const float *__restrict__ vmax,
-    const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int64_t m, int r, int r64, int q_heads, int group,
-    float scale_log2) {
-  constexpr int KSTR = D + 8;        // bf16 per key row in LDS
-  constexpr int VSTR = kKT + 8;      // bf16 per value-column row in LDS
-  constexpr int NT = 512;
-  constexpr int KPIECES = (kKT * D / 8 + NT - 1) / NT;     // 16-byte pieces of the key tile per thread
-  constexpr int VPIECES = (DV * kKT / 8 + NT - 1) / NT;    // 16-byte pieces of the value tile per thread
-  __shared__ __attribute__((aligned(16))) uint16_t lk[2][kKT * KSTR];
-  __shared__ __attribute__((aligned(16))) uint16_t lv[2][DV * VSTR];
-  __shared__ __attribute__((aligned(16))) float lw[2][kKT];
+__device__ __forceinline__ int attn_item_pr(const AttnCtx<D, DV> &c, int item) {
+  const int bh = item / c.qtiles;
+  return (bh / c.q_heads) * c.kv_heads + (bh % c.q_heads) / c.group;
+}
+template <int D, int DV>
+__device__ __forceinline__ int attn_item_re(const AttnCtx<D, DV> &c, int pr) {
+  return c.r_eff ? min(c.r_eff[pr], c.r) : c.r;
+}
 
-  const int t = threadIdx.x, wv = t / kWave, l = t % kWave, g = l / 32, c32 = l % 32;
-  const int bh = blockIdx.y, b = bh / q_heads, hq = bh % q_heads;
-  const int pr = b * (q_heads / group) + hq / group;
-  const int64_t q0 = (int64_t)blockIdx.x * 256 + wv * 32;
-  const int re = r_eff ? min(r_eff[pr], r) : r;
-  const bf16_t *Kp = Ks + (size_t)pr * r * D;
-  const bf16_t *Vp = Vt + (size_t)pr * DV * r64;
-  const float *wp = w + (size_t)pr * r;
-
-  uint4 kst[KPIECES], vst[VPIECES];
-  float wst = 0.0f;
-  auto fetch = [&](int k0) {
+// Direct global-to-LDS loads of one tile.  Rows past the last key are clamped to it (and masked after the score
+// product); v_t is zero padded.  With `with_clip`, v_min | v_max of the problem are loaded too.  The per-lane
+// source coordinates were worked out once (AttnCtx::krow, kcol, voff): per tile only the tile offset is added.
+template <int D, int DV, int NW>
+__device__ __forceinline__ void attn_fetch(const AttnCtx<D, DV> &c, int pr, int re, int k0, char *__restrict__ wr,
+                                           bool with_clip) {
+  using G = AttnGeom<D, DV, NW>;
+  const bf16_t *Kp = c.Ks + (size_t)pr * c.r * D;
+  const bf16_t *Vp = c.Vt + (size_t)pr * DV * c.r64 + k0;
 #pragma unroll
-    for (int e = 0; e < KPIECES; ++e) {
-      const int idx = t + e * NT, kk = idx / (D / 8), seg = idx % (D / 8);
-      kst[e] = (idx < kKT * D / 8 && k0 + kk < re)
-                   ? *reinterpret_cast<const uint4 *>(Kp + (size_t)(k0 + kk) * D + seg * 8)
-                   : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int e = 0; e < VPIECES; ++e) {
-      const int idx = t + e * NT, col = idx / (kKT / 8), seg = idx % (kKT / 8);
-      vst[e] = idx < DV * kKT / 8 ? *reinterpret_cast<const uint4 *>(Vp + (size_t)col * r64 + k0 + seg * 8)
-                                  : make_uint4(0, 0, 0, 0);
-    }
-    if (t < kKT) wst = k0 + t < re ? wp[k0 + t] : 0.0f;
-  };
-  auto stash = [&](int buf) {
-#pragma unroll
-    for (int e = 0; e < KPIECES; ++e) {
-      const int idx = t + e * NT, kk = idx / (D / 8), seg = idx % (D / 8);
-      if (idx < kKT * D / 8) *reinterpret_cast<uint4 *>(&lk[buf][kk * KSTR + seg * 8]) = kst[e];
-    }
-#pragma unroll
-    for (int e = 0; e < VPIECES; ++e) {
-      const int idx = t + e * NT, col = idx / (kKT / 8), seg = idx % (kKT / 8);
-      if (idx < DV * kKT / 8) *reinterpret_cast<uint4 *>(&lv[buf][col * VSTR + seg * 8]) = vst[e];
-    }
-    if (t < kKT) lw[buf][t] = wst;
-  };
-
-  fetch(0);
-  // Q fragments: B operand of S^T = K Q^T: query c32, features 16 kb + 8 g .. + 7
-  bf16x8 qf[D / 16];
-  {
-    const int64_t row = q0 + c32 < m ? q0 + c32 : m - 1;
-    const uint4 *src = reinterpret_cast<const uint4 *>(Q + ((size_t)bh * m + row) * D + 8 * g);
-#pragma unroll
-    for (int kb = 0; kb < D / 16; ++kb) {
-      const uint4 v = src[2 * kb];
-      qf[kb] = *reinterpret_cast<const bf16x8 *>(&v);
-    }
+  for (int e = 0; e < G::KLOADS; ++e) {
+    const bf16_t *src = Kp + min(k0 + c.krow[e], re - 1) * D + c.kcol[e];
+    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(wr + G::OFF_K + (e * NW + c.wv) * 1024), 16, 0, 0);
   }
-  floatx16 acc[DV / 32];
 #pragma unroll
-  for (int i = 0; i < DV / 32; ++i)
+  for (int e = 0; e < G::VLOADS; ++e)
+    __builtin_amdgcn_global_load_lds((gptr_t)(Vp + c.voff[e]), (lptr_t)(wr + G::OFF_V + (e * NW + c.wv) * 1024), 16, 0,
+                                     0);
+  if (c.wv == 0)
+    __builtin_amdgcn_global_load_lds((gptr_t)(c.w + (size_t)pr * c.r + min(k0 + c.l, re - 1)),
+                                     (lptr_t)(wr + G::OFF_W), 4, 0, 0);
+  if (with_clip) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
-  float mref = -INFINITY, den = 0.0f;      // reference exponent (log2 domain) and normaliser of query c32
-  stash(0);
-  __syncthreads();
-
-  int buf = 0;
-  for (int k0 = 0; k0 < re; k0 += kKT, buf ^= 1) {
-    const bool more = k0 + kKT < re;
-    if (more) fetch(k0 + kKT);
-    // ---- S^T = K Q^T for the two 32-key halves -----------------------------------------------------------
-    floatx16 st[2];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) st[mt][v] = 0.0f;
-#pragma unroll
-    for (int kb = 0; kb < D / 16; ++kb) {
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lk[buf][(32 * mt + c32) * KSTR + 16 * kb + 8 * g]);
-        st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kb], st[mt], 0, 0, 0);
+    for (int q = 0; q < G::CLOADS; ++q)
+      if (c.wv == (q + 1) % NW) {
+        const int e = min(q * 64 + c.l, 2 * DV - 1);
+        const float *src = e < DV ? c.vmin + (size_t)pr * DV + e : c.vmax + (size_t)pr * DV + (e - DV);
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(wr + G::OFF_C + q * 256), 4, 0, 0);
       }
-    }
-    if (k0 + kKT > re) {                                     // ragged last tile: mask the missing keys
+  }
+}
+
+template <int D, int DV, int NW>
+__device__ __forceinline__ void attn_load_q(AttnCtx<D, DV> &c, int item) {
+  const int bh = item / c.qtiles;
+  const int64_t q0 = (int64_t)(item % c.qtiles) * (NW * 32) + c.wv * 32;
+  const int64_t row = q0 + c.c32 < c.m ? q0 + c.c32 : c.m - 1;
+  const uint4 *src = reinterpret_cast<const uint4 *>(c.Q + ((size_t)bh * c.m + row) * D + 8 * c.g);
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+  for (int kb = 0; kb < D / 16; ++kb) {
+    const uint4 v = src[2 * kb];
+    c.qf[kb] = *reinterpret_cast<const bf16x8 *>(&v);
+  }
+}
+
+// One 64-key tile of one item: reads LDS buffer `rd`, starts filling `wr` with the following tile.  The two are
+// __restrict__ so that, once inlined, the compiler knows the buffer being filled is not the one being read and
+// does not make LDS reads wait for the loads just issued.  (One pointer per buffer on purpose: the compiler
+// can only keep a handful of such distinctions apart.)
+// Returns false after the last tile of the workgroup's last item.
+template <int D, int DV, int NW>
+__device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restrict__ rd, char *__restrict__ wr) {
+  using G = AttnGeom<D, DV, NW>;
+  const uint16_t *lkr = reinterpret_cast<const uint16_t *>(rd + G::OFF_K);
+  const uint16_t *lvr = reinterpret_cast<const uint16_t *>(rd + G::OFF_V);
+  const float *lwr = reinterpret_cast<const float *>(rd + G::OFF_W);
+  // Nothing is outstanding here (every call ends with a full wait).  Saying so explicitly keeps the compiler from
+  // guarding the first use of the Q fragments with a wait that would also cover the loads issued just below.
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
+  const int g = c.g, c32 = c.c32;
+  // ---- what comes next: the following tile of this item, or tile 0 of the workgroup's next item -----------------
+  const bool last_tile = c.k0 + kKT >= c.re;
+  const int nitem = last_tile ? c.item + c.stride : c.item;
+  const bool more = nitem < c.total_items;
+  const int npr = (last_tile && more) ? attn_item_pr(c, nitem) : c.pr;
+  const int nre = (last_tile && more) ? attn_item_re(c, npr) : c.re;
+  const int nk0 = last_tile ? 0 : c.k0 + kKT;
+  // Loads for the next tile fly during all of this tile's math; none are issued in the very last iteration, so
+  // no direct-to-LDS load is outstanding when the workgroup ends.
+  // The clip vectors travel with tiles 0 and 1 of an item, so both buffers hold them and the epilogue can read
+  // them from the buffer it is not filling.
+  if (!last_tile || more) attn_fetch<D, DV, NW>(c, npr, nre, nk0, wr, nk0 <= kKT);
+  // ---- S^T = K Q^T for the two 32-key halves -----------------------------------------------------------
+  floatx16 st[2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (k0 + 32 * mt + 8 * (v / 4) + 4 * g + (v % 4) >= re) st[mt][v] = -INFINITY;
-    }
-    // ---- row maximum of the raw scores; move the reference only if it is more than the slack behind ------------
-    float mx = st[0][0];
+  for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int v = 0; v < 16; ++v) st[mt][v] = 0.0f;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[mt][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * scale_log2;
-    const bool jump = mx > mref + kRescaleSlack;
-    if (__builtin_amdgcn_ballot_w64(jump) != 0) {
-      const float alpha = jump ? __builtin_amdgcn_exp2f(mref - mx) : 1.0f;
-      mref = jump ? mx : mref;
-      den *= alpha;
-#pragma unroll
-      for (int i = 0; i < DV / 32; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][v] *= alpha;
-    }
-    // ---- P = exp2(S c - mref), normaliser, bf16 operand ---------------------------------------------------------
-    const float nm = -mref;
-    float dl = 0.0f;
-    bf16x8 pf[4];
+  for (int kb = 0; kb < D / 16; ++kb) {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
-      floatx16 p;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(st[mt][v], scale_log2, nm));
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 wv4 = *reinterpret_cast<const float4 *>(&lw[buf][32 * mt + 8 * q + 4 * g]);
-        dl = fmaf(p[4 * q + 0], wv4.x, dl);
-        dl = fmaf(p[4 * q + 1], wv4.y, dl);
-        dl = fmaf(p[4 * q + 2], wv4.z, dl);
-        dl = fmaf(p[4 * q + 3], wv4.w, dl);
-      }
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const floatx8 ph = {p[8 * h + 0], p[8 * h + 1], p[8 * h + 2], p[8 * h + 3],
-                            p[8 * h + 4], p[8 * h + 5], p[8 * h + 6], p[8 * h + 7]};
-        pf[2 * mt + h] = __builtin_convertvector(ph, bf16x8);
-      }
+      const int slot = (2 * kb + g) ^ c.krow_sw;
+      const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lkr[(32 * mt + c32) * D + slot * 8]);
+      st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, c.qf[kb], st[mt], 0, 0, 0);
     }
-    den += dl;
-    // ---- O^T += V_S^T P^T ------------------------------------------------------------------------------------
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-#pragma unroll
-      for (int i = 0; i < DV / 32; ++i) {
-        const uint16_t *rowp = &lv[buf][(32 * i + c32) * VSTR + 16 * kb + 4 * g];
-        const uint2 lo = *reinterpret_cast<const uint2 *>(rowp);
-        const uint2 hi = *reinterpret_cast<const uint2 *>(rowp + 8);
-        const uint4 av = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&av), pf[kb], acc[i], 0, 0,
-                                                         0);
-      }
-    }
-    if (more) stash(buf ^ 1);
-    __syncthreads();
   }
-  // ---- epilogue: guard, divide, clip, store -------------------------------------------------------------------
-  den += __shfl_xor(den, 32, kWave);
-  const bool ok = den > 0.0f;
-  const float inv = ok ? 1.0f / den : 0.0f;
-  if (q0 + c32 < m) {
-    bf16_t *orow = out + ((size_t)bh * m + q0 + c32) * DV;
+  // The Q fragments are dead after the last score product of an item: the next item's are loaded into the same
+  // registers now and arrive during the softmax, value product and epilogue of this tile.
+  if (last_tile && more) attn_load_q<D, DV, NW>(c, nitem);
+  if (c.k0 + kKT > c.re) {                                   // ragged last tile: mask the missing keys
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (c.k0 + 32 * mt + 8 * (v / 4) + 4 * g + (v % 4) >= c.re) st[mt][v] = -INFINITY;
+  }
+  // ---- row maximum of the raw scores; move the reference only if it is more than the slack behind ------------
+  float mx = st[0][0];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[mt][v]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * c.scale_log2;
+  const bool jump = mx > c.mref + kRescaleSlack;
+  if (__builtin_amdgcn_ballot_w64(jump) != 0) {
+    const float alpha = jump ? __builtin_amdgcn_exp2f(c.mref - mx) : 1.0f;
+    c.mref = jump ? mx : c.mref;
+    c.den *= alpha;
 #pragma unroll
     for (int i = 0; i < DV / 32; ++i)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int col = 32 * i + 8 * q + 4 * g;
-        const float4 lo = *reinterpret_cast<const float4 *>(vmin + (size_t)pr * DV + col);
-        const float4 hi = *reinterpret_cast<const float4 *>(vmax + (size_t)pr * DV + col);
-        floatx4 o = {acc[i][4 * q + 0] * inv, acc[i][4 * q + 1] * inv, acc[i][4 * q + 2] * inv,
-                     acc[i][4 * q + 3] * inv};
-        if (!ok) o = {0.f, 0.f, 0.f, 0.f};
-        o[0] = fminf(fmaxf(o[0], lo.x), hi.x);
-        o[1] = fminf(fmaxf(o[1], lo.y), hi.y);
-        o[2] = fminf(fmaxf(o[2], lo.z), hi.z);
-        o[3] = fminf(fmaxf(o[3], lo.w), hi.w);
-        const bf16x4 ob = __builtin_convertvector(o, bf16x4);
-        *reinterpret_cast<uint2 *>(orow + col) = *reinterpret_cast<const uint2 *>(&ob);
-      }
+      for (int v = 0; v < 16; ++v) c.acc[i][v] *= alpha;
+  }
+  // ---- P = exp2(S c - mref), normaliser, bf16 operand ---------------------------------------------------------
+  const float nm = -c.mref;
+  float dl = 0.0f;
+  bf16x8 pf[4];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt) {
+    floatx16 p;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(st[mt][v], c.scale_log2, nm));
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 wv4 = *reinterpret_cast<const float4 *>(&lwr[32 * mt + 8 * q + 4 * g]);
+      dl = fmaf(p[4 * q + 0], wv4.x, dl);
+      dl = fmaf(p[4 * q + 1], wv4.y, dl);
+      dl = fmaf(p[4 * q + 2], wv4.z, dl);
+      dl = fmaf(p[4 * q + 3], wv4.w, dl);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const floatx8 ph = {p[8 * h + 0], p[8 * h + 1], p[8 * h + 2], p[8 * h + 3],
+                          p[8 * h + 4], p[8 * h + 5], p[8 * h + 6], p[8 * h + 7]};
+      pf[2 * mt + h] = __builtin_convertvector(ph, bf16x8);
+    }
+  }
+  c.den += dl;
+  // ---- O^T += V_S^T P^T: A operand = keys {16kb + 4g + 0..3, 16kb + 8 + 4g + 0..3} of value column c32 -----------
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+    for (int i = 0; i < DV / 32; ++i) {
+      const uint16_t *rowp = &lvr[(32 * i + c32) * kKT + 4 * g];
+      const uint2 lo = *reinterpret_cast<const uint2 *>(rowp + ((2 * kb) ^ c.vrow_sw) * 8);
+      const uint2 hi = *reinterpret_cast<const uint2 *>(rowp + ((2 * kb + 1) ^ c.vrow_sw) * 8);
+      const uint4 av = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      c.acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&av), pf[kb], c.acc[i], 0,
+                                                         0, 0);
+    }
+  }
+  if (last_tile) {
+    // ---- epilogue of the item: guard, divide, clip, store; then start the next item --------------------------------
+    const float dn = c.den + __shfl_xor(c.den, 32, kWave);
+    const bool ok = dn > 0.0f;
+    const float inv = ok ? 1.0f / dn : 0.0f;
+    const int bh = c.item / c.qtiles;
+    const int64_t qrow = (int64_t)(c.item % c.qtiles) * (NW * 32) + c.wv * 32 + c32;
+    if (qrow < c.m) {
+      bf16_t *orow = c.out + ((size_t)bh * c.m + qrow) * DV;
+      const float *clip = reinterpret_cast<const float *>(rd + G::OFF_C);
+#pragma unroll
+      for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = 32 * i + 8 * q + 4 * g;
+          const float4 lo = *reinterpret_cast<const float4 *>(&clip[col]);
+          const float4 hi = *reinterpret_cast<const float4 *>(&clip[DV + col]);
+          floatx4 o = {c.acc[i][4 * q + 0] * inv, c.acc[i][4 * q + 1] * inv, c.acc[i][4 * q + 2] * inv,
+                       c.acc[i][4 * q + 3] * inv};
+          if (!ok) o = {0.f, 0.f, 0.f, 0.f};
+          o[0] = fminf(fmaxf(o[0], lo.x), hi.x);
+          o[1] = fminf(fmaxf(o[1], lo.y), hi.y);
+          o[2] = fminf(fmaxf(o[2], lo.z), hi.z);
+          o[3] = fminf(fmaxf(o[3], lo.w), hi.w);
+          const bf16x4 ob = __builtin_convertvector(o, bf16x4);
+          *reinterpret_cast<uint2 *>(orow + col) = *reinterpret_cast<const uint2 *>(&ob);
+        }
+    }
+    if (!more) return false;
+#pragma unroll
+    for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) c.acc[i][v] = 0.0f;
+    c.mref = -INFINITY;
+    c.den = 0.0f;
+  }
+  __builtin_amdgcn_s_waitcnt(0);       // this wave's share of the next tile (and the next Q fragments) has arrived
+  __syncthreads();
+  c.item = nitem; c.pr = npr; c.re = nre; c.k0 = nk0;
+  return true;
+}
+
+template <int D, int DV, int NW>
+__global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const bf16_t *__restrict__ Vt,
+    const float *__restrict__ w, const float *__restrict__ vmin, const float *__restrict__ vmax,
+    const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int64_t m, int r, int r64, int q_heads, int group,
+    int qtiles, int total_items, float scale_log2) {
+  using G = AttnGeom<D, DV, NW>;
+  __shared__ __attribute__((aligned(16))) char buf0[G::BYTES];
+  __shared__ __attribute__((aligned(16))) char buf1[G::BYTES];
+
+  AttnCtx<D, DV> c;
+  c.Q = Q; c.Ks = Ks; c.Vt = Vt; c.w = w; c.vmin = vmin; c.vmax = vmax; c.r_eff = r_eff; c.out = out;
+  c.m = m; c.r = r; c.r64 = r64; c.q_heads = q_heads; c.group = group; c.kv_heads = q_heads / group;
+  c.qtiles = qtiles; c.total_items = total_items; c.stride = (int)gridDim.x; c.scale_log2 = scale_log2;
+  const int t = threadIdx.x;
+  c.wv = t / kWave; c.l = t % kWave; c.g = c.l / 32; c.c32 = c.l % 32;
+  c.krow_sw = (c.c32 / G::KRP) % G::KPPR;          // slot permutation of this lane's operand rows
+  c.vrow_sw = (c.c32 / G::VRP) % G::VPPR;
+#pragma unroll
+  for (int e = 0; e < G::KLOADS; ++e) {      // LDS piece (e NW + wv) 64 + l holds key row `row`, logical piece `slot ^ ...`
+    const int idx = (e * NW + c.wv) * 64 + c.l, row = idx / G::KPPR, slot = idx % G::KPPR;
+    c.krow[e] = row;
+    c.kcol[e] = (slot ^ ((row / G::KRP) % G::KPPR)) * 8;
+  }
+#pragma unroll
+  for (int e = 0; e < G::VLOADS; ++e) {
+    const int idx = (e * NW + c.wv) * 64 + c.l, row = idx / G::VPPR, slot = idx % G::VPPR;
+    c.voff[e] = row * r64 + (slot ^ ((row / G::VRP) % G::VPPR)) * 8;
+  }
+
+  // An item is one (batch*head, query tile) pair; this workgroup takes items blockIdx.x, + gridDim.x, ...
+  c.item = blockIdx.x;
+  if (c.item >= total_items) return;
+  c.pr = attn_item_pr(c, c.item);
+  c.re = attn_item_re(c, c.pr);
+  c.k0 = 0;
+  attn_fetch<D, DV, NW>(c, c.pr, c.re, 0, buf0, true);
+  attn_load_q<D, DV, NW>(c, c.item);
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) c.acc[i][v] = 0.0f;
+  c.mref = -INFINITY;
+  c.den = 0.0f;
+  __builtin_amdgcn_s_waitcnt(0);           // tile 0 and the Q fragments have arrived
+  __syncthreads();
+  while (attn_tile<D, DV, NW>(c, buf0, buf1) && attn_tile<D, DV, NW>(c, buf1, buf0)) {
   }
 }
 
@@ -574,13 +694,31 @@ __global__ __launch_bounds__(kThreads) void k_pack_values(const float *__restric
   from_float(j < r ? v_s[((size_t)pr * r + j) * dv + c] : 0.0f, &v_t[((size_t)pr * dv + c) * r64 + j]);
 }
 
+// Number of compute units of the current device (queried once per process and device).
+int compute_units() {
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (!cached[dev]) {
+    int n = 0;
+    cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+  }
+  return cached[dev];
+}
+
 template <int D, int DV>
 int launch_mfma2(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
+  constexpr int NW = WILDCAT_ATTN_NW;
   const int r64 = (s.r + 63) / 64 * 64;
-  const dim3 grid((unsigned)((s.m + 255) / 256), s.batch * s.q_heads);
-  hipLaunchKernelGGL((k_wtd_attn_mfma2<D, DV>), grid, dim3(512), 0, s.stream, (const bf16_t *)Q,
+  const int64_t qtiles = (s.m + NW * 32 - 1) / (NW * 32);
+  const int64_t total = qtiles * s.batch * s.q_heads;
+  if (total > INT32_MAX) return WILDCAT_EUNSUPPORTED;
+  const int64_t resident = (int64_t)compute_units() * (8 / NW);     // workgroups that fit on the device at once
+  const unsigned grid = (unsigned)(total < resident ? total : resident);
+  hipLaunchKernelGGL((k_wtd_attn_mfma2<D, DV, NW>), dim3(grid), dim3(NW * 64), 0, s.stream, (const bf16_t *)Q,
                      (const bf16_t *)cs->k_s, (const bf16_t *)cs->v_t, cs->w, cs->v_min, cs->v_max, cs->r_eff,
-                     (bf16_t *)out, s.m, s.r, r64, s.q_heads, s.group, (float)(s.beta * (double)kLog2e));
+                     (bf16_t *)out, s.m, s.r, r64, s.q_heads, s.group, (int)qtiles, (int)total,
+                     (float)(s.beta * (double)kLog2e));
   return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
 }
 
