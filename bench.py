@@ -50,10 +50,13 @@ class HipEvents:
         return float(ms.value)
 
 
-def step_loop_bytes(P, n, d, r, es):
-    """Algorithmic HBM bytes of the r launches of the RPNys step kernel: per launch i and key, the key row
-    (d * es), the i earlier Cholesky entries of that key (8 i), the new entry (8), and p read + written (16)."""
-    return float(P) * n * (r * (d * es + 8 + 16) + 8.0 * r * (r - 1) / 2.0)
+def step_loop_bytes(P, n, d, r, es, single_launch):
+    """Algorithmic HBM bytes of the RPNys selection loop.  Per step i and key: the i earlier Cholesky entries of
+    that key (8 i), the new entry (8), and p written for the other workgroups plus read back during the pivot
+    search (16).  The key rows (d * es per key) are read once when the loop is one persistent launch that keeps
+    them in registers, and once per step when the loop is one launch per step."""
+    key_reads = 1 if single_launch else r
+    return float(P) * n * (key_reads * d * es + r * (8 + 16) + 8.0 * r * (r - 1) / 2.0)
 
 
 def cpu_baseline(w, budget_heads):
@@ -151,13 +154,15 @@ def main():
     loop_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in loop_ev]))
     ph = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(3)] for m in marks]).mean(axis=0)
     P = s.problems
-    loop_bytes = step_loop_bytes(P, s.n, s.d, s.r, es)
+    single = wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, s.d, 1 if s.dtype == "bf16" else 0)
+    launches = 1 if single else s.r
+    loop_bytes = step_loop_bytes(P, s.n, s.d, s.r, es, single)
     achieved = loop_bytes / (loop_ms * 1e-3) / 1e9
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", "rpnys_step_traffic.json")
+    tfile = os.path.join(ROOT, "profiles", "rpnys_loop_traffic.json")
     if os.path.exists(tfile) and args.cfg == 4:
         with open(tfile) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+            traffic = json.load(f).get("single_launch" if single else "per_step", {}).get("hbm_bytes_per_launch")
     attn_flops = float(s.batch * s.q_heads) * s.n * (4.0 * s.r * s.d + 2.0 * s.r)
     attn_tflops = attn_flops / (ph[2] * 1e-3) / 1e12
 
@@ -175,10 +180,11 @@ def main():
                    "uniform_seed": s.uniform_seed, "data_seed": s.data_seed},
         "phases_ms": {"query_radius": float(ph[0]), "compress_kv": float(ph[1]), "rpnys_loop": loop_ms,
                       "wtd_attn": float(ph[2])},
-        "roofline": {"kernel": "k_step (RPNys selection loop, one launch per step)", "bound": "hbm",
+        "roofline": {"kernel": ("k_rpnys_persistent (RPNys selection loop, all %d steps in one launch)" % s.r) if single
+                               else "k_step (RPNys selection loop, one launch per step)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "launches": s.r, "avg_launch_ms": loop_ms / s.r,
-                     "algorithmic_bytes_per_launch": loop_bytes / s.r},
+                     "traffic": traffic, "launches": launches, "avg_launch_ms": loop_ms / launches,
+                     "algorithmic_bytes_per_launch": loop_bytes / launches},
         "wtd_attn": {"bound": "mfma", "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS},
     }

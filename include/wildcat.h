@@ -89,7 +89,8 @@ typedef struct {
 typedef struct {
   int32_t *idx;   /* [P, r]  pivot index into the n keys, in selection order; -1 in */
                   /*         unused slots (rank exhausted before r pivots)          */
-  int32_t *r_eff; /* [P]     number of pivots drawn                                 */
+  int32_t *r_eff; /* [P]     number of pivots drawn (-1: internal wait timed out, the    */
+                  /*         call's outputs are invalid; never expected)            */
   void *k_s;      /* [P, r, d]  storage dtype: original (un-recentred) key rows     */
   float *v_s;     /* [P, r, dv] W V                                                 */
   float *w;       /* [P, r]     W 1                                                 */
@@ -149,6 +150,12 @@ int wildcat_compress_kv(const void *K, const void *V, int64_t n, int32_t d, int3
  * attention. */
 int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *out, int64_t m,
                      int32_t d, int32_t r, const wildcat_opts *opts);
+
+/* HOST (queries the current device).  1 if wildcat_compress_kv will run the RPNys selection loop
+ * (Alg. 1) of this shape as one persistent launch -- all key slabs of all problems resident on the
+ * device at once, keys held in registers -- and 0 if it will issue one launch per step; negative
+ * wildcat_status for invalid arguments.  For profiling and reporting only. */
+int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts);
 
 /* Rewrites cs->v_t from cs->v_s (both device buffers, see wildcat_coreset) for a coreset
  * of r rows and value width dv; batch and kv_heads are read from opts, whose dtype must

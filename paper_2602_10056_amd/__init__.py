@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libwildcat.so")
 
 WILDCAT_F32, WILDCAT_BF16 = 0, 1
 EXPORTS = ("wildcat_version", "wildcat_strerror", "wildcat_workspace_bytes", "wildcat_draw_uniforms",
-           "wildcat_query_radius", "wildcat_compress_kv", "wildcat_wtd_attn", "wildcat_pack_values")
+           "wildcat_query_radius", "wildcat_compress_kv", "wildcat_wtd_attn", "wildcat_pack_values",
+           "wildcat_rpnys_single_launch")
 
 
 class WildcatError(RuntimeError):
@@ -74,6 +75,8 @@ def load_library(force: bool = False):
     lib.wildcat_wtd_attn.restype = ctypes.c_int
     lib.wildcat_wtd_attn.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Coreset), ctypes.c_void_p, ctypes.c_int64,
                                      ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
+    lib.wildcat_rpnys_single_launch.restype = ctypes.c_int
+    lib.wildcat_rpnys_single_launch.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
     lib.wildcat_pack_values.restype = ctypes.c_int
     lib.wildcat_pack_values.argtypes = [ctypes.POINTER(_Coreset), ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
     _lib = lib
@@ -153,6 +156,16 @@ def workspace_bytes(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16):
     o = _Opts()
     o.batch, o.kv_heads, o.dv, o.dtype = batch, kv_heads, dv, dtype
     return load_library().wildcat_workspace_bytes(n, d, r, ctypes.byref(o))
+
+
+def rpnys_single_launch(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16):
+    """True if compress_kv runs the selection loop of this shape as one persistent launch (needs a GPU)."""
+    o = _Opts()
+    o.batch, o.kv_heads, o.dv, o.dtype = batch, kv_heads, dv, dtype
+    rc = load_library().wildcat_rpnys_single_launch(n, d, r, ctypes.byref(o))
+    if rc < 0:
+        _check(rc, "wildcat_rpnys_single_launch")
+    return bool(rc)
 
 
 def query_radius(Q, kv_heads=None):

@@ -1,6 +1,8 @@
 // Host-side pieces of the C ABI that launch nothing: option resolution, the workspace plan,
 // the documented uniform stream and error strings.
 #include <cmath>
+#include <cstdlib>
+#include <cstring>
 
 #include "common.h"
 
@@ -38,6 +40,18 @@ int resolve_shape(int64_t n, int64_t m_arg, int32_t d, int32_t r, const wildcat_
   return WILDCAT_OK;
 }
 
+int compute_units() {
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (!cached[dev]) {
+    int n = 0;
+    cached[dev] =
+        (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+  }
+  return cached[dev];
+}
+
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 Plan make_plan(const Shape &s) {
@@ -66,7 +80,7 @@ Plan make_plan(const Shape &s) {
   p.off_kp = take(P * n * p.dpad * es);
   p.off_d0 = take(P * n * 8);
   p.off_p = take(2 * P * n * 8);
-  p.off_bsum = take(2 * P * p.nblk * 8);
+  p.off_bsum = take(P * r * p.nblk * 8);
   p.off_scal = take(P * 8 * 8);
   p.off_F = take(P * n * r * 8);
   p.off_L = take(P * r * r * 8);
@@ -76,6 +90,11 @@ Plan make_plan(const Shape &s) {
   p.off_vminpart = take(P * p.nb0 * (size_t)s.dv * 4);
   p.off_vmaxpart = take(P * p.nb0 * (size_t)s.dv * 4);
   p.off_u = take(P * r * 8);
+  p.off_sync = take(4);
+  // Single-launch loop if all slabs can be resident (refined against real occupancy at launch).  The environment
+  // variable WILDCAT_RPNYS_LOOP=steps forces one launch per step (a tuning and debugging switch).
+  const char *mode = std::getenv("WILDCAT_RPNYS_LOOP");
+  p.persistent = s.r >= 2 && (int64_t)p.nblk * s.P <= 2 * 1024 && !(mode && std::strcmp(mode, "steps") == 0);
   p.total = off;
   return p;
 }

@@ -38,10 +38,14 @@ struct Plan {
   int nchunk;       // n-chunks of the Gram pass (each a whole number of slabs)
   int slabs_per_chunk;
   size_t off_kbar, off_kp, off_d0, off_p, off_bsum, off_scal, off_F, off_L, off_gpart, off_g,
-      off_mpart, off_vminpart, off_vmaxpart, off_u;
+      off_mpart, off_vminpart, off_vmaxpart, off_u, off_sync;
+  bool persistent;  // try the single-launch selection loop (all slabs of all problems resident at once)
   size_t total;
 };
 Plan make_plan(const Shape &s);
+
+// Number of compute units of the current device (queried once per process and device).
+int compute_units();
 
 // ---- storage types ---------------------------------------------------------------------------
 struct bf16_t { uint16_t bits; };

@@ -22,6 +22,7 @@
 // the previous launch left, so no grid-wide synchronisation happens inside a kernel.
 #include <climits>
 #include <cmath>
+#include <cstdlib>
 
 #include "common.h"
 
@@ -248,7 +249,8 @@ __global__ __launch_bounds__(kThreads) void k_init_p(int64_t n, int64_t npad, in
                                                      const double *__restrict__ scal, double *__restrict__ sq_floor,
                                                      double *__restrict__ p0, double *__restrict__ bsum0,
                                                      int32_t *__restrict__ idx, int32_t *__restrict__ r_eff,
-                                                     double *__restrict__ u_gen, unsigned long long seed) {
+                                                     double *__restrict__ u_gen, unsigned long long seed,
+                                                     int *__restrict__ sync_error) {
   __shared__ double sm[kThreads / kWave];
   const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
   const double beta_tau = scal[(size_t)pr * 8 + 2];
@@ -263,7 +265,9 @@ __global__ __launch_bounds__(kThreads) void k_init_p(int64_t n, int64_t npad, in
     loc += v;
   }
   const double tot = block_sum(loc, sm);
-  if (t == 0) bsum0[(size_t)pr * nblk + b] = tot;
+  double *bs = bsum0 + (size_t)pr * r * nblk;               // [r][nblk]: row 0 = initial sums, the rest unpublished
+  if (t == 0) bs[b] = tot;
+  for (int i = 1 + t; i < r; i += kThreads) bs[(size_t)i * nblk + b] = -1.0;
   if (b == 0) {
     for (int i = t; i < r; i += kThreads) {
       idx[(size_t)pr * r + i] = -1;
@@ -272,12 +276,17 @@ __global__ __launch_bounds__(kThreads) void k_init_p(int64_t n, int64_t npad, in
         u_gen[(size_t)pr * r + i] = (double)(mix64(seed + ctr * 0x9E3779B97F4A7C15ull) >> 11) * 0x1.0p-53;
       }
     }
-    if (t == 0) r_eff[pr] = r;
+    if (t == 0) {
+      r_eff[pr] = r;
+      if (pr == 0) *sync_error = 0;
+    }
   }
 }
 
 // --------------------------------------------------------------------------------------------
-// One RPNys step (body of the loop of Alg. 1) for step index i.  grid (nblk, P).
+// One RPNys step (body of the loop of Alg. 1) for step index i, as a device function shared by the two
+// drivers below: `k_step` (one launch per step, grid (nblk, P)) and `k_rpnys_persistent` (one launch for the
+// whole loop, workgroups of a problem synchronising through a counter in memory).
 // --------------------------------------------------------------------------------------------
 struct StepArgs {
   const void *Kp;         // [P][dpad/4][npad][4] packed keys
@@ -286,7 +295,7 @@ struct StepArgs {
   const double *floor;    // [P][npad]
   const double *u;        // [P][r]
   double *p;              // [2][P][npad]   residual diagonal, double-buffered by step parity
-  double *bsum;           // [2][P][nblk]   per-slab sums of p, same parity
+  double *bsum;           // [P][r][nblk]   per-slab sums of p entering each step; -1 = not yet published
   double *F;              // [P][nblk][r][slab]
   double *L;              // [P][r][r] Cholesky factor of h(K_S,K_S), row-major, lower triangle
   int32_t *idx, *r_eff;
@@ -314,20 +323,86 @@ struct HistVec<2> {
   }
 };
 
-template <typename T, int KPT>
-__global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
-  extern __shared__ double dyn[];
-  double *g = dyn;             // [r]    F_j(s), j < i : row i of L
-  double *ksc = dyn + a.r;     // [dpad] k_s - kbar
-  __shared__ double sm[kThreads / kWave];
-  __shared__ int smi[kThreads / kWave];
-  __shared__ double s_base, s_ps;
+// The packed features of a thread's KPT keys, kept in registers across steps by the persistent driver
+// (NC chunks of 4 features; NC = 0: not kept, streamed from memory every step).
+template <typename T, int KPT, int NC>
+struct KeyRegs {
+  float x[NC > 0 ? NC : 1][KPT][kChunk / (sizeof(T) == 2 ? 2 : 1)];   // bf16 pairs stay packed in one 32-bit lane
+};
+template <typename T, int KPT, int NC>
+__device__ __forceinline__ void load_key_regs(KeyRegs<T, KPT, NC> &kr, const T *kp, int64_t npad) {
+  if constexpr (NC > 0) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      if constexpr (sizeof(T) == 2) {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(kp + (size_t)c * npad * kChunk);
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+          kr.x[c][k][0] = __uint_as_float(src[2 * k]);
+          kr.x[c][k][1] = __uint_as_float(src[2 * k + 1]);
+        }
+      } else {
+        float x[KPT][kChunk];
+        load_chunk<T, KPT>(kp + (size_t)c * npad * kChunk, x);
+#pragma unroll
+        for (int k = 0; k < KPT; ++k)
+#pragma unroll
+          for (int e = 0; e < kChunk; ++e) kr.x[c][k][e] = x[k][e];
+      }
+    }
+  }
+}
+template <typename T, int KPT, int NC>
+__device__ __forceinline__ void key_chunk(const KeyRegs<T, KPT, NC> &kr, int c, float (&x)[KPT][kChunk]) {
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    if constexpr (sizeof(T) == 2) {
+      uint32_t lo = __float_as_uint(kr.x[c][k][0]), hi = __float_as_uint(kr.x[c][k][1]);
+      // Opaque to the optimiser on purpose: the widened values are loop-invariant across steps, and hoisting them
+      // out of the step loop would need four times the registers of the packed form.
+      asm volatile("" : "+v"(lo), "+v"(hi));
+      x[k][0] = __uint_as_float(lo << 16); x[k][1] = __uint_as_float(lo & 0xffff0000u);
+      x[k][2] = __uint_as_float(hi << 16); x[k][3] = __uint_as_float(hi & 0xffff0000u);
+    } else {
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) {
+        float v = kr.x[c][k][e];
+        asm volatile("" : "+v"(v));          // keeps the fp64 widening inside the step (see above)
+        x[k][e] = v;
+      }
+    }
+  }
+}
+
+// Device-coherent accesses for the few values one workgroup writes and another reads within the persistent
+// launch (slab sums, p, history rows): such stores are written through to memory and such loads bypass the
+// non-coherent caches, so no cache-wide write-back or invalidate is needed between steps.
+__device__ __forceinline__ void st_dev(double *p, double v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double ld_dev(const double *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct StepShared {
+  double sm[kThreads / kWave];
+  int smi[kThreads / kWave];
+  double s_base, s_ps;
+};
+
+// Returns 1 after a step, 0 (state untouched) when the residual mass is exhausted, -1 if a bounded wait for another
+// workgroup's slab sum ran out (POLL only).
+// pown / flo: residual diagonal and floor of this thread's keys (registers); on return pown is updated.
+template <typename T, int KPT, int NC, bool POLL>
+__device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int pr, double *g, double *ksc,
+                                          StepShared &sh, const KeyRegs<T, KPT, NC> &kr, double (&pown)[KPT],
+                                          const double (&flo)[KPT], int *error, long long spin_limit) {
   constexpr int SLAB = kThreads * KPT;
-  const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
+  const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
   const int rd = i & 1, wr = rd ^ 1;
-  const double *bs = a.bsum + ((size_t)rd * a.P + pr) * a.nblk;
-  double *bs_next = a.bsum + ((size_t)wr * a.P + pr) * a.nblk;
+  const double *bs = a.bsum + ((size_t)pr * a.r + i) * a.nblk;
+  double *bs_next = a.bsum + ((size_t)pr * a.r + i + 1) * a.nblk;     // written only if i + 1 < r
   const double *pin = a.p + ((size_t)rd * a.P + pr) * a.npad;
   double *pout = a.p + ((size_t)wr * a.P + pr) * a.npad;
   double *Fb = a.F + ((size_t)pr * a.nblk + b) * a.r * SLAB;
@@ -339,27 +414,38 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
   const int e0 = t * per < a.nblk ? t * per : a.nblk;
   const int e1 = e0 + per < a.nblk ? e0 + per : a.nblk;
   double loc = 0.0;
-  for (int e = e0; e < e1; ++e) loc += bs[e];
+  if constexpr (POLL) {
+    // The slab sums double as arrival flags: a slot holds -1 until its workgroup has finished the previous step
+    // (and its p and history row have completed), so polling them is the synchronisation between steps, and the
+    // successful poll already has the values.  Bounded: gives up after spin_limit rounds.
+    long long spins = 0;
+    while (true) {
+      int ok = 1;
+      loc = 0.0;
+      for (int e = e0; e < e1; ++e) {
+        const double v = ld_dev(bs + e);
+        ok &= v >= 0.0;
+        loc += v;
+      }
+      if (__syncthreads_and(ok)) break;
+      if (++spins > spin_limit || __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+        if (t == 0) __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        spins = -1;
+      }
+      if (__syncthreads_or(spins < 0)) return -1;
+      __builtin_amdgcn_s_sleep(1);
+    }
+  } else {
+    for (int e = e0; e < e1; ++e) loc += ld_dev(bs + e);
+  }
   double mass;
-  double inc = block_incl_scan(loc, sm, &mass);
+  double inc = block_incl_scan(loc, sh.sm, &mass);
   double excl = __shfl_up(inc, 1, kWave);          // exclusive prefix = inclusive prefix of thread t-1
   if (lane == 0) {
     excl = 0.0;
-    for (int k = 0; k < t / kWave; ++k) excl += sm[k];
+    for (int k = 0; k < t / kWave; ++k) excl += sh.sm[k];
   }
-
-  if (!(mass > 0.0)) {
-    // Residual mass exhausted: h(K,K) is reproduced exactly by the pivots so far.  Carry the (all-zero)
-    // state into the other parity, leave row i of F zero, record the number of pivots once.
-#pragma unroll
-    for (int k = 0; k < KPT; ++k) {
-      pout[l_glob + k] = 0.0;
-      Fb[(size_t)i * SLAB + l_loc + k] = 0.0;
-    }
-    if (t == 0) bs_next[b] = 0.0;
-    if (b == 0 && t == 0 && a.r_eff[pr] > i) a.r_eff[pr] = i;
-    return;
-  }
+  if (!(mass > 0.0)) return 0;                     // h(K,K) is reproduced exactly by the pivots so far
 
   // ---- 2. the slab holding the draw: first slab whose inclusive prefix exceeds u * mass ----------------------
   double target = a.u[(size_t)pr * a.r + i] * mass;
@@ -369,23 +455,23 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
   {
     double run = excl;
     for (int e = e0; e < e1; ++e) {
-      const double v = bs[e], nxt = run + v;
+      const double v = ld_dev(bs + e), nxt = run + v;
       if (nxt > target && cand == INT_MAX) { cand = e; cand_base = run; }
       if (v > 0.0) last_pos = e;
       run = nxt;
     }
   }
-  int bstar = block_reduce<int>(cand, smi, MinOp());
+  int bstar = block_reduce<int>(cand, sh.smi, MinOp());
   if (bstar == INT_MAX) {
     // Rounding left no slab above u * mass (u within an ulp of 1): take the last index of positive mass.
-    bstar = block_reduce<int>(last_pos, smi, MaxOp());
+    bstar = block_reduce<int>(last_pos, sh.smi, MaxOp());
     target = INFINITY;
-    if (t == 0) s_base = 0.0;
+    if (t == 0) sh.s_base = 0.0;
   } else if (cand == bstar) {
-    s_base = cand_base;
+    sh.s_base = cand_base;
   }
   __syncthreads();
-  const double base = s_base;
+  const double base = sh.s_base;
   bstar = bstar < 0 ? 0 : (bstar >= a.nblk ? a.nblk - 1 : bstar);   // only non-finite input can get here
 
   // ---- 3. the index inside that slab ---------------------------------------------------------------
@@ -393,13 +479,13 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
   double pv[KPT];
   loc = 0.0;
 #pragma unroll
-  for (int k = 0; k < KPT; ++k) { pv[k] = ps[l_loc + k]; loc += pv[k]; }
+  for (int k = 0; k < KPT; ++k) { pv[k] = ld_dev(ps + l_loc + k); loc += pv[k]; }
   double tot2;
-  inc = block_incl_scan(loc, sm, &tot2);
+  inc = block_incl_scan(loc, sh.sm, &tot2);
   excl = __shfl_up(inc, 1, kWave);
   if (lane == 0) {
     excl = 0.0;
-    for (int k = 0; k < t / kWave; ++k) excl += sm[k];
+    for (int k = 0; k < t / kWave; ++k) excl += sh.sm[k];
   }
   cand = INT_MAX;
   last_pos = -1;
@@ -413,15 +499,15 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
       run = nxt;
     }
   }
-  int s_loc = block_reduce<int>(cand, smi, MinOp());
-  if (s_loc == INT_MAX) s_loc = block_reduce<int>(last_pos, smi, MaxOp());
+  int s_loc = block_reduce<int>(cand, sh.smi, MinOp());
+  if (s_loc == INT_MAX) s_loc = block_reduce<int>(last_pos, sh.smi, MaxOp());
   if (s_loc < 0) s_loc = 0;                                          // non-finite input only
-  if (s_loc / KPT == t) s_ps = pv[s_loc % KPT];
+  if (s_loc / KPT == t) sh.s_ps = pv[s_loc % KPT];
   const int64_t s_glob = (int64_t)bstar * SLAB + s_loc;
 
   // ---- 4. broadcast data of the pivot: its history column g_j = F_j(s) and k_s - kbar ------------------
   const double *Fs = a.F + ((size_t)pr * a.nblk + bstar) * a.r * SLAB + s_loc;
-  for (int j = t; j < i; j += kThreads) g[j] = Fs[(size_t)j * SLAB];
+  for (int j = t; j < i; j += kThreads) g[j] = ld_dev(Fs + (size_t)j * SLAB);
   const int nc = a.dpad / kChunk;
   const T *Kp = reinterpret_cast<const T *>(a.Kp) + (size_t)pr * nc * a.npad * kChunk;
   double cbp = 0.0;
@@ -431,8 +517,8 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
     ksc[t] = v;
     cbp = kb * v;
   }
-  const double cb = block_sum(cbp, sm);          // <kbar, k_s - kbar>; also publishes g, ksc, s_ps
-  const double inv = 1.0 / sqrt(s_ps);
+  const double cb = block_sum(cbp, sh.sm);       // <kbar, k_s - kbar>; also publishes g, ksc, s_ps
+  const double inv = 1.0 / sqrt(sh.s_ps);
   const double beta_tau = a.scal[(size_t)pr * 8 + 2];
 
   // ---- 5. history product  acc_l = sum_{j<i} F_j(l) g_j  (the O(n i) stream) ---------------------------
@@ -473,11 +559,23 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
     }
   }
 
-  // ---- 6. kernel column  c_l = exp(beta_tau <k_l - kbar, k_s - kbar>)  (the O(n d) stream) ----------------
+  // ---- 6. kernel column  c_l = exp(beta_tau <k_l - kbar, k_s - kbar>)  (the O(n d) stream, or registers) --------
   double dot[KPT];
 #pragma unroll
   for (int k = 0; k < KPT; ++k) dot[k] = 0.0;
-  {
+  if constexpr (NC > 0) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      float x[KPT][kChunk];
+      key_chunk<T, KPT, NC>(kr, c, x);
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) {
+        const double ks = ksc[c * kChunk + e];
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) dot[k] = fma((double)x[k][e], ks, dot[k]);
+      }
+    }
+  } else {
     const T *kp = Kp + (size_t)l_glob * kChunk;
 #pragma unroll 4
     for (int c = 0; c < nc; ++c) {
@@ -500,16 +598,19 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
   for (int k = 0; k < KPT; ++k) {
     const int64_t l = l_glob + k;
     double f = (exp(beta_tau * (dot[k] - cb)) - acc[k]) * inv;
-    double pn = pin[l] - f * f;
-    if (pn <= a.floor[(size_t)pr * a.npad + l]) pn = 0.0;      // also clamps negatives (floor >= 0)
+    double pn = pown[k] - f * f;
+    if (pn <= flo[k]) pn = 0.0;                                  // also clamps negatives (floor >= 0)
     if (l == s_glob) { pn = 0.0; fs = f; own = true; }
     if (l >= a.n) { pn = 0.0; f = 0.0; }
-    Fb[(size_t)i * SLAB + l_loc + k] = f;
-    pout[l] = pn;
+    st_dev(Fb + (size_t)i * SLAB + l_loc + k, f);
+    st_dev(pout + l, pn);
+    pown[k] = pn;
     psum += pn;
   }
-  const double tot = block_sum(psum, sm);
-  if (t == 0) bs_next[b] = tot;
+  const double tot = block_sum(psum, sh.sm);
+  if constexpr (POLL) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's p and history stores have completed
+  __syncthreads();
+  if (t == 0 && i + 1 < a.r) st_dev(bs_next + b, tot);       // publishes the sum and, with it, the whole step
 
   // ---- 8. bookkeeping by the slab that owns the pivot -----------------------------------------------------
   if (b == bstar) {
@@ -519,6 +620,78 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
       Lr[i] = fs;
       a.idx[(size_t)pr * a.r + i] = (int32_t)s_glob;
     }
+  }
+  return 1;
+}
+
+// Driver 1: one launch per step; the kernel boundary is the synchronisation between steps.
+template <typename T, int KPT>
+__global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
+  extern __shared__ double dyn[];
+  __shared__ StepShared sh;
+  constexpr int SLAB = kThreads * KPT;
+  const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
+  const int64_t l_glob = (int64_t)b * SLAB + t * KPT;
+  const double *pin = a.p + ((size_t)(i & 1) * a.P + pr) * a.npad;
+  double pown[KPT], flo[KPT];
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    pown[k] = pin[l_glob + k];
+    flo[k] = a.floor[(size_t)pr * a.npad + l_glob + k];
+  }
+  KeyRegs<T, KPT, 0> none;
+  if (rpnys_step<T, KPT, 0, false>(a, i, b, pr, dyn, dyn + a.r, sh, none, pown, flo, nullptr, 0) == 0) {
+    // Residual mass exhausted: carry the (all-zero) state into the other parity, leave row i of F zero, record
+    // the number of pivots once.
+    double *pout = a.p + ((size_t)((i & 1) ^ 1) * a.P + pr) * a.npad;
+    double *Fb = a.F + ((size_t)pr * a.nblk + b) * a.r * SLAB;
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) {
+      pout[l_glob + k] = 0.0;
+      Fb[(size_t)i * SLAB + t * KPT + k] = 0.0;
+    }
+    if (t == 0 && i + 1 < a.r) a.bsum[((size_t)pr * a.r + i + 1) * a.nblk + b] = 0.0;
+    if (b == 0 && t == 0 && a.r_eff[pr] > i) a.r_eff[pr] = i;
+  }
+}
+
+// Driver 2: the whole loop in one launch.  Requires all nblk * P workgroups to fit on the device at once (the
+// host checks the grid against the kernel's occupancy).  The workgroups of one problem synchronise after every step through
+// the slab sums themselves (see POLL above); the values that cross workgroups (p, slab sums, history rows) are
+// stored and loaded device-coherently (st_dev / ld_dev), so no cache-wide fence is needed.  Every wait is
+// bounded: if a limit is hit (it never should be) the error word is set and every workgroup leaves.  With
+// NC > 0 a thread keeps the packed features of its keys in registers for the whole loop, which removes the
+// O(n d) key stream from every step.
+template <typename T, int KPT, int NC>
+__global__ __launch_bounds__(kThreads, 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit) {
+  extern __shared__ double dyn[];
+  __shared__ StepShared sh;
+  constexpr int SLAB = kThreads * KPT;
+  const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
+  const int64_t l_glob = (int64_t)b * SLAB + t * KPT;
+  const int nc = a.dpad / kChunk;
+  double pown[KPT], flo[KPT];
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    pown[k] = a.p[(size_t)pr * a.npad + l_glob + k];
+    flo[k] = a.floor[(size_t)pr * a.npad + l_glob + k];
+  }
+  KeyRegs<T, KPT, NC> kr;
+  load_key_regs<T, KPT, NC>(kr, reinterpret_cast<const T *>(a.Kp) + ((size_t)pr * nc * a.npad + l_glob) * kChunk,
+                            a.npad);
+  int i = 0, rc = 1;
+  for (; i < a.r; ++i) {
+    rc = rpnys_step<T, KPT, NC, true>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit);
+    if (rc != 1) break;
+  }
+  if (rc == 0) {
+    // Exhausted at step i (every workgroup of the problem sees the same sums and leaves at the same step):
+    // rows i.. of this slab's history are zero for the Gram pass.
+    double *Fb = a.F + ((size_t)pr * a.nblk + b) * a.r * SLAB;
+    for (int j = i; j < a.r; ++j)
+#pragma unroll
+      for (int k = 0; k < KPT; ++k) Fb[(size_t)j * SLAB + t * KPT + k] = 0.0;
+    if (b == 0 && t == 0) a.r_eff[pr] = i;
   }
 }
 
@@ -713,10 +886,33 @@ __global__ void k_gather(const T *__restrict__ K, const int32_t *__restrict__ id
   }
 }
 
+// After the persistent loop: a wait that timed out (never expected) is reported as r_eff = -1 everywhere.
+__global__ void k_check_sync(const int *error, int P, int32_t *r_eff) {
+  if (*error)
+    for (int p = threadIdx.x; p < P; p += blockDim.x) r_eff[p] = -1;
+}
+
 #define LAUNCH_CHECK()                                   \
   do {                                                   \
     if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP; \
   } while (0)
+
+// The single-launch selection loop for this shape, or null if its workgroups cannot all be resident at once
+// (then the loop runs as one launch per step).
+template <typename T, int KPT>
+const void *persistent_kernel(const Shape &s, const Plan &pl) {
+  if (!pl.persistent) return nullptr;
+  const int nc = pl.dpad / kChunk;
+  constexpr int regs_per_chunk = KPT * (sizeof(T) == 2 ? 2 : 4);
+  const void *fn;
+  if (nc == 32 && 32 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0)>;
+  else if (nc == 16 && 16 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, 16>;
+  else fn = (const void *)k_rpnys_persistent<T, KPT, 0>;
+  int per_cu = 0;
+  const size_t lds = (size_t)(s.r + pl.dpad) * sizeof(double);
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, lds) != hipSuccess) return nullptr;
+  return (int64_t)per_cu * compute_units() >= (int64_t)pl.nblk * s.P ? fn : nullptr;
+}
 
 template <typename T, int KPT>
 int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const wildcat_opts *o, uint64_t seed,
@@ -758,18 +954,34 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   LAUNCH_CHECK();
   hipLaunchKernelGGL((k_init_p<KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, s.n, pl.npad, pl.nblk, s.r, s.rank_tol,
                      scal, d0, p, bsum, out->idx, out->r_eff, o->uniforms ? (double *)nullptr : u_gen,
-                     (unsigned long long)seed);
+                     (unsigned long long)seed, (int *)(ws + pl.off_sync));
   LAUNCH_CHECK();
 
   StepArgs a;
   a.Kp = Kp; a.kbar = kbar; a.scal = scal; a.floor = d0; a.u = o->uniforms ? o->uniforms : u_gen;
   a.p = p; a.bsum = bsum; a.F = F; a.L = L; a.idx = out->idx; a.r_eff = out->r_eff;
   a.n = s.n; a.npad = pl.npad; a.P = P; a.nblk = pl.nblk; a.r = s.r; a.dpad = pl.dpad;
-  const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
   if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
-  for (int i = 0; i < s.r; ++i) {
-    hipLaunchKernelGGL((k_step<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), step_lds, st, a, i);
+  const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
+  bool done = false;
+  const void *fn = persistent_kernel<T, KPT>(s, pl);
+  if (fn) {
+    int *err_word = (int *)(ws + pl.off_sync);
+    long long spin_limit = 2000000;    // polls of about a microsecond each: seconds, far beyond any real step
+    void *args[] = {(void *)&a, (void *)&err_word, (void *)&spin_limit};
+    // An ordinary launch: the grid was checked against the device's capacity (persistent_kernel), so on an idle
+    // device every workgroup is resident at once; if other work holds compute units, the late workgroups start
+    // when it ends and the resident ones poll meanwhile (bounded).
+    if (hipLaunchKernel(fn, dim3(pl.nblk, P), dim3(kThreads), args, step_lds, st) != hipSuccess) return WILDCAT_EHIP;
+    hipLaunchKernelGGL(k_check_sync, dim3(1), dim3(64), 0, st, err_word, P, out->r_eff);
     LAUNCH_CHECK();
+    done = true;
+  }
+  if (!done) {
+    for (int i = 0; i < s.r; ++i) {
+      hipLaunchKernelGGL((k_step<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), step_lds, st, a, i);
+      LAUNCH_CHECK();
+    }
   }
   if (o->ev_loop_end && hipEventRecord((hipEvent_t)o->ev_loop_end, st) != hipSuccess) return WILDCAT_EHIP;
 
@@ -824,4 +1036,16 @@ extern "C" int wildcat_compress_kv(const void *K, const void *V, int64_t n, int3
   }
   return pl.kpt == 2 ? run_compress<float, 2>(s, pl, (const float *)K, (const float *)V, opts, seed, out)
                      : run_compress<float, 1>(s, pl, (const float *)K, (const float *)V, opts, seed, out);
+}
+
+extern "C" int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts) {
+  Shape s;
+  int rc = resolve_shape(n, 0, d, r, opts, &s);
+  if (rc != WILDCAT_OK) return rc;
+  if (r > kMaxRank) return WILDCAT_EUNSUPPORTED;
+  const Plan pl = make_plan(s);
+  const void *fn;
+  if (s.dtype == WILDCAT_BF16) fn = pl.kpt == 2 ? persistent_kernel<bf16_t, 2>(s, pl) : persistent_kernel<bf16_t, 1>(s, pl);
+  else fn = pl.kpt == 2 ? persistent_kernel<float, 2>(s, pl) : persistent_kernel<float, 1>(s, pl);
+  return fn ? 1 : 0;
 }

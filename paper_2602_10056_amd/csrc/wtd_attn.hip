@@ -437,7 +437,7 @@ __device__ __forceinline__ int attn_item_pr(const AttnCtx<D, DV> &c, int item) {
 }
 template <int D, int DV>
 __device__ __forceinline__ int attn_item_re(const AttnCtx<D, DV> &c, int pr) {
-  return c.r_eff ? min(c.r_eff[pr], c.r) : c.r;
+  return c.r_eff ? max(min(c.r_eff[pr], c.r), 1) : c.r;      // never below 1: the tile loads clamp rows to re - 1
 }
 
 // Direct global-to-LDS loads of one tile.  Rows past the last key are clamped to it (and masked after the score
@@ -692,18 +692,6 @@ __global__ __launch_bounds__(kThreads) void k_pack_values(const float *__restric
   if (gid >= r64 * dv) return;
   const int c = gid / r64, j = gid % r64;
   from_float(j < r ? v_s[((size_t)pr * r + j) * dv + c] : 0.0f, &v_t[((size_t)pr * dv + c) * r64 + j]);
-}
-
-// Number of compute units of the current device (queried once per process and device).
-int compute_units() {
-  static int cached[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (!cached[dev]) {
-    int n = 0;
-    cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
-  }
-  return cached[dev];
 }
 
 template <int D, int DV>
