@@ -92,6 +92,8 @@ def main():
     ap.add_argument("--cfg", type=int, default=4, help="workload catalogue entry (4 = headline shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact", action="store_true")
+    ap.add_argument("--sweep-n", action="store_true",
+                    help="also time the path at n = 4K ... 128K (same recipe, r fixed) and add it as 'scaling_in_n'")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates profiler byte counters)")
     args = ap.parse_args()
@@ -209,6 +211,38 @@ def main():
             del Kx, Vx
         except Exception as e:           # context only; never fatal
             res["exact_attention"] = {"error": str(e)[:200]}
+
+    if args.sweep_n:
+        del Q, K, V, ws, out
+        torch.cuda.empty_cache()
+        sweep = []
+        for n2 in (4096, 8192, 16384, 32768, 65536, 131072):
+            w2 = wl.make(args.cfg, n=n2)
+            s2 = w2["shape"]
+            Q2, K2, V2 = (torch.from_numpy(w2[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
+            u2 = torch.from_numpy(w2["u"]).to(dev)
+            ws2 = torch.empty(wc.workspace_bytes(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d, 1 if es == 2 else 0),
+                              dtype=torch.uint8, device=dev)
+
+            def pass2():
+                cs2 = wc.compress_kv(K2, V2, s2.r, wc.query_radius(Q2, s2.kv_heads), uniforms=u2, workspace=ws2)
+                return wc.wtd_attn(Q2, cs2)
+
+            pass2()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(3):
+                pass2()
+            b.record()
+            torch.cuda.synchronize()
+            ms2 = a.elapsed_time(b) / 3
+            sweep.append({"n": n2, "ms": ms2, "tokens_per_s": s2.batch * n2 / (ms2 * 1e-3), "us_per_token": ms2 * 1e3 / n2,
+                          "single_launch_loop": wc.rpnys_single_launch(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d,
+                                                                      1 if es == 2 else 0)})
+            del Q2, K2, V2, ws2, w2
+            torch.cuda.empty_cache()
+        res["scaling_in_n"] = sweep
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, s.kv_heads)

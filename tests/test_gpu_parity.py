@@ -283,3 +283,43 @@ def test_full_size_config2():
 
 def test_full_size_config3():
     print(_full_size(3, heads=[0, 9], prefix_r=64))
+
+
+def test_both_loop_drivers_agree_bit_for_bit(monkeypatch):
+    """The persistent single-launch loop and the one-launch-per-step loop run the same step function: identical
+    pivots, weights and values; both equal the oracle."""
+    w = wl.make(4, q_heads=4, kv_heads=2, n=4096, r=160)
+    s = w["shape"]
+    assert wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads) is True
+    o1, c1 = run_gpu(w)
+    monkeypatch.setenv("WILDCAT_RPNYS_LOOP", "steps")
+    assert wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads) is False
+    o2, c2 = run_gpu(w)
+    monkeypatch.delenv("WILDCAT_RPNYS_LOOP")
+    for a, b in ((o1, o2), (c1.idx, c2.idx), (c1.w, c2.w), (c1.v_s, c2.v_s), (c1.r_eff, c2.r_eff), (c1.v_t, c2.v_t)):
+        assert torch.equal(a, b)
+    check_against_oracle(w, o2, c2)
+
+
+def test_rank_exhaustion_per_step_driver(monkeypatch):
+    monkeypatch.setenv("WILDCAT_RPNYS_LOOP", "steps")
+    test_rank_exhaustion_with_duplicate_keys()
+
+
+def test_pack_values_matches_compress_output():
+    w = wl.make(2, batch=1, q_heads=2, kv_heads=2, n=1024, r=100)
+    out, cs = run_gpu(w)
+    ref = cs.v_t.clone()
+    cs.v_t.zero_()
+    wc.pack_values(cs)
+    assert torch.equal(cs.v_t, ref)
+    r64 = cs.v_t.shape[-1]
+    assert r64 == 128 and torch.all(cs.v_t[..., 100:] == 0)
+    np.testing.assert_array_equal(cs.v_t[..., :100].float().cpu().numpy(),
+                                  cs.v_s.to(torch.bfloat16).float().transpose(-1, -2).cpu().numpy())
+
+
+def test_full_size_config5_long_context():
+    """n = 131072, r = 1024 (one launch per step: 2048 slabs do not fit on the device at once).  One head is
+    checked in full against the oracle, the others on their first 48 pivots."""
+    print(_full_size(5, heads=[2], prefix_r=48))
