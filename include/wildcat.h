@@ -97,12 +97,18 @@ typedef struct {
   float *v_min;   /* [P, dv]    column minima of V (Alg. 4, first line)             */
   float *v_max;   /* [P, dv]    column maxima of V                                  */
   double *tau;    /* [P]        temperature used (eq. (kernel-temperature))         */
-  void *v_t;      /* [P, dv, r64] bf16, r64 = r rounded up to a multiple of 64:     */
-                  /*         v_s transposed, rounded to bf16 and zero padded -- the */
-                  /*         MFMA operand form of V_S.  bf16 storage only (NULL for */
-                  /*         fp32).  Written by wildcat_compress_kv; after editing  */
-                  /*         v_s by hand refresh it with wildcat_pack_values.  May  */
-                  /*         be NULL: WtdAttn then converts v_s on the fly (slower) */
+  void *v_t;      /* [P, dv, r64] fp16, r64 = r rounded up to a multiple of 64: the */
+                  /*         MFMA operand form of V_S for bf16 storage,             */
+                  /*           v_t[p, c, j] = fp16(v_s[p, j, c] / v_scale[p]),      */
+                  /*         zero for j >= r.  fp16 rather than bf16 because Nystrom */
+                  /*         weights have both signs: the sums of Alg. 3 cancel, and */
+                  /*         8 significand bits are then too few.  Written by       */
+                  /*         wildcat_compress_kv; after editing v_s by hand refresh */
+                  /*         both with wildcat_pack_values.  NULL for fp32 storage. */
+                  /*         If v_t or v_scale is NULL with bf16 storage, WtdAttn   */
+                  /*         reads v_s instead, on the vector ALU (far slower).     */
+  float *v_scale; /* [P]     power of two that keeps v_t inside fp16's range:       */
+                  /*         2^(e - 14), e = exponent of max |v_s[p]| (1 if 0)      */
 } wildcat_coreset;
 
 /* Library version as major*10000 + minor*100 + patch. */
@@ -157,7 +163,7 @@ int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *out, int64_
  * wildcat_status for invalid arguments.  For profiling and reporting only. */
 int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts);
 
-/* Rewrites cs->v_t from cs->v_s (both device buffers, see wildcat_coreset) for a coreset
+/* Rewrites cs->v_t and cs->v_scale from cs->v_s (device buffers, see wildcat_coreset) for a coreset
  * of r rows and value width dv; batch and kv_heads are read from opts, whose dtype must
  * be WILDCAT_BF16.  For callers who assemble a coreset themselves instead of taking it
  * from wildcat_compress_kv (Alg. 3 accepts any weighted coreset). */

@@ -41,6 +41,7 @@ class _Coreset(ctypes.Structure):
         ("idx", ctypes.c_void_p), ("r_eff", ctypes.c_void_p), ("k_s", ctypes.c_void_p),
         ("v_s", ctypes.c_void_p), ("w", ctypes.c_void_p), ("v_min", ctypes.c_void_p),
         ("v_max", ctypes.c_void_p), ("tau", ctypes.c_void_p), ("v_t", ctypes.c_void_p),
+        ("v_scale", ctypes.c_void_p),
     ]
 
 
@@ -111,13 +112,15 @@ class Coreset:
     v_min: "torch.Tensor"   # [B, Hkv, dv] float32
     v_max: "torch.Tensor"   # [B, Hkv, dv] float32
     tau: "torch.Tensor"     # [B, Hkv] float64
-    v_t: "torch.Tensor" = None   # [B, Hkv, dv, r64] bfloat16 (bf16 storage only): MFMA operand copy of v_s
+    v_t: "torch.Tensor" = None      # [B, Hkv, dv, r64] float16 (bf16 storage only): v_s^T / v_scale, MFMA operand
+    v_scale: "torch.Tensor" = None  # [B, Hkv] float32 power of two
 
     def c_struct(self):
         return _Coreset(self.idx.data_ptr(), self.r_eff.data_ptr() if self.r_eff is not None else None,
                         self.k_s.data_ptr(), self.v_s.data_ptr(), self.w.data_ptr(), self.v_min.data_ptr(),
                         self.v_max.data_ptr(), self.tau.data_ptr() if self.tau is not None else None,
-                        self.v_t.data_ptr() if self.v_t is not None else None)
+                        self.v_t.data_ptr() if self.v_t is not None else None,
+                        self.v_scale.data_ptr() if self.v_scale is not None else None)
 
 
 def _dtype_code(t):
@@ -213,8 +216,9 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
         v_min=torch.empty((B, H, dv), dtype=torch.float32, device=dev),
         v_max=torch.empty((B, H, dv), dtype=torch.float32, device=dev),
         tau=torch.empty((B, H), dtype=torch.float64, device=dev),
-        v_t=(torch.empty((B, H, dv, (r + 63) // 64 * 64), dtype=torch.bfloat16, device=dev)
+        v_t=(torch.empty((B, H, dv, (r + 63) // 64 * 64), dtype=torch.float16, device=dev)
              if code == WILDCAT_BF16 else None),
+        v_scale=torch.empty((B, H), dtype=torch.float32, device=dev) if code == WILDCAT_BF16 else None,
     )
     o = _opts(B, H, H, n, dv, code, beta, rank_tol, r_q.contiguous(), uniforms, workspace)
     if loop_events is not None:
@@ -226,11 +230,13 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
 
 
 def pack_values(cs: Coreset):
-    """Allocates (if needed) and fills cs.v_t from cs.v_s: for coresets assembled by hand (bf16 storage)."""
+    """Allocates (if needed) and fills cs.v_t, cs.v_scale from cs.v_s: for coresets assembled by hand (bf16 storage)."""
     import torch
     B, H, r, dv = cs.v_s.shape
     if cs.v_t is None:
-        cs.v_t = torch.empty((B, H, dv, (r + 63) // 64 * 64), dtype=torch.bfloat16, device=cs.v_s.device)
+        cs.v_t = torch.empty((B, H, dv, (r + 63) // 64 * 64), dtype=torch.float16, device=cs.v_s.device)
+    if cs.v_scale is None:
+        cs.v_scale = torch.empty((B, H), dtype=torch.float32, device=cs.v_s.device)
     o = _opts(B, H, H, 0, dv, WILDCAT_BF16, None)
     c = cs.c_struct()
     _check(load_library().wildcat_pack_values(ctypes.byref(c), r, dv, ctypes.byref(o)), "wildcat_pack_values")

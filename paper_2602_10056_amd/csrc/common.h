@@ -47,6 +47,9 @@ Plan make_plan(const Shape &s);
 // Number of compute units of the current device (queried once per process and device).
 int compute_units();
 
+// Writes the packed half-precision values v_t and their scale v_scale (see wildcat_coreset) from v_s [P, r, dv].
+int enqueue_pack_values(int P, int r, int dv, const float *v_s, void *v_t, float *v_scale, hipStream_t stream);
+
 // ---- storage types ---------------------------------------------------------------------------
 struct bf16_t { uint16_t bits; };
 

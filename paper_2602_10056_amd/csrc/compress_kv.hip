@@ -804,8 +804,7 @@ constexpr int kSolveCols = 8, kPanel = 32;
 __global__ __launch_bounds__(kSolveCols * 32) void k_solve(const double *__restrict__ L,
                                                            const double *__restrict__ Gt,
                                                            const int32_t *__restrict__ r_eff, int r, int dv,
-                                                           float *__restrict__ v_s, float *__restrict__ w,
-                                                           bf16_t *__restrict__ v_t, int r64) {
+                                                           float *__restrict__ v_s, float *__restrict__ w) {
   extern __shared__ double dyn[];
   double *gc = dyn;                                   // [kSolveCols][r]
   double *ld = gc + (size_t)kSolveCols * r;           // [32][33] diagonal block (reciprocals on the diagonal)
@@ -864,12 +863,6 @@ __global__ __launch_bounds__(kSolveCols * 32) void k_solve(const double *__restr
     const float val = j < re ? (float)gc[(size_t)c * r + j] : 0.0f;
     if (c0 + c < dv) v_s[((size_t)pr * r + j) * dv + c0 + c] = val;
     else w[(size_t)pr * r + j] = val;
-  }
-  if (v_t) {                                           // MFMA operand copy: transposed, bf16, zero padded to r64
-    for (int e = t; e < ncol * r64; e += nt) {
-      const int c = e / r64, j = e % r64;
-      if (c0 + c < dv) from_float(j < re ? (float)gc[(size_t)c * r + j] : 0.0f, &v_t[((size_t)pr * dv + c0 + c) * r64 + j]);
-    }
   }
 }
 
@@ -1004,9 +997,12 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
       hipFuncSetAttribute((const void *)k_solve, hipFuncAttributeMaxDynamicSharedMemorySize, (int)solve_lds) != hipSuccess)
     return WILDCAT_EHIP;
   hipLaunchKernelGGL(k_solve, dim3((dv1 + kSolveCols - 1) / kSolveCols, P), dim3(kSolveCols * 32), solve_lds, st, L, Gt,
-                     out->r_eff, s.r, s.dv, out->v_s, out->w,
-                     s.dtype == WILDCAT_BF16 ? (bf16_t *)out->v_t : (bf16_t *)nullptr, (s.r + 63) / 64 * 64);
+                     out->r_eff, s.r, s.dv, out->v_s, out->w);
   LAUNCH_CHECK();
+  if (s.dtype == WILDCAT_BF16 && out->v_t && out->v_scale) {      // MFMA operand form of V_S for WtdAttn
+    const int rc = enqueue_pack_values(P, s.r, s.dv, out->v_s, out->v_t, out->v_scale, st);
+    if (rc != WILDCAT_OK) return rc;
+  }
   hipLaunchKernelGGL((k_gather<T>), dim3(s.r, P), dim3(64), 0, st, K, out->idx, s.n, s.d, s.r, (T *)out->k_s);
   LAUNCH_CHECK();
   return WILDCAT_OK;

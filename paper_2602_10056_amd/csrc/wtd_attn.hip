@@ -6,11 +6,10 @@
 // sign of the normaliser (A w) unchanged, so the max shift does not alter the "> 0" guard.
 //
 // Two kernels:
-//   k_wtd_attn_mfma   bf16 storage.  Works on transposed tiles so that all softmax state of a query
-//                     lives in one lane pair:  S^T = K_S Q^T  and  O^T = V_S^T P^T  with
-//                     v_mfma_f32_32x32x16_bf16.  The normaliser sum_s P_s w_s is accumulated in fp32 on
-//                     the vector ALU from the unrounded P (w may be negative and large).
-//   k_wtd_attn_simple any storage type / width, fp32 arithmetic on the vector ALU (the fp32 path).
+//   k_wtd_attn_mfma2  bf16 storage with packed values (coreset fields v_t, v_scale), d and dv of 64 or 128:
+//                     transposed tiles on v_mfma_f32_32x32x16, pipelined through LDS.
+//   k_wtd_attn_simple any storage type / width, fp32 arithmetic on the vector ALU (the fp32 path, and bf16
+//                     shapes the MFMA kernel does not cover).
 #include <climits>
 #include <cmath>
 
@@ -21,6 +20,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -193,181 +193,25 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 }
 
 // --------------------------------------------------------------------------------------------
-// bf16 MFMA kernel.  Workgroup = NW wavefronts, each owning 32 queries; key tiles of 64.
+// MFMA kernel for bf16 storage (needs the packed half-precision values v_t of the coreset).
 //
-// v_mfma_f32_32x32x16_bf16 operand layout (lane l, g = l / 32):
+// v_mfma_f32_32x32x16_{bf16,f16} operand layout (lane l, g = l / 32):
 //   A (32 x 16): row l % 32, k = 8 g .. 8 g + 7        B (16 x 32): column l % 32, k = 8 g .. 8 g + 7
 //   D (32 x 32): column l % 32, register v holds row 8 (v / 4) + 4 g + (v % 4)
-// S^T tile: rows = keys, columns = queries, so lane l holds 16 key scores of query l % 32 and lane l ^ 32
-// the other 16.  Registers 8h .. 8h+7 of such a tile, converted to bf16, are used directly as the B
-// operand of the value product; the A operand (V_S^T, rows = value columns) is read from LDS with the
-// matching key order {16h + 4g + 0..3, 16h + 8 + 4g + 0..3}.
-// --------------------------------------------------------------------------------------------
-constexpr int kKT = 64;
-
-template <int D, int DV, int NW>
-__global__ __launch_bounds__(NW * kWave) void k_wtd_attn_mfma(
-    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const float *__restrict__ Vs,
-    const float *__restrict__ w, const float *__restrict__ vmin, const float *__restrict__ vmax,
-    const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int64_t m, int r, int q_heads, int group,
-    float scale_log2) {
-  constexpr int KSTR = D + 8;       // bf16 elements per key row in LDS (16-byte pad against bank conflicts)
-  constexpr int VSTR = kKT + 8;     // bf16 elements per value-column row in LDS
-  constexpr int NT = NW * kWave;
-  __shared__ __attribute__((aligned(16))) uint16_t lk[kKT * KSTR];
-  __shared__ __attribute__((aligned(16))) uint16_t lv[DV * VSTR];
-  __shared__ __attribute__((aligned(16))) float lw[kKT];
-
-  const int t = threadIdx.x, wv = t / kWave, l = t % kWave, g = l / 32, c32 = l % 32;
-  const int bh = blockIdx.y, b = bh / q_heads, hq = bh % q_heads;
-  const int pr = b * (q_heads / group) + hq / group;
-  const int64_t q0 = (int64_t)blockIdx.x * (NW * 32) + wv * 32;
-  const int re = r_eff ? min(r_eff[pr], r) : r;
-
-  // Q fragments (B operand of S^T = K Q^T): query c32, features 16 kb + 8 g .. + 7
-  bf16x8 qf[D / 16];
-  {
-    const int64_t row = q0 + c32 < m ? q0 + c32 : m - 1;
-    const uint4 *src = reinterpret_cast<const uint4 *>(Q + ((size_t)bh * m + row) * D + 8 * g);
-#pragma unroll
-    for (int kb = 0; kb < D / 16; ++kb) {
-      const uint4 v = src[2 * kb];
-      qf[kb] = *reinterpret_cast<const bf16x8 *>(&v);
-    }
-  }
-  floatx16 acc[DV / 32];
-#pragma unroll
-  for (int i = 0; i < DV / 32; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
-  float mrun = -INFINITY, den = 0.0f;
-
-  const bf16_t *Kp = Ks + (size_t)pr * r * D;
-  const float *Vp = Vs + (size_t)pr * r * DV;
-  const float *wp = w + (size_t)pr * r;
-
-  for (int k0 = 0; k0 < re; k0 += kKT) {
-    __syncthreads();
-    // ---- stage the key tile [64][D] (16-byte pieces) ------------------------------------------------
-    for (int e = t; e < kKT * (D / 8); e += NT) {
-      const int kk = e / (D / 8), seg = e % (D / 8);
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (k0 + kk < re) v = *reinterpret_cast<const uint4 *>(Kp + (size_t)(k0 + kk) * D + seg * 8);
-      *reinterpret_cast<uint4 *>(&lk[kk * KSTR + seg * 8]) = v;
-    }
-    // ---- stage the value tile transposed, fp32 -> bf16: lv[col][key] -------------------------------------
-    for (int e = t; e < kKT * (DV / 4); e += NT) {
-      const int kk = e / (DV / 4), cs = e % (DV / 4);   // consecutive threads read one value row contiguously
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (k0 + kk < re) v = *reinterpret_cast<const float4 *>(Vp + (size_t)(k0 + kk) * DV + cs * 4);
-      const floatx4 fv = {v.x, v.y, v.z, v.w};
-      const bf16x4 bv = __builtin_convertvector(fv, bf16x4);
-      const uint16_t *bits = reinterpret_cast<const uint16_t *>(&bv);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) lv[(cs * 4 + q) * VSTR + kk] = bits[q];
-    }
-    if (t < kKT) lw[t] = k0 + t < re ? wp[k0 + t] : 0.0f;
-    __syncthreads();
-
-    // ---- S^T = K Q^T for the two 32-key halves ------------------------------------------------------------
-    floatx16 st[2];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) st[mt][v] = 0.0f;
-#pragma unroll
-      for (int kb = 0; kb < D / 16; ++kb) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lk[(32 * mt + c32) * KSTR + 16 * kb + 8 * g]);
-        st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kb], st[mt], 0, 0, 0);
-      }
-    }
-    // ---- online softmax in the log2 domain ----------------------------------------------------------------
-    float mx = -INFINITY;
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = k0 + 32 * mt + 8 * (v / 4) + 4 * g + (v % 4);
-        const float x = key < re ? st[mt][v] * scale_log2 : -INFINITY;
-        st[mt][v] = x;
-        mx = fmaxf(mx, x);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float mnew = fmaxf(mrun, mx);
-    const float alpha = __builtin_amdgcn_exp2f(mrun - mnew);
-    mrun = mnew;
-    float dl = 0.0f;
-    bf16x8 pf[4];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      floatx16 p;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(st[mt][v] - mnew);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 wv4 = *reinterpret_cast<const float4 *>(&lw[32 * mt + 8 * q + 4 * g]);
-        dl = fmaf(p[4 * q + 0], wv4.x, dl);
-        dl = fmaf(p[4 * q + 1], wv4.y, dl);
-        dl = fmaf(p[4 * q + 2], wv4.z, dl);
-        dl = fmaf(p[4 * q + 3], wv4.w, dl);
-      }
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const floatx8 ph = {p[8 * h + 0], p[8 * h + 1], p[8 * h + 2], p[8 * h + 3],
-                            p[8 * h + 4], p[8 * h + 5], p[8 * h + 6], p[8 * h + 7]};
-        pf[2 * mt + h] = __builtin_convertvector(ph, bf16x8);
-      }
-    }
-    den = den * alpha + dl;
-    if (alpha != 1.0f) {
-#pragma unroll
-      for (int i = 0; i < DV / 32; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][v] *= alpha;
-    }
-    // ---- O^T += V_S^T P^T ---------------------------------------------------------------------------------------
-#pragma unroll
-    for (int i = 0; i < DV / 32; ++i) {
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb) {
-        const uint16_t *rowp = &lv[(32 * i + c32) * VSTR + 16 * kb + 4 * g];
-        const uint2 lo = *reinterpret_cast<const uint2 *>(rowp);
-        const uint2 hi = *reinterpret_cast<const uint2 *>(rowp + 8);
-        const uint4 av = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&av), pf[kb], acc[i], 0, 0,
-                                                         0);
-      }
-    }
-  }
-  // ---- epilogue: guard, divide, clip, store ------------------------------------------------------------------
-  den += __shfl_xor(den, 32, kWave);
-  const bool ok = den > 0.0f;
-  const float inv = ok ? 1.0f / den : 0.0f;
-  if (q0 + c32 < m) {
-    bf16_t *orow = out + ((size_t)bh * m + q0 + c32) * DV;
-#pragma unroll
-    for (int i = 0; i < DV / 32; ++i)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int col = 32 * i + 8 * q + 4 * g;
-        const float4 lo = *reinterpret_cast<const float4 *>(vmin + (size_t)pr * DV + col);
-        const float4 hi = *reinterpret_cast<const float4 *>(vmax + (size_t)pr * DV + col);
-        floatx4 o = {acc[i][4 * q + 0] * inv, acc[i][4 * q + 1] * inv, acc[i][4 * q + 2] * inv,
-                     acc[i][4 * q + 3] * inv};
-        if (!ok) o = {0.f, 0.f, 0.f, 0.f};
-        o[0] = fminf(fmaxf(o[0], lo.x), hi.x);
-        o[1] = fminf(fmaxf(o[1], lo.y), hi.y);
-        o[2] = fminf(fmaxf(o[2], lo.z), hi.z);
-        o[3] = fminf(fmaxf(o[3], lo.w), hi.w);
-        const bf16x4 ob = __builtin_convertvector(o, bf16x4);
-        *reinterpret_cast<uint2 *>(orow + col) = *reinterpret_cast<const uint2 *>(&ob);
-      }
-  }
-}
-
-
-// --------------------------------------------------------------------------------------------
-// Pipelined bf16 MFMA kernel (needs the transposed bf16 values v_t of the coreset).
+// The kernel works on transposed tiles so that all softmax state of a query lives in one lane pair:
+// S^T = K_S Q^T (bf16 operands) and O^T = V_S^T P^T.  In an S^T tile rows = keys and columns = queries, so lane l
+// holds 16 key scores of query l % 32 and lane l ^ 32 the other 16.  Registers 8h .. 8h+7 of such a tile, converted
+// to half precision, are used directly as the B operand of the value product; the A operand (V_S^T, rows = value
+// columns) is read from LDS with the matching key order {16h + 4g + 0..3, 16h + 8 + 4g + 0..3}.
+//
+// The value product runs on fp16 operands, not bf16.  Nystrom weights have both signs, so numerator and normaliser
+// of Alg. 3 can be far smaller than the sum of the magnitudes of their terms (hundreds of times for some queries of
+// the long-context workload); operand rounding is relative to the terms, and the 8-bit significand of bf16 then
+// costs several per cent of the output range.  fp16 carries 11 bits at the same MFMA rate.  Its narrow exponent is
+// handled by construction: P lies in (0, 2^8] with the row maximum >= 1 (see below), and v_t stores V_S^T divided
+// by a per-problem power of two (coreset field v_scale) that is multiplied back in the epilogue.  The normaliser
+// sum_s P_s w_s is accumulated in fp32 on the vector ALU from the unrounded P.
+//
 // Workgroup = NW wavefronts, each owning 32 queries; two workgroups (NW = 4) share a compute unit so that one
 // wave's exp/convert work overlaps another's MFMAs.  Key tiles of 64 are double-buffered in LDS and filled
 // with direct global-to-LDS loads (global_load_lds_dwordx4: lane i of a wave writes 16 bytes at base + 16 i),
@@ -380,8 +224,10 @@ __global__ __launch_bounds__(NW * kWave) void k_wtd_attn_mfma(
 // The running maximum is only a reference point for exp(): any reference within 2^8 of the true row maximum
 // keeps every exponential in range, and a change of reference multiplies numerator and normaliser of a row
 // alike.  So the accumulators are rescaled only when a row's maximum has grown by more than 8 (log2 units)
-// since its reference was set -- rare after the first tile -- instead of on every tile.
+// since its reference was set -- rare after the first tile -- instead of on every tile.  The reference is always
+// a maximum the row has already seen, so the largest P of a row is >= 1 and every P is <= 2^8.
 // --------------------------------------------------------------------------------------------
+constexpr int kKT = 64;
 constexpr float kRescaleSlack = 8.0f;
 #ifndef WILDCAT_ATTN_NW
 #define WILDCAT_ATTN_NW 4
@@ -393,8 +239,9 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 // Kernel arguments and per-wave state of the pipelined kernel, passed by reference to the per-tile function.
 template <int D, int DV>
 struct AttnCtx {
-  const bf16_t *Q, *Ks, *Vt;
-  const float *w, *vmin, *vmax;
+  const bf16_t *Q, *Ks;
+  const uint16_t *Vt;         // fp16 bit patterns
+  const float *w, *vmin, *vmax, *vscale;
   const int32_t *r_eff;
   bf16_t *out;
   int64_t m;
@@ -409,6 +256,7 @@ struct AttnCtx {
   bf16x8 qf[D / 16];          // Q fragments: B operand of S^T = K Q^T (query c32, features 16 kb + 8 g .. + 7)
   floatx16 acc[DV / 32];      // O^T accumulators
   float mref, den;            // reference exponent (log2 domain) and normaliser of query c32
+  float vsc, nvsc;            // v_scale of this item's problem and of the next item's
 };
 
 template <int D, int DV, int NW>
@@ -448,7 +296,7 @@ __device__ __forceinline__ void attn_fetch(const AttnCtx<D, DV> &c, int pr, int 
                                            bool with_clip) {
   using G = AttnGeom<D, DV, NW>;
   const bf16_t *Kp = c.Ks + (size_t)pr * c.r * D;
-  const bf16_t *Vp = c.Vt + (size_t)pr * DV * c.r64 + k0;
+  const uint16_t *Vp = c.Vt + (size_t)pr * DV * c.r64 + k0;
 #pragma unroll
   for (int e = 0; e < G::KLOADS; ++e) {
     const bf16_t *src = Kp + min(k0 + c.krow[e], re - 1) * D + c.kcol[e];
@@ -529,7 +377,10 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
   }
   // The Q fragments are dead after the last score product of an item: the next item's are loaded into the same
   // registers now and arrive during the softmax, value product and epilogue of this tile.
-  if (last_tile && more) attn_load_q<D, DV, NW>(c, nitem);
+  if (last_tile && more) {
+    attn_load_q<D, DV, NW>(c, nitem);
+    c.nvsc = c.vscale[npr];
+  }
   if (c.k0 + kKT > c.re) {                                   // ragged last tile: mask the missing keys
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -554,10 +405,11 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
 #pragma unroll
       for (int v = 0; v < 16; ++v) c.acc[i][v] *= alpha;
   }
-  // ---- P = exp2(S c - mref), normaliser, bf16 operand ---------------------------------------------------------
+  // ---- P = exp2(S c - mref), normaliser, fp16 operand (packed conversion, rounds toward zero: the common
+  // relative shortfall of the terms is far below the output rounding, their scatter is that of round-to-nearest) ----
   const float nm = -c.mref;
   float dl = 0.0f;
-  bf16x8 pf[4];
+  f16x8 pf[4];
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
     floatx16 p;
@@ -573,9 +425,13 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const floatx8 ph = {p[8 * h + 0], p[8 * h + 1], p[8 * h + 2], p[8 * h + 3],
-                          p[8 * h + 4], p[8 * h + 5], p[8 * h + 6], p[8 * h + 7]};
-      pf[2 * mt + h] = __builtin_convertvector(ph, bf16x8);
+      const auto h0 = __builtin_amdgcn_cvt_pkrtz(p[8 * h + 0], p[8 * h + 1]);
+      const auto h1 = __builtin_amdgcn_cvt_pkrtz(p[8 * h + 2], p[8 * h + 3]);
+      const auto h2 = __builtin_amdgcn_cvt_pkrtz(p[8 * h + 4], p[8 * h + 5]);
+      const auto h3 = __builtin_amdgcn_cvt_pkrtz(p[8 * h + 6], p[8 * h + 7]);
+      const uint4 hb = make_uint4(*reinterpret_cast<const uint32_t *>(&h0), *reinterpret_cast<const uint32_t *>(&h1),
+                                  *reinterpret_cast<const uint32_t *>(&h2), *reinterpret_cast<const uint32_t *>(&h3));
+      pf[2 * mt + h] = *reinterpret_cast<const f16x8 *>(&hb);
     }
   }
   c.den += dl;
@@ -588,15 +444,15 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
       const uint2 lo = *reinterpret_cast<const uint2 *>(rowp + ((2 * kb) ^ c.vrow_sw) * 8);
       const uint2 hi = *reinterpret_cast<const uint2 *>(rowp + ((2 * kb + 1) ^ c.vrow_sw) * 8);
       const uint4 av = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      c.acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&av), pf[kb], c.acc[i], 0,
-                                                         0, 0);
+      c.acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const f16x8 *>(&av), pf[kb], c.acc[i], 0, 0,
+                                                        0);
     }
   }
   if (last_tile) {
     // ---- epilogue of the item: guard, divide, clip, store; then start the next item --------------------------------
     const float dn = c.den + __shfl_xor(c.den, 32, kWave);
     const bool ok = dn > 0.0f;
-    const float inv = ok ? 1.0f / dn : 0.0f;
+    const float inv = ok ? c.vsc / dn : 0.0f;               // v_t holds V_S^T / v_scale
     const int bh = c.item / c.qtiles;
     const int64_t qrow = (int64_t)(c.item % c.qtiles) * (NW * 32) + c.wv * 32 + c32;
     if (qrow < c.m) {
@@ -627,6 +483,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
       for (int v = 0; v < 16; ++v) c.acc[i][v] = 0.0f;
     c.mref = -INFINITY;
     c.den = 0.0f;
+    c.vsc = c.nvsc;
   }
   __builtin_amdgcn_s_waitcnt(0);       // this wave's share of the next tile (and the next Q fragments) has arrived
   __syncthreads();
@@ -636,16 +493,16 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
 
 template <int D, int DV, int NW>
 __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
-    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const bf16_t *__restrict__ Vt,
-    const float *__restrict__ w, const float *__restrict__ vmin, const float *__restrict__ vmax,
-    const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int64_t m, int r, int r64, int q_heads, int group,
-    int qtiles, int total_items, float scale_log2) {
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const uint16_t *__restrict__ Vt,
+    const float *__restrict__ vscale, const float *__restrict__ w, const float *__restrict__ vmin,
+    const float *__restrict__ vmax, const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int64_t m, int r,
+    int r64, int q_heads, int group, int qtiles, int total_items, float scale_log2) {
   using G = AttnGeom<D, DV, NW>;
   __shared__ __attribute__((aligned(16))) char buf0[G::BYTES];
   __shared__ __attribute__((aligned(16))) char buf1[G::BYTES];
 
   AttnCtx<D, DV> c;
-  c.Q = Q; c.Ks = Ks; c.Vt = Vt; c.w = w; c.vmin = vmin; c.vmax = vmax; c.r_eff = r_eff; c.out = out;
+  c.Q = Q; c.Ks = Ks; c.Vt = Vt; c.vscale = vscale; c.w = w; c.vmin = vmin; c.vmax = vmax; c.r_eff = r_eff; c.out = out;
   c.m = m; c.r = r; c.r64 = r64; c.q_heads = q_heads; c.group = group; c.kv_heads = q_heads / group;
   c.qtiles = qtiles; c.total_items = total_items; c.stride = (int)gridDim.x; c.scale_log2 = scale_log2;
   const int t = threadIdx.x;
@@ -678,20 +535,57 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
     for (int v = 0; v < 16; ++v) c.acc[i][v] = 0.0f;
   c.mref = -INFINITY;
   c.den = 0.0f;
+  c.vsc = c.nvsc = vscale[c.pr];
   __builtin_amdgcn_s_waitcnt(0);           // tile 0 and the Q fragments have arrived
   __syncthreads();
   while (attn_tile<D, DV, NW>(c, buf0, buf1) && attn_tile<D, DV, NW>(c, buf1, buf0)) {
   }
 }
 
-// v_t[pr][c][j] = bf16(v_s[pr][j][c]) for j < r, zero for r <= j < r64.  grid (ceil(r64*dv/256), P).
-__global__ __launch_bounds__(kThreads) void k_pack_values(const float *__restrict__ v_s, int r, int r64, int dv,
-                                                          bf16_t *__restrict__ v_t) {
+// ---- packed values: v_t[pr][c][j] = fp16(v_s[pr][j][c] / v_scale[pr]) for j < r, zero for r <= j < r64 -----------
+// v_scale[pr] = 2^(e - 14) with e the exponent of max |v_s[pr]|: the largest packed magnitude lies in [2^14, 2^15),
+// inside fp16's range with the full significand for everything within 2^-28 of it.  Four small launches:
+// clear, maximum (as a bit pattern, integer atomic: exact and order independent), pack, maximum -> scale.
+__global__ void k_zero_u32(uint32_t *x, int count) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) x[i] = 0u;
+}
+
+__global__ __launch_bounds__(kThreads) void k_vabs_max(const float *__restrict__ v_s, int count, uint32_t *vmax_bits) {
+  __shared__ uint32_t sm[kThreads / kWave];
+  const int pr = blockIdx.y;
+  const int gid = blockIdx.x * kThreads + threadIdx.x;
+  uint32_t b = 0u;
+  if (gid < count) {
+    b = __float_as_uint(v_s[(size_t)pr * count + gid]) & 0x7fffffffu;
+    if (b > 0x7f800000u) b = 0u;                            // NaN: ignored
+  }
+  b = block_reduce<uint32_t>(b, sm, MaxOp());
+  if (threadIdx.x == 0) atomicMax(&vmax_bits[pr], b);
+}
+
+__device__ __forceinline__ float value_scale(uint32_t max_bits) {
+  const int e = (int)(max_bits >> 23);                      // biased exponent of the maximum
+  if (e == 0 || e == 255) return 1.0f;                      // zero / subnormal / infinite maximum: no scaling
+  const int se = min(max(e - 14, 1), 254);
+  return __uint_as_float((uint32_t)se << 23);
+}
+
+__global__ __launch_bounds__(kThreads) void k_pack_values(const float *__restrict__ v_s,
+                                                          const uint32_t *__restrict__ vmax_bits, int r, int r64,
+                                                          int dv, uint16_t *__restrict__ v_t) {
   const int pr = blockIdx.y;
   const int gid = blockIdx.x * kThreads + threadIdx.x;
   if (gid >= r64 * dv) return;
   const int c = gid / r64, j = gid % r64;
-  from_float(j < r ? v_s[((size_t)pr * r + j) * dv + c] : 0.0f, &v_t[((size_t)pr * dv + c) * r64 + j]);
+  const float inv = 1.0f / value_scale(vmax_bits[pr]);      // exact: a power of two
+  const _Float16 h = (_Float16)(j < r ? v_s[((size_t)pr * r + j) * dv + c] * inv : 0.0f);   // round to nearest even
+  v_t[((size_t)pr * dv + c) * r64 + j] = *reinterpret_cast<const uint16_t *>(&h);
+}
+
+__global__ void k_finish_scale(uint32_t *vmax_bits, int count) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) vmax_bits[i] = __float_as_uint(value_scale(vmax_bits[i]));
 }
 
 template <int D, int DV>
@@ -704,19 +598,9 @@ int launch_mfma2(const Shape &s, const void *Q, const wildcat_coreset *cs, void 
   const int64_t resident = (int64_t)compute_units() * (8 / NW);     // workgroups that fit on the device at once
   const unsigned grid = (unsigned)(total < resident ? total : resident);
   hipLaunchKernelGGL((k_wtd_attn_mfma2<D, DV, NW>), dim3(grid), dim3(NW * 64), 0, s.stream, (const bf16_t *)Q,
-                     (const bf16_t *)cs->k_s, (const bf16_t *)cs->v_t, cs->w, cs->v_min, cs->v_max, cs->r_eff,
+                     (const bf16_t *)cs->k_s, (const uint16_t *)cs->v_t, cs->v_scale, cs->w, cs->v_min, cs->v_max, cs->r_eff,
                      (bf16_t *)out, s.m, s.r, r64, s.q_heads, s.group, (int)qtiles, (int)total,
                      (float)(s.beta * (double)kLog2e));
-  return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
-}
-
-template <int D, int DV>
-int launch_mfma(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
-  constexpr int NW = 4;
-  const dim3 grid((unsigned)((s.m + NW * 32 - 1) / (NW * 32)), s.batch * s.q_heads);
-  hipLaunchKernelGGL((k_wtd_attn_mfma<D, DV, NW>), grid, dim3(NW * kWave), 0, s.stream, (const bf16_t *)Q,
-                     (const bf16_t *)cs->k_s, cs->v_s, cs->w, cs->v_min, cs->v_max, cs->r_eff, (bf16_t *)out, s.m, s.r,
-                     s.q_heads, s.group, (float)(s.beta * (double)kLog2e));
   return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
 }
 
@@ -731,6 +615,19 @@ int launch_simple(const Shape &s, const void *Q, const wildcat_coreset *cs, void
 }
 
 }  // namespace
+
+int enqueue_pack_values(int P, int r, int dv, const float *v_s, void *v_t, float *v_scale, hipStream_t stream) {
+  const int r64 = (r + 63) / 64 * 64;
+  uint32_t *bits = reinterpret_cast<uint32_t *>(v_scale);
+  hipLaunchKernelGGL(k_zero_u32, dim3((P + 255) / 256), dim3(256), 0, stream, bits, P);
+  hipLaunchKernelGGL(k_vabs_max, dim3((r * dv + kThreads - 1) / kThreads, P), dim3(kThreads), 0, stream, v_s, r * dv,
+                     bits);
+  hipLaunchKernelGGL(k_pack_values, dim3((r64 * dv + kThreads - 1) / kThreads, P), dim3(kThreads), 0, stream, v_s,
+                     (const uint32_t *)bits, r, r64, dv, (uint16_t *)v_t);
+  hipLaunchKernelGGL(k_finish_scale, dim3((P + 255) / 256), dim3(256), 0, stream, bits, P);
+  return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
+}
+
 }  // namespace wildcat
 
 using namespace wildcat;
@@ -778,27 +675,22 @@ extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *
   int rc = resolve_shape(r, m, d, r, opts, &s);
   if (rc != WILDCAT_OK) return rc;
   if (s.dtype == WILDCAT_BF16) {
-    if (cs->v_t) {
+    if (cs->v_t && cs->v_scale) {
       if (s.d == 64 && s.dv == 64) return launch_mfma2<64, 64>(s, Q, cs, out);
       if (s.d == 128 && s.dv == 128) return launch_mfma2<128, 128>(s, Q, cs, out);
+      if (s.d == 64 && s.dv == 128) return launch_mfma2<64, 128>(s, Q, cs, out);
+      if (s.d == 128 && s.dv == 64) return launch_mfma2<128, 64>(s, Q, cs, out);
     }
-    if (s.d == 64 && s.dv == 64) return launch_mfma<64, 64>(s, Q, cs, out);
-    if (s.d == 128 && s.dv == 128) return launch_mfma<128, 128>(s, Q, cs, out);
-    if (s.d == 64 && s.dv == 128) return launch_mfma<64, 128>(s, Q, cs, out);
-    if (s.d == 64 && s.dv == 256) return launch_mfma<64, 256>(s, Q, cs, out);
     return launch_simple<bf16_t>(s, Q, cs, out);
   }
   return launch_simple<float>(s, Q, cs, out);
 }
 
 extern "C" int wildcat_pack_values(const wildcat_coreset *cs, int32_t r, int32_t dv, const wildcat_opts *opts) {
-  if (!cs || !cs->v_s || !cs->v_t || r < 1 || dv < 1) return WILDCAT_EINVAL;
+  if (!cs || !cs->v_s || !cs->v_t || !cs->v_scale || r < 1 || dv < 1) return WILDCAT_EINVAL;
   Shape s;
   int rc = resolve_shape(r, 0, dv, r, opts, &s);
   if (rc != WILDCAT_OK) return rc;
   if (s.dtype != WILDCAT_BF16) return WILDCAT_EINVAL;
-  const int r64 = (r + 63) / 64 * 64;
-  hipLaunchKernelGGL(k_pack_values, dim3((r64 * dv + kThreads - 1) / kThreads, s.P), dim3(kThreads), 0, s.stream,
-                     cs->v_s, r, r64, dv, (bf16_t *)cs->v_t);
-  return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
+  return enqueue_pack_values(s.P, r, dv, cs->v_s, cs->v_t, cs->v_scale, s.stream);
 }

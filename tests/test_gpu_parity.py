@@ -127,6 +127,7 @@ def test_seed_path_draws_the_documented_uniforms():
 # ---------------------------------------------------------------------------------- WtdAttn alone
 @pytest.mark.parametrize("dtype,n,m,d,dv", [("f32", 300, 77, 64, 64), ("bf16", 1000, 333, 64, 64),
                                             ("bf16", 513, 129, 128, 128), ("bf16", 96, 40, 64, 128),
+                                            ("bf16", 260, 300, 128, 64),
                                             ("bf16", 200, 50, 64, 256), ("bf16", 70, 33, 48, 80),
                                             ("f32", 130, 20, 40, 72)])
 def test_wtd_attn_all_keys_unit_weights_is_exact_attention(dtype, n, m, d, dv):
@@ -140,11 +141,15 @@ def test_wtd_attn_all_keys_unit_weights_is_exact_attention(dtype, n, m, d, dv):
     cs = wc.Coreset(idx=torch.zeros((1, 2, n), dtype=torch.int32, device=dev()), r_eff=None,
                     k_s=to_dev(K, dtype), v_s=to_dev(V, "f32"), w=torch.ones((1, 2, n), device=dev()),
                     v_min=to_dev(V.min(axis=2), "f32"), v_max=to_dev(V.max(axis=2), "f32"), tau=None)
-    out = wc.wtd_attn(to_dev(Q, dtype), cs).float().cpu().numpy()
-    for h in range(2):
-        ref = wo.exact_attention(Q[0, h].astype(np.float64), K[0, h].astype(np.float64), V[0, h].astype(np.float64),
-                                 beta)
-        assert relmax(out[0, h], ref) <= TOL_OUT[dtype]
+    refs = [wo.exact_attention(Q[0, h].astype(np.float64), K[0, h].astype(np.float64), V[0, h].astype(np.float64),
+                               beta) for h in range(2)]
+    # without packed values (vector-ALU kernel), then -- bf16 storage -- with them (MFMA kernel where it applies)
+    for packed in ([False, True] if dtype == "bf16" else [False]):
+        if packed:
+            wc.pack_values(cs)
+        out = wc.wtd_attn(to_dev(Q, dtype), cs).float().cpu().numpy()
+        for h in range(2):
+            assert relmax(out[0, h], refs[h]) <= TOL_OUT[dtype], packed
 
 
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64), ("bf16", 128)])
@@ -163,6 +168,8 @@ def test_wtd_attn_guard_clip_and_oracle_coreset(dtype, d):
     cs = wc.Coreset(idx=torch.zeros((1, 1, r), dtype=torch.int32, device=dev()), r_eff=None, k_s=to_dev(KS, dtype),
                     v_s=to_dev(VS, "f32"), w=to_dev(wts, "f32"), v_min=to_dev(vmin, "f32"), v_max=to_dev(vmax, "f32"),
                     tau=None)
+    if dtype == "bf16":
+        wc.pack_values(cs)                                        # the MFMA kernel needs the packed values
     beta = 1.0 / np.sqrt(d)
     out = wc.wtd_attn(to_dev(Q, dtype), cs).float().cpu().numpy()[0, 0]
     ref = wo.wtd_attn(Q[0, 0].astype(np.float64), KS[0, 0].astype(np.float64), VS[0, 0].astype(np.float64),
@@ -309,14 +316,46 @@ def test_rank_exhaustion_per_step_driver(monkeypatch):
 def test_pack_values_matches_compress_output():
     w = wl.make(2, batch=1, q_heads=2, kv_heads=2, n=1024, r=100)
     out, cs = run_gpu(w)
-    ref = cs.v_t.clone()
+    ref, ref_scale = cs.v_t.clone(), cs.v_scale.clone()
     cs.v_t.zero_()
+    cs.v_scale.zero_()
     wc.pack_values(cs)
-    assert torch.equal(cs.v_t, ref)
+    assert torch.equal(cs.v_t, ref) and torch.equal(cs.v_scale, ref_scale)
     r64 = cs.v_t.shape[-1]
     assert r64 == 128 and torch.all(cs.v_t[..., 100:] == 0)
-    np.testing.assert_array_equal(cs.v_t[..., :100].float().cpu().numpy(),
-                                  cs.v_s.to(torch.bfloat16).float().transpose(-1, -2).cpu().numpy())
+    # v_scale = 2^(e - 14), e the exponent of the largest |v_s| of the problem; v_t = fp16(v_s^T / v_scale)
+    vmax = cs.v_s.abs().amax(dim=(-1, -2)).double()
+    want_scale = torch.exp2(torch.floor(torch.log2(vmax)) - 14).float()
+    assert torch.equal(cs.v_scale, want_scale)
+    want = (cs.v_s / want_scale[..., None, None]).to(torch.float16).transpose(-1, -2)
+    assert torch.equal(cs.v_t[..., :100], want)
+    assert float(cs.v_t.float().abs().amax()) < 2.0 ** 15
+
+
+def test_pack_values_extreme_magnitudes():
+    """Hand-made coresets whose values are far outside fp16's range on either side: the per-problem power-of-two
+    scale brings them back, and WtdAttn with unit weights is exact attention over the coreset rows."""
+    rng = np.random.default_rng(7)
+    r, d, m = 96, 64, 200
+    for mag in (1e-20, 3e7):
+        Kc = wl.round_to_storage(rng.standard_normal((r, d)), "bf16")
+        Vc = (rng.standard_normal((r, d)) * mag).astype(np.float32)
+        Qc = wl.round_to_storage(rng.standard_normal((m, d)), "bf16")
+        dev = "cuda:0"
+        cs = wc.Coreset(
+            idx=torch.zeros((1, 1, r), dtype=torch.int32, device=dev), r_eff=None,
+            k_s=torch.from_numpy(Kc).to(dev).to(torch.bfloat16)[None, None].contiguous(),
+            v_s=torch.from_numpy(Vc).to(dev)[None, None].contiguous(),
+            w=torch.ones((1, 1, r), dtype=torch.float32, device=dev),
+            v_min=torch.from_numpy(Vc.min(0)).to(dev)[None, None].contiguous(),
+            v_max=torch.from_numpy(Vc.max(0)).to(dev)[None, None].contiguous(), tau=None)
+        wc.pack_values(cs)
+        out = wc.wtd_attn(torch.from_numpy(Qc).to(dev).to(torch.bfloat16)[None, None].contiguous(), cs)
+        torch.cuda.synchronize()
+        ref = wo.exact_attention(Qc.astype(np.float64), Kc.astype(np.float64), Vc.astype(np.float64),
+                                     1.0 / np.sqrt(d))
+        err = np.abs(out[0, 0].float().cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max()
+        assert err < 2e-2, (mag, err)
 
 
 def test_full_size_config5_long_context():
