@@ -22,7 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense MFMA rate, the same for bf16 and fp16 operands
 
 
 class HipEvents:
@@ -178,7 +178,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{s.name}: batch {s.batch} x {s.q_heads} query heads / {s.kv_heads} kv heads, "
                                f"n=m={s.n}, d={s.d}, r={s.r}, B=1, {s.dtype} storage; selection loop in fp64, "
-                               f"WtdAttn on bf16 MFMA with fp32 accumulation",
+                               f"WtdAttn on MFMA (bf16 scores, fp16 value product) with fp32 accumulation",
                    "uniform_seed": s.uniform_seed, "data_seed": s.data_seed},
         "phases_ms": {"query_radius": float(ph[0]), "compress_kv": float(ph[1]), "rpnys_loop": loop_ms,
                       "wtd_attn": float(ph[2])},
