@@ -19,7 +19,7 @@ and Practice"):
                     "Optimal choice of rho"
   rpnys             Alg. 1 (RPNys), Sec. 2.3, with the inverse update of the
                     Proposition "Recursive update of kernel inverse"
-  compress_kv       Alg. 2 (CompressKV) with B = 1
+  compress_kv       Alg. 2 (CompressKV), any number of bins B (Sec. 2.5)
   wtd_attn          Alg. 3 (WtdAttn)
   wildcat           Alg. 4 (WildCat)
   splitmix_uniforms the counter-based uniform generator that stands in for the
@@ -35,7 +35,9 @@ exactness at full rank and at the kernel rank; per-step invariants of Alg. 1
 H_S)); monotone residual; exact one-step expectation identity; chi-square of
 pivot frequencies; shift invariance and prefix property; rho_0 ~ 3.19 and the
 constants the paper prints; Lemma 1, Lemma 2 and the trivial value-range bound;
-Theorem 1 by Monte Carlo; guard/clip behaviour.
+Theorem 1 by Monte Carlo; guard/clip behaviour; binning: bins with a common
+mean equal separate one-bin runs, W is the block-diagonal solve, per-bin
+low-rank keys reproduce exact attention, temperature length switch.
 Parity unpinned: absolute values of O-hat, S or W on any of the paper's own
 workloads (the paper prints none).
 """
@@ -243,52 +245,85 @@ def rpnys(Kc, beta_tau, r, u, rank_tol=1e-10, keep_p_trace=False):
 
 
 # ----------------------------------------------------------------------------
-# Alg. 2: CompressKV (B = 1)
+# Alg. 2: CompressKV
 # ----------------------------------------------------------------------------
 @dataclass
 class Coreset:
-    idx: np.ndarray      # [r] pivot indices, -1 in unused slots
-    r_eff: int
+    idx: np.ndarray      # [r] pivot indices into the n keys, -1 in unused slots
+    r_eff: int           # pivots drawn, all bins together
     K_S: np.ndarray      # [r, d]   original (un-recentred) key rows
     V_S: np.ndarray      # [r, d_v] W V
     w: np.ndarray        # [r]      W 1
-    tau: float
+    tau: float           # B = 1: the temperature; B > 1: that of the first bin (see taus)
     beta_tau: float
     kbar: np.ndarray
     R_K: float
-    rp: RpnysResult
+    rp: RpnysResult      # Alg. 1 result of the first (for B = 1: the only) bin
+    taus: np.ndarray = None      # [B] temperature of each bin
+    R_Ks: np.ndarray = None      # [B] key radius of each bin
+    r_effs: np.ndarray = None    # [B] pivots drawn in each bin
+    rps: list = None             # [B] Alg. 1 results, pivot indices local to the bin
 
 
-def compress_kv(K, V, R_Q, beta, r, u, rank_tol=1e-10, keep_p_trace=False):
-    """Alg. 2 with one bin: recentre the keys by their row mean, take R_K as
-    the largest recentred row norm, tau from eq. (kernel-temperature), run
-    Alg. 1 on the recentred keys with kernel exp(beta <.,.> / tau^2), return
-    the original key rows at the pivots (recentred rows plus the mean),
-    V_S = W V and w = W 1.
+def compress_kv(K, V, R_Q, beta, r, u, rank_tol=1e-10, keep_p_trace=False, bins=1,
+                temperature_n="bin"):
+    """Alg. 2: recentre the keys by their row mean (over all n keys), divide the
+    rows into B bins, and for each bin take R_K as the largest recentred row
+    norm of the bin, tau from eq. (kernel-temperature), and run Alg. 1 on the
+    bin's recentred keys with kernel exp(beta <.,.> / tau^2) for r/B pivots.
+    The bins' results are concatenated in bin order: slots b r/B .. (b+1) r/B - 1
+    belong to bin b.  Returns the original key rows at the pivots (recentred
+    rows plus the mean), V_S = W V and w = W 1.
 
-    Unused slots (rank exhaustion) carry idx = -1 and zero key, value and
-    weight, so they add nothing to either sum of Alg. 3.
+    Readings (the paper's text leaves these open):
+      * "Evenly divide (or reshape)": bin b holds the contiguous rows
+        b n/B .. (b+1) n/B - 1; B must divide n and r.
+      * W = (W^b)_b: Alg. 1 on bin b returns Nystrom weights over that bin's
+        keys only, so W is block diagonal and rows b r/B.. of V_S are W^b V^b.
+      * The length passed to getTemperature inside the bin loop is written "n";
+        Thm. 2 states its guarantee for B > 1 with n/B in place of n, so the
+        default (temperature_n="bin") is the bin length; "full" uses n.
+      * Step i of bin b consumes uniform u[b r/B + i].
+
+    Unused slots (rank exhaustion in a bin) carry idx = -1 and zero key, value
+    and weight, so they add nothing to either sum of Alg. 3.
     """
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
+    u = np.asarray(u, dtype=np.float64)
     n, d = K.shape
+    B = int(bins)
+    if B < 1 or n % B or r % B:
+        raise ValueError("bins must divide n and r")
+    if temperature_n not in ("bin", "full"):
+        raise ValueError("temperature_n is 'bin' or 'full'")
+    nb, rb = n // B, r // B
     kbar = K.mean(axis=0)
     Kc = K - kbar
-    R_K = float(np.sqrt(np.einsum("ld,ld->l", Kc, Kc).max()))
-    tau, _, _ = temperature(beta, R_Q, R_K, n)
-    beta_tau = beta / (tau * tau) if math.isfinite(tau) else 0.0
-    rp = rpnys(Kc, beta_tau, r, u, rank_tol=rank_tol, keep_p_trace=keep_p_trace)
-    k = len(rp.S)
     idx = np.full(r, -1, dtype=np.int64)
-    idx[:k] = rp.S
     K_S = np.zeros((r, d))
-    K_S[:k] = K[rp.S]                       # == Kc[S] + kbar, without rounding
     V_S = np.zeros((r, V.shape[1]))
-    V_S[:k] = rp.W @ V
     w = np.zeros(r)
-    w[:k] = rp.W.sum(axis=1)
-    return Coreset(idx=idx, r_eff=k, K_S=K_S, V_S=V_S, w=w, tau=tau,
-                   beta_tau=beta_tau, kbar=kbar, R_K=R_K, rp=rp)
+    taus, R_Ks, r_effs, rps, beta_taus = np.zeros(B), np.zeros(B), np.zeros(B, dtype=np.int64), [], []
+    for b in range(B):
+        rows = slice(b * nb, (b + 1) * nb)
+        Kb = Kc[rows]
+        R_K = float(np.sqrt(np.einsum("ld,ld->l", Kb, Kb).max()))
+        tau, _, _ = temperature(beta, R_Q, R_K, nb if temperature_n == "bin" else n)
+        beta_tau = beta / (tau * tau) if math.isfinite(tau) else 0.0
+        rp = rpnys(Kb, beta_tau, rb, u[b * rb:(b + 1) * rb], rank_tol=rank_tol, keep_p_trace=keep_p_trace)
+        k = len(rp.S)
+        slots = slice(b * rb, b * rb + k)
+        idx[slots] = b * nb + rp.S
+        K_S[slots] = K[b * nb + rp.S]           # == Kc[S] + kbar, without rounding
+        V_S[slots] = rp.W @ V[rows]
+        w[slots] = rp.W.sum(axis=1)
+        taus[b], R_Ks[b], r_effs[b] = tau, R_K, k
+        rps.append(rp)
+        beta_taus.append(beta_tau)
+    return Coreset(idx=idx, r_eff=int(r_effs.sum()), K_S=K_S, V_S=V_S, w=w, tau=float(taus[0]),
+                   beta_tau=beta_taus[0], kbar=kbar, R_K=float(R_Ks[0]), rp=rps[0],
+                   taus=taus, R_Ks=R_Ks, r_effs=r_effs, rps=rps)
 
 
 # ----------------------------------------------------------------------------
@@ -324,7 +359,7 @@ def wtd_attn(Q, K_S, V_S, w, v_min, v_max, beta, chunk=4096):
 # ----------------------------------------------------------------------------
 # Alg. 4: WildCat
 # ----------------------------------------------------------------------------
-def wildcat(Q, K, V, beta, r, u, rank_tol=1e-10, return_coreset=False):
+def wildcat(Q, K, V, beta, r, u, rank_tol=1e-10, return_coreset=False, bins=1, temperature_n="bin"):
     """Alg. 4: column-wise value range, query radius R_Q = max row norm of Q,
     CompressKV, WtdAttn.
 
@@ -339,7 +374,7 @@ def wildcat(Q, K, V, beta, r, u, rank_tol=1e-10, return_coreset=False):
     v_max = V.max(axis=0)
     Q3 = Q if Q.ndim == 3 else Q[None]
     R_Q = float(np.sqrt(np.einsum("hmd,hmd->hm", Q3, Q3).max()))
-    cs = compress_kv(K, V, R_Q, beta, r, u, rank_tol=rank_tol)
+    cs = compress_kv(K, V, R_Q, beta, r, u, rank_tol=rank_tol, bins=bins, temperature_n=temperature_n)
     outs = np.stack([wtd_attn(q, cs.K_S, cs.V_S, cs.w, v_min, v_max, beta) for q in Q3])
     out = outs if Q.ndim == 3 else outs[0]
     if return_coreset:

@@ -445,3 +445,115 @@ def test_theorem1_monte_carlo():
         E = H - H[:, res.S] @ res.W
         errs.append(np.linalg.norm(0.5 * (E + E.T), 2))
     assert np.mean(errs) <= eps
+
+
+# ---------------------------------------------------------------- Alg. 2 with bins (Sec. 2.5)
+def _equal_mean_bins(rng, B, nb, d, scale=0.6):
+    """Keys whose B contiguous bins all have the same row mean c (so the global mean of Alg. 2 is every bin's own)."""
+    c = rng.standard_normal(d) * 0.3
+    blocks = []
+    for _ in range(B):
+        X = rng.standard_normal((nb, d)) * scale * rng.uniform(0.5, 1.5)
+        blocks.append(X - X.mean(axis=0) + c)
+    return np.concatenate(blocks)
+
+
+def test_binned_compress_equals_separate_one_bin_runs_when_bins_share_their_mean():
+    """If every bin has the global mean, the bin loop of Alg. 2 is B independent one-bin CompressKV calls on
+    (K^b, V^b) with r/B pivots each, fed the matching slice of the uniforms, and the results are concatenated with
+    the pivot indices offset by b n/B.  Catches wrong slicing of keys, values or uniforms, a wrong index offset and
+    a temperature computed from the wrong length."""
+    rng = np.random.default_rng(21)
+    B, nb, d, dv, rb, beta, RQ = 4, 60, 5, 3, 6, 0.45, 2.2
+    K = _equal_mean_bins(rng, B, nb, d)
+    V = rng.standard_normal((B * nb, dv))
+    u = rng.uniform(size=B * rb)
+    cs = wo.compress_kv(K, V, RQ, beta, B * rb, u, bins=B)
+    assert cs.r_eff == B * rb and list(cs.r_effs) == [rb] * B
+    for b in range(B):
+        one = wo.compress_kv(K[b * nb:(b + 1) * nb], V[b * nb:(b + 1) * nb], RQ, beta, rb, u[b * rb:(b + 1) * rb])
+        sl = slice(b * rb, (b + 1) * rb)
+        np.testing.assert_array_equal(cs.idx[sl], one.idx + b * nb)
+        np.testing.assert_allclose(cs.taus[b], one.tau, rtol=1e-12)
+        np.testing.assert_allclose(cs.K_S[sl], one.K_S, rtol=0, atol=0)
+        np.testing.assert_allclose(cs.V_S[sl], one.V_S, rtol=1e-7, atol=1e-9)
+        np.testing.assert_allclose(cs.w[sl], one.w, rtol=1e-7, atol=1e-9)
+    # bins really differ (different radii -> different temperatures), so a shared tau would have been caught
+    assert np.ptp(cs.taus) > 1e-3
+
+
+def test_binned_weights_are_the_block_diagonal_nystrom_solve():
+    """W = diag(W^1..W^B) with W^b = h_tau_b(S_b, S_b)^-1 h_tau_b(S_b, K^b) on the globally recentred keys: V_S and w
+    recomputed with a dense r x n matrix W assembled from library solves."""
+    rng = np.random.default_rng(22)
+    B, nb, d, dv, rb, beta, RQ = 3, 50, 4, 6, 5, 0.5, 1.7
+    n, r = B * nb, B * rb
+    K = rng.standard_normal((n, d)) * 0.7 + rng.standard_normal(d)      # bins do NOT share their mean here
+    V = rng.standard_normal((n, dv))
+    u = rng.uniform(size=r)
+    cs = wo.compress_kv(K, V, RQ, beta, r, u, bins=B)
+    Kc = K - K.mean(axis=0)
+    W = np.zeros((r, n))
+    for b in range(B):
+        rows = np.arange(b * nb, (b + 1) * nb)
+        S = cs.idx[b * rb:(b + 1) * rb]
+        assert np.all((S >= b * nb) & (S < (b + 1) * nb)) and len(set(S)) == rb
+        RK = np.sqrt((Kc[rows] ** 2).sum(1).max())
+        tau = wo.temperature(beta, RQ, RK, nb)[0]
+        np.testing.assert_allclose(cs.taus[b], tau, rtol=1e-13)
+        bt = beta / tau ** 2
+        W[b * rb:(b + 1) * rb, rows] = np.linalg.solve(_kernel(Kc[S], Kc[S], bt), _kernel(Kc[S], Kc[rows], bt))
+    np.testing.assert_allclose(cs.V_S, W @ V, rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(cs.w, W.sum(axis=1), rtol=1e-6, atol=1e-8)
+    np.testing.assert_array_equal(cs.K_S, K[cs.idx])
+
+
+def test_binned_wildcat_is_exact_when_every_bin_has_low_kernel_rank():
+    """Each bin's keys take only q <= r/B distinct values: Nystrom is exact within each bin whatever the
+    temperature, hence A-hat = A column by column and Alg. 4 returns exact attention over all n keys.  Fails if the
+    bins' weights were mixed up, normalised jointly, or if slots of one bin picked up values of another."""
+    rng = np.random.default_rng(23)
+    B, nb, d, dv, q, rb, beta = 4, 40, 6, 5, 3, 4, 0.4
+    n = B * nb
+    K = np.concatenate([rng.standard_normal((q, d))[rng.integers(0, q, nb)] for _ in range(B)])
+    V = rng.standard_normal((n, dv))
+    Q = rng.standard_normal((17, d))
+    out, cs, _ = wo.wildcat(Q, K, V, beta, B * rb, rng.uniform(size=B * rb), return_coreset=True, bins=B)
+    assert np.all(cs.r_effs <= q) and cs.r_eff == cs.r_effs.sum() and np.all(cs.r_effs >= 1)
+    for b in range(B):                                  # exhausted bins leave empty slots behind their pivots
+        k = cs.r_effs[b]
+        assert np.all(cs.idx[b * rb + k:(b + 1) * rb] == -1) and np.all(cs.w[b * rb + k:(b + 1) * rb] == 0)
+    np.testing.assert_allclose(out, wo.exact_attention(Q, K, V, beta), rtol=1e-6, atol=1e-8)
+
+
+def test_binned_all_keys_selected_gives_identity_weights():
+    """r/B = n/B: every key of every bin is a pivot, W is a permutation matrix and w = 1."""
+    rng = np.random.default_rng(24)
+    B, nb, d = 3, 7, 4
+    n = B * nb
+    K, V = rng.standard_normal((n, d)), rng.standard_normal((n, 2))
+    cs = wo.compress_kv(K, V, 1.5, 0.5, n, rng.uniform(size=n), bins=B)
+    assert sorted(cs.idx) == list(range(n))
+    np.testing.assert_allclose(cs.w, 1.0, rtol=1e-6)
+    np.testing.assert_allclose(cs.V_S, V[cs.idx], rtol=1e-5, atol=1e-7)
+
+
+def test_binned_temperature_length_switch_and_argument_checks():
+    rng = np.random.default_rng(25)
+    B, nb, d, rb, beta, RQ = 2, 64, 4, 3, 0.5, 2.0
+    K, V = rng.standard_normal((B * nb, d)), rng.standard_normal((B * nb, 2))
+    u = rng.uniform(size=B * rb)
+    Kc = K - K.mean(axis=0)
+    full = wo.compress_kv(K, V, RQ, beta, B * rb, u, bins=B, temperature_n="full")
+    binl = wo.compress_kv(K, V, RQ, beta, B * rb, u, bins=B)
+    for b in range(B):
+        RK = np.sqrt((Kc[b * nb:(b + 1) * nb] ** 2).sum(1).max())
+        np.testing.assert_allclose(full.taus[b], wo.temperature(beta, RQ, RK, B * nb)[0], rtol=1e-13)
+        np.testing.assert_allclose(binl.taus[b], wo.temperature(beta, RQ, RK, nb)[0], rtol=1e-13)
+        assert full.taus[b] > binl.taus[b]                 # tau grows with log n
+    with pytest.raises(ValueError):
+        wo.compress_kv(K, V, RQ, beta, 7, u, bins=2)        # B does not divide r
+    with pytest.raises(ValueError):
+        wo.compress_kv(K[:-1], V[:-1], RQ, beta, 6, u, bins=2)   # B does not divide n
+    one = wo.compress_kv(K, V, RQ, beta, 6, u)              # B = 1 is the default and reports per-bin arrays too
+    assert one.taus.shape == (1,) and one.taus[0] == one.tau and one.r_effs[0] == one.r_eff
