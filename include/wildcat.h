@@ -73,9 +73,15 @@ typedef struct {
   const double *uniforms; /* [P, r] pivot uniforms in [0,1), one per RPNys step,    */
                      /* or NULL: then u[p, i] is element p*r+i of the stream        */
                      /* wildcat_draw_uniforms(seed, ...) documents.                 */
-  int32_t bins;      /* B of Alg. 2.  0 or 1 (no binning) is what this build runs;  */
-                     /* B > 1 returns WILDCAT_EUNSUPPORTED.                         */
-  int32_t reserved0;
+  int32_t bins;      /* B of Alg. 2 (Sec. 2.5); 0 -> 1.  Bin b is the contiguous block  */
+                     /* of rows b n/B .. (b+1) n/B - 1 and gets r/B pivots, stored in  */
+                     /* coreset slots b r/B ..; B must divide n and r (else EINVAL).   */
+                     /* Only wildcat_compress_kv, wildcat_workspace_bytes and          */
+                     /* wildcat_rpnys_single_launch act on it; wildcat_wtd_attn reads  */
+                     /* every slot (ignores coreset.r_eff) when bins > 1.              */
+  int32_t tau_length; /* sequence length in eq. (kernel-temperature) when bins > 1:    */
+                     /* 0 -> the bin length n/B (the effective length Thm. 2 names),   */
+                     /* 1 -> the full length n (Alg. 2 as printed)                     */
   void *stream;      /* hipStream_t                                                 */
   void *ev_loop_begin; /* optional hipEvent_t pair that wildcat_compress_kv records  */
   void *ev_loop_end; /* on the stream right before the first and right after the    */
@@ -87,16 +93,18 @@ typedef struct {
 /* The compressed cache: output of CompressKV, input of WtdAttn.  All buffers are
  * caller-allocated device memory. */
 typedef struct {
-  int32_t *idx;   /* [P, r]  pivot index into the n keys, in selection order; -1 in */
-                  /*         unused slots (rank exhausted before r pivots)          */
-  int32_t *r_eff; /* [P]     number of pivots drawn (-1: internal wait timed out, the    */
-                  /*         call's outputs are invalid; never expected)            */
+  int32_t *idx;   /* [P, r]  pivot index into the n keys, bin by bin in selection   */
+                  /*         order; -1 in unused slots (a bin's rank was exhausted  */
+                  /*         before its r/B pivots)                                 */
+  int32_t *r_eff; /* [P, B]  number of pivots drawn in each bin (-1: internal wait      */
+                  /*         timed out, the call's outputs are invalid; never       */
+                  /*         expected)                                              */
   void *k_s;      /* [P, r, d]  storage dtype: original (un-recentred) key rows     */
   float *v_s;     /* [P, r, dv] W V                                                 */
   float *w;       /* [P, r]     W 1                                                 */
   float *v_min;   /* [P, dv]    column minima of V (Alg. 4, first line)             */
   float *v_max;   /* [P, dv]    column maxima of V                                  */
-  double *tau;    /* [P]        temperature used (eq. (kernel-temperature))         */
+  double *tau;    /* [P, B]     temperature of each bin (eq. (kernel-temperature))  */
   void *v_t;      /* [P, dv, r64] fp16, r64 = r rounded up to a multiple of 64: the */
                   /*         MFMA operand form of V_S for bf16 storage,             */
                   /*           v_t[p, c, j] = fp16(v_s[p, j, c] / v_scale[p]),      */
@@ -135,24 +143,26 @@ int wildcat_draw_uniforms(uint64_t seed, int64_t count, double *host_out);
 int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts,
                          double *r_q_out);
 
-/* CompressKV (Alg. 2, one bin) together with the value range of Alg. 4:
- *   kbar = row mean of K;  R_K = max_l ||k_l - kbar||;  tau from eq.
- *   (kernel-temperature) with opts->r_q;  RPNys (Alg. 1) on the recentred keys
- *   with kernel exp(beta <.,.> / tau^2), the pivot of step i drawn by inverse CDF
- *   from uniform u[p, i]:  s = min{ l : sum_{l'<=l} p_l' > u * sum p };
- *   out->k_s = K[idx], out->v_s = W V, out->w = W 1, out->v_min/v_max, out->tau.
+/* CompressKV (Alg. 2) together with the value range of Alg. 4:
+ *   kbar = row mean of K;  then for each of the B = opts->bins bins of rows:
+ *   R_K = max_l ||k_l - kbar|| over the bin;  tau from eq. (kernel-temperature)
+ *   with opts->r_q;  RPNys (Alg. 1) on the bin's recentred keys with kernel
+ *   exp(beta <.,.> / tau^2) for r/B pivots, the pivot of the bin's step i drawn by
+ *   inverse CDF from uniform u[p, b r/B + i]:  s = min{ l : sum_{l'<=l} p_l' > u * sum p };
+ *   out->k_s = K[idx], out->v_s = W V, out->w = W 1 (W block diagonal over the bins:
+ *   a bin's weights act on the bin's values), out->v_min/v_max, out->tau.
  * K [batch, kv_heads, n, d], V [batch, kv_heads, n, dv] in opts->dtype.
  * Requires 1 <= r <= n, d >= 1, opts != NULL with r_q and workspace set.
- * If the residual mass reaches zero after r_eff < r pivots, the remaining slots get
- * idx = -1 and zero key, value and weight (they then add nothing in WtdAttn). */
+ * If a bin's residual mass reaches zero after r_eff < r/B pivots, its remaining slots
+ * get idx = -1 and zero key, value and weight (they then add nothing in WtdAttn). */
 int wildcat_compress_kv(const void *K, const void *V, int64_t n, int32_t d, int32_t r,
                         uint64_t seed, const wildcat_opts *opts, wildcat_coreset *out);
 
 /* WtdAttn (Alg. 3): out[b, h, i, :] = clip( (A V_S)_i / (A w)_i  if (A w)_i > 0 else 0,
  * v_min, v_max ), A_is = exp(beta <q_i, k_s>), against the coreset of kv head
  * h / (q_heads / kv_heads).  Q [batch, q_heads, m, d], out [batch, q_heads, m, dv] in
- * opts->dtype; cs->idx and cs->tau are not read (cs->r_eff, if not NULL, limits the slots
- * that are read), so any (k_s, v_s, w, v_min, v_max) may be supplied -- e.g. all n keys with unit weights, which is exact
+ * opts->dtype; cs->idx and cs->tau are not read (cs->r_eff, if not NULL and opts->bins <= 1,
+ * limits the slots that are read), so any (k_s, v_s, w, v_min, v_max) may be supplied -- e.g. all n keys with unit weights, which is exact
  * attention. */
 int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *out, int64_t m,
                      int32_t d, int32_t r, const wildcat_opts *opts);

@@ -30,7 +30,7 @@ class _Opts(ctypes.Structure):
         ("m", ctypes.c_int64), ("dv", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("beta", ctypes.c_double), ("rank_tol", ctypes.c_double),
         ("r_q", ctypes.c_void_p), ("uniforms", ctypes.c_void_p),
-        ("bins", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("bins", ctypes.c_int32), ("tau_length", ctypes.c_int32),
         ("stream", ctypes.c_void_p), ("ev_loop_begin", ctypes.c_void_p), ("ev_loop_end", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
     ]
@@ -114,6 +114,7 @@ class Coreset:
     tau: "torch.Tensor"     # [B, Hkv] float64
     v_t: "torch.Tensor" = None      # [B, Hkv, dv, r64] float16 (bf16 storage only): v_s^T / v_scale, MFMA operand
     v_scale: "torch.Tensor" = None  # [B, Hkv] float32 power of two
+    bins: int = 1                   # B of Alg. 2; r_eff and tau are [B, Hkv, bins] when bins > 1
 
     def c_struct(self):
         return _Coreset(self.idx.data_ptr(), self.r_eff.data_ptr() if self.r_eff is not None else None,
@@ -155,16 +156,16 @@ def _opts(batch, q_heads, kv_heads, m, dv, dtype, beta, rank_tol=0.0, r_q=None, 
     return o
 
 
-def workspace_bytes(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16):
+def workspace_bytes(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1):
     o = _Opts()
-    o.batch, o.kv_heads, o.dv, o.dtype = batch, kv_heads, dv, dtype
+    o.batch, o.kv_heads, o.dv, o.dtype, o.bins = batch, kv_heads, dv, dtype, bins
     return load_library().wildcat_workspace_bytes(n, d, r, ctypes.byref(o))
 
 
-def rpnys_single_launch(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16):
+def rpnys_single_launch(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1):
     """True if compress_kv runs the selection loop of this shape as one persistent launch (needs a GPU)."""
     o = _Opts()
-    o.batch, o.kv_heads, o.dv, o.dtype = batch, kv_heads, dv, dtype
+    o.batch, o.kv_heads, o.dv, o.dtype, o.bins = batch, kv_heads, dv, dtype, bins
     rc = load_library().wildcat_rpnys_single_launch(n, d, r, ctypes.byref(o))
     if rc < 0:
         _check(rc, "wildcat_rpnys_single_launch")
@@ -184,10 +185,12 @@ def query_radius(Q, kv_heads=None):
     return out
 
 
-def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, loop_events=None):
+def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, loop_events=None,
+                bins=1, temperature_n="bin"):
     """CompressKV (Alg. 2).  K: [B, Hkv, n, d], V: [B, Hkv, n, dv]; r_q: float64 [B, Hkv] on the device;
     uniforms: optional float64 [B*Hkv, r] on the device (else drawn from `seed`); loop_events: optional pair
-    of raw hipEvent_t handles recorded around the RPNys loop.  Returns a Coreset."""
+    of raw hipEvent_t handles recorded around the RPNys loop; bins: B of Alg. 2 (must divide n and r);
+    temperature_n: "bin" (length n/B in the temperature) or "full" (n).  Returns a Coreset."""
     import torch
     _need(K, "K", 4)
     _need(V, "V", 4)
@@ -202,25 +205,30 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
         raise WildcatError("uniforms must be a contiguous float64 CUDA tensor with batch*kv_heads*r entries")
     code = _dtype_code(K)
     dev = K.device
-    need = workspace_bytes(n, d, r, B, H, dv, code)
+    if temperature_n not in ("bin", "full"):
+        raise WildcatError("temperature_n is 'bin' or 'full'")
+    bins = max(int(bins), 1)
+    need = workspace_bytes(n, d, r, B, H, dv, code, bins)
     if need == 0:
         raise WildcatError("wildcat_workspace_bytes rejected the shape")
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     cs = Coreset(
         idx=torch.empty((B, H, r), dtype=torch.int32, device=dev),
-        r_eff=torch.empty((B, H), dtype=torch.int32, device=dev),
+        r_eff=torch.empty((B, H) if bins == 1 else (B, H, bins), dtype=torch.int32, device=dev),
         k_s=torch.empty((B, H, r, d), dtype=K.dtype, device=dev),
         v_s=torch.empty((B, H, r, dv), dtype=torch.float32, device=dev),
         w=torch.empty((B, H, r), dtype=torch.float32, device=dev),
         v_min=torch.empty((B, H, dv), dtype=torch.float32, device=dev),
         v_max=torch.empty((B, H, dv), dtype=torch.float32, device=dev),
-        tau=torch.empty((B, H), dtype=torch.float64, device=dev),
+        tau=torch.empty((B, H) if bins == 1 else (B, H, bins), dtype=torch.float64, device=dev),
         v_t=(torch.empty((B, H, dv, (r + 63) // 64 * 64), dtype=torch.float16, device=dev)
              if code == WILDCAT_BF16 else None),
         v_scale=torch.empty((B, H), dtype=torch.float32, device=dev) if code == WILDCAT_BF16 else None,
+        bins=bins,
     )
     o = _opts(B, H, H, n, dv, code, beta, rank_tol, r_q.contiguous(), uniforms, workspace)
+    o.bins, o.tau_length = bins, int(temperature_n == "full")
     if loop_events is not None:
         o.ev_loop_begin, o.ev_loop_end = loop_events
     c = cs.c_struct()
@@ -254,15 +262,18 @@ def wtd_attn(Q, cs: Coreset, beta=None, out=None):
     if out is None:
         out = torch.empty((B, Hq, m, dv), dtype=Q.dtype, device=Q.device)
     o = _opts(B, Hq, Hkv, m, dv, _dtype_code(Q), beta)
+    o.bins = cs.bins
     c = cs.c_struct()
     _check(load_library().wildcat_wtd_attn(Q.data_ptr(), ctypes.byref(c), out.data_ptr(), m, d, r, ctypes.byref(o)),
            "wildcat_wtd_attn")
     return out
 
 
-def wildcat(Q, K, V, r, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, return_coreset=False):
+def wildcat(Q, K, V, r, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, return_coreset=False,
+            bins=1, temperature_n="bin"):
     """WildCat (Alg. 4): query radius, CompressKV, WtdAttn."""
     r_q = query_radius(Q, K.shape[1])
-    cs = compress_kv(K, V, r, r_q, seed=seed, uniforms=uniforms, beta=beta, rank_tol=rank_tol, workspace=workspace)
+    cs = compress_kv(K, V, r, r_q, seed=seed, uniforms=uniforms, beta=beta, rank_tol=rank_tol, workspace=workspace,
+                     bins=bins, temperature_n=temperature_n)
     out = wtd_attn(Q, cs, beta=beta)
     return (out, cs) if return_coreset else out

@@ -33,8 +33,10 @@ int resolve_shape(int64_t n, int64_t m_arg, int32_t d, int32_t r, const wildcat_
   s->beta = o->beta > 0.0 ? o->beta : 1.0 / std::sqrt((double)d);
   if (!std::isfinite(o->rank_tol) || o->rank_tol >= 1.0) return WILDCAT_EINVAL;
   s->rank_tol = o->rank_tol == 0.0 ? 1e-10 : (o->rank_tol < 0.0 ? 0.0 : o->rank_tol);
-  if (o->bins < 0) return WILDCAT_EINVAL;
-  if (o->bins > 1) return WILDCAT_EUNSUPPORTED;
+  if (o->bins < 0 || o->tau_length < 0 || o->tau_length > 1) return WILDCAT_EINVAL;
+  s->bins = o->bins > 1 ? o->bins : 1;
+  s->tau_full_n = o->tau_length;
+  if ((int64_t)s->P * s->bins > (1 << 20)) return WILDCAT_EINVAL;
   if (d > kMaxWidth || s->dv > kMaxWidth) return WILDCAT_EUNSUPPORTED;
   s->stream = (hipStream_t)o->stream;
   return WILDCAT_OK;
@@ -118,8 +120,8 @@ extern "C" const char *wildcat_strerror(int status) {
 
 extern "C" size_t wildcat_workspace_bytes(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts) {
   Shape s;
-  if (resolve_shape(n, 0, d, r, opts, &s) != WILDCAT_OK || r > kMaxRank) return 0;
-  return make_plan(s).total;
+  if (resolve_shape(n, 0, d, r, opts, &s) != WILDCAT_OK || !bins_divide(s) || r / s.bins > kMaxRank) return 0;
+  return make_plan(bin_view(s)).total;
 }
 
 static inline uint64_t mix64(uint64_t z) {

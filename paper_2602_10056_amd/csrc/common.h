@@ -20,9 +20,24 @@ struct Shape {
   int batch, q_heads, kv_heads, group, P;
   int64_t n, m;
   int d, dv, r, dtype;
+  int bins;          // B of Alg. 2 (>= 1)
+  int tau_full_n;    // temperature from the full length n instead of the bin length n / B
   double beta, rank_tol;
   hipStream_t stream;
 };
+
+// The bin loop of Alg. 2 as a batch: the same shape with every bin as a problem of its own
+// (P * B problems of n / B keys and r / B pivots; contiguous bins are a reshape of K and V).  `bins` is kept.
+// Bins are equal, contiguous blocks of rows with equal shares of the rank: B must divide n and r.
+inline bool bins_divide(const Shape &s) { return s.n % s.bins == 0 && s.r % s.bins == 0; }
+
+inline Shape bin_view(const Shape &s) {
+  Shape v = s;
+  v.P = s.P * s.bins;
+  v.n = s.n / s.bins;
+  v.r = s.r / s.bins;
+  return v;
+}
 
 // Fills `s` from the raw arguments with the defaults of wildcat_opts; returns a wildcat_status.
 int resolve_shape(int64_t n, int64_t m_arg, int32_t d, int32_t r, const wildcat_opts *o, Shape *s);

@@ -1,4 +1,9 @@
-// CompressKV (Alg. 2, one bin) with the RPNys selection loop (Alg. 1) for gfx950.
+// CompressKV (Alg. 2) with the RPNys selection loop (Alg. 1) for gfx950.
+//
+// Bins (Sec. 2.5) are handled as a batch: B contiguous bins of n/B keys are a reshape of K and V, so every kernel
+// below simply sees P * B problems of n/B keys and r/B pivots ("problem" = one bin of one (batch, kv head) pair).
+// Only three things know about the grouping: the key mean and the value range are taken over all bins of a head
+// (k_col_final), the temperature reads R_Q of the bin's head (k_tau), and pivot indices are made global at the end.
 //
 // The selection loop is bound by HBM bandwidth: step i must touch, for every key l, the i numbers
 // already computed for that key.  Everything here is laid out so that this stream is contiguous and
@@ -72,27 +77,32 @@ __global__ __launch_bounds__(kThreads) void k_col_stats(const T *__restrict__ K,
   }
 }
 
-// pass 2: grid P.  kbar = column sums / n; v_min, v_max; clears the R_K^2 accumulator.
+// pass 2: grid P (problems = bins).  The mean of Alg. 2 and the value range of Alg. 4 belong to the whole head:
+// they are combined over the `bins` consecutive problems of the head, in a fixed order, and kbar is written once
+// per bin so that later kernels index it by problem.  n = keys per bin.  Clears the R_K^2 accumulator.
 __global__ __launch_bounds__(kThreads) void k_col_final(const double *__restrict__ mpart,
                                                         const float *__restrict__ vminpart,
                                                         const float *__restrict__ vmaxpart, int64_t n, int dv,
-                                                        int dpad, int nb0, double *__restrict__ kbar,
+                                                        int dpad, int nb0, int bins, double *__restrict__ kbar,
                                                         float *__restrict__ vmin, float *__restrict__ vmax,
                                                         unsigned long long *__restrict__ scal) {
   const int t = threadIdx.x, pr = blockIdx.x;
+  const int head = pr / bins;
+  const size_t part0 = (size_t)head * bins * nb0;
+  const int nparts = bins * nb0;
   if (t < dpad) {
     double s = 0.0;
-    for (int b = 0; b < nb0; ++b) s += mpart[((size_t)pr * nb0 + b) * dpad + t];
-    kbar[(size_t)pr * dpad + t] = s / (double)n;
+    for (int b = 0; b < nparts; ++b) s += mpart[(part0 + b) * dpad + t];
+    kbar[(size_t)pr * dpad + t] = s / ((double)n * (double)bins);
   }
-  if (t < dv) {
+  if (t < dv && pr % bins == 0) {
     float mn = INFINITY, mx = -INFINITY;
-    for (int b = 0; b < nb0; ++b) {
-      mn = fminf(mn, vminpart[((size_t)pr * nb0 + b) * dv + t]);
-      mx = fmaxf(mx, vmaxpart[((size_t)pr * nb0 + b) * dv + t]);
+    for (int b = 0; b < nparts; ++b) {
+      mn = fminf(mn, vminpart[(part0 + b) * dv + t]);
+      mx = fmaxf(mx, vmaxpart[(part0 + b) * dv + t]);
     }
-    vmin[(size_t)pr * dv + t] = mn;
-    vmax[(size_t)pr * dv + t] = mx;
+    vmin[(size_t)head * dv + t] = mn;
+    vmax[(size_t)head * dv + t] = mx;
   }
   if (t == 0) scal[(size_t)pr * 8] = 0ull;
 }
@@ -210,12 +220,13 @@ __device__ double lambert_w0(double z) {
   return w;
 }
 
-__global__ void k_tau(int P, int64_t n, double beta, const double *__restrict__ r_q, double *__restrict__ scal,
-                      double *__restrict__ tau_out) {
+// P problems (bins), r_q per head (bins consecutive problems); n = the sequence length that enters b0.
+__global__ void k_tau(int P, int bins, int64_t n, double beta, const double *__restrict__ r_q,
+                      double *__restrict__ scal, double *__restrict__ tau_out) {
   const int pr = blockIdx.x * blockDim.x + threadIdx.x;
   if (pr >= P) return;
   const double rk = sqrt(__longlong_as_double(((const long long *)scal)[(size_t)pr * 8]));
-  const double rq = r_q[pr];
+  const double rq = r_q[pr / bins];
   double tau, beta_tau;
   if (!(rk > 0.0) || !(rq > 0.0)) {
     tau = INFINITY;
@@ -879,6 +890,14 @@ __global__ void k_gather(const T *__restrict__ K, const int32_t *__restrict__ id
   }
 }
 
+// Pivot indices are found relative to the bin; the caller gets indices into the head's n keys.
+__global__ void k_globalise_idx(int32_t *idx, int r, int bins, int64_t n_bin, int total) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= total) return;
+  const int bin = (e / r) % bins;
+  if (idx[e] >= 0) idx[e] += (int32_t)(bin * n_bin);
+}
+
 // After the persistent loop: a wait that timed out (never expected) is reported as r_eff = -1 everywhere.
 __global__ void k_check_sync(const int *error, int P, int32_t *r_eff) {
   if (*error)
@@ -907,6 +926,7 @@ const void *persistent_kernel(const Shape &s, const Plan &pl) {
   return (int64_t)per_cu * compute_units() >= (int64_t)pl.nblk * s.P ? fn : nullptr;
 }
 
+// `s` is the bin view of the request (wildcat::bin_view): P problems = bins, n keys and r pivots per bin.
 template <typename T, int KPT>
 int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const wildcat_opts *o, uint64_t seed,
                  wildcat_coreset *out) {
@@ -934,7 +954,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
                      lpr, mpart, vminpart, vmaxpart);
   LAUNCH_CHECK();
   hipLaunchKernelGGL(k_col_final, dim3(P), dim3(kThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
-                     pl.nb0, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
+                     pl.nb0, s.bins, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
   LAUNCH_CHECK();
   const int nc = pl.dpad / kChunk;
   const int64_t packs = (pl.npad * nc + kThreads - 1) / kThreads;
@@ -943,7 +963,8 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   hipLaunchKernelGGL((k_sqnorm<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, Kp, kbar, s.n, pl.npad, pl.dpad, d0,
                      (unsigned long long *)scal);
   LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_tau, dim3((P + 63) / 64), dim3(64), 0, st, P, s.n, s.beta, o->r_q, scal, out->tau);
+  hipLaunchKernelGGL(k_tau, dim3((P + 63) / 64), dim3(64), 0, st, P, s.bins, s.tau_full_n ? s.n * s.bins : s.n, s.beta,
+                     o->r_q, scal, out->tau);
   LAUNCH_CHECK();
   hipLaunchKernelGGL((k_init_p<KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, s.n, pl.npad, pl.nblk, s.r, s.rank_tol,
                      scal, d0, p, bsum, out->idx, out->r_eff, o->uniforms ? (double *)nullptr : u_gen,
@@ -999,12 +1020,17 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   hipLaunchKernelGGL(k_solve, dim3((dv1 + kSolveCols - 1) / kSolveCols, P), dim3(kSolveCols * 32), solve_lds, st, L, Gt,
                      out->r_eff, s.r, s.dv, out->v_s, out->w);
   LAUNCH_CHECK();
-  if (s.dtype == WILDCAT_BF16 && out->v_t && out->v_scale) {      // MFMA operand form of V_S for WtdAttn
-    const int rc = enqueue_pack_values(P, s.r, s.dv, out->v_s, out->v_t, out->v_scale, st);
+  if (s.dtype == WILDCAT_BF16 && out->v_t && out->v_scale) {      // MFMA operand form of V_S for WtdAttn, per head
+    const int rc = enqueue_pack_values(P / s.bins, s.r * s.bins, s.dv, out->v_s, out->v_t, out->v_scale, st);
     if (rc != WILDCAT_OK) return rc;
   }
   hipLaunchKernelGGL((k_gather<T>), dim3(s.r, P), dim3(64), 0, st, K, out->idx, s.n, s.d, s.r, (T *)out->k_s);
   LAUNCH_CHECK();
+  if (s.bins > 1) {
+    const int total = P * s.r;
+    hipLaunchKernelGGL(k_globalise_idx, dim3((total + 255) / 256), dim3(256), 0, st, out->idx, s.r, s.bins, s.n, total);
+    LAUNCH_CHECK();
+  }
   return WILDCAT_OK;
 }
 
@@ -1016,10 +1042,13 @@ using namespace wildcat;
 extern "C" int wildcat_compress_kv(const void *K, const void *V, int64_t n, int32_t d, int32_t r, uint64_t seed,
                                    const wildcat_opts *opts, wildcat_coreset *out) {
   if (!K || !V || !opts || !out) return WILDCAT_EINVAL;
-  Shape s;
-  int rc = resolve_shape(n, 0, d, r, opts, &s);
+  Shape whole;
+  int rc = resolve_shape(n, 0, d, r, opts, &whole);
   if (rc != WILDCAT_OK) return rc;
-  if (r > kMaxRank) return WILDCAT_EUNSUPPORTED;
+  if (!bins_divide(whole)) return WILDCAT_EINVAL;
+  const Shape s = bin_view(whole);
+  if (s.r > kMaxRank) return WILDCAT_EUNSUPPORTED;
+  if (s.P > 65535 || (int64_t)s.P * s.r > INT32_MAX) return WILDCAT_EUNSUPPORTED;   // problems index grid.y / grid.z
   if (!opts->r_q) return WILDCAT_EINVAL;
   if (!out->idx || !out->r_eff || !out->k_s || !out->v_s || !out->w || !out->v_min || !out->v_max || !out->tau)
     return WILDCAT_EINVAL;
@@ -1035,10 +1064,12 @@ extern "C" int wildcat_compress_kv(const void *K, const void *V, int64_t n, int3
 }
 
 extern "C" int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts) {
-  Shape s;
-  int rc = resolve_shape(n, 0, d, r, opts, &s);
+  Shape whole;
+  int rc = resolve_shape(n, 0, d, r, opts, &whole);
   if (rc != WILDCAT_OK) return rc;
-  if (r > kMaxRank) return WILDCAT_EUNSUPPORTED;
+  if (!bins_divide(whole)) return WILDCAT_EINVAL;
+  const Shape s = bin_view(whole);
+  if (s.r > kMaxRank) return WILDCAT_EUNSUPPORTED;
   const Plan pl = make_plan(s);
   const void *fn;
   if (s.dtype == WILDCAT_BF16) fn = pl.kpt == 2 ? persistent_kernel<bf16_t, 2>(s, pl) : persistent_kernel<bf16_t, 1>(s, pl);

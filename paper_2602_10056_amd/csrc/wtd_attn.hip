@@ -674,6 +674,14 @@ extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *
   Shape s;
   int rc = resolve_shape(r, m, d, r, opts, &s);
   if (rc != WILDCAT_OK) return rc;
+  // With bins, an exhausted bin leaves empty slots in the middle of the coreset (zero key, value and weight: they
+  // add nothing), so every slot is read and cs->r_eff, which is then per bin, is not consulted.
+  wildcat_coreset all_slots;
+  if (s.bins > 1) {
+    all_slots = *cs;
+    all_slots.r_eff = nullptr;
+    cs = &all_slots;
+  }
   if (s.dtype == WILDCAT_BF16) {
     if (cs->v_t && cs->v_scale) {
       if (s.d == 64 && s.dv == 64) return launch_mfma2<64, 64>(s, Q, cs, out);

@@ -21,6 +21,11 @@ V: [batch, kv_heads, n, d_v]; m = n and d_v = d throughout; beta = 1/sqrt(d)):
      N(0,1) entries, then a rotary position rotation of Q and K
   5  8 heads, n=131072, d=128, r=1024, bf16; keys with log-normal norms
      (sigma 0.5) times uniform directions, 16 leading "sink" keys of 4x norm
+  6  binned (Sec. 2.5): 8 heads, n=65536, d=64, r=64 in B=16 bins, bf16; Q, K, V
+     all i.i.d. N(0,1) -- the setting of the paper's FlashAttention-2 comparison
+     (Sec. 5.4: d=64, r=64, B=16, n from 2^13 to 2^18; head count not stated)
+
+Shapes 1-5 use one bin (B = 1); `bins` can be overridden for any of them.
 """
 from __future__ import annotations
 
@@ -41,6 +46,7 @@ class Shape:
     dtype: str          # "f32" | "bf16"
     data_seed: int
     uniform_seed: int
+    bins: int = 1       # B of Alg. 2
 
     @property
     def problems(self):
@@ -61,12 +67,13 @@ SHAPES = {
     3: Shape("cfg3_mixture_bf16", 1, 16, 16, 16384, 128, 256, "bf16", 103, 203),
     4: Shape("cfg4_gqa_rope_bf16", 1, 32, 8, 32768, 128, 512, "bf16", 104, 204),
     5: Shape("cfg5_heavytail_bf16", 1, 8, 8, 131072, 128, 1024, "bf16", 105, 205),
+    6: Shape("cfg6_gauss_binned_bf16", 1, 8, 8, 65536, 64, 64, "bf16", 106, 206, bins=16),
 }
 
 
 def shape(cfg, **override):
     """The catalogue shape `cfg`, optionally shrunk (n=, r=, batch=, q_heads=,
-    kv_heads=) for tests that keep the recipe but not the size."""
+    kv_heads=, bins=) for tests that keep the recipe but not the size."""
     s = SHAPES[cfg]
     if override:
         fields = {k: getattr(s, k) for k in s.__dataclass_fields__}
@@ -74,6 +81,8 @@ def shape(cfg, **override):
         s = Shape(**fields)
     if s.q_heads % s.kv_heads:
         raise ValueError("q_heads must be a multiple of kv_heads")
+    if s.bins < 1 or s.n % s.bins or s.r % s.bins:
+        raise ValueError("bins must divide n and r")
     return s
 
 
@@ -140,6 +149,9 @@ def make_kv_head(cfg, s, b, h):
         norms[:min(16, n)] = 4.0 * np.sqrt(d)
         K = norms[:, None] * dirs
         V = g.standard_normal((n, d))
+    elif cfg == 6:
+        K = g.standard_normal((n, d))
+        V = g.standard_normal((n, d))
     else:
         raise ValueError(cfg)
     return round_to_storage(K, s.dtype), round_to_storage(V, s.dtype)
@@ -161,7 +173,7 @@ def make_q_head(cfg, s, b, hq):
         Q = mu[g.integers(0, 64, size=n)] + 0.25 * g.standard_normal((n, d))
     elif cfg == 4:
         Q = _rope(g.standard_normal((n, d)), d)
-    elif cfg in (1, 5):
+    elif cfg in (1, 5, 6):
         Q = g.standard_normal((n, d))
     else:
         raise ValueError(cfg)

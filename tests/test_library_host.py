@@ -57,6 +57,11 @@ def test_workspace_bytes():
     assert wc.workspace_bytes(100, 0, 10) == 0
     assert wc.workspace_bytes(100, 64, 10, dtype=7) == 0
     assert wc.workspace_bytes(100000, 64, 5000) == 0        # rank limit of this build
+    # bins: B problems of n/B keys and r/B pivots each -- the history shrinks by B
+    c = wc.workspace_bytes(4096, 64, 128, batch=4, kv_heads=8, bins=16)
+    assert 0 < c < a / 4
+    assert wc.workspace_bytes(4096, 64, 128, bins=3) == 0   # B must divide n and r
+    assert wc.workspace_bytes(100000, 64, 5000, bins=4) > 0  # the rank limit applies per bin
 
 
 def test_entry_points_reject_bad_arguments_before_launching():
@@ -77,8 +82,14 @@ def test_entry_points_reject_bad_arguments_before_launching():
     o.workspace, o.workspace_bytes = 264, 1 << 40
     assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -2   # misaligned
     assert lib.wildcat_compress_kv(one, one, 128, 64, 129, 0, ctypes.byref(o), ctypes.byref(c)) == -1  # r > n
+    o.bins = 3
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # 3 !| n, r
     o.bins = 4
-    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -4   # binning
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 18, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # 4 | n, 4 !| r
+    o.bins, o.tau_length = 4, 2
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # bad switch
+    o.bins, o.tau_length = -1, 0
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1
     o.bins = 0
     o.q_heads, o.kv_heads = 6, 4
     assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # 6 % 4

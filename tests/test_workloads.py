@@ -7,7 +7,8 @@ from paper_2602_10056_amd import workloads as wl
 
 @pytest.mark.parametrize("cfg,ov", [(1, {}), (2, dict(batch=1, q_heads=2, kv_heads=2, n=256)),
                                     (3, dict(q_heads=2, kv_heads=2, n=512)), (4, dict(q_heads=4, kv_heads=2, n=512)),
-                                    (5, dict(q_heads=1, kv_heads=1, n=1024))])
+                                    (5, dict(q_heads=1, kv_heads=1, n=1024)),
+                                    (6, dict(q_heads=2, kv_heads=2, n=1024))])
 def test_make_is_deterministic_and_storage_exact(cfg, ov):
     a, b = wl.make(cfg, **ov), wl.make(cfg, **ov)
     s = a["shape"]
@@ -19,6 +20,15 @@ def test_make_is_deterministic_and_storage_exact(cfg, ov):
         for k in ("Q", "K", "V"):
             wl.bf16_bits(a[k])            # raises if a value is not bf16-representable
     assert not np.array_equal(a["K"][0, 0], a["V"][0, 0])
+    assert s.bins == (16 if cfg == 6 else 1) and s.n % s.bins == 0 and s.r % s.bins == 0
+
+
+def test_bins_must_divide_length_and_rank():
+    with pytest.raises(ValueError):
+        wl.shape(6, n=1000)
+    with pytest.raises(ValueError):
+        wl.shape(2, bins=3)
+    assert wl.shape(2, bins=4).bins == 4
 
 
 def test_bf16_rounding_is_nearest_even():
