@@ -73,7 +73,8 @@ def cpu_baseline(w, budget_heads):
     done = 0
     for h in range(budget_heads):
         Qg = w["Q"][0, h * s.group:(h + 1) * s.group].astype(np.float64)
-        wo.wildcat(Qg, w["K"][0, h].astype(np.float64), w["V"][0, h].astype(np.float64), s.beta, s.r, w["u"][h])
+        wo.wildcat(Qg, w["K"][0, h].astype(np.float64), w["V"][0, h].astype(np.float64), s.beta, s.r, w["u"][h],
+                   bins=s.bins)
         done += 1
         if time.perf_counter() - t0 > 20.0:
             break
@@ -115,7 +116,7 @@ def main():
     es = 2 if s.dtype == "bf16" else 4
     Q, K, V = (torch.from_numpy(w[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
     u = torch.from_numpy(w["u"]).to(dev)
-    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.d, 1 if s.dtype == "bf16" else 0),
+    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.d, 1 if s.dtype == "bf16" else 0, s.bins),
                      dtype=torch.uint8, device=dev)
     out = torch.empty((s.batch, s.q_heads, s.n, s.d), dtype=tdt, device=dev)
     hev = HipEvents()
@@ -129,7 +130,7 @@ def main():
         r_q = wc.query_radius(Q, s.kv_heads)
         if k is not None:
             marks[k][1].record()
-        cs = wc.compress_kv(K, V, s.r, r_q, uniforms=u, workspace=ws, loop_events=ev)
+        cs = wc.compress_kv(K, V, s.r, r_q, uniforms=u, workspace=ws, loop_events=ev, bins=s.bins)
         if k is not None:
             marks[k][2].record()
         wc.wtd_attn(Q, cs, out=out)
@@ -156,9 +157,10 @@ def main():
     loop_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in loop_ev]))
     ph = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(3)] for m in marks]).mean(axis=0)
     P = s.problems
-    single = wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, s.d, 1 if s.dtype == "bf16" else 0)
-    launches = 1 if single else s.r
-    loop_bytes = step_loop_bytes(P, s.n, s.d, s.r, es, single)
+    single = wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, s.d, 1 if s.dtype == "bf16" else 0, s.bins)
+    launches = 1 if single else s.r // s.bins
+    # with bins the loop is P * B independent problems of n / B keys and r / B steps
+    loop_bytes = step_loop_bytes(P * s.bins, s.n // s.bins, s.d, s.r // s.bins, es, single)
     achieved = loop_bytes / (loop_ms * 1e-3) / 1e9
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "rpnys_loop_traffic.json")
@@ -177,12 +179,12 @@ def main():
         "dtype": "f64",
         "data": "synthetic",
         "config": {"workload": f"{s.name}: batch {s.batch} x {s.q_heads} query heads / {s.kv_heads} kv heads, "
-                               f"n=m={s.n}, d={s.d}, r={s.r}, B=1, {s.dtype} storage; selection loop in fp64, "
+                               f"n=m={s.n}, d={s.d}, r={s.r}, B={s.bins}, {s.dtype} storage; selection loop in fp64, "
                                f"WtdAttn on MFMA (bf16 scores, fp16 value product) with fp32 accumulation",
                    "uniform_seed": s.uniform_seed, "data_seed": s.data_seed},
         "phases_ms": {"query_radius": float(ph[0]), "compress_kv": float(ph[1]), "rpnys_loop": loop_ms,
                       "wtd_attn": float(ph[2])},
-        "roofline": {"kernel": ("k_rpnys_persistent (RPNys selection loop, all %d steps in one launch)" % s.r) if single
+        "roofline": {"kernel": ("k_rpnys_persistent (RPNys selection loop, all %d steps in one launch)" % (s.r // s.bins)) if single
                                else "k_step (RPNys selection loop, one launch per step)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "launches": launches, "avg_launch_ms": loop_ms / launches,
@@ -216,16 +218,17 @@ def main():
         del Q, K, V, ws, out
         torch.cuda.empty_cache()
         sweep = []
-        for n2 in (4096, 8192, 16384, 32768, 65536, 131072):
+        for n2 in (4096, 8192, 16384, 32768, 65536, 131072) + ((262144,) if s.bins > 1 else ()):
             w2 = wl.make(args.cfg, n=n2)
             s2 = w2["shape"]
             Q2, K2, V2 = (torch.from_numpy(w2[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
             u2 = torch.from_numpy(w2["u"]).to(dev)
-            ws2 = torch.empty(wc.workspace_bytes(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d, 1 if es == 2 else 0),
-                              dtype=torch.uint8, device=dev)
+            ws2 = torch.empty(wc.workspace_bytes(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d, 1 if es == 2 else 0,
+                                                 s2.bins), dtype=torch.uint8, device=dev)
 
             def pass2():
-                cs2 = wc.compress_kv(K2, V2, s2.r, wc.query_radius(Q2, s2.kv_heads), uniforms=u2, workspace=ws2)
+                cs2 = wc.compress_kv(K2, V2, s2.r, wc.query_radius(Q2, s2.kv_heads), uniforms=u2, workspace=ws2,
+                                     bins=s2.bins)
                 return wc.wtd_attn(Q2, cs2)
 
             pass2()
@@ -239,7 +242,7 @@ def main():
             ms2 = a.elapsed_time(b) / 3
             sweep.append({"n": n2, "ms": ms2, "tokens_per_s": s2.batch * n2 / (ms2 * 1e-3), "us_per_token": ms2 * 1e3 / n2,
                           "single_launch_loop": wc.rpnys_single_launch(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d,
-                                                                      1 if es == 2 else 0)})
+                                                                      1 if es == 2 else 0, s2.bins)})
             del Q2, K2, V2, ws2, w2
             torch.cuda.empty_cache()
         res["scaling_in_n"] = sweep

@@ -77,34 +77,51 @@ __global__ __launch_bounds__(kThreads) void k_col_stats(const T *__restrict__ K,
   }
 }
 
-// pass 2: grid P (problems = bins).  The mean of Alg. 2 and the value range of Alg. 4 belong to the whole head:
-// they are combined over the `bins` consecutive problems of the head, in a fixed order, and kbar is written once
-// per bin so that later kernels index it by problem.  n = keys per bin.  Clears the R_K^2 accumulator.
+// pass 2: grid = heads.  The mean of Alg. 2 and the value range of Alg. 4 belong to the whole head: they are
+// combined over the `bins` consecutive problems of the head in a fixed order (thread (rr, cc) takes partials
+// rr, rr + rif, ... of column cc, then the rif partial results are added in turn), and kbar is written once per bin
+// so that later kernels index it by problem.  n = keys per bin.  Clears the R_K^2 accumulators of the head's bins.
 __global__ __launch_bounds__(kThreads) void k_col_final(const double *__restrict__ mpart,
                                                         const float *__restrict__ vminpart,
                                                         const float *__restrict__ vmaxpart, int64_t n, int dv,
-                                                        int dpad, int nb0, int bins, double *__restrict__ kbar,
-                                                        float *__restrict__ vmin, float *__restrict__ vmax,
+                                                        int dpad, int nb0, int bins, int lpr,
+                                                        double *__restrict__ kbar, float *__restrict__ vmin,
+                                                        float *__restrict__ vmax,
                                                         unsigned long long *__restrict__ scal) {
-  const int t = threadIdx.x, pr = blockIdx.x;
-  const int head = pr / bins;
+  __shared__ double sd[kThreads];
+  __shared__ float smn[kThreads], smx[kThreads];
+  const int t = threadIdx.x, head = blockIdx.x;
+  const int rif = kThreads / lpr, rr = t / lpr, cc = t % lpr;
   const size_t part0 = (size_t)head * bins * nb0;
   const int nparts = bins * nb0;
-  if (t < dpad) {
-    double s = 0.0;
-    for (int b = 0; b < nparts; ++b) s += mpart[(part0 + b) * dpad + t];
-    kbar[(size_t)pr * dpad + t] = s / ((double)n * (double)bins);
-  }
-  if (t < dv && pr % bins == 0) {
-    float mn = INFINITY, mx = -INFINITY;
-    for (int b = 0; b < nparts; ++b) {
-      mn = fminf(mn, vminpart[(part0 + b) * dv + t]);
-      mx = fmaxf(mx, vmaxpart[(part0 + b) * dv + t]);
+  double acc = 0.0;
+  float mn = INFINITY, mx = -INFINITY;
+#pragma unroll 8
+  for (int b = rr; b < nparts; b += rif) {
+    if (cc < dpad) acc += mpart[(part0 + b) * dpad + cc];
+    if (cc < dv) {
+      mn = fminf(mn, vminpart[(part0 + b) * dv + cc]);
+      mx = fmaxf(mx, vmaxpart[(part0 + b) * dv + cc]);
     }
-    vmin[(size_t)head * dv + t] = mn;
-    vmax[(size_t)head * dv + t] = mx;
   }
-  if (t == 0) scal[(size_t)pr * 8] = 0ull;
+  sd[t] = acc; smn[t] = mn; smx[t] = mx;
+  __syncthreads();
+  if (rr == 0) {
+    for (int q = 1; q < rif; ++q) {
+      acc += sd[q * lpr + cc];
+      mn = fminf(mn, smn[q * lpr + cc]);
+      mx = fmaxf(mx, smx[q * lpr + cc]);
+    }
+    if (cc < dpad) {
+      const double mean = acc / ((double)n * (double)bins);
+      for (int b = 0; b < bins; ++b) kbar[((size_t)head * bins + b) * dpad + cc] = mean;
+    }
+    if (cc < dv) {
+      vmin[(size_t)head * dv + cc] = mn;
+      vmax[(size_t)head * dv + cc] = mx;
+    }
+  }
+  for (int b = t; b < bins; b += kThreads) scal[((size_t)head * bins + b) * 8] = 0ull;
 }
 
 // --------------------------------------------------------------------------------------------
@@ -129,6 +146,123 @@ __global__ __launch_bounds__(kThreads) void k_pack(const T *__restrict__ K, int6
   T *dst = Kp + (((size_t)pr * nc + c) * npad + l) * kChunk;
 #pragma unroll
   for (int e = 0; e < kChunk; ++e) dst[e] = out[e];
+}
+
+// --------------------------------------------------------------------------------------------
+// Fused first pass for the common widths (rows of K and V that are a power-of-two number of 16-byte pieces):
+// one read of K produces both the packed copy Kp and the column sums, one read of V the column minima and maxima.
+// grid (nb, P); the workgroup owns keys [blk * kpw, (blk + 1) * kpw), kpw a multiple of the tile height.
+//   * K rows are contiguous in memory, so a tile of TK rows is read as one linear run of 16-byte pieces (lane i of
+//     a wavefront takes piece i), parked in LDS with an 8-byte row pad, and written back out chunk by chunk: for a
+//     fixed chunk c the TK keys of the tile are contiguous in Kp, so stores are full lines too.
+//   * A thread always holds the same piece column (256 is a multiple of the pieces per row), so the column sums,
+//     minima and maxima accumulate in registers and are combined once at the end, in a fixed order.
+// Same partial-result layout as k_col_stats (pass 2 is k_col_final).
+// --------------------------------------------------------------------------------------------
+template <typename T> struct Piece;                    // 16 bytes of a row as floats
+template <> struct Piece<float> {
+  static constexpr int N = 4;
+  __device__ static void unpack(uint4 v, float (&x)[4]) {
+    x[0] = __uint_as_float(v.x); x[1] = __uint_as_float(v.y); x[2] = __uint_as_float(v.z); x[3] = __uint_as_float(v.w);
+  }
+};
+template <> struct Piece<bf16_t> {
+  static constexpr int N = 8;
+  __device__ static void unpack(uint4 v, float (&x)[8]) {
+    x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xffff0000u);
+    x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xffff0000u);
+    x[4] = __uint_as_float(v.z << 16); x[5] = __uint_as_float(v.z & 0xffff0000u);
+    x[6] = __uint_as_float(v.w << 16); x[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_pack_stats(const T *__restrict__ K, const T *__restrict__ V, int64_t n,
+                                                         int64_t npad, int d, int dv, int kpw, int tk, int nb,
+                                                         T *__restrict__ Kp, double *__restrict__ mpart,
+                                                         float *__restrict__ vminpart, float *__restrict__ vmaxpart) {
+  constexpr int EPP = Piece<T>::N;                       // elements per 16-byte piece
+  extern __shared__ __attribute__((aligned(16))) char tile[];   // tk rows of (d * sizeof(T) + 8) bytes
+  __shared__ double sks[kThreads][EPP];
+  __shared__ float smn[kThreads][EPP], smx[kThreads][EPP];
+  const int t = threadIdx.x, blk = blockIdx.x, pr = blockIdx.y;
+  const int ppr = d / EPP, ppv = dv / EPP;               // pieces per K row / V row (powers of two <= 64)
+  const int rowb = d * (int)sizeof(T) + 8;
+  const int nc = d / kChunk;
+  const int64_t key0 = (int64_t)blk * kpw;
+  const int64_t key1 = key0 + kpw < npad ? key0 + kpw : npad;
+  const T *Kpr = K + (size_t)pr * n * d;
+
+  // ---- K: pack and column sums ---------------------------------------------------------------------------
+  const int jk = t % ppr, rk = t / ppr, rpp = kThreads / ppr;
+  double ksum[EPP];
+#pragma unroll
+  for (int e = 0; e < EPP; ++e) ksum[e] = 0.0;
+  for (int64_t tile0 = key0; tile0 < key1; tile0 += tk) {
+    for (int lr = rk; lr < tk; lr += rpp) {
+      const int64_t row = tile0 + lr;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (row < n) v = *reinterpret_cast<const uint4 *>(Kpr + (size_t)row * d + jk * EPP);
+      float x[EPP];
+      Piece<T>::unpack(v, x);
+#pragma unroll
+      for (int e = 0; e < EPP; ++e) ksum[e] += (double)x[e];
+      uint2 *dst = reinterpret_cast<uint2 *>(tile + (size_t)lr * rowb + jk * 16);
+      dst[0] = make_uint2(v.x, v.y);
+      dst[1] = make_uint2(v.z, v.w);
+    }
+    __syncthreads();
+    for (int item = t; item < nc * tk; item += kThreads) {
+      const int l = item % tk, c = item / tk;
+      const char *src = tile + (size_t)l * rowb + c * (kChunk * (int)sizeof(T));
+      T *dst = Kp + (((size_t)pr * nc + c) * npad + tile0 + l) * kChunk;
+      if constexpr (sizeof(T) == 2) {
+        *reinterpret_cast<uint2 *>(dst) = *reinterpret_cast<const uint2 *>(src);
+      } else {
+        const uint2 a = reinterpret_cast<const uint2 *>(src)[0], b = reinterpret_cast<const uint2 *>(src)[1];
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(a.x, a.y, b.x, b.y);
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- V: column minima and maxima -------------------------------------------------------------------------
+  const int jv = t % ppv, rv = t / ppv, rpv = kThreads / ppv;
+  float mn[EPP], mx[EPP];
+#pragma unroll
+  for (int e = 0; e < EPP; ++e) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+  const T *Vpr = V + (size_t)pr * n * dv;
+  const int64_t vend = key1 < n ? key1 : n;
+#pragma unroll 4
+  for (int64_t row = key0 + rv; row < vend; row += rpv) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(Vpr + (size_t)row * dv + jv * EPP);
+    float x[EPP];
+    Piece<T>::unpack(v, x);
+#pragma unroll
+    for (int e = 0; e < EPP; ++e) { mn[e] = fminf(mn[e], x[e]); mx[e] = fmaxf(mx[e], x[e]); }
+  }
+
+  // ---- combine the threads that share a piece column, in row-group order ----------------------------------------
+#pragma unroll
+  for (int e = 0; e < EPP; ++e) { sks[t][e] = ksum[e]; smn[t][e] = mn[e]; smx[t][e] = mx[e]; }
+  __syncthreads();
+  const size_t slot = (size_t)pr * nb + blk;
+  if (t < d) {
+    const int j = t / EPP, e = t % EPP;
+    double acc = 0.0;
+    for (int q = 0; q < rpp; ++q) acc += sks[q * ppr + j][e];
+    mpart[slot * d + t] = acc;
+  }
+  if (t < dv) {
+    const int j = t / EPP, e = t % EPP;
+    float lo = INFINITY, hi = -INFINITY;
+    for (int q = 0; q < rpv; ++q) {
+      lo = fminf(lo, smn[q * ppv + j][e]);
+      hi = fmaxf(hi, smx[q * ppv + j][e]);
+    }
+    vminpart[slot * dv + t] = lo;
+    vmaxpart[slot * dv + t] = hi;
+  }
 }
 
 // Loads the kChunk packed features of KPT adjacent keys as floats.
@@ -788,6 +922,109 @@ __global__ __launch_bounds__(kThreads) void k_gram(const double *__restrict__ F,
   }
 }
 
+// --------------------------------------------------------------------------------------------
+// Gram pass for small ranks (r <= R <= 16; the binned regime of Sec. 2.5, where a bin gets a handful of pivots):
+// the 128-row tiles above would be almost empty, and the pass is a pure stream over V.  Here a thread owns 4
+// adjacent value columns of every (256 / tpr)-th key of the chunk and keeps R x 4 fp64 accumulators; tpr threads
+// cover one value row with 8- or 16-byte loads, so a wavefront reads whole rows back to back.  The partial sums
+// are combined in a fixed order (lane butterfly, then the four wavefronts in turn).
+// grid (nchunk, 1, P); same partial-sum layout as k_gram.
+// --------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void load_value4(const T *__restrict__ row, int col, int dv, bool vec, double (&v)[4]);
+template <>
+__device__ __forceinline__ void load_value4<float>(const float *__restrict__ row, int col, int dv, bool vec,
+                                                   double (&v)[4]) {
+  if (vec) {
+    const float4 x = *reinterpret_cast<const float4 *>(row + col);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = col + c < dv ? (double)row[col + c] : 0.0;
+  }
+}
+template <>
+__device__ __forceinline__ void load_value4<bf16_t>(const bf16_t *__restrict__ row, int col, int dv, bool vec,
+                                                    double (&v)[4]) {
+  if (vec) {
+    float x[kChunk];
+    unpack_bf16x4(*reinterpret_cast<const uint2 *>(row + col), x);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = (double)x[c];
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] = col + c < dv ? (double)to_float(row[col + c]) : 0.0;
+  }
+}
+
+template <typename T, int R>
+__global__ __launch_bounds__(kThreads) void k_gram_small(const double *__restrict__ F, const T *__restrict__ V,
+                                                         int64_t n, int nblk, int slab, int r, int dv, int tpr,
+                                                         int slabs_per_chunk, int nchunk,
+                                                         double *__restrict__ gpart) {
+  __shared__ double red[kThreads / kWave][kWave][5];
+  const int t = threadIdx.x, ch = blockIdx.x, pr = blockIdx.z;
+  const int lane = t & (kWave - 1), wv = t / kWave;
+  const int kg = t / tpr, cg = t % tpr, kgs = kThreads / tpr;     // key group, column group, key groups
+  const int col = 4 * cg;
+  const bool active = col < dv;
+  const bool vec = dv % 4 == 0;                                  // rows stay 4-element aligned
+  double acc[R][4], rs[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    rs[j] = 0.0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[j][c] = 0.0;
+  }
+  const int sb0 = ch * slabs_per_chunk;
+  const int sb1 = sb0 + slabs_per_chunk < nblk ? sb0 + slabs_per_chunk : nblk;
+  const T *Vp = V + (size_t)pr * n * dv;
+  for (int sb = sb0; sb < sb1; ++sb) {
+    const double *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
+#pragma unroll 2
+    for (int k0 = 0; k0 < slab; k0 += kgs) {
+      const int l_loc = k0 + kg;
+      const int64_t l = (int64_t)sb * slab + l_loc;
+      if (l >= n || !active) continue;
+      double v[4], f[R];
+      load_value4<T>(Vp + (size_t)l * dv, col, dv, vec, v);
+#pragma unroll
+      for (int j = 0; j < R; ++j) f[j] = j < r ? Fslab[(size_t)j * slab + l_loc] : 0.0;
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        rs[j] += f[j];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[j][c] = fma(f[j], v[c], acc[j][c]);
+      }
+    }
+  }
+  const int dv1 = dv + 1;
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    double x[5] = {acc[j][0], acc[j][1], acc[j][2], acc[j][3], rs[j]};
+    for (int off = tpr; off < kWave; off <<= 1)                   // key groups inside the wavefront
+#pragma unroll
+      for (int c = 0; c < 5; ++c) x[c] += __shfl_xor(x[c], off, kWave);
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 5; ++c) red[wv][lane][c] = x[c];
+    __syncthreads();
+    if (wv == 0 && lane < tpr && j < r) {
+      double *dst = gpart + (((size_t)pr * nchunk + ch) * r + j) * dv1;
+      double tot[5];
+#pragma unroll
+      for (int c = 0; c < 5; ++c) tot[c] = red[0][lane][c];
+      for (int w2 = 1; w2 < kThreads / kWave; ++w2)
+#pragma unroll
+        for (int c = 0; c < 5; ++c) tot[c] += red[w2][lane][c];
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (col + c < dv) dst[col + c] = tot[c];
+      if (lane == 0) dst[dv] = tot[4];
+    }
+  }
+}
+
 // Gt[pr][c][a] = sum over chunks (in chunk order) of gpart[pr][chunk][a][c].  grid (ceil(r*dv1/256), P).
 __global__ __launch_bounds__(kThreads) void k_gram_reduce(const double *__restrict__ gpart, int r, int dv1,
                                                           int nchunk, double *__restrict__ Gt) {
@@ -950,15 +1187,32 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
 
   int lpr = 1;
   while (lpr < s.d || lpr < s.dv || lpr < pl.dpad) lpr <<= 1;
-  hipLaunchKernelGGL((k_col_stats<T>), dim3(pl.nb0, P), dim3(kThreads), 0, st, K, V, s.n, s.d, s.dv, pl.dpad, pl.nb0,
-                     lpr, mpart, vminpart, vmaxpart);
-  LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_col_final, dim3(P), dim3(kThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
-                     pl.nb0, s.bins, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
-  LAUNCH_CHECK();
   const int nc = pl.dpad / kChunk;
-  const int64_t packs = (pl.npad * nc + kThreads - 1) / kThreads;
-  hipLaunchKernelGGL((k_pack<T>), dim3((unsigned)packs, P), dim3(kThreads), 0, st, K, s.n, pl.npad, s.d, pl.dpad, Kp);
+  constexpr int epp = 16 / (int)sizeof(T);
+  auto pow2_pieces = [](int width) {
+    const int pieces = width / epp;
+    return width % epp == 0 && pieces >= 1 && pieces <= kWave && (pieces & (pieces - 1)) == 0;
+  };
+  int nparts = pl.nb0;                                        // partial results per problem
+  if (pow2_pieces(s.d) && pow2_pieces(s.dv)) {
+    const int tk = s.d * (int)sizeof(T) <= 256 ? 64 : 32;     // tile height: at most 33 KB of LDS for the tile
+    int64_t kpw = (pl.npad + pl.nb0 - 1) / pl.nb0;
+    kpw = (kpw + tk - 1) / tk * tk;
+    nparts = (int)((pl.npad + kpw - 1) / kpw);                // <= nb0
+    const size_t lds = (size_t)tk * (s.d * sizeof(T) + 8);
+    hipLaunchKernelGGL((k_pack_stats<T>), dim3(nparts, P), dim3(kThreads), lds, st, K, V, s.n, pl.npad, s.d, s.dv,
+                       (int)kpw, tk, nparts, Kp, mpart, vminpart, vmaxpart);
+    LAUNCH_CHECK();
+  } else {
+    hipLaunchKernelGGL((k_col_stats<T>), dim3(pl.nb0, P), dim3(kThreads), 0, st, K, V, s.n, s.d, s.dv, pl.dpad, pl.nb0,
+                       lpr, mpart, vminpart, vmaxpart);
+    LAUNCH_CHECK();
+    const int64_t packs = (pl.npad * nc + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL((k_pack<T>), dim3((unsigned)packs, P), dim3(kThreads), 0, st, K, s.n, pl.npad, s.d, pl.dpad, Kp);
+    LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(k_col_final, dim3(P / s.bins), dim3(kThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
+                     nparts, s.bins, lpr, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
   LAUNCH_CHECK();
   hipLaunchKernelGGL((k_sqnorm<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, Kp, kbar, s.n, pl.npad, pl.dpad, d0,
                      (unsigned long long *)scal);
@@ -1000,7 +1254,20 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   if (o->ev_loop_end && hipEventRecord((hipEvent_t)o->ev_loop_end, st) != hipSuccess) return WILDCAT_EHIP;
 
   const int rtiles = (s.r + kGramRows - 1) / kGramRows;
-  if (s.dv <= 64) {
+  if (s.r <= 16) {
+    int tpr = 1;
+    while (tpr * 4 < s.dv) tpr <<= 1;                        // threads per value row (<= 64: dv <= kMaxWidth)
+    const dim3 grid(pl.nchunk, 1, P);
+    if (s.r <= 4)
+      hipLaunchKernelGGL((k_gram_small<T, 4>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
+                         pl.slabs_per_chunk, pl.nchunk, gpart);
+    else if (s.r <= 8)
+      hipLaunchKernelGGL((k_gram_small<T, 8>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
+                         pl.slabs_per_chunk, pl.nchunk, gpart);
+    else
+      hipLaunchKernelGGL((k_gram_small<T, 16>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
+                         tpr, pl.slabs_per_chunk, pl.nchunk, gpart);
+  } else if (s.dv <= 64) {
     hipLaunchKernelGGL((k_gram<T, 4>), dim3(pl.nchunk, rtiles, P), dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab,
                        s.r, s.dv, pl.slabs_per_chunk, pl.nchunk, 1, gpart);
   } else {
