@@ -127,7 +127,7 @@ def main():
         ev = loop_ev[k] if k is not None else None
         if k is not None:
             marks[k][0].record()
-        r_q = wc.query_radius(Q, s.kv_heads)
+        r_q = wc.query_radius(Q, s.kv_heads, workspace=ws)
         if k is not None:
             marks[k][1].record()
         cs = wc.compress_kv(K, V, s.r, r_q, uniforms=u, workspace=ws, loop_events=ev, bins=s.bins)
@@ -227,7 +227,7 @@ def main():
                                                  s2.bins), dtype=torch.uint8, device=dev)
 
             def pass2():
-                cs2 = wc.compress_kv(K2, V2, s2.r, wc.query_radius(Q2, s2.kv_heads), uniforms=u2, workspace=ws2,
+                cs2 = wc.compress_kv(K2, V2, s2.r, wc.query_radius(Q2, s2.kv_heads, workspace=ws2), uniforms=u2, workspace=ws2,
                                      bins=s2.bins)
                 return wc.wtd_attn(Q2, cs2)
 

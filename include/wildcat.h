@@ -127,8 +127,8 @@ const char *wildcat_strerror(int status);
 
 /* HOST.  Bytes of workspace wildcat_compress_kv needs for keys of length n, width
  * d, rank r under *opts (batch, kv_heads, dv, dtype are read; opts may be NULL).
- * Returns 0 for invalid arguments.  wildcat_query_radius and wildcat_wtd_attn need
- * no workspace. */
+ * Returns 0 for invalid arguments.  wildcat_wtd_attn needs no workspace;
+ * wildcat_query_radius can use one (see there). */
 size_t wildcat_workspace_bytes(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts);
 
 /* HOST.  Fills host_out[0..count) with the library's pivot uniforms for `seed`:
@@ -139,7 +139,10 @@ int wildcat_draw_uniforms(uint64_t seed, int64_t count, double *host_out);
 
 /* R_Q of Alg. 4: r_q_out[p] = max over the query rows of every query head that
  * shares kv head p of ||q||_2.  Q is [batch, q_heads, m, d] in opts->dtype.
- * r_q_out: device [P] doubles. */
+ * r_q_out: device [P] doubles.  No workspace is required; if opts->workspace offers at
+ * least 8 * (4096 + batch * q_heads) bytes (e.g. the workspace of the wildcat_compress_kv call
+ * that follows on the same stream) it is used as scratch for per-workgroup maxima, which
+ * is several times faster than the atomic updates of r_q_out used otherwise.  Same result. */
 int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts,
                          double *r_q_out);
 

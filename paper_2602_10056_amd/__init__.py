@@ -172,14 +172,15 @@ def rpnys_single_launch(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, 
     return bool(rc)
 
 
-def query_radius(Q, kv_heads=None):
-    """R_Q of Alg. 4 per (batch, kv_head): float64 tensor [B, Hkv].  Q: [B, Hq, m, d]."""
+def query_radius(Q, kv_heads=None, workspace=None):
+    """R_Q of Alg. 4 per (batch, kv_head): float64 tensor [B, Hkv].  Q: [B, Hq, m, d].  `workspace`: optional
+    uint8 device tensor used as scratch (any later call on the stream may overwrite it)."""
     import torch
     _need(Q, "Q", 4)
     B, Hq, m, d = Q.shape
     kv_heads = kv_heads or Hq
     out = torch.empty((B, kv_heads), dtype=torch.float64, device=Q.device)
-    o = _opts(B, Hq, kv_heads, m, 0, _dtype_code(Q), None)
+    o = _opts(B, Hq, kv_heads, m, 0, _dtype_code(Q), None, workspace=workspace)
     _check(load_library().wildcat_query_radius(Q.data_ptr(), m, d, ctypes.byref(o), out.data_ptr()),
            "wildcat_query_radius")
     return out
@@ -272,7 +273,14 @@ def wtd_attn(Q, cs: Coreset, beta=None, out=None):
 def wildcat(Q, K, V, r, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, return_coreset=False,
             bins=1, temperature_n="bin"):
     """WildCat (Alg. 4): query radius, CompressKV, WtdAttn."""
-    r_q = query_radius(Q, K.shape[1])
+    if workspace is None:
+        import torch
+        bins_ = max(int(bins), 1)
+        need = workspace_bytes(K.shape[2], K.shape[3], r, K.shape[0], K.shape[1], V.shape[3], _dtype_code(K), bins_)
+        if need == 0:
+            raise WildcatError("wildcat_workspace_bytes rejected the shape")
+        workspace = torch.empty(need, dtype=torch.uint8, device=K.device)
+    r_q = query_radius(Q, K.shape[1], workspace=workspace)
     cs = compress_kv(K, V, r, r_q, seed=seed, uniforms=uniforms, beta=beta, rank_tol=rank_tol, workspace=workspace,
                      bins=bins, temperature_n=temperature_n)
     out = wtd_attn(Q, cs, beta=beta)

@@ -77,31 +77,44 @@ __global__ __launch_bounds__(kThreads) void k_col_stats(const T *__restrict__ K,
   }
 }
 
-// pass 2: grid = heads.  The mean of Alg. 2 and the value range of Alg. 4 belong to the whole head: they are
-// combined over the `bins` consecutive problems of the head in a fixed order (thread (rr, cc) takes partials
-// rr, rr + rif, ... of column cc, then the rif partial results are added in turn), and kbar is written once per bin
-// so that later kernels index it by problem.  n = keys per bin.  Clears the R_K^2 accumulators of the head's bins.
-__global__ __launch_bounds__(kThreads) void k_col_final(const double *__restrict__ mpart,
-                                                        const float *__restrict__ vminpart,
-                                                        const float *__restrict__ vmaxpart, int64_t n, int dv,
-                                                        int dpad, int nb0, int bins, int lpr,
-                                                        double *__restrict__ kbar, float *__restrict__ vmin,
-                                                        float *__restrict__ vmax,
-                                                        unsigned long long *__restrict__ scal) {
-  __shared__ double sd[kThreads];
-  __shared__ float smn[kThreads], smx[kThreads];
+// pass 2: grid = heads, 1024 threads.  The mean of Alg. 2 and the value range of Alg. 4 belong to the whole head:
+// they are combined over the `bins` consecutive problems of the head in a fixed order (thread (rr, cc) takes
+// partials rr, rr + rif, ... of column cc -- eight loads in flight at a time -- then the rif partial results are
+// added in turn), and kbar is written once per bin so that later kernels index it by problem.  n = keys per bin.
+// Clears the R_K^2 accumulators of the head's bins.
+constexpr int kFinalThreads = 1024;
+
+__global__ __launch_bounds__(kFinalThreads) void k_col_final(const double *__restrict__ mpart,
+                                                             const float *__restrict__ vminpart,
+                                                             const float *__restrict__ vmaxpart, int64_t n, int dv,
+                                                             int dpad, int nb0, int bins, int lpr,
+                                                             double *__restrict__ kbar, float *__restrict__ vmin,
+                                                             float *__restrict__ vmax,
+                                                             unsigned long long *__restrict__ scal) {
+  __shared__ double sd[kFinalThreads];
+  __shared__ float smn[kFinalThreads], smx[kFinalThreads];
   const int t = threadIdx.x, head = blockIdx.x;
-  const int rif = kThreads / lpr, rr = t / lpr, cc = t % lpr;
+  const int rif = kFinalThreads / lpr, rr = t / lpr, cc = t % lpr;
   const size_t part0 = (size_t)head * bins * nb0;
   const int nparts = bins * nb0;
   double acc = 0.0;
   float mn = INFINITY, mx = -INFINITY;
-#pragma unroll 8
-  for (int b = rr; b < nparts; b += rif) {
-    if (cc < dpad) acc += mpart[(part0 + b) * dpad + cc];
-    if (cc < dv) {
-      mn = fminf(mn, vminpart[(part0 + b) * dv + cc]);
-      mx = fmaxf(mx, vmaxpart[(part0 + b) * dv + cc]);
+  for (int b0 = rr; b0 < nparts; b0 += 8 * rif) {
+    double x[8];
+    float lo[8], hi[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int b = b0 + q * rif;
+      const bool ok = b < nparts;
+      x[q] = (ok && cc < dpad) ? mpart[(part0 + b) * dpad + cc] : 0.0;
+      lo[q] = (ok && cc < dv) ? vminpart[(part0 + b) * dv + cc] : INFINITY;
+      hi[q] = (ok && cc < dv) ? vmaxpart[(part0 + b) * dv + cc] : -INFINITY;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      acc += x[q];
+      mn = fminf(mn, lo[q]);
+      mx = fmaxf(mx, hi[q]);
     }
   }
   sd[t] = acc; smn[t] = mn; smx[t] = mx;
@@ -121,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void k_col_final(const double *__restrict
       vmax[(size_t)head * dv + cc] = mx;
     }
   }
-  for (int b = t; b < bins; b += kThreads) scal[((size_t)head * bins + b) * 8] = 0ull;
+  for (int b = t; b < bins; b += kFinalThreads) scal[((size_t)head * bins + b) * 8] = 0ull;
 }
 
 // --------------------------------------------------------------------------------------------
@@ -332,7 +345,13 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm(const T *__restrict__ Kp, c
     mx = fmax(mx, acc[k]);
   }
   mx = block_reduce<double>(mx, sm, MaxOp());
-  if (t == 0) atomicMax(&scal[(size_t)pr * 8], (unsigned long long)__double_as_longlong(mx));
+  if (t == 0) {
+    // The accumulator only grows, so a workgroup whose maximum is not above what is already there has nothing to
+    // add (a stale read merely costs an atomic that changes nothing): most workgroups skip the contended atomic.
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(mx);
+    if (bits > __hip_atomic_load(&scal[(size_t)pr * 8], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+      atomicMax(&scal[(size_t)pr * 8], bits);
+  }
 }
 
 // --------------------------------------------------------------------------------------------
@@ -1114,9 +1133,11 @@ __global__ __launch_bounds__(kSolveCols * 32) void k_solve(const double *__restr
   }
 }
 
-// K_S = original key rows at the pivots (Alg. 2: recentred pivots plus the mean), zero in unused slots.
+// K_S = original key rows at the pivots (Alg. 2: recentred pivots plus the mean), zero in unused slots.  Pivot indices
+// were found relative to the bin; once the row is read, the slot's index is rewritten as an index into the head's
+// n * bins keys.  grid (r, P), n = keys per bin.
 template <typename T>
-__global__ void k_gather(const T *__restrict__ K, const int32_t *__restrict__ idx, int64_t n, int d, int r,
+__global__ void k_gather(const T *__restrict__ K, int32_t *__restrict__ idx, int64_t n, int d, int r, int bins,
                          T *__restrict__ k_s) {
   const int i = blockIdx.x, pr = blockIdx.y;
   const int s = idx[(size_t)pr * r + i];
@@ -1125,14 +1146,8 @@ __global__ void k_gather(const T *__restrict__ K, const int32_t *__restrict__ id
     from_float(0.0f, &z);
     k_s[((size_t)pr * r + i) * d + j] = s >= 0 ? K[((size_t)pr * n + s) * d + j] : z;
   }
-}
-
-// Pivot indices are found relative to the bin; the caller gets indices into the head's n keys.
-__global__ void k_globalise_idx(int32_t *idx, int r, int bins, int64_t n_bin, int total) {
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= total) return;
-  const int bin = (e / r) % bins;
-  if (idx[e] >= 0) idx[e] += (int32_t)(bin * n_bin);
+  __syncthreads();                                       // every thread has read the local index
+  if (threadIdx.x == 0 && bins > 1 && s >= 0) idx[(size_t)pr * r + i] = s + (int32_t)((pr % bins) * n);
 }
 
 // After the persistent loop: a wait that timed out (never expected) is reported as r_eff = -1 everywhere.
@@ -1211,7 +1226,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     hipLaunchKernelGGL((k_pack<T>), dim3((unsigned)packs, P), dim3(kThreads), 0, st, K, s.n, pl.npad, s.d, pl.dpad, Kp);
     LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(k_col_final, dim3(P / s.bins), dim3(kThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
+  hipLaunchKernelGGL(k_col_final, dim3(P / s.bins), dim3(kFinalThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
                      nparts, s.bins, lpr, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
   LAUNCH_CHECK();
   hipLaunchKernelGGL((k_sqnorm<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, Kp, kbar, s.n, pl.npad, pl.dpad, d0,
@@ -1291,13 +1306,9 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     const int rc = enqueue_pack_values(P / s.bins, s.r * s.bins, s.dv, out->v_s, out->v_t, out->v_scale, st);
     if (rc != WILDCAT_OK) return rc;
   }
-  hipLaunchKernelGGL((k_gather<T>), dim3(s.r, P), dim3(64), 0, st, K, out->idx, s.n, s.d, s.r, (T *)out->k_s);
+  hipLaunchKernelGGL((k_gather<T>), dim3(s.r, P), dim3(64), 0, st, K, out->idx, s.n, s.d, s.r, s.bins,
+                     (T *)out->k_s);
   LAUNCH_CHECK();
-  if (s.bins > 1) {
-    const int total = P * s.r;
-    hipLaunchKernelGGL(k_globalise_idx, dim3((total + 255) / 256), dim3(256), 0, st, out->idx, s.r, s.bins, s.n, total);
-    LAUNCH_CHECK();
-  }
   return WILDCAT_OK;
 }
 

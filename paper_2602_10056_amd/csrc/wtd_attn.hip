@@ -37,6 +37,14 @@ __global__ void k_zero_u64(unsigned long long *x, int count) {
   if (i < count) x[i] = 0ull;
 }
 
+// The accumulator holds the bit pattern of the largest norm so far (sqrt is monotone and correctly rounded, so the
+// largest norm is the root of the largest squared norm).  It only grows: a workgroup whose maximum is not above
+// what is already there skips the contended atomic (a stale read merely costs an atomic that changes nothing).
+__device__ __forceinline__ void publish_radius(unsigned long long *acc, double max_sq) {
+  const unsigned long long bits = (unsigned long long)__double_as_longlong(sqrt(max_sq));
+  if (bits > __hip_atomic_load(acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(acc, bits);
+}
+
 // Generic version: one thread per query row.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_qnorm_max(const T *__restrict__ Q, int64_t m, int d, int q_heads,
@@ -55,7 +63,7 @@ __global__ __launch_bounds__(kThreads) void k_qnorm_max(const T *__restrict__ Q,
     }
   }
   s = block_reduce<double>(s, sm, MaxOp());
-  if (threadIdx.x == 0) atomicMax(&acc[pr], (unsigned long long)__double_as_longlong(s));
+  if (threadIdx.x == 0) publish_radius(&acc[pr], s);
 }
 
 // Coalesced version for rows that are a power-of-two number (<= 64) of 16-byte pieces: LPR lanes share a
@@ -83,7 +91,8 @@ __device__ __forceinline__ double sumsq16(const uint4 v, bf16_t) {
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_qnorm_max_vec(const T *__restrict__ Q, int64_t m, int d, int lpr,
                                                             int q_heads, int group,
-                                                            unsigned long long *__restrict__ acc) {
+                                                            unsigned long long *__restrict__ acc,
+                                                            double *__restrict__ partial) {
   __shared__ double sm[kThreads / kWave];
   const int bh = blockIdx.y;
   const int b = bh / q_heads, hq = bh % q_heads;
@@ -98,12 +107,23 @@ __global__ __launch_bounds__(kThreads) void k_qnorm_max_vec(const T *__restrict_
     best = fmax(best, s);
   }
   best = block_reduce<double>(best, sm, MaxOp());
-  if (threadIdx.x == 0) atomicMax(&acc[pr], (unsigned long long)__double_as_longlong(best));
+  if (threadIdx.x == 0) {
+    if (partial) partial[(size_t)bh * gridDim.x + blockIdx.x] = best;     // combined by k_radius_final
+    else publish_radius(&acc[pr], best);
+  }
 }
 
-__global__ void k_sqrt_inplace(double *x, int count) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < count) x[i] = sqrt(x[i]);
+// Second stage when scratch memory is available: thousands of atomics on a handful of addresses serialise (they
+// cost more than reading Q), plain per-workgroup results combined here do not.  grid P; `count` = group * blocks
+// consecutive partial maxima of squared norms belong to one kv head.
+__global__ __launch_bounds__(kThreads) void k_radius_final(const double *__restrict__ partial, int count,
+                                                           double *__restrict__ r_q_out) {
+  __shared__ double sm[kThreads / kWave];
+  const int pr = blockIdx.x;
+  double best = 0.0;
+  for (int e = threadIdx.x; e < count; e += kThreads) best = fmax(best, partial[(size_t)pr * count + e]);
+  best = block_reduce<double>(best, sm, MaxOp());
+  if (threadIdx.x == 0) r_q_out[pr] = sqrt(best);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -595,7 +615,15 @@ int launch_mfma2(const Shape &s, const void *Q, const wildcat_coreset *cs, void 
   const int64_t qtiles = (s.m + NW * 32 - 1) / (NW * 32);
   const int64_t total = qtiles * s.batch * s.q_heads;
   if (total > INT32_MAX) return WILDCAT_EUNSUPPORTED;
-  const int64_t resident = (int64_t)compute_units() * (8 / NW);     // workgroups that fit on the device at once
+  // Persistent grid: as many workgroups as fit on the device at once (two per compute unit by the launch bounds,
+  // three where the registers of the narrower instantiations allow it).
+  static int per_cu = 0;
+  if (per_cu == 0) {
+    int occ = 0;
+    per_cu = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void *)k_wtd_attn_mfma2<D, DV, NW>, NW * 64,
+                                                           0) == hipSuccess && occ >= 1) ? occ : 8 / NW;
+  }
+  const int64_t resident = (int64_t)compute_units() * per_cu;
   const unsigned grid = (unsigned)(total < resident ? total : resident);
   hipLaunchKernelGGL((k_wtd_attn_mfma2<D, DV, NW>), dim3(grid), dim3(NW * 64), 0, s.stream, (const bf16_t *)Q,
                      (const bf16_t *)cs->k_s, (const uint16_t *)cs->v_t, cs->v_scale, cs->w, cs->v_min, cs->v_max, cs->r_eff,
@@ -637,22 +665,34 @@ extern "C" int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const w
   Shape s;
   int rc = resolve_shape(m, m, d, 1, opts, &s);
   if (rc != WILDCAT_OK) return rc;
-  hipLaunchKernelGGL(k_zero_u64, dim3((s.P + 255) / 256), dim3(256), 0, s.stream, (unsigned long long *)r_q_out, s.P);
-  if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP;
   const int es = s.dtype == WILDCAT_BF16 ? 2 : 4;
   const int pieces = (d * es) % 16 == 0 ? d * es / 16 : 0;
-  if (pieces >= 1 && pieces <= kWave && (pieces & (pieces - 1)) == 0) {
-    const int rows_per_pass = kThreads / pieces;
-    int64_t blocks = (m + rows_per_pass - 1) / rows_per_pass;
-    const int64_t cap = (4096 + s.batch * s.q_heads - 1) / (s.batch * s.q_heads);
-    if (blocks > cap) blocks = cap;
+  const bool vec = pieces >= 1 && pieces <= kWave && (pieces & (pieces - 1)) == 0;
+  const int rows_per_pass = vec ? kThreads / pieces : kThreads;
+  int64_t blocks = (m + rows_per_pass - 1) / rows_per_pass;
+  const int64_t cap = (4096 + s.batch * s.q_heads - 1) / (s.batch * s.q_heads);
+  if (blocks > cap) blocks = cap;
+  // Optional scratch (see wildcat_query_radius in wildcat.h): one double per workgroup.
+  const size_t scratch = (size_t)s.batch * s.q_heads * blocks * sizeof(double);
+  double *partial = (vec && opts && opts->workspace && !((uintptr_t)opts->workspace & 255) &&
+                     opts->workspace_bytes >= scratch) ? (double *)opts->workspace : nullptr;
+  if (!partial) {
+    hipLaunchKernelGGL(k_zero_u64, dim3((s.P + 255) / 256), dim3(256), 0, s.stream, (unsigned long long *)r_q_out, s.P);
+    if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP;
+  }
+  if (vec) {
     const dim3 grid((unsigned)blocks, s.batch * s.q_heads);
     if (s.dtype == WILDCAT_BF16)
       hipLaunchKernelGGL((k_qnorm_max_vec<bf16_t>), grid, dim3(kThreads), 0, s.stream, (const bf16_t *)Q, m, d, pieces,
-                         s.q_heads, s.group, (unsigned long long *)r_q_out);
+                         s.q_heads, s.group, (unsigned long long *)r_q_out, partial);
     else
       hipLaunchKernelGGL((k_qnorm_max_vec<float>), grid, dim3(kThreads), 0, s.stream, (const float *)Q, m, d, pieces,
-                         s.q_heads, s.group, (unsigned long long *)r_q_out);
+                         s.q_heads, s.group, (unsigned long long *)r_q_out, partial);
+    if (partial) {
+      if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP;
+      hipLaunchKernelGGL(k_radius_final, dim3(s.P), dim3(kThreads), 0, s.stream, partial, (int)(s.group * blocks),
+                         r_q_out);
+    }
   } else {
     const dim3 grid((unsigned)((m + kThreads - 1) / kThreads), s.batch * s.q_heads);
     if (s.dtype == WILDCAT_BF16)
@@ -662,8 +702,6 @@ extern "C" int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const w
       hipLaunchKernelGGL((k_qnorm_max<float>), grid, dim3(kThreads), 0, s.stream, (const float *)Q, m, d, s.q_heads,
                          s.group, (unsigned long long *)r_q_out);
   }
-  if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP;
-  hipLaunchKernelGGL(k_sqrt_inplace, dim3((s.P + 255) / 256), dim3(256), 0, s.stream, r_q_out, s.P);
   return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
 }
 

@@ -193,9 +193,14 @@ def test_wtd_attn_guard_clip_and_oracle_coreset(dtype, d):
 def test_query_radius_grouped():
     rng = np.random.default_rng(3)
     Q = wl.round_to_storage(rng.standard_normal((2, 6, 700, 64)) * rng.uniform(0.5, 2, (2, 6, 1, 1)), "bf16")
-    got = wc.query_radius(to_dev(Q, "bf16"), kv_heads=2).cpu().numpy()
     nrm = np.sqrt((Q.astype(np.float64) ** 2).sum(-1)).reshape(2, 2, 3 * 700).max(-1)
+    got = wc.query_radius(to_dev(Q, "bf16"), kv_heads=2).cpu().numpy()            # atomic maxima
     np.testing.assert_allclose(got, nrm, rtol=1e-14)
+    scratch = torch.empty(8 * (4096 + 12), dtype=torch.uint8, device=dev())
+    got2 = wc.query_radius(to_dev(Q, "bf16"), kv_heads=2, workspace=scratch).cpu().numpy()   # per-workgroup maxima
+    np.testing.assert_array_equal(got2, got)
+    small = torch.empty(256, dtype=torch.uint8, device=dev())                      # too small: ignored, same result
+    np.testing.assert_array_equal(wc.query_radius(to_dev(Q, "bf16"), kv_heads=2, workspace=small).cpu().numpy(), got)
 
 
 # ---------------------------------------------------------------------------------- degenerate inputs
