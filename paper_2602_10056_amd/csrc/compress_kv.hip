@@ -949,32 +949,37 @@ __global__ __launch_bounds__(kThreads) void k_gram(const double *__restrict__ F,
 // are combined in a fixed order (lane butterfly, then the four wavefronts in turn).
 // grid (nchunk, 1, P); same partial-sum layout as k_gram.
 // --------------------------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ void load_value4(const T *__restrict__ row, int col, int dv, bool vec, double (&v)[4]);
-template <>
-__device__ __forceinline__ void load_value4<float>(const float *__restrict__ row, int col, int dv, bool vec,
-                                                   double (&v)[4]) {
-  if (vec) {
-    const float4 x = *reinterpret_cast<const float4 *>(row + col);
-    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-  } else {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) v[c] = col + c < dv ? (double)row[col + c] : 0.0;
+// Four adjacent value columns of one row, kept in storage form until they are used (so that several rows can be
+// in flight per thread without spending fp64 registers on them).  `vec`: rows are 4-element aligned.
+template <typename T> struct Value4;
+template <> struct Value4<float> {
+  float4 raw;
+  __device__ __forceinline__ void load(const float *__restrict__ row, int col, int dv, bool vec) {
+    if (vec) raw = *reinterpret_cast<const float4 *>(row + col);
+    else raw = make_float4(col < dv ? row[col] : 0.f, col + 1 < dv ? row[col + 1] : 0.f,
+                           col + 2 < dv ? row[col + 2] : 0.f, col + 3 < dv ? row[col + 3] : 0.f);
   }
-}
-template <>
-__device__ __forceinline__ void load_value4<bf16_t>(const bf16_t *__restrict__ row, int col, int dv, bool vec,
-                                                    double (&v)[4]) {
-  if (vec) {
+  __device__ __forceinline__ void widen(double (&v)[4]) const { v[0] = raw.x; v[1] = raw.y; v[2] = raw.z; v[3] = raw.w; }
+};
+template <> struct Value4<bf16_t> {
+  uint2 raw;
+  __device__ __forceinline__ void load(const bf16_t *__restrict__ row, int col, int dv, bool vec) {
+    if (vec) {
+      raw = *reinterpret_cast<const uint2 *>(row + col);
+    } else {
+      uint32_t e[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) e[c] = col + c < dv ? row[col + c].bits : 0u;
+      raw = make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
+    }
+  }
+  __device__ __forceinline__ void widen(double (&v)[4]) const {
     float x[kChunk];
-    unpack_bf16x4(*reinterpret_cast<const uint2 *>(row + col), x);
+    unpack_bf16x4(raw, x);
 #pragma unroll
     for (int c = 0; c < 4; ++c) v[c] = (double)x[c];
-  } else {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) v[c] = col + c < dv ? (double)to_float(row[col + c]) : 0.0;
   }
-}
+};
 
 template <typename T, int R>
 __global__ __launch_bounds__(kThreads) void k_gram_small(const double *__restrict__ F, const T *__restrict__ V,
@@ -1000,20 +1005,32 @@ __global__ __launch_bounds__(kThreads) void k_gram_small(const double *__restric
   const T *Vp = V + (size_t)pr * n * dv;
   for (int sb = sb0; sb < sb1; ++sb) {
     const double *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
-#pragma unroll 2
-    for (int k0 = 0; k0 < slab; k0 += kgs) {
-      const int l_loc = k0 + kg;
-      const int64_t l = (int64_t)sb * slab + l_loc;
-      if (l >= n || !active) continue;
-      double v[4], f[R];
-      load_value4<T>(Vp + (size_t)l * dv, col, dv, vec, v);
+    constexpr int U = R <= 4 ? 4 : (R <= 8 ? 2 : 1);             // keys in flight per thread
+    for (int k0 = 0; k0 < slab; k0 += U * kgs) {
+      Value4<T> raw[U];
+      double f[U][R];
+      bool ok[U];
 #pragma unroll
-      for (int j = 0; j < R; ++j) f[j] = j < r ? Fslab[(size_t)j * slab + l_loc] : 0.0;
+      for (int q = 0; q < U; ++q) {
+        const int l_loc = k0 + q * kgs + kg;
+        const int64_t l = (int64_t)sb * slab + l_loc;
+        ok[q] = active && l_loc < slab && l < n;                  // F is zero beyond n, V does not exist there
+        const int l_safe = ok[q] ? l_loc : 0;
+        raw[q].load(Vp + (size_t)(ok[q] ? l : 0) * dv, active ? col : 0, dv, vec);
 #pragma unroll
-      for (int j = 0; j < R; ++j) {
-        rs[j] += f[j];
+        for (int j = 0; j < R; ++j) f[q][j] = (ok[q] && j < r) ? Fslab[(size_t)j * slab + l_safe] : 0.0;
+      }
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc[j][c] = fma(f[j], v[c], acc[j][c]);
+      for (int q = 0; q < U; ++q) {
+        double v[4];
+        raw[q].widen(v);
+        if (!ok[q]) v[0] = v[1] = v[2] = v[3] = 0.0;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+          rs[j] += f[q][j];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[j][c] = fma(f[q][j], v[c], acc[j][c]);
+        }
       }
     }
   }
