@@ -116,9 +116,9 @@ def main():
     es = 2 if s.dtype == "bf16" else 4
     Q, K, V = (torch.from_numpy(w[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
     u = torch.from_numpy(w["u"]).to(dev)
-    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.d, 1 if s.dtype == "bf16" else 0, s.bins),
+    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins),
                      dtype=torch.uint8, device=dev)
-    out = torch.empty((s.batch, s.q_heads, s.n, s.d), dtype=tdt, device=dev)
+    out = torch.empty((s.batch, s.q_heads, s.m, s.dv), dtype=tdt, device=dev)
     hev = HipEvents()
     loop_ev = [(hev.create(), hev.create()) for _ in range(args.steps)]
     marks = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
@@ -157,7 +157,7 @@ def main():
     loop_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in loop_ev]))
     ph = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(3)] for m in marks]).mean(axis=0)
     P = s.problems
-    single = wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, s.d, 1 if s.dtype == "bf16" else 0, s.bins)
+    single = wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins)
     launches = 1 if single else s.r // s.bins
     # with bins the loop is P * B independent problems of n / B keys and r / B steps
     loop_bytes = step_loop_bytes(P * s.bins, s.n // s.bins, s.d, s.r // s.bins, es, single)
@@ -167,7 +167,7 @@ def main():
     if os.path.exists(tfile) and args.cfg == 4:
         with open(tfile) as f:
             traffic = json.load(f).get("single_launch" if single else "per_step", {}).get("hbm_bytes_per_launch")
-    attn_flops = float(s.batch * s.q_heads) * s.n * (4.0 * s.r * s.d + 2.0 * s.r)
+    attn_flops = float(s.batch * s.q_heads) * s.m * (2.0 * s.r * (s.d + s.dv) + 2.0 * s.r)
     attn_tflops = attn_flops / (ph[2] * 1e-3) / 1e12
 
     res = {
@@ -179,7 +179,7 @@ def main():
         "dtype": "f64",
         "data": "synthetic",
         "config": {"workload": f"{s.name}: batch {s.batch} x {s.q_heads} query heads / {s.kv_heads} kv heads, "
-                               f"n=m={s.n}, d={s.d}, r={s.r}, B={s.bins}, {s.dtype} storage; selection loop in fp64, "
+                               f"n={s.n}, m={s.m}, d={s.d}, d_v={s.dv}, r={s.r}, B={s.bins}, {s.dtype} storage; selection loop in fp64, "
                                f"WtdAttn on MFMA (bf16 scores, fp16 value product) with fp32 accumulation",
                    "uniform_seed": s.uniform_seed, "data_seed": s.data_seed},
         "phases_ms": {"query_radius": float(ph[0]), "compress_kv": float(ph[1]), "rpnys_loop": loop_ms,

@@ -8,7 +8,7 @@ returned as float32 holding exactly representable values, so both consumers
 see identical numbers.
 
 Workloads (Q: [batch, q_heads, m, d], K: [batch, kv_heads, n, d],
-V: [batch, kv_heads, n, d_v]; m = n and d_v = d throughout; beta = 1/sqrt(d)):
+V: [batch, kv_heads, n, d_v]; m = n and d_v = d unless stated; beta = 1/sqrt(d)):
 
   1  one head, n=1024, d=64, r=64, fp32; i.i.d. N(0,1), keys scaled by 1/sqrt(d)
      (the Gaussian inputs of the paper's FlashAttention-2 study, Sec. 5.4)
@@ -24,6 +24,14 @@ V: [batch, kv_heads, n, d_v]; m = n and d_v = d throughout; beta = 1/sqrt(d)):
   6  binned (Sec. 2.5): 8 heads, n=65536, d=64, r=64 in B=16 bins, bf16; Q, K, V
      all i.i.d. N(0,1) -- the setting of the paper's FlashAttention-2 comparison
      (Sec. 5.4: d=64, r=64, B=16, n from 2^13 to 2^18; head count not stated)
+
+  7  binned, m != n and d_v != d: the single attention layer of the paper's image
+     generation benchmark (Sec. 5.1: Q 4096 x 64, K 1024 x 64, V 1024 x 256,
+     r=96, B=8); 8 images x 1 head, fp32; tokens from a 64-component Gaussian
+     mixture as in workload 3 (the benchmark's real activations need the model)
+  8  binned with one pivot per bin: the first tokens-to-token layer of the
+     paper's image classification benchmark (Sec. 5.2: n=m=3136, d=64,
+     r=B=224, i.e. bins of 14 keys); 8 images x 1 head, fp32; mixture tokens
 
 Shapes 1-5 use one bin (B = 1); `bins` can be overridden for any of them.
 """
@@ -47,6 +55,16 @@ class Shape:
     data_seed: int
     uniform_seed: int
     bins: int = 1       # B of Alg. 2
+    m_: int = 0         # queries per head (0: n)
+    dv_: int = 0        # value width (0: d)
+
+    @property
+    def m(self):
+        return self.m_ or self.n
+
+    @property
+    def dv(self):
+        return self.dv_ or self.d
 
     @property
     def problems(self):
@@ -68,6 +86,8 @@ SHAPES = {
     4: Shape("cfg4_gqa_rope_bf16", 1, 32, 8, 32768, 128, 512, "bf16", 104, 204),
     5: Shape("cfg5_heavytail_bf16", 1, 8, 8, 131072, 128, 1024, "bf16", 105, 205),
     6: Shape("cfg6_gauss_binned_bf16", 1, 8, 8, 65536, 64, 64, "bf16", 106, 206, bins=16),
+    7: Shape("cfg7_imagegen_layer_f32", 8, 1, 1, 1024, 64, 96, "f32", 107, 207, bins=8, m_=4096, dv_=256),
+    8: Shape("cfg8_t2t_layer1_f32", 8, 1, 1, 3136, 64, 224, "f32", 108, 208, bins=224),
 }
 
 
@@ -123,9 +143,11 @@ def _head_rng(s, kind, b, h):
 
 
 def make_kv_head(cfg, s, b, h):
-    """(K [n,d], V [n,d]) of key/value head (b, h), storage-rounded float32."""
+    """(K [n,d], V [n,dv]) of key/value head (b, h), storage-rounded float32."""
     g = _head_rng(s, 0, b, h)
-    n, d = s.n, s.d
+    n, d, dv = s.n, s.d, s.dv
+    if dv != d and cfg not in (3, 7, 8):
+        raise ValueError("this recipe has d_v = d")
     if cfg == 1:
         K = g.standard_normal((n, d)) / np.sqrt(d)
         V = g.standard_normal((n, d))
@@ -134,10 +156,10 @@ def make_kv_head(cfg, s, b, h):
             + 0.1 * g.standard_normal((n, d))
         V = g.standard_normal((n, 32)) @ (g.standard_normal((32, d)) / np.sqrt(32.0)) \
             + 0.1 * g.standard_normal((n, d))
-    elif cfg == 3:
+    elif cfg in (3, 7, 8):
         mu = _centres(s, b, h)
         K = mu[g.integers(0, 64, size=n)] + 0.25 * g.standard_normal((n, d))
-        V = g.standard_normal((n, d))
+        V = g.standard_normal((n, dv))
     elif cfg == 4:
         K = _rope(g.standard_normal((n, d)), d)
         V = g.standard_normal((n, d))
@@ -164,11 +186,11 @@ def _centres(s, b, h_kv):
 def make_q_head(cfg, s, b, hq):
     """Q [m,d] of query head (b, hq), storage-rounded float32."""
     g = _head_rng(s, 1, b, hq)
-    n, d = s.n, s.d
+    n, d = s.m, s.d
     if cfg == 2:
         Q = g.standard_normal((n, 32)) @ (g.standard_normal((32, d)) / np.sqrt(32.0)) \
             + 0.1 * g.standard_normal((n, d))
-    elif cfg == 3:
+    elif cfg in (3, 7, 8):
         mu = _centres(s, b, hq // s.group)
         Q = mu[g.integers(0, 64, size=n)] + 0.25 * g.standard_normal((n, d))
     elif cfg == 4:
@@ -186,12 +208,12 @@ def uniforms(s):
 
 
 def make(cfg, **override):
-    """All tensors of workload `cfg`: dict with Q [B,Hq,n,d], K, V [B,Hkv,n,d]
+    """All tensors of workload `cfg`: dict with Q [B,Hq,m,d], K [B,Hkv,n,d], V [B,Hkv,n,dv]
     (float32 holding storage-exact values), u [B*Hkv, r], and the Shape."""
     s = shape(cfg, **override)
-    Q = np.empty((s.batch, s.q_heads, s.n, s.d), dtype=np.float32)
+    Q = np.empty((s.batch, s.q_heads, s.m, s.d), dtype=np.float32)
     K = np.empty((s.batch, s.kv_heads, s.n, s.d), dtype=np.float32)
-    V = np.empty((s.batch, s.kv_heads, s.n, s.d), dtype=np.float32)
+    V = np.empty((s.batch, s.kv_heads, s.n, s.dv), dtype=np.float32)
     for b in range(s.batch):
         for h in range(s.kv_heads):
             K[b, h], V[b, h] = make_kv_head(cfg, s, b, h)

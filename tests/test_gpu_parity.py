@@ -441,3 +441,19 @@ def test_binned_rank_ablation_corner_full_length():
     w = wl.make(4, q_heads=8, kv_heads=2, bins=64)
     out, cs = run_gpu(w)
     print(check_against_oracle(w, out, cs))
+
+
+# ---------------------------------------------------------------------------------- m != n, d_v != d (image-model layers)
+@pytest.mark.parametrize("cfg,ov", [
+    (7, {}),                                   # Q 4096 x 64, K 1024 x 64, V 1024 x 256, r = 96 in 8 bins, fp32
+    (7, dict(dtype="bf16", batch=2)),          # the same layer in bf16 storage (d_v = 256: vector-ALU WtdAttn)
+    (8, {}),                                   # n = m = 3136, 224 bins of 14 keys with one pivot each
+    (3, dict(q_heads=2, kv_heads=2, n=2048, m_=700, dv_=64, r=128)),    # bf16, d = 128, d_v = 64: MFMA <128, 64>
+    (2, dict(batch=1, q_heads=2, kv_heads=2, n=1024, m_=3000, r=64)),   # more queries than keys, one bin
+])
+def test_rectangular_shapes(cfg, ov):
+    w = wl.make(cfg, **ov)
+    s = w["shape"]
+    out, cs = run_gpu(w)
+    assert tuple(out.shape) == (s.batch, s.q_heads, s.m, s.dv) and tuple(cs.v_s.shape) == (s.batch, s.kv_heads, s.r, s.dv)
+    print(cfg, check_against_oracle(w, out, cs))

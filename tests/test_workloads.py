@@ -8,19 +8,23 @@ from paper_2602_10056_amd import workloads as wl
 @pytest.mark.parametrize("cfg,ov", [(1, {}), (2, dict(batch=1, q_heads=2, kv_heads=2, n=256)),
                                     (3, dict(q_heads=2, kv_heads=2, n=512)), (4, dict(q_heads=4, kv_heads=2, n=512)),
                                     (5, dict(q_heads=1, kv_heads=1, n=1024)),
-                                    (6, dict(q_heads=2, kv_heads=2, n=1024))])
+                                    (6, dict(q_heads=2, kv_heads=2, n=1024)), (7, dict(batch=2)),
+                                    (8, dict(batch=1))])
 def test_make_is_deterministic_and_storage_exact(cfg, ov):
     a, b = wl.make(cfg, **ov), wl.make(cfg, **ov)
     s = a["shape"]
     for k in ("Q", "K", "V", "u"):
         np.testing.assert_array_equal(a[k], b[k])
-    assert a["Q"].shape == (s.batch, s.q_heads, s.n, s.d) and a["K"].shape == (s.batch, s.kv_heads, s.n, s.d)
+    assert a["Q"].shape == (s.batch, s.q_heads, s.m, s.d) and a["K"].shape == (s.batch, s.kv_heads, s.n, s.d)
+    assert a["V"].shape == (s.batch, s.kv_heads, s.n, s.dv)
+    if cfg == 7:
+        assert (s.m, s.n, s.d, s.dv, s.r, s.bins) == (4096, 1024, 64, 256, 96, 8)
     assert a["u"].shape == (s.problems, s.r) and a["u"].min() >= 0 and a["u"].max() < 1
     if s.dtype == "bf16":
         for k in ("Q", "K", "V"):
             wl.bf16_bits(a[k])            # raises if a value is not bf16-representable
     assert not np.array_equal(a["K"][0, 0], a["V"][0, 0])
-    assert s.bins == (16 if cfg == 6 else 1) and s.n % s.bins == 0 and s.r % s.bins == 0
+    assert s.bins == {6: 16, 7: 8, 8: 224}.get(cfg, 1) and s.n % s.bins == 0 and s.r % s.bins == 0
 
 
 def test_bins_must_divide_length_and_rank():
