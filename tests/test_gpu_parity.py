@@ -457,3 +457,46 @@ def test_rectangular_shapes(cfg, ov):
     out, cs = run_gpu(w)
     assert tuple(out.shape) == (s.batch, s.q_heads, s.m, s.dv) and tuple(cs.v_s.shape) == (s.batch, s.kv_heads, s.r, s.dv)
     print(cfg, check_against_oracle(w, out, cs))
+
+
+# ---------------------------------------------------------------------------------- KV-cache use: decode against a stored coreset
+@pytest.mark.parametrize("m", [1, 7, 64])
+def test_decode_against_stored_coreset_with_exact_sink_and_recent_tokens(m):
+    """The paper's cache-compression setting (Sec. 5.3): the first and last 32 context tokens stay uncompressed, the
+    rest is compressed once (with a caller-supplied query radius), and later a few new queries attend to
+    [first 32 | coreset | last 32].  Exact tokens are coreset rows with unit weight and V_S = v (Alg. 3 accepts any
+    weighted coreset).  Checked against the oracle's Alg. 3 on the same assembly built from the oracle's Alg. 2."""
+    keep, heads, hq, n, d, r, bins = 32, 2, 4, 2048 + 64, 128, 192, 16
+    w = wl.make(4, q_heads=hq, kv_heads=heads, n=n, r=r, bins=bins)
+    s = w["shape"]
+    K, V = w["K"], w["V"]
+    mid = slice(keep, n - keep)
+    nm = n - 2 * keep
+    r_q = np.full((1, heads), 1.25 * np.sqrt(d))                    # a bound the caller knows, not measured from Q
+    Kd, Vd = to_dev(K, "bf16"), to_dev(V, "bf16")
+    u = torch.from_numpy(w["u"]).to(dev())
+    cs = wc.compress_kv(Kd[:, :, mid].contiguous(), Vd[:, :, mid].contiguous(), r, torch.from_numpy(r_q).to(dev()),
+                        uniforms=u, bins=bins)
+    ends = lambda x: torch.cat([x[:, :, :keep], x[:, :, n - keep:]], dim=2)
+    full = wc.Coreset(
+        idx=torch.zeros((1, heads, r + 2 * keep), dtype=torch.int32, device=dev()), r_eff=None,
+        k_s=torch.cat([Kd[:, :, :keep], cs.k_s, Kd[:, :, n - keep:]], dim=2).contiguous(),
+        v_s=torch.cat([Vd[:, :, :keep].float(), cs.v_s, Vd[:, :, n - keep:].float()], dim=2).contiguous(),
+        w=torch.cat([torch.ones((1, heads, keep), device=dev()), cs.w, torch.ones((1, heads, keep), device=dev())],
+                    dim=2).contiguous(),
+        v_min=torch.minimum(cs.v_min, ends(Vd).float().amin(dim=2)), v_max=torch.maximum(cs.v_max, ends(Vd).float().amax(dim=2)),
+        tau=None)
+    wc.pack_values(full)
+    Qn = w["Q"][:, :, :m]                                            # the "new" queries
+    out = wc.wtd_attn(to_dev(Qn, "bf16"), full).float().cpu().numpy()
+    for h in range(heads):
+        Kh, Vh = K[0, h].astype(np.float64), V[0, h].astype(np.float64)
+        ocs = wo.compress_kv(Kh[mid], Vh[mid], float(r_q[0, h]), s.beta, r, w["u"][h], bins=bins)
+        np.testing.assert_array_equal(cs.idx[0, h].cpu().numpy(), ocs.idx)
+        KS = np.concatenate([Kh[:keep], ocs.K_S, Kh[n - keep:]])
+        VS = np.concatenate([Vh[:keep], ocs.V_S, Vh[n - keep:]])
+        ws_ = np.concatenate([np.ones(keep), ocs.w, np.ones(keep)])
+        for g in range(s.group):
+            ref = wo.wtd_attn(Qn[0, h * s.group + g].astype(np.float64), KS, VS, ws_, Vh.min(0), Vh.max(0), s.beta)
+            assert relmax(out[0, h * s.group + g].astype(np.float64), ref) <= TOL_OUT["bf16"]
+    assert nm % bins == 0
