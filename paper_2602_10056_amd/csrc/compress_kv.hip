@@ -560,11 +560,12 @@ struct StepShared {
 template <typename T, int KPT, int NC, bool POLL>
 __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int pr, double *g, double *ksc,
                                           StepShared &sh, const KeyRegs<T, KPT, NC> &kr, double (&pown)[KPT],
-                                          const double (&flo)[KPT], int *error, long long spin_limit) {
+                                          const double (&flo)[KPT], int *error, long long spin_limit, int hcn) {
   constexpr int SLAB = kThreads * KPT;
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
   const int rd = i & 1, wr = rd ^ 1;
+  double *hc = g + ((a.r + a.dpad + 1) & ~1);                    // history cache [hcn][SLAB] behind g and ksc in LDS
   const double *bs = a.bsum + ((size_t)pr * a.r + i) * a.nblk;
   double *bs_next = a.bsum + ((size_t)pr * a.r + i + 1) * a.nblk;     // written only if i + 1 < r
   const double *pin = a.p + ((size_t)rd * a.P + pr) * a.npad;
@@ -689,17 +690,27 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   // Rows are walked upwards on even steps and downwards on odd steps: the rows a step reads last are the
   // rows the next step reads first, so whatever part of the history the memory-side cache still holds is
   // reused before it is evicted.  (The order is fixed per step, so results stay reproducible.)
+  // The first hcn rows of this slab's history are also kept in LDS (`hc`, persistent driver only): they are the rows
+  // every later step needs, so caching them removes about 2 hcn / r of the stream.  Cached rows are added first, in
+  // ascending order; the direction of the walk alternates over the remaining rows only.
   double acc[KPT];
 #pragma unroll
   for (int k = 0; k < KPT; ++k) acc[k] = 0.0;
   {
     const bool down = (i & 1) != 0;
+    const int nc_rows = i < hcn ? i : hcn;                   // rows [0, nc_rows) come from LDS
+    const int nh = i - nc_rows;                              // rows [nc_rows, i) from memory
+    for (int j = 0; j < nc_rows; ++j) {                       // cached rows, always first and upwards
+      const double gj = g[j];
+#pragma unroll
+      for (int k = 0; k < KPT; ++k) acc[k] = fma(hc[(size_t)j * SLAB + l_loc + k], gj, acc[k]);
+    }
     const ptrdiff_t fstep = down ? -(ptrdiff_t)SLAB : (ptrdiff_t)SLAB;
     const int gstep = down ? -1 : 1;
-    const double *fp = Fb + l_loc + (down ? (size_t)(i - 1) * SLAB : 0);
-    const double *gp = g + (down ? i - 1 : 0);
+    const double *fp = Fb + l_loc + (size_t)(down ? i - 1 : nc_rows) * SLAB;
+    const double *gp = g + (down ? i - 1 : nc_rows);
     int j = 0;
-    for (; j + 8 <= i; j += 8) {
+    for (; j + 8 <= nh; j += 8) {
       HistVec<KPT> h[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) h[q].load(fp + q * fstep);
@@ -712,7 +723,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
       fp += 8 * fstep;
       gp += 8 * gstep;
     }
-    for (; j < i; ++j) {
+    for (; j < nh; ++j) {
       HistVec<KPT> h;
       h.load(fp);
       const double gj = *gp;
@@ -758,6 +769,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   double psum = 0.0;
   double fs = 0.0;
   bool own = false;
+  double fkeep[KPT];
 #pragma unroll
   for (int k = 0; k < KPT; ++k) {
     const int64_t l = l_glob + k;
@@ -767,11 +779,16 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     if (l == s_glob) { pn = 0.0; fs = f; own = true; }
     if (l >= a.n) { pn = 0.0; f = 0.0; }
     st_dev(Fb + (size_t)i * SLAB + l_loc + k, f);
+    fkeep[k] = f;
     st_dev(pout + l, pn);
     pown[k] = pn;
     psum += pn;
   }
   const double tot = block_sum(psum, sh.sm);
+  if (i < hcn) {                                             // this thread's entries of the new row, for its own later reads
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) hc[(size_t)i * SLAB + l_loc + k] = fkeep[k];
+  }
   if constexpr (POLL) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's p and history stores have completed
   __syncthreads();
   if (t == 0 && i + 1 < a.r) st_dev(bs_next + b, tot);       // publishes the sum and, with it, the whole step
@@ -804,7 +821,7 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
     flo[k] = a.floor[(size_t)pr * a.npad + l_glob + k];
   }
   KeyRegs<T, KPT, 0> none;
-  if (rpnys_step<T, KPT, 0, false>(a, i, b, pr, dyn, dyn + a.r, sh, none, pown, flo, nullptr, 0) == 0) {
+  if (rpnys_step<T, KPT, 0, false>(a, i, b, pr, dyn, dyn + a.r, sh, none, pown, flo, nullptr, 0, 0) == 0) {
     // Residual mass exhausted: carry the (all-zero) state into the other parity, leave row i of F zero, record
     // the number of pivots once.
     double *pout = a.p + ((size_t)((i & 1) ^ 1) * a.P + pr) * a.npad;
@@ -827,7 +844,8 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 // NC > 0 a thread keeps the packed features of its keys in registers for the whole loop, which removes the
 // O(n d) key stream from every step.
 template <typename T, int KPT, int NC>
-__global__ __launch_bounds__(kThreads, 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit) {
+__global__ __launch_bounds__(kThreads, 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
+                                                                  int hcn) {
   extern __shared__ double dyn[];
   __shared__ StepShared sh;
   constexpr int SLAB = kThreads * KPT;
@@ -845,7 +863,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_rpnys_persistent(StepArgs a, in
                             a.npad);
   int i = 0, rc = 1;
   for (; i < a.r; ++i) {
-    rc = rpnys_step<T, KPT, NC, true>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit);
+    rc = rpnys_step<T, KPT, NC, true>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
     if (rc != 1) break;
   }
   if (rc == 0) {
@@ -1178,21 +1196,53 @@ __global__ void k_check_sync(const int *error, int P, int32_t *r_eff) {
     if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP; \
   } while (0)
 
-// The single-launch selection loop for this shape, or null if its workgroups cannot all be resident at once
-// (then the loop runs as one launch per step).
+// The single-launch selection loop for this shape (fn = null if its workgroups cannot all be resident at once; then
+// the loop runs as one launch per step), its dynamic LDS size and the number of history rows cached in LDS: whatever
+// LDS the compute unit has left once every workgroup it must hold has its share.
+struct LoopPlan {
+  const void *fn;
+  size_t lds;
+  int hcn;
+};
+
 template <typename T, int KPT>
-const void *persistent_kernel(const Shape &s, const Plan &pl) {
-  if (!pl.persistent) return nullptr;
+LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
+  LoopPlan lp = {nullptr, 0, 0};
+  if (!pl.persistent) return lp;
   const int nc = pl.dpad / kChunk;
   constexpr int regs_per_chunk = KPT * (sizeof(T) == 2 ? 2 : 4);
   const void *fn;
   if (nc == 32 && 32 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0)>;
   else if (nc == 16 && 16 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, 16>;
   else fn = (const void *)k_rpnys_persistent<T, KPT, 0>;
+  const int cus = compute_units();
+  const int64_t wgs = (int64_t)pl.nblk * s.P;
+  const int need = (int)((wgs + cus - 1) / cus);             // workgroups a compute unit must hold
+  const size_t base = (size_t)((s.r + pl.dpad + 1) & ~1) * sizeof(double);
   int per_cu = 0;
-  const size_t lds = (size_t)(s.r + pl.dpad) * sizeof(double);
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, lds) != hipSuccess) return nullptr;
-  return (int64_t)per_cu * compute_units() >= (int64_t)pl.nblk * s.P ? fn : nullptr;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess || per_cu < need) return lp;
+  lp.fn = fn;
+  lp.lds = base;
+  // History cache: optional, and only if the kernel stays resident with it.
+  int dev = 0, lds_cu = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) == hipSuccess && lds_cu > 0) {
+    const int64_t share = (int64_t)lds_cu / need - 2048 - (int64_t)base;    // static LDS and allocation granules
+    const int64_t row = (int64_t)kThreads * KPT * sizeof(double);
+    int hcn = share > 0 ? (int)(share / row) : 0;
+    if (hcn > s.r) hcn = s.r;
+    if (hcn > 0) {
+      const size_t lds = base + (size_t)hcn * row;
+      int per_cu2 = 0;
+      if ((lds <= 64 * 1024 ||
+           hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess) &&
+          hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu2, fn, kThreads, lds) == hipSuccess && per_cu2 >= need) {
+        lp.lds = lds;
+        lp.hcn = hcn;
+      }
+    }
+  }
+  return lp;
 }
 
 // `s` is the bin view of the request (wildcat::bin_view): P problems = bins, n keys and r pivots per bin.
@@ -1264,15 +1314,17 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
   const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
   bool done = false;
-  const void *fn = persistent_kernel<T, KPT>(s, pl);
+  const LoopPlan lp = persistent_kernel<T, KPT>(s, pl);
+  const void *fn = lp.fn;
   if (fn) {
     int *err_word = (int *)(ws + pl.off_sync);
     long long spin_limit = 2000000;    // polls of about a microsecond each: seconds, far beyond any real step
-    void *args[] = {(void *)&a, (void *)&err_word, (void *)&spin_limit};
+    int hcn = lp.hcn;
+    void *args[] = {(void *)&a, (void *)&err_word, (void *)&spin_limit, (void *)&hcn};
     // An ordinary launch: the grid was checked against the device's capacity (persistent_kernel), so on an idle
     // device every workgroup is resident at once; if other work holds compute units, the late workgroups start
     // when it ends and the resident ones poll meanwhile (bounded).
-    if (hipLaunchKernel(fn, dim3(pl.nblk, P), dim3(kThreads), args, step_lds, st) != hipSuccess) return WILDCAT_EHIP;
+    if (hipLaunchKernel(fn, dim3(pl.nblk, P), dim3(kThreads), args, lp.lds, st) != hipSuccess) return WILDCAT_EHIP;
     hipLaunchKernelGGL(k_check_sync, dim3(1), dim3(64), 0, st, err_word, P, out->r_eff);
     LAUNCH_CHECK();
     done = true;
@@ -1367,7 +1419,7 @@ extern "C" int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, cons
   if (s.r > kMaxRank) return WILDCAT_EUNSUPPORTED;
   const Plan pl = make_plan(s);
   const void *fn;
-  if (s.dtype == WILDCAT_BF16) fn = pl.kpt == 2 ? persistent_kernel<bf16_t, 2>(s, pl) : persistent_kernel<bf16_t, 1>(s, pl);
-  else fn = pl.kpt == 2 ? persistent_kernel<float, 2>(s, pl) : persistent_kernel<float, 1>(s, pl);
+  if (s.dtype == WILDCAT_BF16) fn = pl.kpt == 2 ? persistent_kernel<bf16_t, 2>(s, pl).fn : persistent_kernel<bf16_t, 1>(s, pl).fn;
+  else fn = pl.kpt == 2 ? persistent_kernel<float, 2>(s, pl).fn : persistent_kernel<float, 1>(s, pl).fn;
   return fn ? 1 : 0;
 }

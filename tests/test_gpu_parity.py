@@ -301,9 +301,10 @@ def test_full_size_config3():
     print(_full_size(3, heads=[0, 9], prefix_r=64))
 
 
-def test_both_loop_drivers_agree_bit_for_bit(monkeypatch):
-    """The persistent single-launch loop and the one-launch-per-step loop run the same step function: identical
-    pivots, weights and values; both equal the oracle."""
+def test_both_loop_drivers_agree(monkeypatch):
+    """The persistent single-launch loop and the one-launch-per-step loop run the same step function.  The persistent
+    one adds the history rows it keeps in LDS first, so the two differ in the rounding of fp64 sums: identical
+    pivots, weights and values equal to fp32 rounding noise; both equal the oracle."""
     w = wl.make(4, q_heads=4, kv_heads=2, n=4096, r=160)
     s = w["shape"]
     assert wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads) is True
@@ -312,8 +313,10 @@ def test_both_loop_drivers_agree_bit_for_bit(monkeypatch):
     assert wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads) is False
     o2, c2 = run_gpu(w)
     monkeypatch.delenv("WILDCAT_RPNYS_LOOP")
-    for a, b in ((o1, o2), (c1.idx, c2.idx), (c1.w, c2.w), (c1.v_s, c2.v_s), (c1.r_eff, c2.r_eff), (c1.v_t, c2.v_t)):
-        assert torch.equal(a, b)
+    assert torch.equal(c1.idx, c2.idx) and torch.equal(c1.r_eff, c2.r_eff) and torch.equal(c1.k_s, c2.k_s)
+    for a, b in ((c1.w, c2.w), (c1.v_s, c2.v_s)):
+        assert float((a - b).abs().max()) <= 1e-6 * float(b.abs().max())
+    check_against_oracle(w, o1, c1)
     check_against_oracle(w, o2, c2)
 
 
