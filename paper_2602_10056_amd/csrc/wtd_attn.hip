@@ -221,8 +221,11 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 // The kernel works on transposed tiles so that all softmax state of a query lives in one lane pair:
 // S^T = K_S Q^T (bf16 operands) and O^T = V_S^T P^T.  In an S^T tile rows = keys and columns = queries, so lane l
 // holds 16 key scores of query l % 32 and lane l ^ 32 the other 16.  Registers 8h .. 8h+7 of such a tile, converted
-// to half precision, are used directly as the B operand of the value product; the A operand (V_S^T, rows = value
-// columns) is read from LDS with the matching key order {16h + 4g + 0..3, 16h + 8 + 4g + 0..3}.
+// to half precision, are used directly as the B operand of the value product.  They are rows
+// {16h + 4g + 0..3, 16h + 8 + 4g + 0..3} of the tile; so that they are the eight CONSECUTIVE keys 16h + 8g + 0..7
+// that lane group g must supply (and one 16-byte LDS read fetches the matching piece of V_S^T), the key tile is
+// stored with its rows permuted: LDS row rho holds key pi(rho) = rho with bits 2 and 3 exchanged (softmax does
+// not care in which order it sees the keys; only the loads, the weights and the ragged-tile mask follow pi).
 //
 // The value product runs on fp16 operands, not bf16.  Nystrom weights have both signs, so numerator and normaliser
 // of Alg. 3 can be far smaller than the sum of the magnitudes of their terms (hundreds of times for some queries of
@@ -406,7 +409,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        if (c.k0 + 32 * mt + 8 * (v / 4) + 4 * g + (v % 4) >= c.re) st[mt][v] = -INFINITY;
+        if (c.k0 + 32 * mt + 16 * (v / 8) + 8 * g + 4 * ((v / 4) % 2) + (v % 4) >= c.re) st[mt][v] = -INFINITY;
   }
   // ---- row maximum of the raw scores; move the reference only if it is more than the slack behind ------------
   float mx = st[0][0];
@@ -437,7 +440,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
     for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(st[mt][v], c.scale_log2, nm));
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const float4 wv4 = *reinterpret_cast<const float4 *>(&lwr[32 * mt + 8 * q + 4 * g]);
+      const float4 wv4 = *reinterpret_cast<const float4 *>(&lwr[32 * mt + 16 * (q / 2) + 8 * g + 4 * (q % 2)]);
       dl = fmaf(p[4 * q + 0], wv4.x, dl);
       dl = fmaf(p[4 * q + 1], wv4.y, dl);
       dl = fmaf(p[4 * q + 2], wv4.z, dl);
@@ -455,17 +458,13 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
     }
   }
   c.den += dl;
-  // ---- O^T += V_S^T P^T: A operand = keys {16kb + 4g + 0..3, 16kb + 8 + 4g + 0..3} of value column c32 -----------
+  // ---- O^T += V_S^T P^T: A operand = keys 16kb + 8g + 0..7 of value column c32, one 16-byte piece ---------------
 #pragma unroll
   for (int kb = 0; kb < 4; ++kb) {
 #pragma unroll
     for (int i = 0; i < DV / 32; ++i) {
-      const uint16_t *rowp = &lvr[(32 * i + c32) * kKT + 4 * g];
-      const uint2 lo = *reinterpret_cast<const uint2 *>(rowp + ((2 * kb) ^ c.vrow_sw) * 8);
-      const uint2 hi = *reinterpret_cast<const uint2 *>(rowp + ((2 * kb + 1) ^ c.vrow_sw) * 8);
-      const uint4 av = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      c.acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const f16x8 *>(&av), pf[kb], c.acc[i], 0, 0,
-                                                        0);
+      const f16x8 av = *reinterpret_cast<const f16x8 *>(&lvr[(32 * i + c32) * kKT + ((2 * kb + g) ^ c.vrow_sw) * 8]);
+      c.acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, pf[kb], c.acc[i], 0, 0, 0);
     }
   }
   if (last_tile) {
@@ -532,7 +531,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
 #pragma unroll
   for (int e = 0; e < G::KLOADS; ++e) {      // LDS piece (e NW + wv) 64 + l holds key row `row`, logical piece `slot ^ ...`
     const int idx = (e * NW + c.wv) * 64 + c.l, row = idx / G::KPPR, slot = idx % G::KPPR;
-    c.krow[e] = row;
+    c.krow[e] = (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1);      // LDS row `row` holds key pi(row), see attn_tile
     c.kcol[e] = (slot ^ ((row / G::KRP) % G::KPPR)) * 8;
   }
 #pragma unroll
