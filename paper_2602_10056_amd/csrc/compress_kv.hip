@@ -3,7 +3,7 @@
 // Bins (Sec. 2.5) are handled as a batch: B contiguous bins of n/B keys are a reshape of K and V, so every kernel
 // below simply sees P * B problems of n/B keys and r/B pivots ("problem" = one bin of one (batch, kv head) pair).
 // Only three things know about the grouping: the key mean and the value range are taken over all bins of a head
-// (k_col_final), the temperature reads R_Q of the bin's head (k_tau), and pivot indices are made global at the end.
+// (k_col_final), the temperature reads R_Q of the bin's head (k_init_p), and pivot indices are made global at the end.
 //
 // The selection loop is bound by HBM bandwidth: step i must touch, for every key l, the i numbers
 // already computed for that key.  Everything here is laid out so that this stream is contiguous and
@@ -373,34 +373,28 @@ __device__ double lambert_w0(double z) {
   return w;
 }
 
-// P problems (bins), r_q per head (bins consecutive problems); n = the sequence length that enters b0.
-__global__ void k_tau(int P, int bins, int64_t n, double beta, const double *__restrict__ r_q,
-                      double *__restrict__ scal, double *__restrict__ tau_out) {
-  const int pr = blockIdx.x * blockDim.x + threadIdx.x;
-  if (pr >= P) return;
-  const double rk = sqrt(__longlong_as_double(((const long long *)scal)[(size_t)pr * 8]));
-  const double rq = r_q[pr / bins];
-  double tau, beta_tau;
+// Evaluated by one thread of every workgroup of k_init_p (same inputs, same arithmetic, same value everywhere).
+__device__ void temperature(double rk2, double rq, double n, double beta, double *tau, double *beta_tau, double *rk_out) {
+  const double rk = sqrt(rk2);
   if (!(rk > 0.0) || !(rq > 0.0)) {
-    tau = INFINITY;
-    beta_tau = 0.0;
+    *tau = INFINITY;
+    *beta_tau = 0.0;
   } else {
     const double rho0 = sqrt(1.0 + exp(lambert_w0(2.0 * exp(-2.0)) + 2.0));
-    const double b0 = log((double)n) / (beta * rq * rk) + 2.0;
+    const double b0 = log(n) / (beta * rq * rk) + 2.0;
     const double rho = b0 / (2.0 * lambert_w0(b0 / (2.0 * rho0)));
-    tau = sqrt(rho * rk / rq);
-    beta_tau = beta / (tau * tau);
+    *tau = sqrt(rho * rk / rq);
+    *beta_tau = beta / (*tau * *tau);
   }
-  scal[(size_t)pr * 8 + 1] = tau;
-  scal[(size_t)pr * 8 + 2] = beta_tau;
-  scal[(size_t)pr * 8 + 3] = rk;
-  tau_out[pr] = tau;
+  *rk_out = rk;
 }
 
 // --------------------------------------------------------------------------------------------
+// The temperature of the problem (bin) from its R_K^2 (scal[8 pr], left by k_sqnorm) and the R_Q of its head, then
 // Alg. 1, first line: p_l = h_tau(k_l, k_l) = exp(beta_tau ||k_l - kbar||^2); also the per-key floor
 // rank_tol * p_l, the per-slab sums, idx = -1, r_eff = r and (if asked) the uniforms of the seed.
-// grid (nblk, P).  sq_floor holds sq on entry and the floor on exit.
+// grid (nblk, P).  sq_floor holds sq on entry and the floor on exit.  Workgroup 0 of a problem records tau,
+// beta / tau^2 and R_K in scal[8 pr + 1 .. 3] and tau in tau_out.  tau_n = the sequence length that enters b0.
 // --------------------------------------------------------------------------------------------
 __device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -410,14 +404,30 @@ __device__ __forceinline__ unsigned long long mix64(unsigned long long z) {
 
 template <int KPT>
 __global__ __launch_bounds__(kThreads) void k_init_p(int64_t n, int64_t npad, int nblk, int r, double rank_tol,
-                                                     const double *__restrict__ scal, double *__restrict__ sq_floor,
+                                                     int bins, double tau_n, double beta,
+                                                     const double *__restrict__ r_q, double *__restrict__ scal,
+                                                     double *__restrict__ tau_out, double *__restrict__ sq_floor,
                                                      double *__restrict__ p0, double *__restrict__ bsum0,
                                                      int32_t *__restrict__ idx, int32_t *__restrict__ r_eff,
                                                      double *__restrict__ u_gen, unsigned long long seed,
                                                      int *__restrict__ sync_error) {
   __shared__ double sm[kThreads / kWave];
+  __shared__ double s_beta_tau;
   const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
-  const double beta_tau = scal[(size_t)pr * 8 + 2];
+  if (t == 0) {
+    double tau, bt, rk;
+    temperature(__longlong_as_double(((const long long *)scal)[(size_t)pr * 8]), r_q[pr / bins], tau_n, beta, &tau, &bt,
+                &rk);
+    s_beta_tau = bt;
+    if (b == 0) {
+      scal[(size_t)pr * 8 + 1] = tau;
+      scal[(size_t)pr * 8 + 2] = bt;
+      scal[(size_t)pr * 8 + 3] = rk;
+      tau_out[pr] = tau;
+    }
+  }
+  __syncthreads();
+  const double beta_tau = s_beta_tau;
   const int64_t l0 = (int64_t)b * (kThreads * KPT) + t * KPT;
   double loc = 0.0;
 #pragma unroll
@@ -1299,12 +1309,10 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   hipLaunchKernelGGL((k_sqnorm<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, Kp, kbar, s.n, pl.npad, pl.dpad, d0,
                      (unsigned long long *)scal);
   LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_tau, dim3((P + 63) / 64), dim3(64), 0, st, P, s.bins, s.tau_full_n ? s.n * s.bins : s.n, s.beta,
-                     o->r_q, scal, out->tau);
-  LAUNCH_CHECK();
   hipLaunchKernelGGL((k_init_p<KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, s.n, pl.npad, pl.nblk, s.r, s.rank_tol,
-                     scal, d0, p, bsum, out->idx, out->r_eff, o->uniforms ? (double *)nullptr : u_gen,
-                     (unsigned long long)seed, (int *)(ws + pl.off_sync));
+                     s.bins, (double)(s.tau_full_n ? s.n * s.bins : s.n), s.beta, o->r_q, scal, out->tau, d0, p, bsum,
+                     out->idx, out->r_eff, o->uniforms ? (double *)nullptr : u_gen, (unsigned long long)seed,
+                     (int *)(ws + pl.off_sync));
   LAUNCH_CHECK();
 
   StepArgs a;

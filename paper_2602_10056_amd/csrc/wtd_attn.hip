@@ -101,10 +101,20 @@ __global__ __launch_bounds__(kThreads) void k_qnorm_max_vec(const T *__restrict_
   const int sub = threadIdx.x % lpr, rloc = threadIdx.x / lpr;
   const uint4 *base = reinterpret_cast<const uint4 *>(Q + (size_t)bh * m * d);
   double best = 0.0;
-  for (int64_t row = (int64_t)blockIdx.x * rows_per_pass + rloc; row < m; row += (int64_t)gridDim.x * rows_per_pass) {
-    double s = sumsq16(base[row * lpr + sub], T());
-    for (int off = lpr / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
-    best = fmax(best, s);
+  const int64_t stride = (int64_t)gridDim.x * rows_per_pass;
+  for (int64_t row0 = (int64_t)blockIdx.x * rows_per_pass + rloc; row0 < m; row0 += 4 * stride) {
+    uint4 v[4];                                            // four rows in flight per thread
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t row = row0 + q * stride;
+      v[q] = row < m ? base[row * lpr + sub] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      double s = sumsq16(v[q], T());
+      for (int off = lpr / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, kWave);
+      best = fmax(best, s);
+    }
   }
   best = block_reduce<double>(best, sm, MaxOp());
   if (threadIdx.x == 0) {
@@ -563,26 +573,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
 
 // ---- packed values: v_t[pr][c][j] = fp16(v_s[pr][j][c] / v_scale[pr]) for j < r, zero for r <= j < r64 -----------
 // v_scale[pr] = 2^(e - 14) with e the exponent of max |v_s[pr]|: the largest packed magnitude lies in [2^14, 2^15),
-// inside fp16's range with the full significand for everything within 2^-28 of it.  Four small launches:
-// clear, maximum (as a bit pattern, integer atomic: exact and order independent), pack, maximum -> scale.
-__global__ void k_zero_u32(uint32_t *x, int count) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < count) x[i] = 0u;
-}
-
-__global__ __launch_bounds__(kThreads) void k_vabs_max(const float *__restrict__ v_s, int count, uint32_t *vmax_bits) {
-  __shared__ uint32_t sm[kThreads / kWave];
-  const int pr = blockIdx.y;
-  const int gid = blockIdx.x * kThreads + threadIdx.x;
-  uint32_t b = 0u;
-  if (gid < count) {
-    b = __float_as_uint(v_s[(size_t)pr * count + gid]) & 0x7fffffffu;
-    if (b > 0x7f800000u) b = 0u;                            // NaN: ignored
-  }
-  b = block_reduce<uint32_t>(b, sm, MaxOp());
-  if (threadIdx.x == 0) atomicMax(&vmax_bits[pr], b);
-}
-
+// inside fp16's range with the full significand for everything within 2^-28 of it.  Two small launches: the scale
+// (one workgroup per problem, so no atomics and nothing to clear), then the packing.
 __device__ __forceinline__ float value_scale(uint32_t max_bits) {
   const int e = (int)(max_bits >> 23);                      // biased exponent of the maximum
   if (e == 0 || e == 255) return 1.0f;                      // zero / subnormal / infinite maximum: no scaling
@@ -590,21 +582,50 @@ __device__ __forceinline__ float value_scale(uint32_t max_bits) {
   return __uint_as_float((uint32_t)se << 23);
 }
 
+constexpr int kScaleThreads = 1024;
+
+__global__ __launch_bounds__(kScaleThreads) void k_value_scale(const float *__restrict__ v_s, int count,
+                                                               float *__restrict__ v_scale) {
+  __shared__ uint32_t sm[kScaleThreads / kWave];
+  const int pr = blockIdx.x, t = threadIdx.x;
+  const float *src = v_s + (size_t)pr * count;
+  uint32_t b = 0u;
+  for (int g0 = t; g0 < count; g0 += 8 * kScaleThreads) {   // eight loads in flight per thread
+    uint32_t x[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int gid = g0 + q * kScaleThreads;
+      x[q] = gid < count ? __float_as_uint(src[gid]) & 0x7fffffffu : 0u;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      if (x[q] > 0x7f800000u) x[q] = 0u;                    // NaN: ignored
+      b = b > x[q] ? b : x[q];
+    }
+  }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) {
+    const uint32_t o = __shfl_xor(b, off, kWave);
+    b = b > o ? b : o;
+  }
+  if (t % kWave == 0) sm[t / kWave] = b;
+  __syncthreads();
+  if (t == 0) {
+    for (int k = 1; k < kScaleThreads / kWave; ++k) b = b > sm[k] ? b : sm[k];
+    v_scale[pr] = value_scale(b);
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void k_pack_values(const float *__restrict__ v_s,
-                                                          const uint32_t *__restrict__ vmax_bits, int r, int r64,
-                                                          int dv, uint16_t *__restrict__ v_t) {
+                                                          const float *__restrict__ v_scale, int r, int r64, int dv,
+                                                          uint16_t *__restrict__ v_t) {
   const int pr = blockIdx.y;
   const int gid = blockIdx.x * kThreads + threadIdx.x;
   if (gid >= r64 * dv) return;
   const int c = gid / r64, j = gid % r64;
-  const float inv = 1.0f / value_scale(vmax_bits[pr]);      // exact: a power of two
+  const float inv = 1.0f / v_scale[pr];                     // exact: a power of two
   const _Float16 h = (_Float16)(j < r ? v_s[((size_t)pr * r + j) * dv + c] * inv : 0.0f);   // round to nearest even
   v_t[((size_t)pr * dv + c) * r64 + j] = *reinterpret_cast<const uint16_t *>(&h);
-}
-
-__global__ void k_finish_scale(uint32_t *vmax_bits, int count) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < count) vmax_bits[i] = __float_as_uint(value_scale(vmax_bits[i]));
 }
 
 template <int D, int DV>
@@ -645,13 +666,9 @@ int launch_simple(const Shape &s, const void *Q, const wildcat_coreset *cs, void
 
 int enqueue_pack_values(int P, int r, int dv, const float *v_s, void *v_t, float *v_scale, hipStream_t stream) {
   const int r64 = (r + 63) / 64 * 64;
-  uint32_t *bits = reinterpret_cast<uint32_t *>(v_scale);
-  hipLaunchKernelGGL(k_zero_u32, dim3((P + 255) / 256), dim3(256), 0, stream, bits, P);
-  hipLaunchKernelGGL(k_vabs_max, dim3((r * dv + kThreads - 1) / kThreads, P), dim3(kThreads), 0, stream, v_s, r * dv,
-                     bits);
+  hipLaunchKernelGGL(k_value_scale, dim3(P), dim3(kScaleThreads), 0, stream, v_s, r * dv, v_scale);
   hipLaunchKernelGGL(k_pack_values, dim3((r64 * dv + kThreads - 1) / kThreads, P), dim3(kThreads), 0, stream, v_s,
-                     (const uint32_t *)bits, r, r64, dv, (uint16_t *)v_t);
-  hipLaunchKernelGGL(k_finish_scale, dim3((P + 255) / 256), dim3(256), 0, stream, bits, P);
+                     (const float *)v_scale, r, r64, dv, (uint16_t *)v_t);
   return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
 }
 
