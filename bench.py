@@ -50,13 +50,14 @@ class HipEvents:
         return float(ms.value)
 
 
-def step_loop_bytes(P, n, d, r, es, single_launch):
+def step_loop_bytes(P, n, d, r, es, single_launch, hs=8):
     """Algorithmic HBM bytes of the RPNys selection loop.  Per step i and key: the i earlier Cholesky entries of
-    that key (8 i), the new entry (8), and p written for the other workgroups plus read back during the pivot
-    search (16).  The key rows (d * es per key) are read once when the loop is one persistent launch that keeps
-    them in registers, and once per step when the loop is one launch per step."""
+    that key (hs i; hs = 8 bytes, 4 in the fp32-history fast mode), the new entry (hs), and p written for the other
+    workgroups plus read back during the pivot search (16).  The key rows (d * es per key) are read once when the
+    loop is one persistent launch that keeps them in registers, and once per step when the loop is one launch per
+    step."""
     key_reads = 1 if single_launch else r
-    return float(P) * n * (key_reads * d * es + r * (8 + 16) + 8.0 * r * (r - 1) / 2.0)
+    return float(P) * n * (key_reads * d * es + r * (hs + 16) + float(hs) * r * (r - 1) / 2.0)
 
 
 def cpu_baseline(w, budget_heads):
@@ -91,6 +92,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--cfg", type=int, default=4, help="workload catalogue entry (4 = headline shape)")
+    ap.add_argument("--history", choices=("f64", "f32"), default="f64",
+                    help="precision of the selection loop's history rows (f32 = the fast mode; default f64)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact", action="store_true")
     ap.add_argument("--sweep-n", action="store_true",
@@ -116,8 +119,8 @@ def main():
     es = 2 if s.dtype == "bf16" else 4
     Q, K, V = (torch.from_numpy(w[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
     u = torch.from_numpy(w["u"]).to(dev)
-    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins),
-                     dtype=torch.uint8, device=dev)
+    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins,
+                                        args.history), dtype=torch.uint8, device=dev)
     out = torch.empty((s.batch, s.q_heads, s.m, s.dv), dtype=tdt, device=dev)
     hev = HipEvents()
     loop_ev = [(hev.create(), hev.create()) for _ in range(args.steps)]
@@ -130,7 +133,8 @@ def main():
         r_q = wc.query_radius(Q, s.kv_heads, workspace=ws)
         if k is not None:
             marks[k][1].record()
-        cs = wc.compress_kv(K, V, s.r, r_q, uniforms=u, workspace=ws, loop_events=ev, bins=s.bins)
+        cs = wc.compress_kv(K, V, s.r, r_q, uniforms=u, workspace=ws, loop_events=ev, bins=s.bins,
+                            history=args.history)
         if k is not None:
             marks[k][2].record()
         wc.wtd_attn(Q, cs, out=out)
@@ -157,14 +161,16 @@ def main():
     loop_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in loop_ev]))
     ph = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(3)] for m in marks]).mean(axis=0)
     P = s.problems
-    single = wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins)
+    single = wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins,
+                                    args.history)
     launches = 1 if single else s.r // s.bins
     # with bins the loop is P * B independent problems of n / B keys and r / B steps
-    loop_bytes = step_loop_bytes(P * s.bins, s.n // s.bins, s.d, s.r // s.bins, es, single)
+    loop_bytes = step_loop_bytes(P * s.bins, s.n // s.bins, s.d, s.r // s.bins, es, single,
+                                 8 if args.history == "f64" else 4)
     achieved = loop_bytes / (loop_ms * 1e-3) / 1e9
     traffic = None
     tfile = os.path.join(ROOT, "profiles", "rpnys_loop_traffic.json")
-    if os.path.exists(tfile) and args.cfg == 4:
+    if os.path.exists(tfile) and args.cfg == 4 and args.history == "f64":
         with open(tfile) as f:
             traffic = json.load(f).get("single_launch" if single else "per_step", {}).get("hbm_bytes_per_launch")
     attn_flops = float(s.batch * s.q_heads) * s.m * (2.0 * s.r * (s.d + s.dv) + 2.0 * s.r)
@@ -179,7 +185,7 @@ def main():
         "dtype": "f64",
         "data": "synthetic",
         "config": {"workload": f"{s.name}: batch {s.batch} x {s.q_heads} query heads / {s.kv_heads} kv heads, "
-                               f"n={s.n}, m={s.m}, d={s.d}, d_v={s.dv}, r={s.r}, B={s.bins}, {s.dtype} storage; selection loop in fp64, "
+                               f"n={s.n}, m={s.m}, d={s.d}, d_v={s.dv}, r={s.r}, B={s.bins}, {s.dtype} storage; selection loop in fp64{' with fp32 history rows (fast mode)' if args.history == 'f32' else ''}, "
                                f"WtdAttn on MFMA (bf16 scores, fp16 value product) with fp32 accumulation",
                    "uniform_seed": s.uniform_seed, "data_seed": s.data_seed},
         "phases_ms": {"query_radius": float(ph[0]), "compress_kv": float(ph[1]), "rpnys_loop": loop_ms,
@@ -224,11 +230,11 @@ def main():
             Q2, K2, V2 = (torch.from_numpy(w2[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
             u2 = torch.from_numpy(w2["u"]).to(dev)
             ws2 = torch.empty(wc.workspace_bytes(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d, 1 if es == 2 else 0,
-                                                 s2.bins), dtype=torch.uint8, device=dev)
+                                                 s2.bins, args.history), dtype=torch.uint8, device=dev)
 
             def pass2():
                 cs2 = wc.compress_kv(K2, V2, s2.r, wc.query_radius(Q2, s2.kv_heads, workspace=ws2), uniforms=u2, workspace=ws2,
-                                     bins=s2.bins)
+                                     bins=s2.bins, history=args.history)
                 return wc.wtd_attn(Q2, cs2)
 
             pass2()
@@ -242,7 +248,7 @@ def main():
             ms2 = a.elapsed_time(b) / 3
             sweep.append({"n": n2, "ms": ms2, "tokens_per_s": s2.batch * n2 / (ms2 * 1e-3), "us_per_token": ms2 * 1e3 / n2,
                           "single_launch_loop": wc.rpnys_single_launch(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d,
-                                                                      1 if es == 2 else 0, s2.bins)})
+                                                                      1 if es == 2 else 0, s2.bins, args.history)})
             del Q2, K2, V2, ws2, w2
             torch.cuda.empty_cache()
         res["scaling_in_n"] = sweep

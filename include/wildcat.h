@@ -45,6 +45,15 @@ extern "C" {
 
 typedef enum { WILDCAT_F32 = 0, WILDCAT_BF16 = 1 } wildcat_dtype;
 
+/* WILDCAT_HISTORY_F64 (default): every quantity that decides a pivot is float64, and the pivots
+ * are those a float64 implementation of Alg. 1 draws from the same uniforms.
+ * WILDCAT_HISTORY_F32 (fast mode): the history rows are stored in fp32, which halves the memory
+ * traffic of the loop.  Each row is rounded before it is used, so the factorisation stays
+ * consistent, but the residual diagonal differs from the float64 one by about 1e-7 relative:
+ * pivots are still drawn from (that) residual by the same inverse-CDF rule, yet at large n some
+ * differ from the float64 reference's.  Sums and the residual diagonal itself stay float64. */
+typedef enum { WILDCAT_HISTORY_F64 = 0, WILDCAT_HISTORY_F32 = 1 } wildcat_history;
+
 typedef enum {
   WILDCAT_OK = 0,
   WILDCAT_EINVAL = -1,      /* null pointer, bad shape / dtype / option            */
@@ -82,6 +91,9 @@ typedef struct {
   int32_t tau_length; /* sequence length in eq. (kernel-temperature) when bins > 1:    */
                      /* 0 -> the bin length n/B (the effective length Thm. 2 names),   */
                      /* 1 -> the full length n (Alg. 2 as printed)                     */
+  int32_t history;   /* wildcat_history: precision in which the selection loop keeps   */
+                     /* its history (the partial Cholesky rows it re-reads every step) */
+  int32_t reserved1;
   void *stream;      /* hipStream_t                                                 */
   void *ev_loop_begin; /* optional hipEvent_t pair that wildcat_compress_kv records  */
   void *ev_loop_end; /* on the stream right before the first and right after the    */
@@ -126,7 +138,7 @@ int wildcat_version(void);
 const char *wildcat_strerror(int status);
 
 /* HOST.  Bytes of workspace wildcat_compress_kv needs for keys of length n, width
- * d, rank r under *opts (batch, kv_heads, dv, dtype are read; opts may be NULL).
+ * d, rank r under *opts (batch, kv_heads, dv, dtype, bins, history are read; opts may be NULL).
  * Returns 0 for invalid arguments.  wildcat_wtd_attn needs no workspace;
  * wildcat_query_radius can use one (see there). */
 size_t wildcat_workspace_bytes(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts);

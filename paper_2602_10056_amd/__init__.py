@@ -31,6 +31,7 @@ class _Opts(ctypes.Structure):
         ("beta", ctypes.c_double), ("rank_tol", ctypes.c_double),
         ("r_q", ctypes.c_void_p), ("uniforms", ctypes.c_void_p),
         ("bins", ctypes.c_int32), ("tau_length", ctypes.c_int32),
+        ("history", ctypes.c_int32), ("reserved1", ctypes.c_int32),
         ("stream", ctypes.c_void_p), ("ev_loop_begin", ctypes.c_void_p), ("ev_loop_end", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
     ]
@@ -156,16 +157,24 @@ def _opts(batch, q_heads, kv_heads, m, dv, dtype, beta, rank_tol=0.0, r_q=None, 
     return o
 
 
-def workspace_bytes(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1):
+def _history_code(history):
+    if history not in ("f64", "f32"):
+        raise WildcatError("history is 'f64' or 'f32'")
+    return int(history == "f32")
+
+
+def workspace_bytes(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1, history="f64"):
     o = _Opts()
     o.batch, o.kv_heads, o.dv, o.dtype, o.bins = batch, kv_heads, dv, dtype, bins
+    o.history = _history_code(history)
     return load_library().wildcat_workspace_bytes(n, d, r, ctypes.byref(o))
 
 
-def rpnys_single_launch(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1):
+def rpnys_single_launch(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1, history="f64"):
     """True if compress_kv runs the selection loop of this shape as one persistent launch (needs a GPU)."""
     o = _Opts()
     o.batch, o.kv_heads, o.dv, o.dtype, o.bins = batch, kv_heads, dv, dtype, bins
+    o.history = _history_code(history)
     rc = load_library().wildcat_rpnys_single_launch(n, d, r, ctypes.byref(o))
     if rc < 0:
         _check(rc, "wildcat_rpnys_single_launch")
@@ -187,11 +196,12 @@ def query_radius(Q, kv_heads=None, workspace=None):
 
 
 def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, loop_events=None,
-                bins=1, temperature_n="bin"):
+                bins=1, temperature_n="bin", history="f64"):
     """CompressKV (Alg. 2).  K: [B, Hkv, n, d], V: [B, Hkv, n, dv]; r_q: float64 [B, Hkv] on the device;
     uniforms: optional float64 [B*Hkv, r] on the device (else drawn from `seed`); loop_events: optional pair
     of raw hipEvent_t handles recorded around the RPNys loop; bins: B of Alg. 2 (must divide n and r);
-    temperature_n: "bin" (length n/B in the temperature) or "full" (n).  Returns a Coreset."""
+    temperature_n: "bin" (length n/B in the temperature) or "full" (n); history: "f64" (pivots identical to a
+    float64 reference) or "f32" (fast mode, see wildcat_history in include/wildcat.h).  Returns a Coreset."""
     import torch
     _need(K, "K", 4)
     _need(V, "V", 4)
@@ -209,7 +219,7 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
     if temperature_n not in ("bin", "full"):
         raise WildcatError("temperature_n is 'bin' or 'full'")
     bins = max(int(bins), 1)
-    need = workspace_bytes(n, d, r, B, H, dv, code, bins)
+    need = workspace_bytes(n, d, r, B, H, dv, code, bins, history)
     if need == 0:
         raise WildcatError("wildcat_workspace_bytes rejected the shape")
     if workspace is None:
@@ -229,7 +239,7 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
         bins=bins,
     )
     o = _opts(B, H, H, n, dv, code, beta, rank_tol, r_q.contiguous(), uniforms, workspace)
-    o.bins, o.tau_length = bins, int(temperature_n == "full")
+    o.bins, o.tau_length, o.history = bins, int(temperature_n == "full"), _history_code(history)
     if loop_events is not None:
         o.ev_loop_begin, o.ev_loop_end = loop_events
     c = cs.c_struct()
@@ -271,17 +281,18 @@ def wtd_attn(Q, cs: Coreset, beta=None, out=None):
 
 
 def wildcat(Q, K, V, r, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, return_coreset=False,
-            bins=1, temperature_n="bin"):
+            bins=1, temperature_n="bin", history="f64"):
     """WildCat (Alg. 4): query radius, CompressKV, WtdAttn."""
     if workspace is None:
         import torch
         bins_ = max(int(bins), 1)
-        need = workspace_bytes(K.shape[2], K.shape[3], r, K.shape[0], K.shape[1], V.shape[3], _dtype_code(K), bins_)
+        need = workspace_bytes(K.shape[2], K.shape[3], r, K.shape[0], K.shape[1], V.shape[3], _dtype_code(K), bins_,
+                               history)
         if need == 0:
             raise WildcatError("wildcat_workspace_bytes rejected the shape")
         workspace = torch.empty(need, dtype=torch.uint8, device=K.device)
     r_q = query_radius(Q, K.shape[1], workspace=workspace)
     cs = compress_kv(K, V, r, r_q, seed=seed, uniforms=uniforms, beta=beta, rank_tol=rank_tol, workspace=workspace,
-                     bins=bins, temperature_n=temperature_n)
+                     bins=bins, temperature_n=temperature_n, history=history)
     out = wtd_attn(Q, cs, beta=beta)
     return (out, cs) if return_coreset else out

@@ -36,6 +36,8 @@ int resolve_shape(int64_t n, int64_t m_arg, int32_t d, int32_t r, const wildcat_
   if (o->bins < 0 || o->tau_length < 0 || o->tau_length > 1) return WILDCAT_EINVAL;
   s->bins = o->bins > 1 ? o->bins : 1;
   s->tau_full_n = o->tau_length;
+  if (o->history != WILDCAT_HISTORY_F64 && o->history != WILDCAT_HISTORY_F32) return WILDCAT_EINVAL;
+  s->history_f32 = o->history == WILDCAT_HISTORY_F32;
   if ((int64_t)s->P * s->bins > (1 << 20)) return WILDCAT_EINVAL;
   if (d > kMaxWidth || s->dv > kMaxWidth) return WILDCAT_EUNSUPPORTED;
   s->stream = (hipStream_t)o->stream;
@@ -84,7 +86,7 @@ Plan make_plan(const Shape &s) {
   p.off_p = take(2 * P * n * 8);
   p.off_bsum = take(P * r * p.nblk * 8);
   p.off_scal = take(P * 8 * 8);
-  p.off_F = take(P * n * r * 8);
+  p.off_F = take(P * n * r * (s.history_f32 ? 4 : 8));
   p.off_L = take(P * r * r * 8);
   p.off_gpart = take(P * p.nchunk * r * dv1 * 8);
   p.off_g = take(P * r * dv1 * 8);

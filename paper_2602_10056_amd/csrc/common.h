@@ -22,6 +22,7 @@ struct Shape {
   int d, dv, r, dtype;
   int bins;          // B of Alg. 2 (>= 1)
   int tau_full_n;    // temperature from the full length n instead of the bin length n / B
+  int history_f32;   // history rows of the selection loop in fp32 (fast mode) instead of fp64
   double beta, rank_tol;
   hipStream_t stream;
 };

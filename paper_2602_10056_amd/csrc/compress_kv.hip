@@ -470,7 +470,7 @@ struct StepArgs {
   const double *u;        // [P][r]
   double *p;              // [2][P][npad]   residual diagonal, double-buffered by step parity
   double *bsum;           // [P][r][nblk]   per-slab sums of p entering each step; -1 = not yet published
-  double *F;              // [P][nblk][r][slab]
+  void *F;                // [P][nblk][r][slab] history rows, fp64 or (fast mode) fp32
   double *L;              // [P][r][r] Cholesky factor of h(K_S,K_S), row-major, lower triangle
   int32_t *idx, *r_eff;
   int64_t n, npad;
@@ -481,18 +481,32 @@ struct StepArgs {
 // exceeds every cache, so they are issued as non-temporal loads, which measurably raises the sustained
 // HBM read rate on this part.
 typedef double dbl2 __attribute__((ext_vector_type(2)));
-template <int KPT>
+typedef float flt2 __attribute__((ext_vector_type(2)));
+template <int KPT, typename H>
 struct HistVec;
 template <>
-struct HistVec<1> {
+struct HistVec<1, double> {
   double v[1];
   __device__ __forceinline__ void load(const double *p) { v[0] = __builtin_nontemporal_load(p); }
 };
 template <>
-struct HistVec<2> {
+struct HistVec<2, double> {
   double v[2];
   __device__ __forceinline__ void load(const double *p) {
     const dbl2 x = __builtin_nontemporal_load(reinterpret_cast<const dbl2 *>(p));
+    v[0] = x.x; v[1] = x.y;
+  }
+};
+template <>
+struct HistVec<1, float> {
+  float v[1];
+  __device__ __forceinline__ void load(const float *p) { v[0] = __builtin_nontemporal_load(p); }
+};
+template <>
+struct HistVec<2, float> {
+  float v[2];
+  __device__ __forceinline__ void load(const float *p) {
+    const flt2 x = __builtin_nontemporal_load(reinterpret_cast<const flt2 *>(p));
     v[0] = x.x; v[1] = x.y;
   }
 };
@@ -557,6 +571,12 @@ __device__ __forceinline__ void st_dev(double *p, double v) {
 __device__ __forceinline__ double ld_dev(const double *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_dev(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 struct StepShared {
   double sm[kThreads / kWave];
@@ -567,7 +587,10 @@ struct StepShared {
 // Returns 1 after a step, 0 (state untouched) when the residual mass is exhausted, -1 if a bounded wait for another
 // workgroup's slab sum ran out (POLL only).
 // pown / flo: residual diagonal and floor of this thread's keys (registers); on return pown is updated.
-template <typename T, int KPT, int NC, bool POLL>
+// H = storage type of the history rows: double (pivots identical to a float64 reference) or float (fast mode: half
+// the bytes; the row is rounded to fp32 BEFORE it enters the residual update, so the factorisation stays consistent
+// with what later steps read back).
+template <typename T, int KPT, int NC, bool POLL, typename H>
 __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int pr, double *g, double *ksc,
                                           StepShared &sh, const KeyRegs<T, KPT, NC> &kr, double (&pown)[KPT],
                                           const double (&flo)[KPT], int *error, long long spin_limit, int hcn) {
@@ -575,12 +598,12 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
   const int rd = i & 1, wr = rd ^ 1;
-  double *hc = g + ((a.r + a.dpad + 1) & ~1);                    // history cache [hcn][SLAB] behind g and ksc in LDS
+  H *hc = reinterpret_cast<H *>(g + ((a.r + a.dpad + 1) & ~1));  // history cache [hcn][SLAB] behind g and ksc in LDS
   const double *bs = a.bsum + ((size_t)pr * a.r + i) * a.nblk;
   double *bs_next = a.bsum + ((size_t)pr * a.r + i + 1) * a.nblk;     // written only if i + 1 < r
   const double *pin = a.p + ((size_t)rd * a.P + pr) * a.npad;
   double *pout = a.p + ((size_t)wr * a.P + pr) * a.npad;
-  double *Fb = a.F + ((size_t)pr * a.nblk + b) * a.r * SLAB;
+  H *Fb = reinterpret_cast<H *>(a.F) + ((size_t)pr * a.nblk + b) * a.r * SLAB;
   const int l_loc = t * KPT;
   const int64_t l_glob = (int64_t)b * SLAB + l_loc;
 
@@ -681,8 +704,8 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   const int64_t s_glob = (int64_t)bstar * SLAB + s_loc;
 
   // ---- 4. broadcast data of the pivot: its history column g_j = F_j(s) and k_s - kbar ------------------
-  const double *Fs = a.F + ((size_t)pr * a.nblk + bstar) * a.r * SLAB + s_loc;
-  for (int j = t; j < i; j += kThreads) g[j] = ld_dev(Fs + (size_t)j * SLAB);
+  const H *Fs = reinterpret_cast<const H *>(a.F) + ((size_t)pr * a.nblk + bstar) * a.r * SLAB + s_loc;
+  for (int j = t; j < i; j += kThreads) g[j] = (double)ld_dev(Fs + (size_t)j * SLAB);
   const int nc = a.dpad / kChunk;
   const T *Kp = reinterpret_cast<const T *>(a.Kp) + (size_t)pr * nc * a.npad * kChunk;
   double cbp = 0.0;
@@ -713,32 +736,32 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     for (int j = 0; j < nc_rows; ++j) {                       // cached rows, always first and upwards
       const double gj = g[j];
 #pragma unroll
-      for (int k = 0; k < KPT; ++k) acc[k] = fma(hc[(size_t)j * SLAB + l_loc + k], gj, acc[k]);
+      for (int k = 0; k < KPT; ++k) acc[k] = fma((double)hc[(size_t)j * SLAB + l_loc + k], gj, acc[k]);
     }
     const ptrdiff_t fstep = down ? -(ptrdiff_t)SLAB : (ptrdiff_t)SLAB;
     const int gstep = down ? -1 : 1;
-    const double *fp = Fb + l_loc + (size_t)(down ? i - 1 : nc_rows) * SLAB;
+    const H *fp = Fb + l_loc + (size_t)(down ? i - 1 : nc_rows) * SLAB;
     const double *gp = g + (down ? i - 1 : nc_rows);
     int j = 0;
     for (; j + 8 <= nh; j += 8) {
-      HistVec<KPT> h[8];
+      HistVec<KPT, H> h[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) h[q].load(fp + q * fstep);
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
         const double gj = gp[q * gstep];
 #pragma unroll
-        for (int k = 0; k < KPT; ++k) acc[k] = fma(h[q].v[k], gj, acc[k]);
+        for (int k = 0; k < KPT; ++k) acc[k] = fma((double)h[q].v[k], gj, acc[k]);
       }
       fp += 8 * fstep;
       gp += 8 * gstep;
     }
     for (; j < nh; ++j) {
-      HistVec<KPT> h;
+      HistVec<KPT, H> h;
       h.load(fp);
       const double gj = *gp;
 #pragma unroll
-      for (int k = 0; k < KPT; ++k) acc[k] = fma(h.v[k], gj, acc[k]);
+      for (int k = 0; k < KPT; ++k) acc[k] = fma((double)h.v[k], gj, acc[k]);
       fp += fstep;
       gp += gstep;
     }
@@ -783,12 +806,12 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
 #pragma unroll
   for (int k = 0; k < KPT; ++k) {
     const int64_t l = l_glob + k;
-    double f = (exp(beta_tau * (dot[k] - cb)) - acc[k]) * inv;
+    double f = (double)(H)((exp(beta_tau * (dot[k] - cb)) - acc[k]) * inv);     // as stored
     double pn = pown[k] - f * f;
     if (pn <= flo[k]) pn = 0.0;                                  // also clamps negatives (floor >= 0)
     if (l == s_glob) { pn = 0.0; fs = f; own = true; }
     if (l >= a.n) { pn = 0.0; f = 0.0; }
-    st_dev(Fb + (size_t)i * SLAB + l_loc + k, f);
+    st_dev(Fb + (size_t)i * SLAB + l_loc + k, (H)f);
     fkeep[k] = f;
     st_dev(pout + l, pn);
     pown[k] = pn;
@@ -797,7 +820,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   const double tot = block_sum(psum, sh.sm);
   if (i < hcn) {                                             // this thread's entries of the new row, for its own later reads
 #pragma unroll
-    for (int k = 0; k < KPT; ++k) hc[(size_t)i * SLAB + l_loc + k] = fkeep[k];
+    for (int k = 0; k < KPT; ++k) hc[(size_t)i * SLAB + l_loc + k] = (H)fkeep[k];
   }
   if constexpr (POLL) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's p and history stores have completed
   __syncthreads();
@@ -816,7 +839,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
 }
 
 // Driver 1: one launch per step; the kernel boundary is the synchronisation between steps.
-template <typename T, int KPT>
+template <typename T, int KPT, typename H>
 __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
   extern __shared__ double dyn[];
   __shared__ StepShared sh;
@@ -831,15 +854,15 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
     flo[k] = a.floor[(size_t)pr * a.npad + l_glob + k];
   }
   KeyRegs<T, KPT, 0> none;
-  if (rpnys_step<T, KPT, 0, false>(a, i, b, pr, dyn, dyn + a.r, sh, none, pown, flo, nullptr, 0, 0) == 0) {
+  if (rpnys_step<T, KPT, 0, false, H>(a, i, b, pr, dyn, dyn + a.r, sh, none, pown, flo, nullptr, 0, 0) == 0) {
     // Residual mass exhausted: carry the (all-zero) state into the other parity, leave row i of F zero, record
     // the number of pivots once.
     double *pout = a.p + ((size_t)((i & 1) ^ 1) * a.P + pr) * a.npad;
-    double *Fb = a.F + ((size_t)pr * a.nblk + b) * a.r * SLAB;
+    H *Fb = reinterpret_cast<H *>(a.F) + ((size_t)pr * a.nblk + b) * a.r * SLAB;
 #pragma unroll
     for (int k = 0; k < KPT; ++k) {
       pout[l_glob + k] = 0.0;
-      Fb[(size_t)i * SLAB + t * KPT + k] = 0.0;
+      Fb[(size_t)i * SLAB + t * KPT + k] = (H)0;
     }
     if (t == 0 && i + 1 < a.r) a.bsum[((size_t)pr * a.r + i + 1) * a.nblk + b] = 0.0;
     if (b == 0 && t == 0 && a.r_eff[pr] > i) a.r_eff[pr] = i;
@@ -853,7 +876,7 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 // bounded: if a limit is hit (it never should be) the error word is set and every workgroup leaves.  With
 // NC > 0 a thread keeps the packed features of its keys in registers for the whole loop, which removes the
 // O(n d) key stream from every step.
-template <typename T, int KPT, int NC>
+template <typename T, int KPT, int NC, typename H>
 __global__ __launch_bounds__(kThreads, 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
                                                                   int hcn) {
   extern __shared__ double dyn[];
@@ -873,16 +896,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_rpnys_persistent(StepArgs a, in
                             a.npad);
   int i = 0, rc = 1;
   for (; i < a.r; ++i) {
-    rc = rpnys_step<T, KPT, NC, true>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
+    rc = rpnys_step<T, KPT, NC, true, H>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
     if (rc != 1) break;
   }
   if (rc == 0) {
     // Exhausted at step i (every workgroup of the problem sees the same sums and leaves at the same step):
     // rows i.. of this slab's history are zero for the Gram pass.
-    double *Fb = a.F + ((size_t)pr * a.nblk + b) * a.r * SLAB;
+    H *Fb = reinterpret_cast<H *>(a.F) + ((size_t)pr * a.nblk + b) * a.r * SLAB;
     for (int j = i; j < a.r; ++j)
 #pragma unroll
-      for (int k = 0; k < KPT; ++k) Fb[(size_t)j * SLAB + t * KPT + k] = 0.0;
+      for (int k = 0; k < KPT; ++k) Fb[(size_t)j * SLAB + t * KPT + k] = (H)0;
     if (b == 0 && t == 0) a.r_eff[pr] = i;
   }
 }
@@ -895,8 +918,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_rpnys_persistent(StepArgs a, in
 // --------------------------------------------------------------------------------------------
 constexpr int kGramRows = 128, kGramKT = 16;
 
-template <typename T, int CW>
-__global__ __launch_bounds__(kThreads) void k_gram(const double *__restrict__ F, const T *__restrict__ V, int64_t n,
+template <typename T, int CW, typename H>
+__global__ __launch_bounds__(kThreads) void k_gram(const H *__restrict__ F, const T *__restrict__ V, int64_t n,
                                                    int nblk, int slab, int r, int dv, int slabs_per_chunk,
                                                    int nchunk, int ncoltiles, double *__restrict__ gpart) {
   __shared__ double Fs[kGramRows][kGramKT + 1];
@@ -916,7 +939,7 @@ __global__ __launch_bounds__(kThreads) void k_gram(const double *__restrict__ F,
   const int sb0 = ch * slabs_per_chunk;
   const int sb1 = sb0 + slabs_per_chunk < nblk ? sb0 + slabs_per_chunk : nblk;
   for (int sb = sb0; sb < sb1; ++sb) {
-    const double *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
+    const H *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
     for (int k0 = 0; k0 < slab; k0 += kGramKT) {
       const int64_t lbase = (int64_t)sb * slab + k0;
       if (lbase >= n) break;
@@ -924,12 +947,18 @@ __global__ __launch_bounds__(kThreads) void k_gram(const double *__restrict__ F,
       {  // F tile: 128 rows x 16 keys; thread loads 8 consecutive keys of one row
         const int row = t / 2, seg = (t % 2) * 8;
         const bool ok = a0 + row < r;
-        const double *src = Fslab + (size_t)(a0 + row) * slab + k0 + seg;
+        const H *src = Fslab + (size_t)(a0 + row) * slab + k0 + seg;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-          const double2 v = ok ? *reinterpret_cast<const double2 *>(src + e) : make_double2(0.0, 0.0);
-          Fs[row][seg + e] = v.x;
-          Fs[row][seg + e + 1] = v.y;
+          if constexpr (sizeof(H) == 8) {
+            const double2 v = ok ? *reinterpret_cast<const double2 *>(src + e) : make_double2(0.0, 0.0);
+            Fs[row][seg + e] = v.x;
+            Fs[row][seg + e + 1] = v.y;
+          } else {
+            const float2 v = ok ? *reinterpret_cast<const float2 *>(src + e) : make_float2(0.f, 0.f);
+            Fs[row][seg + e] = (double)v.x;
+            Fs[row][seg + e + 1] = (double)v.y;
+          }
         }
       }
       for (int e = t; e < kGramKT * 16 * CW; e += kThreads) {  // V tile: 16 keys x (16 CW) columns, as fp64
@@ -1009,8 +1038,8 @@ template <> struct Value4<bf16_t> {
   }
 };
 
-template <typename T, int R>
-__global__ __launch_bounds__(kThreads) void k_gram_small(const double *__restrict__ F, const T *__restrict__ V,
+template <typename T, int R, typename H>
+__global__ __launch_bounds__(kThreads) void k_gram_small(const H *__restrict__ F, const T *__restrict__ V,
                                                          int64_t n, int nblk, int slab, int r, int dv, int tpr,
                                                          int slabs_per_chunk, int nchunk,
                                                          double *__restrict__ gpart) {
@@ -1032,7 +1061,7 @@ __global__ __launch_bounds__(kThreads) void k_gram_small(const double *__restric
   const int sb1 = sb0 + slabs_per_chunk < nblk ? sb0 + slabs_per_chunk : nblk;
   const T *Vp = V + (size_t)pr * n * dv;
   for (int sb = sb0; sb < sb1; ++sb) {
-    const double *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
+    const H *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
     constexpr int U = R <= 4 ? 4 : (R <= 8 ? 2 : 1);             // keys in flight per thread
     for (int k0 = 0; k0 < slab; k0 += U * kgs) {
       Value4<T> raw[U];
@@ -1046,7 +1075,7 @@ __global__ __launch_bounds__(kThreads) void k_gram_small(const double *__restric
         const int l_safe = ok[q] ? l_loc : 0;
         raw[q].load(Vp + (size_t)(ok[q] ? l : 0) * dv, active ? col : 0, dv, vec);
 #pragma unroll
-        for (int j = 0; j < R; ++j) f[q][j] = (ok[q] && j < r) ? Fslab[(size_t)j * slab + l_safe] : 0.0;
+        for (int j = 0; j < R; ++j) f[q][j] = (ok[q] && j < r) ? (double)Fslab[(size_t)j * slab + l_safe] : 0.0;
       }
 #pragma unroll
       for (int q = 0; q < U; ++q) {
@@ -1215,16 +1244,16 @@ struct LoopPlan {
   int hcn;
 };
 
-template <typename T, int KPT>
+template <typename T, int KPT, typename H>
 LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
   LoopPlan lp = {nullptr, 0, 0};
   if (!pl.persistent) return lp;
   const int nc = pl.dpad / kChunk;
   constexpr int regs_per_chunk = KPT * (sizeof(T) == 2 ? 2 : 4);
   const void *fn;
-  if (nc == 32 && 32 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0)>;
-  else if (nc == 16 && 16 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, 16>;
-  else fn = (const void *)k_rpnys_persistent<T, KPT, 0>;
+  if (nc == 32 && 32 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H>;
+  else if (nc == 16 && 16 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, 16, H>;
+  else fn = (const void *)k_rpnys_persistent<T, KPT, 0, H>;
   const int cus = compute_units();
   const int64_t wgs = (int64_t)pl.nblk * s.P;
   const int need = (int)((wgs + cus - 1) / cus);             // workgroups a compute unit must hold
@@ -1238,7 +1267,7 @@ LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
   if (hipGetDevice(&dev) == hipSuccess &&
       hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) == hipSuccess && lds_cu > 0) {
     const int64_t share = (int64_t)lds_cu / need - 2048 - (int64_t)base;    // static LDS and allocation granules
-    const int64_t row = (int64_t)kThreads * KPT * sizeof(double);
+    const int64_t row = (int64_t)kThreads * KPT * sizeof(H);
     int hcn = share > 0 ? (int)(share / row) : 0;
     if (hcn > s.r) hcn = s.r;
     if (hcn > 0) {
@@ -1256,7 +1285,7 @@ LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
 }
 
 // `s` is the bin view of the request (wildcat::bin_view): P problems = bins, n keys and r pivots per bin.
-template <typename T, int KPT>
+template <typename T, int KPT, typename H>
 int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const wildcat_opts *o, uint64_t seed,
                  wildcat_coreset *out) {
   char *ws = (char *)o->workspace;
@@ -1266,7 +1295,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   double *p = (double *)(ws + pl.off_p);
   double *bsum = (double *)(ws + pl.off_bsum);
   double *scal = (double *)(ws + pl.off_scal);
-  double *F = (double *)(ws + pl.off_F);
+  H *F = (H *)(ws + pl.off_F);
   double *L = (double *)(ws + pl.off_L);
   double *gpart = (double *)(ws + pl.off_gpart);
   double *Gt = (double *)(ws + pl.off_g);
@@ -1322,7 +1351,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
   const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
   bool done = false;
-  const LoopPlan lp = persistent_kernel<T, KPT>(s, pl);
+  const LoopPlan lp = persistent_kernel<T, KPT, H>(s, pl);
   const void *fn = lp.fn;
   if (fn) {
     int *err_word = (int *)(ws + pl.off_sync);
@@ -1339,7 +1368,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   }
   if (!done) {
     for (int i = 0; i < s.r; ++i) {
-      hipLaunchKernelGGL((k_step<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), step_lds, st, a, i);
+      hipLaunchKernelGGL((k_step<T, KPT, H>), dim3(pl.nblk, P), dim3(kThreads), step_lds, st, a, i);
       LAUNCH_CHECK();
     }
   }
@@ -1351,20 +1380,20 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     while (tpr * 4 < s.dv) tpr <<= 1;                        // threads per value row (<= 64: dv <= kMaxWidth)
     const dim3 grid(pl.nchunk, 1, P);
     if (s.r <= 4)
-      hipLaunchKernelGGL((k_gram_small<T, 4>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
+      hipLaunchKernelGGL((k_gram_small<T, 4, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
                          pl.slabs_per_chunk, pl.nchunk, gpart);
     else if (s.r <= 8)
-      hipLaunchKernelGGL((k_gram_small<T, 8>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
+      hipLaunchKernelGGL((k_gram_small<T, 8, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
                          pl.slabs_per_chunk, pl.nchunk, gpart);
     else
-      hipLaunchKernelGGL((k_gram_small<T, 16>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
+      hipLaunchKernelGGL((k_gram_small<T, 16, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
                          tpr, pl.slabs_per_chunk, pl.nchunk, gpart);
   } else if (s.dv <= 64) {
-    hipLaunchKernelGGL((k_gram<T, 4>), dim3(pl.nchunk, rtiles, P), dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab,
+    hipLaunchKernelGGL((k_gram<T, 4, H>), dim3(pl.nchunk, rtiles, P), dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab,
                        s.r, s.dv, pl.slabs_per_chunk, pl.nchunk, 1, gpart);
   } else {
     const int ncoltiles = (s.dv + 127) / 128;
-    hipLaunchKernelGGL((k_gram<T, 8>), dim3(pl.nchunk * ncoltiles, rtiles, P), dim3(kThreads), 0, st, F, V, s.n,
+    hipLaunchKernelGGL((k_gram<T, 8, H>), dim3(pl.nchunk * ncoltiles, rtiles, P), dim3(kThreads), 0, st, F, V, s.n,
                        pl.nblk, pl.slab, s.r, s.dv, pl.slabs_per_chunk, pl.nchunk, ncoltiles, gpart);
   }
   LAUNCH_CHECK();
@@ -1389,6 +1418,31 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   return WILDCAT_OK;
 }
 
+// Storage type T x keys per thread x history type H.
+template <typename T, typename H>
+int dispatch_kpt(const Shape &s, const Plan &pl, const void *K, const void *V, const wildcat_opts *o, uint64_t seed,
+                 wildcat_coreset *out) {
+  return pl.kpt == 2 ? run_compress<T, 2, H>(s, pl, (const T *)K, (const T *)V, o, seed, out)
+                     : run_compress<T, 1, H>(s, pl, (const T *)K, (const T *)V, o, seed, out);
+}
+int dispatch_compress(const Shape &s, const Plan &pl, const void *K, const void *V, const wildcat_opts *o,
+                      uint64_t seed, wildcat_coreset *out) {
+  if (s.dtype == WILDCAT_BF16)
+    return s.history_f32 ? dispatch_kpt<bf16_t, float>(s, pl, K, V, o, seed, out)
+                         : dispatch_kpt<bf16_t, double>(s, pl, K, V, o, seed, out);
+  return s.history_f32 ? dispatch_kpt<float, float>(s, pl, K, V, o, seed, out)
+                       : dispatch_kpt<float, double>(s, pl, K, V, o, seed, out);
+}
+template <typename T, typename H>
+bool single_launch_kpt(const Shape &s, const Plan &pl) {
+  return (pl.kpt == 2 ? persistent_kernel<T, 2, H>(s, pl).fn : persistent_kernel<T, 1, H>(s, pl).fn) != nullptr;
+}
+bool dispatch_single_launch(const Shape &s, const Plan &pl) {
+  if (s.dtype == WILDCAT_BF16)
+    return s.history_f32 ? single_launch_kpt<bf16_t, float>(s, pl) : single_launch_kpt<bf16_t, double>(s, pl);
+  return s.history_f32 ? single_launch_kpt<float, float>(s, pl) : single_launch_kpt<float, double>(s, pl);
+}
+
 }  // namespace
 }  // namespace wildcat
 
@@ -1410,12 +1464,7 @@ extern "C" int wildcat_compress_kv(const void *K, const void *V, int64_t n, int3
   const Plan pl = make_plan(s);
   if (!opts->workspace || ((uintptr_t)opts->workspace & 255) || opts->workspace_bytes < pl.total)
     return WILDCAT_EWORKSPACE;
-  if (s.dtype == WILDCAT_BF16) {
-    return pl.kpt == 2 ? run_compress<bf16_t, 2>(s, pl, (const bf16_t *)K, (const bf16_t *)V, opts, seed, out)
-                       : run_compress<bf16_t, 1>(s, pl, (const bf16_t *)K, (const bf16_t *)V, opts, seed, out);
-  }
-  return pl.kpt == 2 ? run_compress<float, 2>(s, pl, (const float *)K, (const float *)V, opts, seed, out)
-                     : run_compress<float, 1>(s, pl, (const float *)K, (const float *)V, opts, seed, out);
+  return dispatch_compress(s, pl, K, V, opts, seed, out);
 }
 
 extern "C" int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts) {
@@ -1426,8 +1475,5 @@ extern "C" int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, cons
   const Shape s = bin_view(whole);
   if (s.r > kMaxRank) return WILDCAT_EUNSUPPORTED;
   const Plan pl = make_plan(s);
-  const void *fn;
-  if (s.dtype == WILDCAT_BF16) fn = pl.kpt == 2 ? persistent_kernel<bf16_t, 2>(s, pl).fn : persistent_kernel<bf16_t, 1>(s, pl).fn;
-  else fn = pl.kpt == 2 ? persistent_kernel<float, 2>(s, pl).fn : persistent_kernel<float, 1>(s, pl).fn;
-  return fn ? 1 : 0;
+  return dispatch_single_launch(s, pl) ? 1 : 0;
 }

@@ -503,3 +503,86 @@ def test_decode_against_stored_coreset_with_exact_sink_and_recent_tokens(m):
             ref = wo.wtd_attn(Qn[0, h * s.group + g].astype(np.float64), KS, VS, ws_, Vh.min(0), Vh.max(0), s.beta)
             assert relmax(out[0, h * s.group + g].astype(np.float64), ref) <= TOL_OUT["bf16"]
     assert nm % bins == 0
+
+
+# ---------------------------------------------------------------------------------- fast mode: fp32 history rows
+def test_fp32_history_small_problem_matches_the_oracle_exactly():
+    """Where the tie margins of the draw (>= 1e-5 here) dwarf fp32 rounding of the history (1e-7), the fast mode
+    draws the float64 pivots; weights and values then agree with the oracle to fp32-history accuracy."""
+    w = wl.make(1)
+    out, cs = run_gpu(w, history="f32")
+    s = w["shape"]
+    ref, ocs, _ = wo.wildcat(w["Q"][0, 0].astype(np.float64), w["K"][0, 0].astype(np.float64),
+                             w["V"][0, 0].astype(np.float64), s.beta, s.r, w["u"][0], return_coreset=True)
+    np.testing.assert_array_equal(cs.idx[0, 0].cpu().numpy(), ocs.idx)
+    assert relmax(cs.w[0, 0].cpu().numpy().astype(np.float64), ocs.w) < 1e-3
+    assert relmax(cs.v_s[0, 0].cpu().numpy().astype(np.float64), ocs.V_S) < 1e-3
+    assert relmax(out[0, 0].cpu().numpy().astype(np.float64), ref) < 1e-3
+
+
+@pytest.mark.parametrize("cfg,ov", [(4, dict(q_heads=4, kv_heads=2, n=4096, r=192)),
+                                    (5, dict(q_heads=2, kv_heads=2, n=8192, r=256)),
+                                    (6, dict(q_heads=2, kv_heads=2, n=8192))])
+def test_fp32_history_is_a_valid_nystrom_compression(cfg, ov):
+    """The fast mode may draw different pivots than float64 once a draw lands within ~1e-7 of a bin edge, so it is
+    checked by what must hold for ANY pivot set: (a) the pivots are distinct keys of the right bin; (b) they agree
+    with the float64 oracle up to the first step whose oracle tie margin is small; (c) V_S and w are the Nystrom
+    compression W = h(S,S)^-1 h(S,K) for the pivots actually chosen (library solve in float64); (d) the attention
+    error against exact attention is of the size the float64 mode gives."""
+    w = wl.make(cfg, **ov)
+    s = w["shape"]
+    out32, cs32 = run_gpu(w, history="f32")
+    out64, cs64 = run_gpu(w)
+    rb, nb = s.r // s.bins, s.n // s.bins
+    for h in range(s.kv_heads):
+        K, V = w["K"][0, h].astype(np.float64), w["V"][0, h].astype(np.float64)
+        Qg = w["Q"][0, h * s.group:(h + 1) * s.group].astype(np.float64)
+        RQ = float(np.sqrt((Qg ** 2).sum(-1).max()))
+        idx = cs32.idx[0, h].cpu().numpy().astype(np.int64)
+        ocs = wo.compress_kv(K, V, RQ, s.beta, s.r, w["u"][h], bins=s.bins)
+        Kc = K - K.mean(axis=0)
+        Wfull_vs, Wfull_w = np.zeros((s.r, s.dv)), np.zeros(s.r)
+        for b in range(s.bins):
+            S = idx[b * rb:(b + 1) * rb]
+            assert np.all((S >= b * nb) & (S < (b + 1) * nb)) and len(set(S)) == rb                  # (a)
+            oS = ocs.idx[b * rb:(b + 1) * rb]
+            diff = np.nonzero(S != oS)[0]
+            if len(diff):                                                                            # (b)
+                assert ocs.rps[b].margin[diff[0]] < 1e-4, (b, diff[0], ocs.rps[b].margin[diff[0]])
+            bt = s.beta / ocs.taus[b] ** 2
+            rows = slice(b * nb, (b + 1) * nb)
+            Wb = np.linalg.solve(np.exp(bt * Kc[S] @ Kc[S].T), np.exp(bt * Kc[S] @ Kc[rows].T))      # (c)
+            Wfull_vs[b * rb:(b + 1) * rb] = Wb @ V[rows]
+            Wfull_w[b * rb:(b + 1) * rb] = Wb.sum(axis=1)
+        ev = relmax(cs32.v_s[0, h].cpu().numpy().astype(np.float64), Wfull_vs)
+        ew = relmax(cs32.w[0, h].cpu().numpy().astype(np.float64), Wfull_w)
+        print(cfg, h, "v_s", ev, "w", ew)
+        assert ev < 2e-2 and ew < 2e-2
+        for g in range(s.group):                                                                     # (d)
+            ex = wo.exact_attention(Qg[g], K, V, s.beta)
+            e32 = relmax(out32[0, h * s.group + g].float().cpu().numpy().astype(np.float64), ex)
+            e64 = relmax(out64[0, h * s.group + g].float().cpu().numpy().astype(np.float64), ex)
+            print("   attention error vs exact: f32 history", e32, "f64 history", e64)
+            assert e32 < 1.5 * e64 + 2e-2
+
+
+def test_fp32_history_full_size_config4():
+    """The fast mode in the benchmark's launch configuration.  On this workload fp32 history rows change no draw
+    (the float64 pivots come out, all 8 x 512 of them); should a draw ever flip, it must be at a near-tie."""
+    w = wl.make(4)
+    s = w["shape"]
+    out, cs = run_gpu(w, history="f32")
+    idx = cs.idx.cpu().numpy()
+    assert torch.isfinite(out.float()).all()
+    for h in (0, 5):
+        Qg = w["Q"][0, h * s.group:(h + 1) * s.group].astype(np.float64)
+        ref, ocs, _ = wo.wildcat(Qg, w["K"][0, h].astype(np.float64), w["V"][0, h].astype(np.float64), s.beta, s.r,
+                                 w["u"][h], return_coreset=True)
+        diff = np.nonzero(idx[0, h] != ocs.idx)[0]
+        if len(diff):
+            assert ocs.rp.margin[diff[0]] < 1e-5, (h, diff[0], ocs.rp.margin[diff[0]])
+            continue
+        assert relmax(cs.w[0, h].cpu().numpy().astype(np.float64), ocs.w) < 1e-4
+        assert relmax(cs.v_s[0, h].cpu().numpy().astype(np.float64), ocs.V_S) < 1e-4
+        for g in range(s.group):
+            assert relmax(out[0, h * s.group + g].float().cpu().numpy().astype(np.float64), ref[g]) <= TOL_OUT["bf16"]

@@ -62,6 +62,9 @@ def test_workspace_bytes():
     assert 0 < c < a / 4
     assert wc.workspace_bytes(4096, 64, 128, bins=3) == 0   # B must divide n and r
     assert wc.workspace_bytes(100000, 64, 5000, bins=4) > 0  # the rank limit applies per bin
+    # fast mode: fp32 history rows halve the dominant term
+    e = wc.workspace_bytes(4096, 64, 128, batch=4, kv_heads=8, history="f32")
+    assert a - e == 32 * 4096 * 128 * 4                      # exactly the 4 bytes saved per history entry
 
 
 def test_entry_points_reject_bad_arguments_before_launching():
@@ -91,6 +94,9 @@ def test_entry_points_reject_bad_arguments_before_launching():
     o.bins, o.tau_length = -1, 0
     assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1
     o.bins = 0
+    o.history = 2
+    assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # unknown mode
+    o.history = 0
     o.q_heads, o.kv_heads = 6, 4
     assert lib.wildcat_compress_kv(one, one, 128, 64, 16, 0, ctypes.byref(o), ctypes.byref(c)) == -1   # 6 % 4
     o.q_heads, o.kv_heads = 0, 0
