@@ -23,8 +23,11 @@
 //     against u * sum p) is fp64, so that the drawn index equals the one a float64 reference draws
 //     from the same uniform.  Sums use a fixed order: results are bit-reproducible run to run.
 //
-// One launch per RPNys step; every workgroup redoes the (cheap) pivot search from the per-slab sums
-// the previous launch left, so no grid-wide synchronisation happens inside a kernel.
+//     (Fast mode, wildcat_history in wildcat.h: the history rows alone are stored in fp32.)
+//
+// Every workgroup redoes the (cheap) pivot search from the per-slab sums the previous step left.  The loop runs as
+// one persistent launch whose workgroups synchronise through those sums when they all fit on the device, and as
+// one launch per step otherwise (see rpnys_step and its two drivers).
 #include <climits>
 #include <cmath>
 #include <cstdlib>
@@ -460,7 +463,7 @@ __global__ __launch_bounds__(kThreads) void k_init_p(int64_t n, int64_t npad, in
 // --------------------------------------------------------------------------------------------
 // One RPNys step (body of the loop of Alg. 1) for step index i, as a device function shared by the two
 // drivers below: `k_step` (one launch per step, grid (nblk, P)) and `k_rpnys_persistent` (one launch for the
-// whole loop, workgroups of a problem synchronising through a counter in memory).
+// whole loop, workgroups of a problem synchronising through the per-slab sums).
 // --------------------------------------------------------------------------------------------
 struct StepArgs {
   const void *Kp;         // [P][dpad/4][npad][4] packed keys
