@@ -1262,7 +1262,14 @@ LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
   const int need = (int)((wgs + cus - 1) / cus);             // workgroups a compute unit must hold
   const size_t base = (size_t)((s.r + pl.dpad + 1) & ~1) * sizeof(double);
   int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess || per_cu < need) return lp;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess) return lp;
+  if (per_cu < need) {
+    // Keys in registers cost too many registers for this many workgroups per compute unit: the variant that
+    // streams the keys every step is leaner and still saves the launches and their gaps.
+    fn = (const void *)k_rpnys_persistent<T, KPT, 0, H>;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess || per_cu < need)
+      return lp;
+  }
   lp.fn = fn;
   lp.lds = base;
   // History cache: optional, and only if the kernel stays resident with it.
