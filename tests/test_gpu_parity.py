@@ -586,3 +586,44 @@ def test_fp32_history_full_size_config4():
         assert relmax(cs.v_s[0, h].cpu().numpy().astype(np.float64), ocs.V_S) < 1e-4
         for g in range(s.group):
             assert relmax(out[0, h * s.group + g].float().cpu().numpy().astype(np.float64), ref[g]) <= TOL_OUT["bf16"]
+
+
+# ---------------------------------------------------------------------------------- capture into a HIP graph
+@pytest.mark.parametrize("cfg,ov", [(4, dict(q_heads=4, kv_heads=2, n=4096, r=128)), (6, dict(q_heads=2, kv_heads=2, n=8192))])
+def test_whole_path_can_be_captured_in_a_graph_and_replayed(cfg, ov):
+    """The library allocates nothing, never synchronises and clears its scratch with kernels, so a serving loop can
+    capture query radius + CompressKV + WtdAttn once and replay them.  Every replay (with eager work and
+    synchronisations in between, and new inputs written into the captured buffers) must equal the eager result."""
+    w = wl.make(cfg, **ov)
+    s = w["shape"]
+    Q, K, V = (to_dev(w[k], s.dtype) for k in ("Q", "K", "V"))
+    u = torch.from_numpy(w["u"]).to(dev())
+    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, wc.WILDCAT_BF16, s.bins),
+                     dtype=torch.uint8, device=dev())
+    eager, ecs = wc.wildcat(Q, K, V, r=s.r, uniforms=u, workspace=ws, return_coreset=True, bins=s.bins)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                 # warm-up on the capture stream's side, as torch asks
+        wc.wildcat(Q, K, V, r=s.r, uniforms=u, workspace=ws, bins=s.bins)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gout, gcs = wc.wildcat(Q, K, V, r=s.r, uniforms=u, workspace=ws, return_coreset=True, bins=s.bins)
+    for rep in range(3):
+        gout.zero_()
+        gcs.idx.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(gout, eager) and torch.equal(gcs.idx, ecs.idx) and torch.equal(gcs.w, ecs.w), rep
+        (K.float() @ K.float().transpose(-1, -2)[..., :64]).sum().item()      # unrelated eager work between replays
+    # new inputs in the captured buffers: the replay must follow them
+    K2 = torch.roll(K, shifts=17, dims=2)
+    V2 = torch.roll(V, shifts=17, dims=2)
+    eager2, ecs2 = wc.wildcat(Q, K2, V2, r=s.r, uniforms=u, return_coreset=True, bins=s.bins)
+    K.copy_(K2)
+    V.copy_(V2)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(gout, eager2) and torch.equal(gcs.idx, ecs2.idx)
