@@ -627,3 +627,30 @@ def test_whole_path_can_be_captured_in_a_graph_and_replayed(cfg, ov):
     graph.replay()
     torch.cuda.synchronize()
     assert torch.equal(gout, eager2) and torch.equal(gcs.idx, ecs2.idx)
+
+
+# ---------------------------------------------------------------------------------- odd widths: the generic kernels
+@pytest.mark.parametrize("dtype,n,m,d,dv,r,bins", [("f32", 700, 300, 40, 30, 12, 1), ("f32", 720, 100, 40, 30, 12, 2),
+                                                   ("bf16", 512, 200, 24, 10, 20, 1), ("bf16", 600, 64, 72, 100, 48, 4),
+                                                   ("f32", 300, 50, 7, 3, 5, 1)])
+def test_odd_widths_take_the_generic_kernels(dtype, n, m, d, dv, r, bins):
+    """Widths that are not a power-of-two number of 16-byte pieces (or not even 4-element aligned) bypass the fused
+    pack/statistics pass, the vectorised query radius, the vectorised small-rank Gram pass and the MFMA WtdAttn."""
+    rng = np.random.default_rng(n + d)
+    Q = wl.round_to_storage(rng.standard_normal((1, 2, m, d)), dtype)
+    K = wl.round_to_storage(rng.standard_normal((1, 2, n, d)) * 0.7 + rng.standard_normal((1, 2, 1, d)) * 0.3, dtype)
+    V = wl.round_to_storage(rng.standard_normal((1, 2, n, dv)), dtype)
+    u = rng.random((2, r))
+    beta = 1.0 / np.sqrt(d)
+    out, cs = wc.wildcat(to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), r=r, uniforms=torch.from_numpy(u).to(dev()),
+                         return_coreset=True, bins=bins)
+    torch.cuda.synchronize()
+    for h in range(2):
+        ref, ocs, (vmin, vmax, RQ) = wo.wildcat(Q[0, h].astype(np.float64), K[0, h].astype(np.float64),
+                                                V[0, h].astype(np.float64), beta, r, u[h], return_coreset=True, bins=bins)
+        np.testing.assert_array_equal(cs.idx[0, h].cpu().numpy(), ocs.idx)
+        np.testing.assert_allclose(cs.tau[0, h].cpu().numpy().reshape(-1), ocs.taus, rtol=1e-12)
+        np.testing.assert_array_equal(cs.v_min[0, h].cpu().numpy(), vmin.astype(np.float32))
+        assert relmax(cs.w[0, h].cpu().numpy().astype(np.float64), ocs.w) <= TOL_COMPRESSED
+        assert relmax(cs.v_s[0, h].cpu().numpy().astype(np.float64), ocs.V_S) <= TOL_COMPRESSED
+        assert relmax(out[0, h].float().cpu().numpy().astype(np.float64), ref) <= TOL_OUT[dtype]
