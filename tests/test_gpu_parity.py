@@ -654,3 +654,34 @@ def test_odd_widths_take_the_generic_kernels(dtype, n, m, d, dv, r, bins):
         assert relmax(cs.w[0, h].cpu().numpy().astype(np.float64), ocs.w) <= TOL_COMPRESSED
         assert relmax(cs.v_s[0, h].cpu().numpy().astype(np.float64), ocs.V_S) <= TOL_COMPRESSED
         assert relmax(out[0, h].float().cpu().numpy().astype(np.float64), ref) <= TOL_OUT[dtype]
+
+
+# ---------------------------------------------------------------------------------- extremes of the supported range
+@pytest.mark.parametrize("dtype,n,m,d,dv,r", [("f32", 1, 3, 8, 8, 1), ("f32", 5, 1, 1, 1, 5), ("bf16", 3, 200, 64, 64, 2),
+                                              ("bf16", 1024, 500, 256, 256, 64), ("f32", 1024, 100, 256, 256, 32)])
+def test_smallest_and_widest_shapes(dtype, n, m, d, dv, r):
+    rng = np.random.default_rng(1000 + n + d)
+    Q = wl.round_to_storage(rng.standard_normal((1, 1, m, d)), dtype)
+    K = wl.round_to_storage(rng.standard_normal((1, 1, n, d)) * (0.5 if d > 1 else 1.0), dtype)
+    V = wl.round_to_storage(rng.standard_normal((1, 1, n, dv)), dtype)
+    u = rng.random((1, r))
+    beta = 1.0 / np.sqrt(d)
+    out, cs = wc.wildcat(to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), r=r, uniforms=torch.from_numpy(u).to(dev()),
+                         return_coreset=True)
+    torch.cuda.synchronize()
+    ref, ocs, _ = wo.wildcat(Q[0, 0].astype(np.float64), K[0, 0].astype(np.float64), V[0, 0].astype(np.float64), beta, r,
+                             u[0], return_coreset=True)
+    np.testing.assert_array_equal(cs.idx[0, 0].cpu().numpy(), ocs.idx)
+    assert int(cs.r_eff[0, 0]) == ocs.r_eff
+    if r == n and ocs.r_eff == n:                       # every key chosen: W is a permutation, the result exact attention
+        ex = wo.exact_attention(Q[0, 0].astype(np.float64), K[0, 0].astype(np.float64), V[0, 0].astype(np.float64), beta)
+        assert relmax(ref, ex) < 1e-6
+    assert relmax(out[0, 0].float().cpu().numpy().astype(np.float64), ref) <= TOL_OUT[dtype]
+
+
+def test_largest_supported_rank():
+    """r = 2048 (the limit of the core solve, whose right-hand sides sit in LDS): 141 KB of dynamic LDS."""
+    w = wl.make(2, batch=1, q_heads=1, kv_heads=1, n=4096, r=2048)
+    out, cs = run_gpu(w)
+    print(check_against_oracle(w, out, cs))
+    assert wc.workspace_bytes(4096, 64, 2049) == 0
