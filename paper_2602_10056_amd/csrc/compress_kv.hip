@@ -745,19 +745,22 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     const int gstep = down ? -1 : 1;
     const H *fp = Fb + l_loc + (size_t)(down ? i - 1 : nc_rows) * SLAB;
     const double *gp = g + (down ? i - 1 : nc_rows);
+    // Rows in flight per thread: eight 16-byte loads with two keys per thread, twelve narrower ones with one key
+    // (those workgroups are small and few, and eight 8-byte loads each would not keep the memory system busy).
+    constexpr int U = KPT == 1 ? 12 : 8;
     int j = 0;
-    for (; j + 8 <= nh; j += 8) {
-      HistVec<KPT, H> h[8];
+    for (; j + U <= nh; j += U) {
+      HistVec<KPT, H> h[U];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) h[q].load(fp + q * fstep);
+      for (int q = 0; q < U; ++q) h[q].load(fp + q * fstep);
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
+      for (int q = 0; q < U; ++q) {
         const double gj = gp[q * gstep];
 #pragma unroll
         for (int k = 0; k < KPT; ++k) acc[k] = fma((double)h[q].v[k], gj, acc[k]);
       }
-      fp += 8 * fstep;
-      gp += 8 * gstep;
+      fp += U * fstep;
+      gp += U * gstep;
     }
     for (; j < nh; ++j) {
       HistVec<KPT, H> h;
@@ -880,7 +883,7 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 // NC > 0 a thread keeps the packed features of its keys in registers for the whole loop, which removes the
 // O(n d) key stream from every step.
 template <typename T, int KPT, int NC, typename H>
-__global__ __launch_bounds__(kThreads, 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
+__global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
                                                                   int hcn) {
   extern __shared__ double dyn[];
   __shared__ StepShared sh;
