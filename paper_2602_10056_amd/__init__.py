@@ -56,6 +56,10 @@ def load_library(force: bool = False):
         return _lib
     if not os.path.exists(LIB_PATH):
         raise WildcatError(f"{LIB_PATH} not found: build it first (python __graft_entry__.py)")
+    # torch first: it ships its own HIP runtime, and the library must bind to the runtime that owns the tensors'
+    # memory and streams.  Loaded before torch, the library would pull in the system's runtime as a second one
+    # in the process, and its launches would fail there (no device).
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     for name in EXPORTS:
         if not hasattr(lib, name):

@@ -106,3 +106,20 @@ def test_entry_points_reject_bad_arguments_before_launching():
     o.dtype = 3
     assert lib.wildcat_wtd_attn(one, ctypes.byref(c), one, 16, 64, 16, ctypes.byref(o)) == -1
     assert lib.wildcat_query_radius(one, 0, 64, ctypes.byref(o), one) == -1
+
+
+def test_library_shares_the_hip_runtime_of_torch():
+    """Loaded before torch, the library would bring a second HIP runtime into the process (the system's, next to
+    the one torch ships) and launch on a runtime that has no device.  load_library() imports torch first."""
+    import subprocess, sys
+    code = (
+        "import paper_2602_10056_amd as wc\n"
+        "wc.load_library()\n"
+        "import torch\n"
+        "paths = {l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l}\n"
+        "print(len(paths))\n"
+    )
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.strip().splitlines()[-1] == "1"
