@@ -32,6 +32,11 @@
  *     boundary.  Non-finite inputs give unspecified (but memory-safe) results.
  *   - Calls that share a workspace or output buffers must be ordered by the
  *     caller (same stream, or events).
+ *   - The library depends on the HIP runtime (libamdhip64) and must use the
+ *     same copy of it as the code that allocated the buffers and created the
+ *     stream: a host program that ships its own runtime loads that first and
+ *     this library afterwards.  On a second runtime in the process every
+ *     launch fails (WILDCAT_EHIP).
  */
 #ifndef WILDCAT_H
 #define WILDCAT_H
