@@ -245,10 +245,14 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 // by a per-problem power of two (coreset field v_scale) that is multiplied back in the epilogue.  The normaliser
 // sum_s P_s w_s is accumulated in fp32 on the vector ALU from the unrounded P.
 //
-// Workgroup = NW wavefronts, each owning 32 queries; two workgroups (NW = 4) share a compute unit so that one
-// wave's exp/convert work overlaps another's MFMAs.  Key tiles of 64 are double-buffered in LDS and filled
-// with direct global-to-LDS loads (global_load_lds_dwordx4: lane i of a wave writes 16 bytes at base + 16 i),
-// issued for tile t+1 before the math of tile t: no staging registers, one barrier per tile.
+// Workgroup = NW = 8 wavefronts, each owning 32 queries, one workgroup per compute unit (two waves per SIMD, so
+// that one wave's exp/convert work overlaps another's MFMAs).  Key tiles of 64 go through a ring of three LDS
+// buffers filled with direct global-to-LDS loads (global_load_lds_dwordx4: lane i of a wave writes 16 bytes at
+// base + 16 i): while tile t is computed, tile t+1 is in LDS or about to arrive and the loads of tile t+2 are
+// issued.  A tile's loads therefore have two tile times to complete -- under load the trip to L2 and back takes
+// longer than one -- and the wait at the end of a tile leaves the youngest tile's loads in flight (loads complete
+// in order, so "at most LPF outstanding" means everything older has arrived).  No staging registers, one
+// barrier per tile.
 //
 // Direct loads cannot pad rows, so bank conflicts are avoided by permuting the 16-byte pieces of a row:
 // piece p of row q is stored in slot p ^ ((q / rows_per_256B) % pieces_per_row).  Sixteen consecutive rows
@@ -263,11 +267,18 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 constexpr int kKT = 64;
 constexpr float kRescaleSlack = 8.0f;
 #ifndef WILDCAT_ATTN_NW
-#define WILDCAT_ATTN_NW 4
+#define WILDCAT_ATTN_NW 8
 #endif
 
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
+
+// A 64-key tile of an item: item = (batch*head, query tile) pair, pr its coreset, re the number of filled slots,
+// k0 the first key of the tile.  item >= total_items marks the end of the workgroup's list; pr, re and k0 then
+// still name a valid tile (loads of it are harmless and never used).
+struct TilePos {
+  int item, pr, re, k0;
+};
 
 // Kernel arguments and per-wave state of the pipelined kernel, passed by reference to the per-tile function.
 template <int D, int DV>
@@ -281,11 +292,12 @@ struct AttnCtx {
   int r, r64, q_heads, group, kv_heads, qtiles, total_items, stride;
   float scale_log2;
   int wv, l, g, c32, krow_sw, vrow_sw;
-  // per-lane source coordinates of this wave's tile loads (fixed for the whole kernel)
-  int krow[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW], kcol[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW];
-  int voff[DV * (kKT / 8) / 64 / WILDCAT_ATTN_NW];
-  // state
-  int item, pr, re, k0;
+  // per-lane byte offsets of this wave's tile loads from the tile's first key row / first value column entry
+  // (fixed for the whole kernel; the tile's own address is wave-uniform and stays in scalar registers)
+  uint32_t koff[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW];
+  uint32_t voff[DV * (kKT / 8) / 64 / WILDCAT_ATTN_NW];
+  // state: the tile being computed and the one after it (the one after that is being fetched)
+  TilePos cur, nxt;
   bf16x8 qf[D / 16];          // Q fragments: B operand of S^T = K Q^T (query c32, features 16 kb + 8 g .. + 7)
   floatx16 acc[DV / 32];      // O^T accumulators
   float mref, den;            // reference exponent (log2 domain) and normaliser of query c32
@@ -302,13 +314,18 @@ struct AttnGeom {
   static constexpr int VLOADS = DV * VPPR / 64 / NW;     // ... of the value tile
   static constexpr int CLOADS = (2 * DV + 63) / 64;      // wave-wide 256-byte loads of the clip vectors
   static_assert(KLOADS * NW * 64 == kKT * KPPR && VLOADS * NW * 64 == DV * VPPR, "tiles must split evenly");
-  static_assert(DV % 32 == 0 && CLOADS <= NW + 1, "clip vectors are loaded by waves 1..");
+  static_assert(DV % 32 == 0 && CLOADS <= NW - 1, "clip vectors are loaded by waves 1 .. CLOADS");
   // One LDS buffer (bytes): key tile | value tile | weights | clip vectors (v_min | v_max)
   static constexpr int OFF_K = 0;
   static constexpr int OFF_V = OFF_K + kKT * D * 2;
   static constexpr int OFF_W = OFF_V + DV * kKT * 2;
   static constexpr int OFF_C = OFF_W + kKT * 4;
   static constexpr int BYTES = OFF_C + CLOADS * 256;
+  // A wave's 1 KB loads per tile, and the s_waitcnt immediate "vmcnt(LPF), nothing else" (vmcnt is split over bits
+  // 3:0 and 15:14; 7 and 15 in the other two fields mean: do not wait for those counters).
+  static constexpr int LPF = KLOADS + VLOADS;
+  static constexpr int WAIT_LPF = (LPF & 15) | ((LPF >> 4) << 14) | (7 << 4) | (15 << 8);
+  static_assert(LPF >= 1 && LPF < 64, "vmcnt has six bits");
 };
 
 template <int D, int DV>
@@ -320,37 +337,83 @@ template <int D, int DV>
 __device__ __forceinline__ int attn_item_re(const AttnCtx<D, DV> &c, int pr) {
   return c.r_eff ? max(min(c.r_eff[pr], c.r), 1) : c.r;      // never below 1: the tile loads clamp rows to re - 1
 }
+// The tile after p in this workgroup's list: the next tile of the item, else tile 0 of item + gridDim.x.
+template <int D, int DV>
+__device__ __forceinline__ TilePos attn_advance(const AttnCtx<D, DV> &c, const TilePos p) {
+  TilePos n = p;
+  if (p.item >= c.total_items) return n;
+  if (p.k0 + kKT < p.re) {
+    n.k0 = p.k0 + kKT;
+    return n;
+  }
+  n.item = p.item + c.stride;
+  n.k0 = 0;
+  if (n.item < c.total_items) {
+    n.pr = attn_item_pr(c, n.item);
+    n.re = attn_item_re(c, n.pr);
+  }
+  return n;
+}
 
-// Direct global-to-LDS loads of one tile.  Rows past the last key are clamped to it (and masked after the score
-// product); v_t is zero padded.  With `with_clip`, v_min | v_max of the problem are loaded too.  The per-lane
-// source coordinates were worked out once (AttnCtx::krow, kcol, voff): per tile only the tile offset is added.
+// Direct global-to-LDS loads of one tile.  A tile's address is wave-uniform (scalar registers); each lane adds a byte
+// offset that was worked out once (AttnCtx::koff, voff), so a piece costs at most one vector add.  Only a ragged
+// last tile (fewer than 64 rows left in the coreset) clamps its rows to the last one; the clamped rows are masked
+// after the score product.  v_t is zero padded to a multiple of 64 columns.
+// Piece e of this wave's share of a tile: the first KLOADS pieces are 1 KB of keys each, the rest 1 KB of values.
 template <int D, int DV, int NW>
-__device__ __forceinline__ void attn_fetch(const AttnCtx<D, DV> &c, int pr, int re, int k0, char *__restrict__ wr,
-                                           bool with_clip) {
+__device__ __forceinline__ void attn_fetch_piece(const AttnCtx<D, DV> &c, const TilePos &p, char *__restrict__ wr,
+                                                 int e) {
   using G = AttnGeom<D, DV, NW>;
-  const bf16_t *Kp = c.Ks + (size_t)pr * c.r * D;
-  const uint16_t *Vp = c.Vt + (size_t)pr * DV * c.r64 + k0;
-#pragma unroll
-  for (int e = 0; e < G::KLOADS; ++e) {
-    const bf16_t *src = Kp + min(k0 + c.krow[e], re - 1) * D + c.kcol[e];
-    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(wr + G::OFF_K + (e * NW + c.wv) * 1024), 16, 0, 0);
+  if (e < G::KLOADS) {
+    const char *tile = reinterpret_cast<const char *>(c.Ks + ((size_t)p.pr * c.r + p.k0) * D);
+    uint32_t off = c.koff[e];
+    if (p.k0 + kKT > p.re) {                                   // ragged: row = min(row, re - 1 - k0)
+      const uint32_t row = off / (2 * D), last = (uint32_t)(p.re - 1 - p.k0);
+      off = min(row, last) * (2 * D) + off % (2 * D);
+    }
+    __builtin_amdgcn_global_load_lds((gptr_t)(tile + off), (lptr_t)(wr + G::OFF_K + (e * NW + c.wv) * 1024), 16, 0, 0);
+  } else {
+    const int v = e - G::KLOADS;
+    const char *tile = reinterpret_cast<const char *>(c.Vt + (size_t)p.pr * DV * c.r64 + p.k0);
+    __builtin_amdgcn_global_load_lds((gptr_t)(tile + c.voff[v]), (lptr_t)(wr + G::OFF_V + (v * NW + c.wv) * 1024), 16,
+                                     0, 0);
   }
-#pragma unroll
-  for (int e = 0; e < G::VLOADS; ++e)
-    __builtin_amdgcn_global_load_lds((gptr_t)(Vp + c.voff[e]), (lptr_t)(wr + G::OFF_V + (e * NW + c.wv) * 1024), 16, 0,
-                                     0);
-  if (c.wv == 0)
-    __builtin_amdgcn_global_load_lds((gptr_t)(c.w + (size_t)pr * c.r + min(k0 + c.l, re - 1)),
-                                     (lptr_t)(wr + G::OFF_W), 4, 0, 0);
-  if (with_clip) {
-#pragma unroll
-    for (int q = 0; q < G::CLOADS; ++q)
-      if (c.wv == (q + 1) % NW) {
-        const int e = min(q * 64 + c.l, 2 * DV - 1);
-        const float *src = e < DV ? c.vmin + (size_t)pr * DV + e : c.vmax + (size_t)pr * DV + (e - DV);
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(wr + G::OFF_C + q * 256), 4, 0, 0);
-      }
+}
+
+// The small pieces of a tile: its weights (wave 0) and v_min | v_max of its problem (waves 1 ..), so that every
+// buffer of the ring holds the clip vectors of the item its tile belongs to.  c.wv is wave-uniform (scalar), so
+// these are scalar branches; a wave issues at most one of the loads.
+template <int D, int DV, int NW>
+__device__ __forceinline__ void attn_fetch_small(const AttnCtx<D, DV> &c, const TilePos &p, char *__restrict__ wr) {
+  using G = AttnGeom<D, DV, NW>;
+  static_assert(DV % 64 == 0, "a wave's 64 clip entries lie in v_min or in v_max, not across");
+  if (c.wv == 0) {
+    const float *tile = c.w + (size_t)p.pr * c.r + p.k0;
+    const int j = p.k0 + kKT > p.re ? min(c.l, p.re - 1 - p.k0) : c.l;
+    __builtin_amdgcn_global_load_lds((gptr_t)(tile + j), (lptr_t)(wr + G::OFF_W), 4, 0, 0);
+  } else if (c.wv <= G::CLOADS) {
+    const int q = c.wv - 1;                                   // entries 64 q .. 64 q + 63 of v_min | v_max
+    const float *vec = q < DV / 64 ? c.vmin + (size_t)p.pr * DV + 64 * q : c.vmax + (size_t)p.pr * DV + (64 * q - DV);
+    __builtin_amdgcn_global_load_lds((gptr_t)(vec + c.l), (lptr_t)(wr + G::OFF_C + q * 256), 4, 0, 0);
   }
+}
+
+// The 1 KB pieces of a tile.  They are issued AFTER everything else a wave loads during a tile, so that "at most
+// LPF loads outstanding" at the end of the tile means: only these.
+template <int D, int DV, int NW>
+__device__ __forceinline__ void attn_fetch_big(const AttnCtx<D, DV> &c, const TilePos &p, char *__restrict__ wr) {
+  using G = AttnGeom<D, DV, NW>;
+#pragma unroll
+  for (int e = 0; e < G::LPF; ++e) attn_fetch_piece<D, DV, NW>(c, p, wr, e);
+}
+
+// A whole tile (used before the loop).  `wr` is __restrict__ here too: the compiler's bookkeeping of direct-to-LDS
+// loads only tells buffers apart whose loads it has seen through such a pointer, and falls back to "wait for
+// every load" at the first LDS read of a buffer it has no record for.
+template <int D, int DV, int NW>
+__device__ __forceinline__ void attn_fetch_tile(const AttnCtx<D, DV> &c, const TilePos &p, char *__restrict__ wr) {
+  attn_fetch_small<D, DV, NW>(c, p, wr);
+  attn_fetch_big<D, DV, NW>(c, p, wr);
 }
 
 template <int D, int DV, int NW>
@@ -366,10 +429,11 @@ __device__ __forceinline__ void attn_load_q(AttnCtx<D, DV> &c, int item) {
   }
 }
 
-// One 64-key tile of one item: reads LDS buffer `rd`, starts filling `wr` with the following tile.  The two are
-// __restrict__ so that, once inlined, the compiler knows the buffer being filled is not the one being read and
-// does not make LDS reads wait for the loads just issued.  (One pointer per buffer on purpose: the compiler
-// can only keep a handful of such distinctions apart.)
+// One 64-key tile of one item: reads LDS buffer `rd` (tile c.cur) and starts filling `wr` with the tile after
+// the next one.  The three ring buffers are distinct arrays and the two pointers are __restrict__, so that, once
+// this function is inlined at its three places in the ring, the compiler can tell the buffer being read from the
+// two with loads in flight and does not make LDS reads wait for them.  (One pointer per buffer on purpose: the
+// compiler can only keep a handful of such distinctions apart.)
 // Returns false after the last tile of the workgroup's last item.
 template <int D, int DV, int NW>
 __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restrict__ rd, char *__restrict__ wr) {
@@ -377,22 +441,16 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
   const uint16_t *lkr = reinterpret_cast<const uint16_t *>(rd + G::OFF_K);
   const uint16_t *lvr = reinterpret_cast<const uint16_t *>(rd + G::OFF_V);
   const float *lwr = reinterpret_cast<const float *>(rd + G::OFF_W);
-  // Nothing is outstanding here (every call ends with a full wait).  Saying so explicitly keeps the compiler from
-  // guarding the first use of the Q fragments with a wait that would also cover the loads issued just below.
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
+  // Already true here (see the end of this function); said again because, where the loop's back edge meets its
+  // entry, the compiler otherwise guards the first use of the Q fragments with a wait for EVERY load in flight.
+  __builtin_amdgcn_s_waitcnt(G::WAIT_LPF);
   const int g = c.g, c32 = c.c32;
-  // ---- what comes next: the following tile of this item, or tile 0 of the workgroup's next item -----------------
-  const bool last_tile = c.k0 + kKT >= c.re;
-  const int nitem = last_tile ? c.item + c.stride : c.item;
-  const bool more = nitem < c.total_items;
-  const int npr = (last_tile && more) ? attn_item_pr(c, nitem) : c.pr;
-  const int nre = (last_tile && more) ? attn_item_re(c, npr) : c.re;
-  const int nk0 = last_tile ? 0 : c.k0 + kKT;
-  // Loads for the next tile fly during all of this tile's math; none are issued in the very last iteration, so
-  // no direct-to-LDS load is outstanding when the workgroup ends.
-  // The clip vectors travel with tiles 0 and 1 of an item, so both buffers hold them and the epilogue can read
-  // them from the buffer it is not filling.
-  if (!last_tile || more) attn_fetch<D, DV, NW>(c, npr, nre, nk0, wr, nk0 <= kKT);
+  const bool last_tile = c.cur.k0 + kKT >= c.cur.re;         // then c.nxt is tile 0 of the workgroup's next item
+  const bool more = c.nxt.item < c.total_items;
+  // The tile after the next one is fetched during this tile.  Past the end of the list it is a valid tile again
+  // (never used), so every wave issues the same loads in every tile and the wait below needs no cases.
+  const TilePos fut = attn_advance(c, c.nxt);
+  attn_fetch_small<D, DV, NW>(c, fut, wr);
   // ---- S^T = K Q^T for the two 32-key halves -----------------------------------------------------------
   floatx16 st[2];
 #pragma unroll
@@ -411,15 +469,16 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
   // The Q fragments are dead after the last score product of an item: the next item's are loaded into the same
   // registers now and arrive during the softmax, value product and epilogue of this tile.
   if (last_tile && more) {
-    attn_load_q<D, DV, NW>(c, nitem);
-    c.nvsc = c.vscale[npr];
+    attn_load_q<D, DV, NW>(c, c.nxt.item);
+    c.nvsc = c.vscale[c.nxt.pr];
   }
-  if (c.k0 + kKT > c.re) {                                   // ragged last tile: mask the missing keys
+  attn_fetch_big<D, DV, NW>(c, fut, wr);                     // youngest loads of the tile, see attn_fetch_big
+  if (c.cur.k0 + kKT > c.cur.re) {                           // ragged last tile: mask the missing keys
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        if (c.k0 + 32 * mt + 16 * (v / 8) + 8 * g + 4 * ((v / 4) % 2) + (v % 4) >= c.re) st[mt][v] = -INFINITY;
+        if (c.cur.k0 + 32 * mt + 16 * (v / 8) + 8 * g + 4 * ((v / 4) % 2) + (v % 4) >= c.cur.re) st[mt][v] = -INFINITY;
   }
   // ---- row maximum of the raw scores; move the reference only if it is more than the slack behind ------------
   float mx = st[0][0];
@@ -482,8 +541,8 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
     const float dn = c.den + __shfl_xor(c.den, 32, kWave);
     const bool ok = dn > 0.0f;
     const float inv = ok ? c.vsc / dn : 0.0f;               // v_t holds V_S^T / v_scale
-    const int bh = c.item / c.qtiles;
-    const int64_t qrow = (int64_t)(c.item % c.qtiles) * (NW * 32) + c.wv * 32 + c32;
+    const int bh = c.cur.item / c.qtiles;
+    const int64_t qrow = (int64_t)(c.cur.item % c.qtiles) * (NW * 32) + c.wv * 32 + c32;
     if (qrow < c.m) {
       bf16_t *orow = c.out + ((size_t)bh * c.m + qrow) * DV;
       const float *clip = reinterpret_cast<const float *>(rd + G::OFF_C);
@@ -514,9 +573,14 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
     c.den = 0.0f;
     c.vsc = c.nvsc;
   }
-  __builtin_amdgcn_s_waitcnt(0);       // this wave's share of the next tile (and the next Q fragments) has arrived
-  __syncthreads();
-  c.item = nitem; c.pr = npr; c.re = nre; c.k0 = nk0;
+  // This wave's share of the NEXT tile (issued one tile ago), the small pieces of the one after it and, at the end
+  // of an item, the next Q fragments have arrived; the 1 KB pieces issued in this tile stay in flight.  A bare
+  // s_barrier on purpose: __syncthreads() would first wait for every outstanding load.  All LDS reads of this tile
+  // have been consumed by the MFMAs and sums above, so after the barrier `rd` may be overwritten.
+  __builtin_amdgcn_s_waitcnt(G::WAIT_LPF);
+  __builtin_amdgcn_s_barrier();
+  c.cur = c.nxt;
+  c.nxt = fut;
   return true;
 }
 
@@ -529,46 +593,52 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
   using G = AttnGeom<D, DV, NW>;
   __shared__ __attribute__((aligned(16))) char buf0[G::BYTES];
   __shared__ __attribute__((aligned(16))) char buf1[G::BYTES];
+  __shared__ __attribute__((aligned(16))) char buf2[G::BYTES];
 
   AttnCtx<D, DV> c;
   c.Q = Q; c.Ks = Ks; c.Vt = Vt; c.vscale = vscale; c.w = w; c.vmin = vmin; c.vmax = vmax; c.r_eff = r_eff; c.out = out;
   c.m = m; c.r = r; c.r64 = r64; c.q_heads = q_heads; c.group = group; c.kv_heads = q_heads / group;
   c.qtiles = qtiles; c.total_items = total_items; c.stride = (int)gridDim.x; c.scale_log2 = scale_log2;
   const int t = threadIdx.x;
-  c.wv = t / kWave; c.l = t % kWave; c.g = c.l / 32; c.c32 = c.l % 32;
+  c.wv = __builtin_amdgcn_readfirstlane(t / kWave);          // wave-uniform: keep it in a scalar register
+  c.l = t % kWave; c.g = c.l / 32; c.c32 = c.l % 32;
   c.krow_sw = (c.c32 / G::KRP) % G::KPPR;          // slot permutation of this lane's operand rows
   c.vrow_sw = (c.c32 / G::VRP) % G::VPPR;
 #pragma unroll
   for (int e = 0; e < G::KLOADS; ++e) {      // LDS piece (e NW + wv) 64 + l holds key row `row`, logical piece `slot ^ ...`
     const int idx = (e * NW + c.wv) * 64 + c.l, row = idx / G::KPPR, slot = idx % G::KPPR;
-    c.krow[e] = (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1);      // LDS row `row` holds key pi(row), see attn_tile
-    c.kcol[e] = (slot ^ ((row / G::KRP) % G::KPPR)) * 8;
+    const int krow = (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1); // LDS row `row` holds key pi(row), see attn_tile
+    c.koff[e] = (uint32_t)(krow * D + (slot ^ ((row / G::KRP) % G::KPPR)) * 8) * 2;
   }
 #pragma unroll
   for (int e = 0; e < G::VLOADS; ++e) {
     const int idx = (e * NW + c.wv) * 64 + c.l, row = idx / G::VPPR, slot = idx % G::VPPR;
-    c.voff[e] = row * r64 + (slot ^ ((row / G::VRP) % G::VPPR)) * 8;
+    c.voff[e] = (uint32_t)(row * r64 + (slot ^ ((row / G::VRP) % G::VPPR)) * 8) * 2;
   }
 
   // An item is one (batch*head, query tile) pair; this workgroup takes items blockIdx.x, + gridDim.x, ...
-  c.item = blockIdx.x;
-  if (c.item >= total_items) return;
-  c.pr = attn_item_pr(c, c.item);
-  c.re = attn_item_re(c, c.pr);
-  c.k0 = 0;
-  attn_fetch<D, DV, NW>(c, c.pr, c.re, 0, buf0, true);
-  attn_load_q<D, DV, NW>(c, c.item);
+  c.cur.item = blockIdx.x;
+  if (c.cur.item >= total_items) return;
+  c.cur.pr = attn_item_pr(c, c.cur.item);
+  c.cur.re = attn_item_re(c, c.cur.pr);
+  c.cur.k0 = 0;
+  c.nxt = attn_advance(c, c.cur);
+  attn_fetch_tile<D, DV, NW>(c, c.cur, buf0);
+  attn_fetch_tile<D, DV, NW>(c, c.nxt, buf1);
+  attn_load_q<D, DV, NW>(c, c.cur.item);
 #pragma unroll
   for (int i = 0; i < DV / 32; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) c.acc[i][v] = 0.0f;
   c.mref = -INFINITY;
   c.den = 0.0f;
-  c.vsc = c.nvsc = vscale[c.pr];
-  __builtin_amdgcn_s_waitcnt(0);           // tile 0 and the Q fragments have arrived
+  c.vsc = c.nvsc = vscale[c.cur.pr];
+  __builtin_amdgcn_s_waitcnt(0);           // tiles 0 and 1 and the Q fragments have arrived
   __syncthreads();
-  while (attn_tile<D, DV, NW>(c, buf0, buf1) && attn_tile<D, DV, NW>(c, buf1, buf0)) {
+  while (attn_tile<D, DV, NW>(c, buf0, buf2) && attn_tile<D, DV, NW>(c, buf1, buf0) &&
+         attn_tile<D, DV, NW>(c, buf2, buf1)) {
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): no direct-to-LDS load is in flight when the workgroup ends
 }
 
 // ---- packed values: v_t[pr][c][j] = fp16(v_s[pr][j][c] / v_scale[pr]) for j < r, zero for r <= j < r64 -----------
@@ -737,7 +807,9 @@ extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *
     cs = &all_slots;
   }
   if (s.dtype == WILDCAT_BF16) {
-    if (cs->v_t && cs->v_scale) {
+    // the MFMA kernel addresses a problem's packed values with 32-bit byte offsets
+    const bool fits = (int64_t)((s.r + 63) / 64 * 64) * s.dv * 2 <= (int64_t)UINT32_MAX;
+    if (cs->v_t && cs->v_scale && fits) {
       if (s.d == 64 && s.dv == 64) return launch_mfma2<64, 64>(s, Q, cs, out);
       if (s.d == 128 && s.dv == 128) return launch_mfma2<128, 128>(s, Q, cs, out);
       if (s.d == 64 && s.dv == 128) return launch_mfma2<64, 128>(s, Q, cs, out);
