@@ -245,16 +245,17 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 // by a per-problem power of two (coreset field v_scale) that is multiplied back in the epilogue.  The normaliser
 // sum_s P_s w_s is accumulated in fp32 on the vector ALU from the unrounded P.
 //
-// Workgroup = NW = 8 wavefronts, each owning 32 queries, one workgroup per compute unit (two waves per SIMD, so
-// that one wave's exp/convert work overlaps another's MFMAs).  Key tiles of 64 go through a ring of three LDS
-// buffers filled with direct global-to-LDS loads (global_load_lds_dwordx4: lane i of a wave writes 16 bytes at
-// base + 16 i): while tile t is computed, tile t+1 is in LDS or about to arrive and the loads of tile t+2 are
-// issued.  A tile's loads therefore have two tile times to complete -- under load the trip to L2 and back takes
-// longer than one -- and the wait at the end of a tile leaves the youngest tile's loads in flight (loads complete
-// in order, so "at most LPF outstanding" means everything older has arrived).  No staging registers, one
-// barrier per tile.
+// Workgroup = NW = 8 wavefronts, each owning 32 queries, one or more workgroups per compute unit (at least two
+// waves per SIMD, so that one wave's exp/convert work overlaps another's MFMAs).  Key tiles of 64 are
+// double-buffered in LDS.  While tile t is computed, the global loads of tile t+2 fly into a few staging
+// registers (each wave fetches 1 KB pieces: lane i holds bytes 16 i .. 16 i + 15); at the start of tile t+1 they
+// are stored into the buffer tile t-1 was read from.  So a tile's loads have a whole tile time to arrive -- under
+// load the trip to L2 and back takes about that long -- and the wait for them is an ordinary register dependence.
+// (Direct global-to-LDS loads, which need no staging registers, were measured and dropped: while one is in flight
+// the compiler turns every wait for an LDS operand into a wait for ALL outstanding LDS reads, which rules out
+// requesting operands ahead of the MFMAs that use them.)  One barrier per tile.
 //
-// Direct loads cannot pad rows, so bank conflicts are avoided by permuting the 16-byte pieces of a row:
+// Rows are not padded; bank conflicts are avoided by permuting the 16-byte pieces of a row:
 // piece p of row q is stored in slot p ^ ((q / rows_per_256B) % pieces_per_row).  Sixteen consecutive rows
 // then put the same logical piece into sixteen different 16-byte bank groups.
 //
@@ -265,13 +266,13 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 // a maximum the row has already seen, so the largest P of a row is >= 1 and every P is <= 2^8.
 // --------------------------------------------------------------------------------------------
 constexpr int kKT = 64;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr float kRescaleSlack = 8.0f;
+constexpr int kSchedMfma = 0x008, kSchedDsRead = 0x100;      // instruction classes of sched_group_barrier
 #ifndef WILDCAT_ATTN_NW
 #define WILDCAT_ATTN_NW 8
 #endif
 
-typedef const __attribute__((address_space(1))) void *gptr_t;
-typedef __attribute__((address_space(3))) void *lptr_t;
 
 // A 64-key tile of an item: item = (batch*head, query tile) pair, pr its coreset, re the number of filled slots,
 // k0 the first key of the tile.  item >= total_items marks the end of the workgroup's list; pr, re and k0 then
@@ -296,8 +297,10 @@ struct AttnCtx {
   // (fixed for the whole kernel; the tile's own address is wave-uniform and stays in scalar registers)
   uint32_t koff[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW];
   uint32_t voff[DV * (kKT / 8) / 64 / WILDCAT_ATTN_NW];
-  // state: the tile being computed and the one after it (the one after that is being fetched)
+  // state: the tile being computed and the one after it, whose data is in the staging registers (or on its way)
   TilePos cur, nxt;
+  u32x4 stage[(kKT * (D / 8) + DV * (kKT / 8)) / 64 / WILDCAT_ATTN_NW];   // this wave's 1 KB pieces of tile nxt
+  float stage_small;          // wave 0: weight of key l of tile nxt; waves 1 .. CLOADS: 64 entries of v_min | v_max
   bf16x8 qf[D / 16];          // Q fragments: B operand of S^T = K Q^T (query c32, features 16 kb + 8 g .. + 7)
   floatx16 acc[DV / 32];      // O^T accumulators
   float mref, den;            // reference exponent (log2 domain) and normaliser of query c32
@@ -321,11 +324,7 @@ struct AttnGeom {
   static constexpr int OFF_W = OFF_V + DV * kKT * 2;
   static constexpr int OFF_C = OFF_W + kKT * 4;
   static constexpr int BYTES = OFF_C + CLOADS * 256;
-  // A wave's 1 KB loads per tile, and the s_waitcnt immediate "vmcnt(LPF), nothing else" (vmcnt is split over bits
-  // 3:0 and 15:14; 7 and 15 in the other two fields mean: do not wait for those counters).
-  static constexpr int LPF = KLOADS + VLOADS;
-  static constexpr int WAIT_LPF = (LPF & 15) | ((LPF >> 4) << 14) | (7 << 4) | (15 << 8);
-  static_assert(LPF >= 1 && LPF < 64, "vmcnt has six bits");
+  static constexpr int LPF = KLOADS + VLOADS;            // a wave's 1 KB pieces per tile
 };
 
 template <int D, int DV>
@@ -355,65 +354,54 @@ __device__ __forceinline__ TilePos attn_advance(const AttnCtx<D, DV> &c, const T
   return n;
 }
 
-// Direct global-to-LDS loads of one tile.  A tile's address is wave-uniform (scalar registers); each lane adds a byte
-// offset that was worked out once (AttnCtx::koff, voff), so a piece costs at most one vector add.  Only a ragged
-// last tile (fewer than 64 rows left in the coreset) clamps its rows to the last one; the clamped rows are masked
-// after the score product.  v_t is zero padded to a multiple of 64 columns.
-// Piece e of this wave's share of a tile: the first KLOADS pieces are 1 KB of keys each, the rest 1 KB of values.
+// Global loads of one tile into the staging registers.  A tile's address is wave-uniform (scalar registers); each
+// lane adds a byte offset that was worked out once (AttnCtx::koff, voff).  Only a ragged last tile (fewer than 64
+// rows left in the coreset) clamps its rows to the last one; the clamped rows are masked after the score product.
+// v_t is zero padded to a multiple of 64 columns.  The first KLOADS pieces are 1 KB of keys each, the rest 1 KB of
+// values; the small piece is the tile's weights (wave 0) or a quarter of v_min | v_max of its problem (waves
+// 1 .. CLOADS), so that each LDS buffer holds the clip vectors of the item its tile belongs to.  c.wv is
+// wave-uniform (scalar), so those are scalar branches.
 template <int D, int DV, int NW>
-__device__ __forceinline__ void attn_fetch_piece(const AttnCtx<D, DV> &c, const TilePos &p, char *__restrict__ wr,
-                                                 int e) {
+__device__ __forceinline__ void attn_stage_tile(AttnCtx<D, DV> &c, const TilePos &p) {
   using G = AttnGeom<D, DV, NW>;
-  if (e < G::KLOADS) {
-    const char *tile = reinterpret_cast<const char *>(c.Ks + ((size_t)p.pr * c.r + p.k0) * D);
+  static_assert(DV % 64 == 0, "a wave's 64 clip entries lie in v_min or in v_max, not across");
+  const bool ragged = p.k0 + kKT > p.re;
+  const char *ktile = reinterpret_cast<const char *>(c.Ks + ((size_t)p.pr * c.r + p.k0) * D);
+  const char *vtile = reinterpret_cast<const char *>(c.Vt + (size_t)p.pr * DV * c.r64 + p.k0);
+#pragma unroll
+  for (int e = 0; e < G::KLOADS; ++e) {
     uint32_t off = c.koff[e];
-    if (p.k0 + kKT > p.re) {                                   // ragged: row = min(row, re - 1 - k0)
+    if (ragged) {                                             // row = min(row, re - 1 - k0)
       const uint32_t row = off / (2 * D), last = (uint32_t)(p.re - 1 - p.k0);
       off = min(row, last) * (2 * D) + off % (2 * D);
     }
-    __builtin_amdgcn_global_load_lds((gptr_t)(tile + off), (lptr_t)(wr + G::OFF_K + (e * NW + c.wv) * 1024), 16, 0, 0);
-  } else {
-    const int v = e - G::KLOADS;
-    const char *tile = reinterpret_cast<const char *>(c.Vt + (size_t)p.pr * DV * c.r64 + p.k0);
-    __builtin_amdgcn_global_load_lds((gptr_t)(tile + c.voff[v]), (lptr_t)(wr + G::OFF_V + (v * NW + c.wv) * 1024), 16,
-                                     0, 0);
+    c.stage[e] = *reinterpret_cast<const u32x4 *>(ktile + off);
   }
-}
-
-// The small pieces of a tile: its weights (wave 0) and v_min | v_max of its problem (waves 1 ..), so that every
-// buffer of the ring holds the clip vectors of the item its tile belongs to.  c.wv is wave-uniform (scalar), so
-// these are scalar branches; a wave issues at most one of the loads.
-template <int D, int DV, int NW>
-__device__ __forceinline__ void attn_fetch_small(const AttnCtx<D, DV> &c, const TilePos &p, char *__restrict__ wr) {
-  using G = AttnGeom<D, DV, NW>;
-  static_assert(DV % 64 == 0, "a wave's 64 clip entries lie in v_min or in v_max, not across");
+#pragma unroll
+  for (int e = 0; e < G::VLOADS; ++e) c.stage[G::KLOADS + e] = *reinterpret_cast<const u32x4 *>(vtile + c.voff[e]);
   if (c.wv == 0) {
     const float *tile = c.w + (size_t)p.pr * c.r + p.k0;
-    const int j = p.k0 + kKT > p.re ? min(c.l, p.re - 1 - p.k0) : c.l;
-    __builtin_amdgcn_global_load_lds((gptr_t)(tile + j), (lptr_t)(wr + G::OFF_W), 4, 0, 0);
+    c.stage_small = tile[ragged ? min(c.l, p.re - 1 - p.k0) : c.l];
   } else if (c.wv <= G::CLOADS) {
     const int q = c.wv - 1;                                   // entries 64 q .. 64 q + 63 of v_min | v_max
     const float *vec = q < DV / 64 ? c.vmin + (size_t)p.pr * DV + 64 * q : c.vmax + (size_t)p.pr * DV + (64 * q - DV);
-    __builtin_amdgcn_global_load_lds((gptr_t)(vec + c.l), (lptr_t)(wr + G::OFF_C + q * 256), 4, 0, 0);
+    c.stage_small = vec[c.l];
   }
 }
 
-// The 1 KB pieces of a tile.  They are issued AFTER everything else a wave loads during a tile, so that "at most
-// LPF loads outstanding" at the end of the tile means: only these.
+// Stores the staged tile into LDS buffer `wr`: piece e of wave wv is bytes (e NW + wv) 1024 .. + 1023 of the key
+// (then value) tile, 16 per lane.
 template <int D, int DV, int NW>
-__device__ __forceinline__ void attn_fetch_big(const AttnCtx<D, DV> &c, const TilePos &p, char *__restrict__ wr) {
+__device__ __forceinline__ void attn_store_tile(const AttnCtx<D, DV> &c, char *__restrict__ wr) {
   using G = AttnGeom<D, DV, NW>;
 #pragma unroll
-  for (int e = 0; e < G::LPF; ++e) attn_fetch_piece<D, DV, NW>(c, p, wr, e);
-}
-
-// A whole tile (used before the loop).  `wr` is __restrict__ here too: the compiler's bookkeeping of direct-to-LDS
-// loads only tells buffers apart whose loads it has seen through such a pointer, and falls back to "wait for
-// every load" at the first LDS read of a buffer it has no record for.
-template <int D, int DV, int NW>
-__device__ __forceinline__ void attn_fetch_tile(const AttnCtx<D, DV> &c, const TilePos &p, char *__restrict__ wr) {
-  attn_fetch_small<D, DV, NW>(c, p, wr);
-  attn_fetch_big<D, DV, NW>(c, p, wr);
+  for (int e = 0; e < G::KLOADS; ++e)
+    *reinterpret_cast<u32x4 *>(wr + G::OFF_K + (e * NW + c.wv) * 1024 + c.l * 16) = c.stage[e];
+#pragma unroll
+  for (int e = 0; e < G::VLOADS; ++e)
+    *reinterpret_cast<u32x4 *>(wr + G::OFF_V + (e * NW + c.wv) * 1024 + c.l * 16) = c.stage[G::KLOADS + e];
+  if (c.wv == 0) reinterpret_cast<float *>(wr + G::OFF_W)[c.l] = c.stage_small;
+  else if (c.wv <= G::CLOADS) reinterpret_cast<float *>(wr + G::OFF_C + (c.wv - 1) * 256)[c.l] = c.stage_small;
 }
 
 template <int D, int DV, int NW>
@@ -429,11 +417,8 @@ __device__ __forceinline__ void attn_load_q(AttnCtx<D, DV> &c, int item) {
   }
 }
 
-// One 64-key tile of one item: reads LDS buffer `rd` (tile c.cur) and starts filling `wr` with the tile after
-// the next one.  The three ring buffers are distinct arrays and the two pointers are __restrict__, so that, once
-// this function is inlined at its three places in the ring, the compiler can tell the buffer being read from the
-// two with loads in flight and does not make LDS reads wait for them.  (One pointer per buffer on purpose: the
-// compiler can only keep a handful of such distinctions apart.)
+// One 64-key tile of one item: reads LDS buffer `rd` (tile c.cur); first stores the staged tile c.nxt into `wr`
+// (free since the barrier that ended the previous tile) and starts the loads of the tile after it.
 // Returns false after the last tile of the workgroup's last item.
 template <int D, int DV, int NW>
 __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restrict__ rd, char *__restrict__ wr) {
@@ -441,38 +426,55 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
   const uint16_t *lkr = reinterpret_cast<const uint16_t *>(rd + G::OFF_K);
   const uint16_t *lvr = reinterpret_cast<const uint16_t *>(rd + G::OFF_V);
   const float *lwr = reinterpret_cast<const float *>(rd + G::OFF_W);
-  // Already true here (see the end of this function); said again because, where the loop's back edge meets its
-  // entry, the compiler otherwise guards the first use of the Q fragments with a wait for EVERY load in flight.
-  __builtin_amdgcn_s_waitcnt(G::WAIT_LPF);
   const int g = c.g, c32 = c.c32;
   const bool last_tile = c.cur.k0 + kKT >= c.cur.re;         // then c.nxt is tile 0 of the workgroup's next item
   const bool more = c.nxt.item < c.total_items;
-  // The tile after the next one is fetched during this tile.  Past the end of the list it is a valid tile again
-  // (never used), so every wave issues the same loads in every tile and the wait below needs no cases.
+  attn_store_tile<D, DV, NW>(c, wr);
+  // Past the end of the workgroup's list this is a valid tile again (never used), so every tile does the same.
   const TilePos fut = attn_advance(c, c.nxt);
-  attn_fetch_small<D, DV, NW>(c, fut, wr);
+  attn_stage_tile<D, DV, NW>(c, fut);
   // ---- S^T = K Q^T for the two 32-key halves -----------------------------------------------------------
   floatx16 st[2];
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
     for (int v = 0; v < 16; ++v) st[mt][v] = 0.0f;
+  // The K operands are requested two feature blocks (four MFMAs) ahead of their use, through a ring of three
+  // operand pairs; the sched_group_barrier sequence below makes the compiler keep that order (left alone it
+  // requests each pair right before the MFMAs that need it and then waits out the LDS latency eight times).
+  constexpr int KB = D / 16;
+  auto k_operand = [&](int kb, int mt) {
+    const int slot = (2 * kb + g) ^ c.krow_sw;
+    return *reinterpret_cast<const bf16x8 *>(&lkr[(32 * mt + c32) * D + slot * 8]);
+  };
+  bf16x8 ka[3][2];
 #pragma unroll
-  for (int kb = 0; kb < D / 16; ++kb) {
+  for (int kb = 0; kb < 2 && kb < KB; ++kb)
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      const int slot = (2 * kb + g) ^ c.krow_sw;
-      const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&lkr[(32 * mt + c32) * D + slot * 8]);
-      st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, c.qf[kb], st[mt], 0, 0, 0);
+    for (int mt = 0; mt < 2; ++mt) ka[kb][mt] = k_operand(kb, mt);
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb) {
+    if (kb + 2 < KB) {
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) ka[(kb + 2) % 3][mt] = k_operand(kb + 2, mt);
     }
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+      st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb % 3][mt], c.qf[kb], st[mt], 0, 0, 0);
   }
+  __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 4, 0);
+#pragma unroll
+  for (int kb = 0; kb + 2 < KB; ++kb) {
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(kSchedMfma, 4, 0);
   // The Q fragments are dead after the last score product of an item: the next item's are loaded into the same
   // registers now and arrive during the softmax, value product and epilogue of this tile.
   if (last_tile && more) {
     attn_load_q<D, DV, NW>(c, c.nxt.item);
     c.nvsc = c.vscale[c.nxt.pr];
   }
-  attn_fetch_big<D, DV, NW>(c, fut, wr);                     // youngest loads of the tile, see attn_fetch_big
   if (c.cur.k0 + kKT > c.cur.re) {                           // ragged last tile: mask the missing keys
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -573,11 +575,10 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
     c.den = 0.0f;
     c.vsc = c.nvsc;
   }
-  // This wave's share of the NEXT tile (issued one tile ago), the small pieces of the one after it and, at the end
-  // of an item, the next Q fragments have arrived; the 1 KB pieces issued in this tile stay in flight.  A bare
-  // s_barrier on purpose: __syncthreads() would first wait for every outstanding load.  All LDS reads of this tile
-  // have been consumed by the MFMAs and sums above, so after the barrier `rd` may be overwritten.
-  __builtin_amdgcn_s_waitcnt(G::WAIT_LPF);
+  // The stores into `wr` have completed (lgkmcnt(0); 0xC07F leaves the other counters alone) and every LDS read of
+  // this tile has been consumed by the MFMAs and sums above, so after the barrier `wr` may be read and `rd`
+  // overwritten.  A bare s_barrier on purpose: __syncthreads() would also wait for the loads in flight.
+  __builtin_amdgcn_s_waitcnt(0xC07F);
   __builtin_amdgcn_s_barrier();
   c.cur = c.nxt;
   c.nxt = fut;
@@ -593,7 +594,6 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
   using G = AttnGeom<D, DV, NW>;
   __shared__ __attribute__((aligned(16))) char buf0[G::BYTES];
   __shared__ __attribute__((aligned(16))) char buf1[G::BYTES];
-  __shared__ __attribute__((aligned(16))) char buf2[G::BYTES];
 
   AttnCtx<D, DV> c;
   c.Q = Q; c.Ks = Ks; c.Vt = Vt; c.vscale = vscale; c.w = w; c.vmin = vmin; c.vmax = vmax; c.r_eff = r_eff; c.out = out;
@@ -623,8 +623,9 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
   c.cur.re = attn_item_re(c, c.cur.pr);
   c.cur.k0 = 0;
   c.nxt = attn_advance(c, c.cur);
-  attn_fetch_tile<D, DV, NW>(c, c.cur, buf0);
-  attn_fetch_tile<D, DV, NW>(c, c.nxt, buf1);
+  attn_stage_tile<D, DV, NW>(c, c.cur);
+  attn_store_tile<D, DV, NW>(c, buf0);
+  attn_stage_tile<D, DV, NW>(c, c.nxt);
   attn_load_q<D, DV, NW>(c, c.cur.item);
 #pragma unroll
   for (int i = 0; i < DV / 32; ++i)
@@ -633,12 +634,9 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
   c.mref = -INFINITY;
   c.den = 0.0f;
   c.vsc = c.nvsc = vscale[c.cur.pr];
-  __builtin_amdgcn_s_waitcnt(0);           // tiles 0 and 1 and the Q fragments have arrived
-  __syncthreads();
-  while (attn_tile<D, DV, NW>(c, buf0, buf2) && attn_tile<D, DV, NW>(c, buf1, buf0) &&
-         attn_tile<D, DV, NW>(c, buf2, buf1)) {
+  __syncthreads();                         // tile 0 is in buf0
+  while (attn_tile<D, DV, NW>(c, buf0, buf1) && attn_tile<D, DV, NW>(c, buf1, buf0)) {
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): no direct-to-LDS load is in flight when the workgroup ends
 }
 
 // ---- packed values: v_t[pr][c][j] = fp16(v_s[pr][j][c] / v_scale[pr]) for j < r, zero for r <= j < r64 -----------
