@@ -295,8 +295,14 @@ struct AttnCtx {
   int wv, l, g, c32, krow_sw, vrow_sw;
   // per-lane byte offsets of this wave's tile loads from the tile's first key row / first value column entry
   // (fixed for the whole kernel; the tile's own address is wave-uniform and stays in scalar registers)
-  uint32_t koff[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW];
+  uint32_t krow[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW], kcol[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW];   // row, byte in row
   uint32_t voff[DV * (kKT / 8) / 64 / WILDCAT_ATTN_NW];
+  // This wave's small piece of a tile (all wave-uniform): 64 floats at sm_base + pr * sm_stride + k0 * sm_tile,
+  // stored at byte sm_dst of the buffer.  Wave 0 carries the tile's weights, waves 1 .. CLOADS a quarter of
+  // v_min | v_max each (so every buffer holds the clip vectors of its tile's problem); the other waves load the
+  // weights too and drop them into a spare corner, which keeps the tile code free of branches.
+  const float *sm_base;
+  int sm_stride, sm_tile, sm_dst;
   // state: the tile being computed and the one after it, whose data is in the staging registers (or on its way)
   TilePos cur, nxt;
   u32x4 stage[(kKT * (D / 8) + DV * (kKT / 8)) / 64 / WILDCAT_ATTN_NW];   // this wave's 1 KB pieces of tile nxt
@@ -323,7 +329,8 @@ struct AttnGeom {
   static constexpr int OFF_V = OFF_K + kKT * D * 2;
   static constexpr int OFF_W = OFF_V + DV * kKT * 2;
   static constexpr int OFF_C = OFF_W + kKT * 4;
-  static constexpr int BYTES = OFF_C + CLOADS * 256;
+  static constexpr int OFF_SPARE = OFF_C + CLOADS * 256;   // where waves without a small piece of their own write
+  static constexpr int BYTES = OFF_SPARE + 256;
   static constexpr int LPF = KLOADS + VLOADS;            // a wave's 1 KB pieces per tile
 };
 
@@ -340,53 +347,36 @@ __device__ __forceinline__ int attn_item_re(const AttnCtx<D, DV> &c, int pr) {
 template <int D, int DV>
 __device__ __forceinline__ TilePos attn_advance(const AttnCtx<D, DV> &c, const TilePos p) {
   TilePos n = p;
-  if (p.item >= c.total_items) return n;
-  if (p.k0 + kKT < p.re) {
-    n.k0 = p.k0 + kKT;
-    return n;
-  }
-  n.item = p.item + c.stride;
-  n.k0 = 0;
-  if (n.item < c.total_items) {
-    n.pr = attn_item_pr(c, n.item);
-    n.re = attn_item_re(c, n.pr);
+  const bool within = p.k0 + kKT < p.re;
+  n.k0 = within ? p.k0 + kKT : 0;
+  if (!within && p.item < c.total_items) {                    // once per item
+    n.item = p.item + c.stride;
+    if (n.item < c.total_items) {
+      n.pr = attn_item_pr(c, n.item);
+      n.re = attn_item_re(c, n.pr);
+    }
   }
   return n;
 }
 
 // Global loads of one tile into the staging registers.  A tile's address is wave-uniform (scalar registers); each
-// lane adds a byte offset that was worked out once (AttnCtx::koff, voff).  Only a ragged last tile (fewer than 64
-// rows left in the coreset) clamps its rows to the last one; the clamped rows are masked after the score product.
-// v_t is zero padded to a multiple of 64 columns.  The first KLOADS pieces are 1 KB of keys each, the rest 1 KB of
-// values; the small piece is the tile's weights (wave 0) or a quarter of v_min | v_max of its problem (waves
-// 1 .. CLOADS), so that each LDS buffer holds the clip vectors of the item its tile belongs to.  c.wv is
-// wave-uniform (scalar), so those are scalar branches.
+// lane adds an offset that was worked out once (AttnCtx::krow, kcol, voff).  In a ragged last tile (fewer than 64
+// rows left in the coreset) the rows are clamped to the last one -- by a minimum that is a no-op in full tiles --
+// and the clamped rows are masked after the score product.  v_t is zero padded to a multiple of 64 columns.  The
+// first KLOADS pieces are 1 KB of keys each, the rest 1 KB of values; for the small piece see AttnCtx::sm_base.
 template <int D, int DV, int NW>
 __device__ __forceinline__ void attn_stage_tile(AttnCtx<D, DV> &c, const TilePos &p) {
   using G = AttnGeom<D, DV, NW>;
-  static_assert(DV % 64 == 0, "a wave's 64 clip entries lie in v_min or in v_max, not across");
-  const bool ragged = p.k0 + kKT > p.re;
+  const uint32_t last = (uint32_t)min(p.re - 1 - p.k0, kKT - 1);      // last row of the tile that exists
   const char *ktile = reinterpret_cast<const char *>(c.Ks + ((size_t)p.pr * c.r + p.k0) * D);
   const char *vtile = reinterpret_cast<const char *>(c.Vt + (size_t)p.pr * DV * c.r64 + p.k0);
 #pragma unroll
-  for (int e = 0; e < G::KLOADS; ++e) {
-    uint32_t off = c.koff[e];
-    if (ragged) {                                             // row = min(row, re - 1 - k0)
-      const uint32_t row = off / (2 * D), last = (uint32_t)(p.re - 1 - p.k0);
-      off = min(row, last) * (2 * D) + off % (2 * D);
-    }
-    c.stage[e] = *reinterpret_cast<const u32x4 *>(ktile + off);
-  }
+  for (int e = 0; e < G::KLOADS; ++e)
+    c.stage[e] = *reinterpret_cast<const u32x4 *>(ktile + (min(c.krow[e], last) * (2 * D) + c.kcol[e]));
 #pragma unroll
   for (int e = 0; e < G::VLOADS; ++e) c.stage[G::KLOADS + e] = *reinterpret_cast<const u32x4 *>(vtile + c.voff[e]);
-  if (c.wv == 0) {
-    const float *tile = c.w + (size_t)p.pr * c.r + p.k0;
-    c.stage_small = tile[ragged ? min(c.l, p.re - 1 - p.k0) : c.l];
-  } else if (c.wv <= G::CLOADS) {
-    const int q = c.wv - 1;                                   // entries 64 q .. 64 q + 63 of v_min | v_max
-    const float *vec = q < DV / 64 ? c.vmin + (size_t)p.pr * DV + 64 * q : c.vmax + (size_t)p.pr * DV + (64 * q - DV);
-    c.stage_small = vec[c.l];
-  }
+  const float *small = c.sm_base + (size_t)p.pr * c.sm_stride + p.k0 * c.sm_tile;
+  c.stage_small = small[min((uint32_t)c.l, c.sm_tile ? last : 63u)];
 }
 
 // Stores the staged tile into LDS buffer `wr`: piece e of wave wv is bytes (e NW + wv) 1024 .. + 1023 of the key
@@ -400,8 +390,7 @@ __device__ __forceinline__ void attn_store_tile(const AttnCtx<D, DV> &c, char *_
 #pragma unroll
   for (int e = 0; e < G::VLOADS; ++e)
     *reinterpret_cast<u32x4 *>(wr + G::OFF_V + (e * NW + c.wv) * 1024 + c.l * 16) = c.stage[G::KLOADS + e];
-  if (c.wv == 0) reinterpret_cast<float *>(wr + G::OFF_W)[c.l] = c.stage_small;
-  else if (c.wv <= G::CLOADS) reinterpret_cast<float *>(wr + G::OFF_C + (c.wv - 1) * 256)[c.l] = c.stage_small;
+  reinterpret_cast<float *>(wr + c.sm_dst)[c.l] = c.stage_small;
 }
 
 template <int D, int DV, int NW>
@@ -607,8 +596,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
 #pragma unroll
   for (int e = 0; e < G::KLOADS; ++e) {      // LDS piece (e NW + wv) 64 + l holds key row `row`, logical piece `slot ^ ...`
     const int idx = (e * NW + c.wv) * 64 + c.l, row = idx / G::KPPR, slot = idx % G::KPPR;
-    const int krow = (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1); // LDS row `row` holds key pi(row), see attn_tile
-    c.koff[e] = (uint32_t)(krow * D + (slot ^ ((row / G::KRP) % G::KPPR)) * 8) * 2;
+    c.krow[e] = (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1);      // LDS row `row` holds key pi(row), see attn_tile
+    c.kcol[e] = (slot ^ ((row / G::KRP) % G::KPPR)) * 16;
   }
 #pragma unroll
   for (int e = 0; e < G::VLOADS; ++e) {
@@ -616,6 +605,15 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
     c.voff[e] = (uint32_t)(row * r64 + (slot ^ ((row / G::VRP) % G::VPPR)) * 8) * 2;
   }
 
+  static_assert(DV % 64 == 0, "a wave's 64 clip entries lie in v_min or in v_max, not across");
+  if (c.wv >= 1 && c.wv <= G::CLOADS) {
+    const int q = c.wv - 1;                                   // entries 64 q .. 64 q + 63 of v_min | v_max
+    c.sm_base = q < DV / 64 ? vmin + 64 * q : vmax + (64 * q - DV);
+    c.sm_stride = DV; c.sm_tile = 0; c.sm_dst = G::OFF_C + 256 * q;
+  } else {
+    c.sm_base = w;
+    c.sm_stride = r; c.sm_tile = 1; c.sm_dst = c.wv == 0 ? G::OFF_W : G::OFF_SPARE;
+  }
   // An item is one (batch*head, query tile) pair; this workgroup takes items blockIdx.x, + gridDim.x, ...
   c.cur.item = blockIdx.x;
   if (c.cur.item >= total_items) return;
