@@ -269,9 +269,25 @@ constexpr int kKT = 64;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr float kRescaleSlack = 8.0f;
 constexpr int kSchedMfma = 0x008, kSchedDsRead = 0x100;      // instruction classes of sched_group_barrier
-#ifndef WILDCAT_ATTN_NW
-#define WILDCAT_ATTN_NW 8
+// Maximum / sum of x over the lane pair {l, l ^ 32}.  The lane-half swap instruction applied to (x, x) returns
+// (lower half of x in both halves, upper half of x in both halves): no trip through the LDS crossbar, which a
+// shuffle would take.
+__device__ __forceinline__ float pair_max(float x) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+
+// Wavefronts per workgroup.  Eight (a wave fetches half as many pieces per tile and each tile serves twice the
+// queries) unless the narrow instantiation's registers allow three waves per SIMD, which four-wave groups can fill.
+#ifndef WILDCAT_ATTN_NW_NARROW
+#define WILDCAT_ATTN_NW_NARROW 4
 #endif
+template <int D, int DV>
+constexpr int attn_waves() { return D == 64 && DV == 64 ? WILDCAT_ATTN_NW_NARROW : 8; }
 
 
 // A 64-key tile of an item: item = (batch*head, query tile) pair, pr its coreset, re the number of filled slots,
@@ -282,7 +298,7 @@ struct TilePos {
 };
 
 // Kernel arguments and per-wave state of the pipelined kernel, passed by reference to the per-tile function.
-template <int D, int DV>
+template <int D, int DV, int NW>
 struct AttnCtx {
   const bf16_t *Q, *Ks;
   const uint16_t *Vt;         // fp16 bit patterns
@@ -295,8 +311,8 @@ struct AttnCtx {
   int wv, l, g, c32, krow_sw, vrow_sw;
   // per-lane byte offsets of this wave's tile loads from the tile's first key row / first value column entry
   // (fixed for the whole kernel; the tile's own address is wave-uniform and stays in scalar registers)
-  uint32_t krow[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW], kcol[kKT * (D / 8) / 64 / WILDCAT_ATTN_NW];   // row, byte in row
-  uint32_t voff[DV * (kKT / 8) / 64 / WILDCAT_ATTN_NW];
+  uint32_t krow[kKT * (D / 8) / 64 / NW], kcol[kKT * (D / 8) / 64 / NW];   // row, byte in row
+  uint32_t voff[DV * (kKT / 8) / 64 / NW];
   // This wave's small piece of a tile (all wave-uniform): 64 floats at sm_base + pr * sm_stride + k0 * sm_tile,
   // stored at byte sm_dst of the buffer.  Wave 0 carries the tile's weights, waves 1 .. CLOADS a quarter of
   // v_min | v_max each (so every buffer holds the clip vectors of its tile's problem); the other waves load the
@@ -305,7 +321,7 @@ struct AttnCtx {
   int sm_stride, sm_tile, sm_dst;
   // state: the tile being computed and the one after it, whose data is in the staging registers (or on its way)
   TilePos cur, nxt;
-  u32x4 stage[(kKT * (D / 8) + DV * (kKT / 8)) / 64 / WILDCAT_ATTN_NW];   // this wave's 1 KB pieces of tile nxt
+  u32x4 stage[(kKT * (D / 8) + DV * (kKT / 8)) / 64 / NW];   // this wave's 1 KB pieces of tile nxt
   float stage_small;          // wave 0: weight of key l of tile nxt; waves 1 .. CLOADS: 64 entries of v_min | v_max
   bf16x8 qf[D / 16];          // Q fragments: B operand of S^T = K Q^T (query c32, features 16 kb + 8 g .. + 7)
   floatx16 acc[DV / 32];      // O^T accumulators
@@ -334,18 +350,18 @@ struct AttnGeom {
   static constexpr int LPF = KLOADS + VLOADS;            // a wave's 1 KB pieces per tile
 };
 
-template <int D, int DV>
-__device__ __forceinline__ int attn_item_pr(const AttnCtx<D, DV> &c, int item) {
+template <int D, int DV, int NW>
+__device__ __forceinline__ int attn_item_pr(const AttnCtx<D, DV, NW> &c, int item) {
   const int bh = item / c.qtiles;
   return (bh / c.q_heads) * c.kv_heads + (bh % c.q_heads) / c.group;
 }
-template <int D, int DV>
-__device__ __forceinline__ int attn_item_re(const AttnCtx<D, DV> &c, int pr) {
+template <int D, int DV, int NW>
+__device__ __forceinline__ int attn_item_re(const AttnCtx<D, DV, NW> &c, int pr) {
   return c.r_eff ? max(min(c.r_eff[pr], c.r), 1) : c.r;      // never below 1: the tile loads clamp rows to re - 1
 }
 // The tile after p in this workgroup's list: the next tile of the item, else tile 0 of item + gridDim.x.
-template <int D, int DV>
-__device__ __forceinline__ TilePos attn_advance(const AttnCtx<D, DV> &c, const TilePos p) {
+template <int D, int DV, int NW>
+__device__ __forceinline__ TilePos attn_advance(const AttnCtx<D, DV, NW> &c, const TilePos p) {
   TilePos n = p;
   const bool within = p.k0 + kKT < p.re;
   n.k0 = within ? p.k0 + kKT : 0;
@@ -365,7 +381,7 @@ __device__ __forceinline__ TilePos attn_advance(const AttnCtx<D, DV> &c, const T
 // and the clamped rows are masked after the score product.  v_t is zero padded to a multiple of 64 columns.  The
 // first KLOADS pieces are 1 KB of keys each, the rest 1 KB of values; for the small piece see AttnCtx::sm_base.
 template <int D, int DV, int NW>
-__device__ __forceinline__ void attn_stage_tile(AttnCtx<D, DV> &c, const TilePos &p) {
+__device__ __forceinline__ void attn_stage_tile(AttnCtx<D, DV, NW> &c, const TilePos &p) {
   using G = AttnGeom<D, DV, NW>;
   const uint32_t last = (uint32_t)min(p.re - 1 - p.k0, kKT - 1);      // last row of the tile that exists
   const char *ktile = reinterpret_cast<const char *>(c.Ks + ((size_t)p.pr * c.r + p.k0) * D);
@@ -382,7 +398,7 @@ __device__ __forceinline__ void attn_stage_tile(AttnCtx<D, DV> &c, const TilePos
 // Stores the staged tile into LDS buffer `wr`: piece e of wave wv is bytes (e NW + wv) 1024 .. + 1023 of the key
 // (then value) tile, 16 per lane.
 template <int D, int DV, int NW>
-__device__ __forceinline__ void attn_store_tile(const AttnCtx<D, DV> &c, char *__restrict__ wr) {
+__device__ __forceinline__ void attn_store_tile(const AttnCtx<D, DV, NW> &c, char *__restrict__ wr) {
   using G = AttnGeom<D, DV, NW>;
 #pragma unroll
   for (int e = 0; e < G::KLOADS; ++e)
@@ -394,7 +410,7 @@ __device__ __forceinline__ void attn_store_tile(const AttnCtx<D, DV> &c, char *_
 }
 
 template <int D, int DV, int NW>
-__device__ __forceinline__ void attn_load_q(AttnCtx<D, DV> &c, int item) {
+__device__ __forceinline__ void attn_load_q(AttnCtx<D, DV, NW> &c, int item) {
   const int bh = item / c.qtiles;
   const int64_t q0 = (int64_t)(item % c.qtiles) * (NW * 32) + c.wv * 32;
   const int64_t row = q0 + c.c32 < c.m ? q0 + c.c32 : c.m - 1;
@@ -410,7 +426,7 @@ __device__ __forceinline__ void attn_load_q(AttnCtx<D, DV> &c, int item) {
 // (free since the barrier that ended the previous tile) and starts the loads of the tile after it.
 // Returns false after the last tile of the workgroup's last item.
 template <int D, int DV, int NW>
-__device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restrict__ rd, char *__restrict__ wr) {
+__device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__restrict__ rd, char *__restrict__ wr) {
   using G = AttnGeom<D, DV, NW>;
   const uint16_t *lkr = reinterpret_cast<const uint16_t *>(rd + G::OFF_K);
   const uint16_t *lvr = reinterpret_cast<const uint16_t *>(rd + G::OFF_V);
@@ -477,7 +493,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
     for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[mt][v]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * c.scale_log2;
+  mx = pair_max(mx) * c.scale_log2;
   const bool jump = mx > c.mref + kRescaleSlack;
   if (__builtin_amdgcn_ballot_w64(jump) != 0) {
     const float alpha = jump ? __builtin_amdgcn_exp2f(c.mref - mx) : 1.0f;
@@ -529,7 +545,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV> &c, const char *__restr
   }
   if (last_tile) {
     // ---- epilogue of the item: guard, divide, clip, store; then start the next item --------------------------------
-    const float dn = c.den + __shfl_xor(c.den, 32, kWave);
+    const float dn = pair_sum(c.den);
     const bool ok = dn > 0.0f;
     const float inv = ok ? c.vsc / dn : 0.0f;               // v_t holds V_S^T / v_scale
     const int bh = c.cur.item / c.qtiles;
@@ -584,7 +600,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
   __shared__ __attribute__((aligned(16))) char buf0[G::BYTES];
   __shared__ __attribute__((aligned(16))) char buf1[G::BYTES];
 
-  AttnCtx<D, DV> c;
+  AttnCtx<D, DV, NW> c;
   c.Q = Q; c.Ks = Ks; c.Vt = Vt; c.vscale = vscale; c.w = w; c.vmin = vmin; c.vmax = vmax; c.r_eff = r_eff; c.out = out;
   c.m = m; c.r = r; c.r64 = r64; c.q_heads = q_heads; c.group = group; c.kv_heads = q_heads / group;
   c.qtiles = qtiles; c.total_items = total_items; c.stride = (int)gridDim.x; c.scale_log2 = scale_log2;
@@ -696,7 +712,7 @@ __global__ __launch_bounds__(kThreads) void k_pack_values(const float *__restric
 
 template <int D, int DV>
 int launch_mfma2(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
-  constexpr int NW = WILDCAT_ATTN_NW;
+  constexpr int NW = attn_waves<D, DV>();
   const int r64 = (s.r + 63) / 64 * 64;
   const int64_t qtiles = (s.m + NW * 32 - 1) / (NW * 32);
   const int64_t total = qtiles * s.batch * s.q_heads;
