@@ -347,6 +347,8 @@ struct AttnGeom {
   static constexpr int OFF_C = OFF_W + kKT * 4;
   static constexpr int OFF_SPARE = OFF_C + CLOADS * 256;   // where waves without a small piece of their own write
   static constexpr int BYTES = OFF_SPARE + 256;
+  static constexpr int OROWB = 64 * 2 + 16;                // bytes of a row of the output staging area (padded)
+  static constexpr int OBYTES = NW * 32 * OROWB;
   static constexpr int LPF = KLOADS + VLOADS;            // a wave's 1 KB pieces per tile
 };
 
@@ -426,7 +428,8 @@ __device__ __forceinline__ void attn_load_q(AttnCtx<D, DV, NW> &c, int item) {
 // (free since the barrier that ended the previous tile) and starts the loads of the tile after it.
 // Returns false after the last tile of the workgroup's last item.
 template <int D, int DV, int NW>
-__device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__restrict__ rd, char *__restrict__ wr) {
+__device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__restrict__ rd, char *__restrict__ wr,
+                                          char *__restrict__ ob) {
   using G = AttnGeom<D, DV, NW>;
   const uint16_t *lkr = reinterpret_cast<const uint16_t *>(rd + G::OFF_K);
   const uint16_t *lvr = reinterpret_cast<const uint16_t *>(rd + G::OFF_V);
@@ -548,16 +551,22 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
     const float dn = pair_sum(c.den);
     const bool ok = dn > 0.0f;
     const float inv = ok ? c.vsc / dn : 0.0f;               // v_t holds V_S^T / v_scale
+    // The accumulators hold a query's row in 8-byte bits spread over (i, q); stored from there, every store would
+    // touch 32 rows with 8 bytes each.  So the converted values go through this wave's corner of LDS, 64 columns at
+    // a time, and leave as whole 128-byte lines (16 bytes per lane, eight rows per store).  No barrier: only this
+    // wave touches its corner, and a wave's LDS operations complete in order.
     const int bh = c.cur.item / c.qtiles;
-    const int64_t qrow = (int64_t)(c.cur.item % c.qtiles) * (NW * 32) + c.wv * 32 + c32;
-    if (qrow < c.m) {
-      bf16_t *orow = c.out + ((size_t)bh * c.m + qrow) * DV;
-      const float *clip = reinterpret_cast<const float *>(rd + G::OFF_C);
+    const int64_t q0 = (int64_t)(c.cur.item % c.qtiles) * (NW * 32) + c.wv * 32;
+    bf16_t *obase = c.out + ((size_t)bh * c.m + q0) * DV;
+    const float *clip = reinterpret_cast<const float *>(rd + G::OFF_C);
+    char *mine = ob + c.wv * (32 * G::OROWB);
 #pragma unroll
-      for (int i = 0; i < DV / 32; ++i)
+    for (int h = 0; h < DV / 64; ++h) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int col = 32 * i + 8 * q + 4 * g;
+          const int i = 2 * h + ii, col = 32 * i + 8 * q + 4 * g;
           const float4 lo = *reinterpret_cast<const float4 *>(&clip[col]);
           const float4 hi = *reinterpret_cast<const float4 *>(&clip[DV + col]);
           floatx4 o = {c.acc[i][4 * q + 0] * inv, c.acc[i][4 * q + 1] * inv, c.acc[i][4 * q + 2] * inv,
@@ -567,9 +576,15 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
           o[1] = fminf(fmaxf(o[1], lo.y), hi.y);
           o[2] = fminf(fmaxf(o[2], lo.z), hi.z);
           o[3] = fminf(fmaxf(o[3], lo.w), hi.w);
-          const bf16x4 ob = __builtin_convertvector(o, bf16x4);
-          *reinterpret_cast<uint2 *>(orow + col) = *reinterpret_cast<const uint2 *>(&ob);
+          const bf16x4 ob4 = __builtin_convertvector(o, bf16x4);
+          *reinterpret_cast<uint2 *>(mine + c32 * G::OROWB + (col - 64 * h) * 2) = *reinterpret_cast<const uint2 *>(&ob4);
         }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {                            // 32 rows x 128 bytes = 256 pieces of 16
+        const int idx = j * 64 + c.l, row = idx / 8, piece = idx % 8;
+        const uint4 v = *reinterpret_cast<const uint4 *>(mine + row * G::OROWB + piece * 16);
+        if (q0 + row < c.m) *reinterpret_cast<uint4 *>(obase + (size_t)row * DV + 64 * h + piece * 8) = v;
+      }
     }
     if (!more) return false;
 #pragma unroll
@@ -591,7 +606,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
 }
 
 template <int D, int DV, int NW>
-__global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void k_wtd_attn_mfma2(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const uint16_t *__restrict__ Vt,
     const float *__restrict__ vscale, const float *__restrict__ w, const float *__restrict__ vmin,
     const float *__restrict__ vmax, const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int64_t m, int r,
@@ -599,6 +614,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
   using G = AttnGeom<D, DV, NW>;
   __shared__ __attribute__((aligned(16))) char buf0[G::BYTES];
   __shared__ __attribute__((aligned(16))) char buf1[G::BYTES];
+  __shared__ __attribute__((aligned(16))) char obuf[G::OBYTES];     // output staging, see the epilogue in attn_tile
 
   AttnCtx<D, DV, NW> c;
   c.Q = Q; c.Ks = Ks; c.Vt = Vt; c.vscale = vscale; c.w = w; c.vmin = vmin; c.vmax = vmax; c.r_eff = r_eff; c.out = out;
@@ -649,7 +665,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void k_wtd_attn_mfma2(
   c.den = 0.0f;
   c.vsc = c.nvsc = vscale[c.cur.pr];
   __syncthreads();                         // tile 0 is in buf0
-  while (attn_tile<D, DV, NW>(c, buf0, buf1) && attn_tile<D, DV, NW>(c, buf1, buf0)) {
+  while (attn_tile<D, DV, NW>(c, buf0, buf1, obuf) && attn_tile<D, DV, NW>(c, buf1, buf0, obuf)) {
   }
 }
 
