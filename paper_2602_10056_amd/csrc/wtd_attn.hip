@@ -669,6 +669,157 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void k_wtd_attn_mfma2(
   }
 }
 
+// --------------------------------------------------------------------------------------------
+// MFMA kernel for fp32 storage (d, dv multiples of the MFMA tile).  Same transposed arrangement as the bf16 kernel,
+// on v_mfma_f32_32x32x2_f32: lane l of the A operand (32 x 2) holds row l % 32, k = l / 32; of the B operand (2 x 32)
+// column l % 32, k = l / 32; D as for the other 32 x 32 shapes.  Everything stays fp32: S^T = K_S Q^T, P = exp2(...)
+// in registers, O^T = V_S^T P^T with P straight from the S^T registers as the B operand.  Register v of an S^T tile
+// holds key 8 (v / 4) + v % 4 in lanes 0..31 and that key + 4 in lanes 32..63, so step v of the value product
+// contracts over exactly these two keys and the A operand is V_S[that key][32 i + l % 32] (a 4-byte LDS read, row
+// stride padded by 8 floats so that the two lane halves fall into different banks).  The contraction index of the
+// score product is permuted likewise: step 4 t + u of lane half g uses feature 8 t + 4 g + u, so a lane reads its
+// key's features 8 t + 4 g .. + 3 with one 16-byte LDS read (row stride padded by 4 floats: every 16-byte bank
+// group is hit by four lanes, which is the best 64 lanes x 16 bytes can do) and holds the matching half of its
+// query row in registers.  Workgroup = NWF waves x 32 queries; 32-key tiles of K_S, V_S and w through LDS.
+// --------------------------------------------------------------------------------------------
+constexpr int kFT = 32;                                       // keys per tile
+
+template <int D, int DV, int NWF>
+__global__ __launch_bounds__(NWF * 64) void k_wtd_attn_mfma_f32(
+    const float *__restrict__ Q, const float *__restrict__ Ks, const float *__restrict__ Vs,
+    const float *__restrict__ w, const float *__restrict__ vmin, const float *__restrict__ vmax,
+    const int32_t *__restrict__ r_eff, float *__restrict__ out, int64_t m, int r, int q_heads, int group,
+    float scale_log2) {
+  constexpr int KROW = D + 4, VROW = DV + 8;                  // padded LDS row strides (floats)
+  __shared__ __attribute__((aligned(16))) float lk[kFT * KROW];
+  __shared__ __attribute__((aligned(16))) float lv[kFT * VROW];
+  __shared__ float lw[kFT];
+  const int t = threadIdx.x, wv = t / kWave, l = t % kWave, g = l / 32, c32 = l % 32;
+  const int bh = blockIdx.y, b = bh / q_heads, hq = bh % q_heads;
+  const int pr = b * (q_heads / group) + hq / group;
+  const int re = r_eff ? max(min(r_eff[pr], r), 1) : r;
+  const int64_t q0 = (int64_t)blockIdx.x * (NWF * 32) + wv * 32;
+  const int64_t qrow = q0 + c32 < m ? q0 + c32 : m - 1;
+
+  // this lane's half of its query row: features 8 t + 4 g + u
+  float qf[D / 2];
+  {
+    const float4 *src = reinterpret_cast<const float4 *>(Q + ((size_t)bh * m + qrow) * D + 4 * g);
+#pragma unroll
+    for (int tt = 0; tt < D / 8; ++tt) {
+      const float4 v = src[2 * tt];
+      qf[4 * tt + 0] = v.x; qf[4 * tt + 1] = v.y; qf[4 * tt + 2] = v.z; qf[4 * tt + 3] = v.w;
+    }
+  }
+  floatx16 acc[DV / 32];
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+  float mrun = -INFINITY, den = 0.0f;
+  const float *Kp = Ks + (size_t)pr * r * D, *Vp = Vs + (size_t)pr * r * DV, *wp = w + (size_t)pr * r;
+
+  for (int k0 = 0; k0 < re; k0 += kFT) {
+    __syncthreads();                                          // the previous tile has been read
+    for (int e = t; e < kFT * (D / 4); e += NWF * 64) {
+      const int kk = e / (D / 4), j = e % (D / 4);
+      const float4 v = k0 + kk < re ? *reinterpret_cast<const float4 *>(Kp + (size_t)(k0 + kk) * D + 4 * j)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+      *reinterpret_cast<float4 *>(&lk[kk * KROW + 4 * j]) = v;
+    }
+    for (int e = t; e < kFT * (DV / 4); e += NWF * 64) {
+      const int kk = e / (DV / 4), j = e % (DV / 4);
+      const float4 v = k0 + kk < re ? *reinterpret_cast<const float4 *>(Vp + (size_t)(k0 + kk) * DV + 4 * j)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+      *reinterpret_cast<float4 *>(&lv[kk * VROW + 4 * j]) = v;
+    }
+    if (t < kFT) lw[t] = k0 + t < re ? wp[k0 + t] : 0.0f;
+    __syncthreads();
+    // ---- S^T = K Q^T --------------------------------------------------------------------------------------
+    floatx16 st;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) st[v] = 0.0f;
+#pragma unroll
+    for (int tt = 0; tt < D / 8; ++tt) {
+      const float4 a = *reinterpret_cast<const float4 *>(&lk[c32 * KROW + 8 * tt + 4 * g]);
+      st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, qf[4 * tt + 0], st, 0, 0, 0);
+      st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, qf[4 * tt + 1], st, 0, 0, 0);
+      st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, qf[4 * tt + 2], st, 0, 0, 0);
+      st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, qf[4 * tt + 3], st, 0, 0, 0);
+    }
+    // register v <-> key k0 + 8 (v / 4) + 4 g + v % 4
+    float mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      st[v] = k0 + 8 * (v / 4) + 4 * g + (v % 4) < re ? st[v] * scale_log2 : -INFINITY;
+      mx = fmaxf(mx, st[v]);
+    }
+    mx = pair_max(mx);
+    const float mnew = fmaxf(mrun, mx);                       // finite: key k0 exists
+    const float alpha = __builtin_amdgcn_exp2f(mrun - mnew);
+    mrun = mnew;
+    float dl = 0.0f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      st[v] = __builtin_amdgcn_exp2f(st[v] - mnew);
+      dl = fmaf(st[v], lw[8 * (v / 4) + 4 * g + (v % 4)], dl);
+    }
+    den = den * alpha + dl;
+    // ---- O^T = alpha O^T + V^T P^T ---------------------------------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][v] *= alpha;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float *vrow = &lv[(8 * (v / 4) + 4 * g + (v % 4)) * VROW + c32];
+#pragma unroll
+      for (int i = 0; i < DV / 32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32 * i], st[v], acc[i], 0, 0, 0);
+    }
+  }
+  // ---- epilogue: guard, divide, clip, store (register v of block i <-> column 32 i + 8 (v / 4) + 4 g + v % 4) ----------
+  const float dn = pair_sum(den);
+  const bool ok = dn > 0.0f;
+  const float inv = ok ? 1.0f / dn : 0.0f;
+  if (q0 + c32 < m) {
+    float *orow = out + ((size_t)bh * m + q0 + c32) * DV;
+#pragma unroll
+    for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = 32 * i + 8 * q + 4 * g;
+        const float4 lo = *reinterpret_cast<const float4 *>(vmin + (size_t)pr * DV + col);
+        const float4 hi = *reinterpret_cast<const float4 *>(vmax + (size_t)pr * DV + col);
+        float4 o = make_float4(acc[i][4 * q + 0] * inv, acc[i][4 * q + 1] * inv, acc[i][4 * q + 2] * inv,
+                               acc[i][4 * q + 3] * inv);
+        if (!ok) o = make_float4(0.f, 0.f, 0.f, 0.f);
+        o.x = fminf(fmaxf(o.x, lo.x), hi.x);
+        o.y = fminf(fmaxf(o.y, lo.y), hi.y);
+        o.z = fminf(fmaxf(o.z, lo.z), hi.z);
+        o.w = fminf(fmaxf(o.w, lo.w), hi.w);
+        *reinterpret_cast<float4 *>(orow + col) = o;
+      }
+  }
+}
+
+template <int D, int DV>
+int launch_mfma_f32(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
+  const float scale = (float)(s.beta * (double)kLog2e);
+  const int64_t heads = (int64_t)s.batch * s.q_heads;
+  // 128 queries per workgroup where that still gives every compute unit two workgroups, else 64
+  const bool wide = (s.m + 127) / 128 * heads >= 2 * (int64_t)compute_units();
+  if (wide) {
+    hipLaunchKernelGGL((k_wtd_attn_mfma_f32<D, DV, 4>), dim3((unsigned)((s.m + 127) / 128), (unsigned)heads), dim3(256),
+                       0, s.stream, (const float *)Q, (const float *)cs->k_s, cs->v_s, cs->w, cs->v_min, cs->v_max,
+                       cs->r_eff, (float *)out, s.m, s.r, s.q_heads, s.group, scale);
+  } else {
+    hipLaunchKernelGGL((k_wtd_attn_mfma_f32<D, DV, 2>), dim3((unsigned)((s.m + 63) / 64), (unsigned)heads), dim3(128),
+                       0, s.stream, (const float *)Q, (const float *)cs->k_s, cs->v_s, cs->w, cs->v_min, cs->v_max,
+                       cs->r_eff, (float *)out, s.m, s.r, s.q_heads, s.group, scale);
+  }
+  return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
+}
+
 // ---- packed values: v_t[pr][c][j] = fp16(v_s[pr][j][c] / v_scale[pr]) for j < r, zero for r <= j < r64 -----------
 // v_scale[pr] = 2^(e - 14) with e the exponent of max |v_s[pr]|: the largest packed magnitude lies in [2^14, 2^15),
 // inside fp16's range with the full significand for everything within 2^-28 of it.  Two small launches: the scale
@@ -844,6 +995,11 @@ extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *
       if (s.d == 128 && s.dv == 64) return launch_mfma2<128, 64>(s, Q, cs, out);
     }
     return launch_simple<bf16_t>(s, Q, cs, out);
+  }
+  if (s.batch * s.q_heads <= 65535) {
+    if (s.d == 64 && s.dv == 64) return launch_mfma_f32<64, 64>(s, Q, cs, out);
+    if (s.d == 64 && s.dv == 256) return launch_mfma_f32<64, 256>(s, Q, cs, out);
+    if (s.d == 128 && s.dv == 128) return launch_mfma_f32<128, 128>(s, Q, cs, out);
   }
   return launch_simple<float>(s, Q, cs, out);
 }
