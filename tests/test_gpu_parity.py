@@ -133,7 +133,8 @@ def test_seed_path_draws_the_documented_uniforms():
                                             ("bf16", 513, 129, 128, 128), ("bf16", 96, 40, 64, 128),
                                             ("bf16", 260, 300, 128, 64),
                                             ("bf16", 200, 50, 64, 256), ("bf16", 70, 33, 48, 80),
-                                            ("f32", 130, 20, 40, 72)])
+                                            ("f32", 130, 20, 40, 72), ("f32", 200, 50, 64, 256),
+                                            ("f32", 131, 90, 128, 128)])
 def test_wtd_attn_all_keys_unit_weights_is_exact_attention(dtype, n, m, d, dv):
     """The coreset = all keys with unit weights turns Alg. 3 into eq. (1): checks the kernel against the
     textbook definition, ragged m and r included, and m != n, d_v != d."""
@@ -154,6 +155,30 @@ def test_wtd_attn_all_keys_unit_weights_is_exact_attention(dtype, n, m, d, dv):
         out = wc.wtd_attn(to_dev(Q, dtype), cs).float().cpu().numpy()
         for h in range(2):
             assert relmax(out[0, h], refs[h]) <= TOL_OUT[dtype], packed
+
+
+def test_wtd_attn_fp32_many_queries_grouped_heads_and_unfilled_slots():
+    """fp32 storage on the matrix cores with enough query tiles for the four-wave workgroups, two query heads per
+    kv head, a ragged query count and coresets whose last slots are unfilled (r_eff < r, ragged last key tile)."""
+    rng = np.random.default_rng(77)
+    m, r, d = 33000, 70, 64
+    Q = rng.standard_normal((1, 4, m, d)).astype(np.float32)
+    KS = rng.standard_normal((1, 2, r, d)).astype(np.float32)
+    VS = rng.standard_normal((1, 2, r, d)).astype(np.float32)
+    wts = rng.uniform(0.5, 1.5, (1, 2, r)).astype(np.float32)
+    r_eff = np.array([[r, 41]], np.int32)
+    KS[0, 1, 41:] = 0; VS[0, 1, 41:] = 0; wts[0, 1, 41:] = 0     # what CompressKV leaves in unfilled slots
+    vmin, vmax = VS.min(axis=2), VS.max(axis=2)
+    cs = wc.Coreset(idx=torch.zeros((1, 2, r), dtype=torch.int32, device=dev()), r_eff=torch.from_numpy(r_eff).to(dev()),
+                    k_s=to_dev(KS, "f32"), v_s=to_dev(VS, "f32"), w=to_dev(wts, "f32"), v_min=to_dev(vmin, "f32"),
+                    v_max=to_dev(vmax, "f32"), tau=None)
+    out = wc.wtd_attn(to_dev(Q, "f32"), cs).cpu().numpy()
+    beta = 1.0 / np.sqrt(d)
+    for h in range(4):
+        p, re = h // 2, int(r_eff[0, h // 2])
+        ref = wo.wtd_attn(Q[0, h].astype(np.float64), KS[0, p, :re].astype(np.float64), VS[0, p, :re].astype(np.float64),
+                          wts[0, p, :re].astype(np.float64), vmin[0, p], vmax[0, p], beta)
+        assert relmax(out[0, h], ref) <= TOL_OUT["f32"], h
 
 
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64), ("bf16", 128)])
