@@ -670,6 +670,178 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void k_wtd_attn_mfma2(
 }
 
 // --------------------------------------------------------------------------------------------
+// Decode shape: few queries per head (new tokens against a stored coreset).  The kernel above would run one
+// workgroup per head through all r keys in sequence, seven of its eight waves idle at m = 1.  Here the query heads
+// that share a kv head are packed into one block of 32 rows (row = head-in-group * m + query), and the key tiles of
+// the coreset are dealt out to the eight waves of the workgroup, which combine their partial (reference, normaliser,
+// accumulators) through LDS at the end.  No tile is used by two waves, so nothing is staged in LDS: each lane loads
+// its MFMA operands straight from memory -- the key row pi(l % 32) of the tile (same row order as in the kernel
+// above) and the piece of v_t for its value column.  Same arithmetic per tile as above (bf16 scores, fp16 value
+// product, fp32 everything else); the sum over the tiles is taken in a different order.
+// --------------------------------------------------------------------------------------------
+constexpr int kDecWaves = 8;
+constexpr int kDecodeRows = 256;                               // packed rows per kv head up to which the decode kernel is used
+
+template <int D, int DV>
+__global__ __launch_bounds__(kDecWaves * 64, 1) void k_wtd_attn_decode(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const uint16_t *__restrict__ Vt,
+    const float *__restrict__ vscale, const float *__restrict__ w, const float *__restrict__ vmin,
+    const float *__restrict__ vmax, const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int m, int r, int r64,
+    int q_heads, int group, float scale_log2) {
+  __shared__ float s_ref[kDecWaves][64], s_den[kDecWaves][64];
+  __shared__ float s_acc[kDecWaves][DV / 32 * 16][64];         // [wave][accumulator register][lane]
+  const int t = threadIdx.x, wv = __builtin_amdgcn_readfirstlane(t / kWave), l = t % kWave, g = l / 32, c32 = l % 32;
+  const int pr = blockIdx.y, kv_heads = q_heads / group, b = pr / kv_heads, kvh = pr % kv_heads;
+  const int re = r_eff ? max(min(r_eff[pr], r), 1) : r;
+  const int rows = group * m;                                  // packed rows of this kv head
+  const int row = min((int)blockIdx.x * 32 + c32, rows - 1);   // this lane's query (clamped duplicates are not stored)
+  const int hq = kvh * group + row / m, qi = row % m;
+  const bf16_t *qrow = Q + (((size_t)b * q_heads + hq) * m + qi) * D;
+  bf16x8 qf[D / 16];
+#pragma unroll
+  for (int kb = 0; kb < D / 16; ++kb) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(qrow + 16 * kb + 8 * g);
+    qf[kb] = *reinterpret_cast<const bf16x8 *>(&v);
+  }
+  floatx16 acc[DV / 32];
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+  float mref = -INFINITY, den = 0.0f;
+  const bf16_t *Kp = Ks + (size_t)pr * r * D;
+  const uint16_t *Vp = Vt + (size_t)pr * DV * r64;
+  const float *wp = w + (size_t)pr * r;
+  const int pi = (c32 & ~12) | ((c32 & 4) << 1) | ((c32 & 8) >> 1);   // row order of a key tile, see above
+
+  for (int k0 = wv * kKT; k0 < re; k0 += kDecWaves * kKT) {
+    // ---- S^T = K Q^T for the two 32-key halves, operands from memory --------------------------------------
+    floatx16 st[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) st[mt][v] = 0.0f;
+      const bf16_t *krow = Kp + (size_t)min(k0 + 32 * mt + pi, re - 1) * D + 8 * g;
+#pragma unroll
+      for (int kb = 0; kb < D / 16; ++kb) {
+        const uint4 kv4 = *reinterpret_cast<const uint4 *>(krow + 16 * kb);
+        st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&kv4), qf[kb], st[mt], 0, 0, 0);
+      }
+    }
+    if (k0 + kKT > re) {                                       // ragged last tile: mask the missing keys
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (k0 + 32 * mt + 16 * (v / 8) + 8 * g + 4 * ((v / 4) % 2) + (v % 4) >= re) st[mt][v] = -INFINITY;
+    }
+    float mx = st[0][0];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[mt][v]);
+    mx = pair_max(mx) * scale_log2;                            // finite: key k0 exists
+    if (mx > mref) {                                           // true running maximum: a wave sees few tiles
+      const float alpha = __builtin_amdgcn_exp2f(mref - mx);   // 0 on the first tile
+      mref = mx;
+      den *= alpha;
+#pragma unroll
+      for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] *= alpha;
+    }
+    const float nm = -mref;
+    float dl = 0.0f;
+    f16x8 pf[4];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      floatx16 p;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(st[mt][v], scale_log2, nm));
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int key = k0 + 32 * mt + 16 * (q / 2) + 8 * g + 4 * (q % 2);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dl = fmaf(p[4 * q + e], wp[min(key + e, re - 1)], dl);   // p is 0 past re
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const auto h0 = __builtin_amdgcn_cvt_pkrtz(p[8 * h + 0], p[8 * h + 1]);
+        const auto h1 = __builtin_amdgcn_cvt_pkrtz(p[8 * h + 2], p[8 * h + 3]);
+        const auto h2 = __builtin_amdgcn_cvt_pkrtz(p[8 * h + 4], p[8 * h + 5]);
+        const auto h3 = __builtin_amdgcn_cvt_pkrtz(p[8 * h + 6], p[8 * h + 7]);
+        const uint4 hb = make_uint4(*reinterpret_cast<const uint32_t *>(&h0), *reinterpret_cast<const uint32_t *>(&h1),
+                                    *reinterpret_cast<const uint32_t *>(&h2), *reinterpret_cast<const uint32_t *>(&h3));
+        pf[2 * mt + h] = *reinterpret_cast<const f16x8 *>(&hb);
+      }
+    }
+    den += dl;
+    // ---- O^T += V_S^T P^T: A operand = keys k0 + 16 kb + 8 g + 0..7 of value column 32 i + c32 (v_t is zero padded) ----
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int i = 0; i < DV / 32; ++i) {
+        const uint4 vv = *reinterpret_cast<const uint4 *>(Vp + (size_t)(32 * i + c32) * r64 + k0 + 16 * kb + 8 * g);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const f16x8 *>(&vv), pf[kb], acc[i], 0, 0, 0);
+      }
+  }
+
+  // ---- combine the waves' partial results: common reference = the largest one --------------------------------------
+  s_ref[wv][l] = mref;
+  __syncthreads();
+  float mall = s_ref[0][l];
+#pragma unroll
+  for (int k = 1; k < kDecWaves; ++k) mall = fmaxf(mall, s_ref[k][l]);
+  const float sc = __builtin_amdgcn_exp2f(mref - mall);        // wave 0 always has a tile, so mall is finite; 0 for idle waves
+  s_den[wv][l] = den * sc;
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s_acc[wv][16 * i + v][l] = acc[i][v] * sc;
+  __syncthreads();
+  float dsum = 0.0f;
+#pragma unroll
+  for (int k = 0; k < kDecWaves; ++k) dsum += s_den[k][l];
+  const float dn = pair_sum(dsum);
+  const bool ok = dn > 0.0f;
+  const float inv = ok ? vscale[pr] / dn : 0.0f;               // v_t holds V_S^T / v_scale
+  // wave wv finishes accumulator registers [R wv, R (wv + 1)): block i = reg / 16, v = reg % 16 <-> column
+  // 32 i + 8 (v / 4) + 4 g + v % 4, i.e. four registers = four consecutive columns
+  constexpr int R = DV / 32 * 16 / kDecWaves;                 // 8 at dv = 128, 4 at dv = 64
+  static_assert(R % 4 == 0, "whole groups of four columns per wave");
+  if ((int)blockIdx.x * 32 + c32 < rows) {
+    bf16_t *orow = out + (((size_t)b * q_heads + hq) * m + qi) * DV;
+#pragma unroll
+    for (int q4 = 0; q4 < R / 4; ++q4) {
+      const int reg = R * wv + 4 * q4, i = reg / 16, v = reg % 16, col = 32 * i + 8 * (v / 4) + 4 * g;
+      floatx4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float a = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kDecWaves; ++k) a += s_acc[k][reg + e][l];
+        a = ok ? a * inv : 0.0f;
+        o[e] = fminf(fmaxf(a, vmin[(size_t)pr * DV + col + e]), vmax[(size_t)pr * DV + col + e]);
+      }
+      const bf16x4 ob = __builtin_convertvector(o, bf16x4);
+      *reinterpret_cast<uint2 *>(orow + col) = *reinterpret_cast<const uint2 *>(&ob);
+    }
+  }
+}
+
+template <int D, int DV>
+int launch_decode(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
+  const int r64 = (s.r + 63) / 64 * 64;
+  const int rows = s.group * (int)s.m;
+  const dim3 grid((unsigned)((rows + 31) / 32), (unsigned)s.P);
+  hipLaunchKernelGGL((k_wtd_attn_decode<D, DV>), grid, dim3(kDecWaves * 64), 0, s.stream, (const bf16_t *)Q,
+                     (const bf16_t *)cs->k_s, (const uint16_t *)cs->v_t, cs->v_scale, cs->w, cs->v_min, cs->v_max,
+                     cs->r_eff, (bf16_t *)out, (int)s.m, s.r, r64, s.q_heads, s.group,
+                     (float)(s.beta * (double)kLog2e));
+  return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
+}
+
+// --------------------------------------------------------------------------------------------
 // MFMA kernel for fp32 storage (d, dv multiples of the MFMA tile).  Same transposed arrangement as the bf16 kernel,
 // on v_mfma_f32_32x32x2_f32: lane l of the A operand (32 x 2) holds row l % 32, k = l / 32; of the B operand (2 x 32)
 // column l % 32, k = l / 32; D as for the other 32 x 32 shapes.  Everything stays fp32: S^T = K_S Q^T, P = exp2(...)
@@ -989,6 +1161,15 @@ extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *
     // the MFMA kernel addresses a problem's packed values with 32-bit byte offsets
     const bool fits = (int64_t)((s.r + 63) / 64 * 64) * s.dv * 2 <= (int64_t)UINT32_MAX;
     if (cs->v_t && cs->v_scale && fits) {
+      // decode shape: so few packed rows per kv head that splitting the keys over the waves of a workgroup beats
+      // giving every head a workgroup of its own
+      // (as long as that leaves compute units idle: its operands come straight from memory, which costs more per
+      // tile than the staged tiles of the kernel above once there is enough work to fill the device)
+      const int64_t packed_rows = (int64_t)s.group * s.m;
+      if (packed_rows <= kDecodeRows && (packed_rows + 31) / 32 * s.P <= compute_units()) {
+        if (s.d == 64 && s.dv == 64) return launch_decode<64, 64>(s, Q, cs, out);
+        if (s.d == 128 && s.dv == 128) return launch_decode<128, 128>(s, Q, cs, out);
+      }
       if (s.d == 64 && s.dv == 64) return launch_mfma2<64, 64>(s, Q, cs, out);
       if (s.d == 128 && s.dv == 128) return launch_mfma2<128, 128>(s, Q, cs, out);
       if (s.d == 64 && s.dv == 128) return launch_mfma2<64, 128>(s, Q, cs, out);

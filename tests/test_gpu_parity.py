@@ -181,12 +181,13 @@ def test_wtd_attn_fp32_many_queries_grouped_heads_and_unfilled_slots():
         assert relmax(out[0, h], ref) <= TOL_OUT["f32"], h
 
 
-@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64), ("bf16", 128)])
-def test_wtd_attn_guard_clip_and_oracle_coreset(dtype, d):
+@pytest.mark.parametrize("dtype,d,m", [("f32", 64, 200), ("bf16", 64, 200), ("bf16", 128, 200), ("bf16", 64, 600),
+                                       ("bf16", 128, 600)])
+def test_wtd_attn_guard_clip_and_oracle_coreset(dtype, d, m):
     """Fed an arbitrary coreset with negative weights: rows whose normaliser is not positive give
     clip(0, v_min, v_max); everything stays inside the value range; matches the oracle's Alg. 3."""
     rng = np.random.default_rng(5 + d)
-    m, r = 200, 100
+    r = 100                                                       # m = 200 takes the decode-shape kernel for bf16, 600 the tiled one
     Q = wl.round_to_storage(rng.standard_normal((1, 1, m, d)), dtype)
     KS = wl.round_to_storage(rng.standard_normal((1, 1, r, d)), dtype)
     VS = rng.standard_normal((1, 1, r, d)).astype(np.float32) * 3
@@ -528,6 +529,33 @@ def test_decode_against_stored_coreset_with_exact_sink_and_recent_tokens(m):
             ref = wo.wtd_attn(Qn[0, h * s.group + g].astype(np.float64), KS, VS, ws_, Vh.min(0), Vh.max(0), s.beta)
             assert relmax(out[0, h * s.group + g].astype(np.float64), ref) <= TOL_OUT["bf16"]
     assert nm % bins == 0
+
+
+@pytest.mark.parametrize("d,m,group,r", [(128, 3, 4, 150), (64, 1, 1, 1100), (128, 40, 2, 64), (64, 9, 8, 700)])
+def test_decode_shape_kernel_ragged_rank_and_unfilled_slots(d, m, group, r):
+    """Few queries per head: the keys are split over the waves of a workgroup and the partial results merged.  Ranks
+    that leave waves without a tile, a ragged last tile, unfilled slots (r_eff < r) and grouped query heads."""
+    rng = np.random.default_rng(d + m + r)
+    P = 3
+    Q = wl.round_to_storage(rng.standard_normal((1, P * group, m, d)), "bf16")
+    KS = wl.round_to_storage(rng.standard_normal((1, P, r, d)), "bf16")
+    VS = (rng.standard_normal((1, P, r, d)) * 2).astype(np.float32)
+    wts = rng.uniform(0.5, 1.5, (1, P, r)).astype(np.float32)
+    r_eff = np.array([[r, max(r // 3, 1), r - 1]], np.int32)
+    for p in range(P):
+        KS[0, p, r_eff[0, p]:] = 0; VS[0, p, r_eff[0, p]:] = 0; wts[0, p, r_eff[0, p]:] = 0
+    vmin, vmax = VS.min(axis=2), VS.max(axis=2)
+    cs = wc.Coreset(idx=torch.zeros((1, P, r), dtype=torch.int32, device=dev()), r_eff=torch.from_numpy(r_eff).to(dev()),
+                    k_s=to_dev(KS, "bf16"), v_s=to_dev(VS, "f32"), w=to_dev(wts, "f32"), v_min=to_dev(vmin, "f32"),
+                    v_max=to_dev(vmax, "f32"), tau=None)
+    wc.pack_values(cs)
+    out = wc.wtd_attn(to_dev(Q, "bf16"), cs).float().cpu().numpy()
+    beta = 1.0 / np.sqrt(d)
+    for h in range(P * group):
+        p, re = h // group, int(r_eff[0, h // group])
+        ref = wo.wtd_attn(Q[0, h].astype(np.float64), KS[0, p, :re].astype(np.float64), VS[0, p, :re].astype(np.float64),
+                          wts[0, p, :re].astype(np.float64), vmin[0, p], vmax[0, p], beta)
+        assert relmax(out[0, h].astype(np.float64), ref) <= TOL_OUT["bf16"], h
 
 
 # ---------------------------------------------------------------------------------- fast mode: fp32 history rows
