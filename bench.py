@@ -220,6 +220,33 @@ def main():
         except Exception as e:           # context only; never fatal
             res["exact_attention"] = {"error": str(e)[:200]}
 
+    if not args.no_exact and args.history == "f64":
+        # Context: the same pass with the selection loop's history rows stored in fp32 (the library's fast mode), and
+        # whether it drew the same pivots as the float64 default just timed.  Not part of `value`.
+        try:
+            ws32 = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0,
+                                                  s.bins, "f32"), dtype=torch.uint8, device=dev)
+
+            def fast_step():
+                r_q = wc.query_radius(Q, s.kv_heads, workspace=ws32)
+                c32 = wc.compress_kv(K, V, s.r, r_q, uniforms=u, workspace=ws32, bins=s.bins, history="f32")
+                wc.wtd_attn(Q, c32, out=out)
+                return c32
+
+            for _ in range(2):
+                c32 = fast_step()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(3):
+                c32 = fast_step()
+            torch.cuda.synchronize()
+            fms = (time.perf_counter() - t1) / 3 * 1e3
+            res["fast_mode"] = {"history": "f32", "ms_per_step": fms, "tokens_per_s": s.batch * s.n / (fms * 1e-3),
+                                "same_pivots_as_f64": bool(torch.equal(c32.idx, cs.idx))}
+            del ws32
+        except Exception as e:           # context only; never fatal
+            res["fast_mode"] = {"error": str(e)[:200]}
+
     if args.sweep_n:
         del Q, K, V, ws, out
         torch.cuda.empty_cache()
