@@ -245,11 +245,11 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 // by a per-problem power of two (coreset field v_scale) that is multiplied back in the epilogue.  The normaliser
 // sum_s P_s w_s is accumulated in fp32 on the vector ALU from the unrounded P.
 //
-// Workgroup = NW = 8 wavefronts, each owning 32 queries, one or more workgroups per compute unit (at least two
-// waves per SIMD, so that one wave's exp/convert work overlaps another's MFMAs).  Key tiles of 64 are
+// Workgroup = NW wavefronts (eight, or four for the narrow instantiation), each owning 32 queries; at least two
+// waves per SIMD, so that one wave's exp/convert work overlaps another's MFMAs.  Key tiles of 64 are
 // double-buffered in LDS.  While tile t is computed, the global loads of tile t+2 fly into a few staging
 // registers (each wave fetches 1 KB pieces: lane i holds bytes 16 i .. 16 i + 15); at the start of tile t+1 they
-// are stored into the buffer tile t-1 was read from.  So a tile's loads have a whole tile time to arrive -- under
+// are stored into the buffer tile t was read from.  So a tile's loads have a whole tile time to arrive -- under
 // load the trip to L2 and back takes about that long -- and the wait for them is an ordinary register dependence.
 // (Direct global-to-LDS loads, which need no staging registers, were measured and dropped: while one is in flight
 // the compiler turns every wait for an LDS operand into a wait for ALL outstanding LDS reads, which rules out
