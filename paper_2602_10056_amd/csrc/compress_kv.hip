@@ -1069,7 +1069,9 @@ __global__ __launch_bounds__(kThreads) void k_gram_small(const H *__restrict__ F
   for (int sb = sb0; sb < sb1; ++sb) {
     const H *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
     constexpr int U = R <= 4 ? 4 : (R <= 8 ? 2 : 1);             // keys in flight per thread
-    for (int k0 = 0; k0 < slab; k0 += U * kgs) {
+    const int64_t left = n - (int64_t)sb * slab;                  // keys of this slab that exist (F is zero beyond them)
+    const int kend = left < slab ? (left > 0 ? (int)left : 0) : slab;
+    for (int k0 = 0; k0 < kend; k0 += U * kgs) {
       Value4<T> raw[U];
       double f[U][R];
       bool ok[U];
