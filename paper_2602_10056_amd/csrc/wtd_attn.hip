@@ -313,16 +313,17 @@ struct AttnCtx {
   // (fixed for the whole kernel; the tile's own address is wave-uniform and stays in scalar registers)
   uint32_t krow[kKT * (D / 8) / 64 / NW], kcol[kKT * (D / 8) / 64 / NW];   // row, byte in row
   uint32_t voff[DV * (kKT / 8) / 64 / NW];
-  // This wave's small piece of a tile (all wave-uniform): 64 floats at sm_base + pr * sm_stride + k0 * sm_tile,
-  // stored at byte sm_dst of the buffer.  Wave 0 carries the tile's weights, waves 1 .. CLOADS a quarter of
-  // v_min | v_max each (so every buffer holds the clip vectors of its tile's problem); the other waves load the
-  // weights too and drop them into a spare corner, which keeps the tile code free of branches.
+  // This wave's small piece of a tile (all wave-uniform): CW floats at sm_base + pr * sm_stride + k0 * sm_tile,
+  // stored at byte sm_dst of the buffer (the second 64, where CW = 128, at sm_dst2).  Wave 0 carries the tile's 64
+  // weights, waves 1 .. CLOADS CW entries of v_min | v_max each (so every buffer holds the clip vectors of its
+  // tile's problem); the other waves load the weights too and drop them into a spare corner, which keeps the tile
+  // code free of branches.
   const float *sm_base;
-  int sm_stride, sm_tile, sm_dst;
+  int sm_stride, sm_tile, sm_dst, sm_dst2;
   // state: the tile being computed and the one after it, whose data is in the staging registers (or on its way)
   TilePos cur, nxt;
   u32x4 stage[(kKT * (D / 8) + DV * (kKT / 8)) / 64 / NW];   // this wave's 1 KB pieces of tile nxt
-  float stage_small;          // wave 0: weight of key l of tile nxt; waves 1 .. CLOADS: 64 entries of v_min | v_max
+  float stage_small, stage_small2;   // wave 0: weight of key l of tile nxt; waves 1 .. CLOADS: entries of v_min | v_max
   bf16x8 qf[D / 16];          // Q fragments: B operand of S^T = K Q^T (query c32, features 16 kb + 8 g .. + 7)
   floatx16 acc[DV / 32];      // O^T accumulators
   float mref, den;            // reference exponent (log2 domain) and normaliser of query c32
@@ -337,7 +338,8 @@ struct AttnGeom {
   static constexpr int VRP = 16 / VPPR;                  // value rows per 256 bytes (= 2)
   static constexpr int KLOADS = kKT * KPPR / 64 / NW;    // wave-wide 1 KB loads of the key tile per wave
   static constexpr int VLOADS = DV * VPPR / 64 / NW;     // ... of the value tile
-  static constexpr int CLOADS = (2 * DV + 63) / 64;      // wave-wide 256-byte loads of the clip vectors
+  static constexpr int CW = 2 * DV / 64 <= NW - 1 ? 64 : 128;   // clip entries a wave carries per tile
+  static constexpr int CLOADS = 2 * DV / CW;             // waves that carry clip entries
   static_assert(KLOADS * NW * 64 == kKT * KPPR && VLOADS * NW * 64 == DV * VPPR, "tiles must split evenly");
   static_assert(DV % 32 == 0 && CLOADS <= NW - 1, "clip vectors are loaded by waves 1 .. CLOADS");
   // One LDS buffer (bytes): key tile | value tile | weights | clip vectors (v_min | v_max)
@@ -345,8 +347,8 @@ struct AttnGeom {
   static constexpr int OFF_V = OFF_K + kKT * D * 2;
   static constexpr int OFF_W = OFF_V + DV * kKT * 2;
   static constexpr int OFF_C = OFF_W + kKT * 4;
-  static constexpr int OFF_SPARE = OFF_C + CLOADS * 256;   // where waves without a small piece of their own write
-  static constexpr int BYTES = OFF_SPARE + 256;
+  static constexpr int OFF_SPARE = OFF_C + 2 * DV * 4;     // where waves without a small piece of their own write
+  static constexpr int BYTES = OFF_SPARE + 512;
   static constexpr int OROWB = 64 * 2 + 16;                // bytes of a row of the output staging area (padded)
   static constexpr int OBYTES = NW * 32 * OROWB;
   static constexpr int LPF = KLOADS + VLOADS;            // a wave's 1 KB pieces per tile
@@ -394,7 +396,9 @@ __device__ __forceinline__ void attn_stage_tile(AttnCtx<D, DV, NW> &c, const Til
 #pragma unroll
   for (int e = 0; e < G::VLOADS; ++e) c.stage[G::KLOADS + e] = *reinterpret_cast<const u32x4 *>(vtile + c.voff[e]);
   const float *small = c.sm_base + (size_t)p.pr * c.sm_stride + p.k0 * c.sm_tile;
-  c.stage_small = small[min((uint32_t)c.l, c.sm_tile ? last : 63u)];
+  const uint32_t j = min((uint32_t)c.l, c.sm_tile ? last : 63u);
+  c.stage_small = small[j];
+  if constexpr (G::CW == 128) c.stage_small2 = small[c.sm_tile ? j : j + 64];
 }
 
 // Stores the staged tile into LDS buffer `wr`: piece e of wave wv is bytes (e NW + wv) 1024 .. + 1023 of the key
@@ -409,6 +413,7 @@ __device__ __forceinline__ void attn_store_tile(const AttnCtx<D, DV, NW> &c, cha
   for (int e = 0; e < G::VLOADS; ++e)
     *reinterpret_cast<u32x4 *>(wr + G::OFF_V + (e * NW + c.wv) * 1024 + c.l * 16) = c.stage[G::KLOADS + e];
   reinterpret_cast<float *>(wr + c.sm_dst)[c.l] = c.stage_small;
+  if constexpr (G::CW == 128) reinterpret_cast<float *>(wr + c.sm_dst2)[c.l] = c.stage_small2;
 }
 
 template <int D, int DV, int NW>
@@ -637,14 +642,14 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void k_wtd_attn_mfma2(
     c.voff[e] = (uint32_t)(row * r64 + (slot ^ ((row / G::VRP) % G::VPPR)) * 8) * 2;
   }
 
-  static_assert(DV % 64 == 0, "a wave's 64 clip entries lie in v_min or in v_max, not across");
+  static_assert(DV % G::CW == 0, "a wave's clip entries lie in v_min or in v_max, not across");
   if (c.wv >= 1 && c.wv <= G::CLOADS) {
-    const int q = c.wv - 1;                                   // entries 64 q .. 64 q + 63 of v_min | v_max
-    c.sm_base = q < DV / 64 ? vmin + 64 * q : vmax + (64 * q - DV);
-    c.sm_stride = DV; c.sm_tile = 0; c.sm_dst = G::OFF_C + 256 * q;
+    const int q = c.wv - 1;                                   // entries CW q .. CW q + CW - 1 of v_min | v_max
+    c.sm_base = q < DV / G::CW ? vmin + G::CW * q : vmax + (G::CW * q - DV);
+    c.sm_stride = DV; c.sm_tile = 0; c.sm_dst = G::OFF_C + 4 * G::CW * q; c.sm_dst2 = c.sm_dst + 256;
   } else {
     c.sm_base = w;
-    c.sm_stride = r; c.sm_tile = 1; c.sm_dst = c.wv == 0 ? G::OFF_W : G::OFF_SPARE;
+    c.sm_stride = r; c.sm_tile = 1; c.sm_dst = c.wv == 0 ? G::OFF_W : G::OFF_SPARE; c.sm_dst2 = G::OFF_SPARE + 256;
   }
   // An item is one (batch*head, query tile) pair; this workgroup takes items blockIdx.x, + gridDim.x, ...
   c.cur.item = blockIdx.x;
@@ -1174,6 +1179,7 @@ extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *
       if (s.d == 128 && s.dv == 128) return launch_mfma2<128, 128>(s, Q, cs, out);
       if (s.d == 64 && s.dv == 128) return launch_mfma2<64, 128>(s, Q, cs, out);
       if (s.d == 128 && s.dv == 64) return launch_mfma2<128, 64>(s, Q, cs, out);
+      if (s.d == 64 && s.dv == 256) return launch_mfma2<64, 256>(s, Q, cs, out);
     }
     return launch_simple<bf16_t>(s, Q, cs, out);
   }
