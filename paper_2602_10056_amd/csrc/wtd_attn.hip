@@ -896,22 +896,46 @@ __global__ __launch_bounds__(NWF * 64) void k_wtd_attn_mfma_f32(
   float mrun = -INFINITY, den = 0.0f;
   const float *Kp = Ks + (size_t)pr * r * D, *Vp = Vs + (size_t)pr * r * DV, *wp = w + (size_t)pr * r;
 
+  // A tile travels memory -> registers -> LDS.  Where the registers allow it (PREFETCH) the loads of tile t+1 are
+  // issued right after tile t has been stored to LDS, so they fly during the MFMAs of tile t.
+  constexpr int NT = NWF * 64, KR = kFT * (D / 4) / NT, VR = kFT * (DV / 4) / NT;
+  static_assert(KR * NT == kFT * (D / 4) && VR * NT == kFT * (DV / 4), "tiles must split evenly");
+  constexpr bool PREFETCH = DV <= 128;
+  float4 kreg[KR], vreg[VR];
+  float wreg = 0.0f;
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int q = 0; q < KR; ++q) {
+      const int e = t + q * NT, kk = e / (D / 4), j = e % (D / 4);
+      kreg[q] = k0 + kk < re ? *reinterpret_cast<const float4 *>(Kp + (size_t)(k0 + kk) * D + 4 * j)
+                             : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int q = 0; q < VR; ++q) {
+      const int e = t + q * NT, kk = e / (DV / 4), j = e % (DV / 4);
+      vreg[q] = k0 + kk < re ? *reinterpret_cast<const float4 *>(Vp + (size_t)(k0 + kk) * DV + 4 * j)
+                             : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (t < kFT) wreg = k0 + t < re ? wp[k0 + t] : 0.0f;
+  };
+  if (PREFETCH) fetch(0);
+
   for (int k0 = 0; k0 < re; k0 += kFT) {
+    if (!PREFETCH) fetch(k0);
     __syncthreads();                                          // the previous tile has been read
-    for (int e = t; e < kFT * (D / 4); e += NWF * 64) {
-      const int kk = e / (D / 4), j = e % (D / 4);
-      const float4 v = k0 + kk < re ? *reinterpret_cast<const float4 *>(Kp + (size_t)(k0 + kk) * D + 4 * j)
-                                    : make_float4(0.f, 0.f, 0.f, 0.f);
-      *reinterpret_cast<float4 *>(&lk[kk * KROW + 4 * j]) = v;
+#pragma unroll
+    for (int q = 0; q < KR; ++q) {
+      const int e = t + q * NT, kk = e / (D / 4), j = e % (D / 4);
+      *reinterpret_cast<float4 *>(&lk[kk * KROW + 4 * j]) = kreg[q];
     }
-    for (int e = t; e < kFT * (DV / 4); e += NWF * 64) {
-      const int kk = e / (DV / 4), j = e % (DV / 4);
-      const float4 v = k0 + kk < re ? *reinterpret_cast<const float4 *>(Vp + (size_t)(k0 + kk) * DV + 4 * j)
-                                    : make_float4(0.f, 0.f, 0.f, 0.f);
-      *reinterpret_cast<float4 *>(&lv[kk * VROW + 4 * j]) = v;
+#pragma unroll
+    for (int q = 0; q < VR; ++q) {
+      const int e = t + q * NT, kk = e / (DV / 4), j = e % (DV / 4);
+      *reinterpret_cast<float4 *>(&lv[kk * VROW + 4 * j]) = vreg[q];
     }
-    if (t < kFT) lw[t] = k0 + t < re ? wp[k0 + t] : 0.0f;
+    if (t < kFT) lw[t] = wreg;
     __syncthreads();
+    if (PREFETCH && k0 + kFT < re) fetch(k0 + kFT);
     // ---- S^T = K Q^T --------------------------------------------------------------------------------------
     floatx16 st;
 #pragma unroll
