@@ -593,10 +593,14 @@ struct StepShared {
 // H = storage type of the history rows: double (pivots identical to a float64 reference) or float (fast mode: half
 // the bytes; the row is rounded to fp32 BEFORE it enters the residual update, so the factorisation stays consistent
 // with what later steps read back).
-template <typename T, int KPT, int NC, bool POLL, typename H>
+// SOLO: the problem has a single slab (small bins), so this workgroup is alone with it: the total mass is carried
+// from step to step in `carry`, the residual diagonal is searched in registers, and nothing is polled, published or
+// written for other workgroups (the history rows still go to memory: the Gram pass reads them).
+template <typename T, int KPT, int NC, bool POLL, typename H, bool SOLO = false>
 __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int pr, double *g, double *ksc,
                                           StepShared &sh, const KeyRegs<T, KPT, NC> &kr, double (&pown)[KPT],
-                                          const double (&flo)[KPT], int *error, long long spin_limit, int hcn) {
+                                          const double (&flo)[KPT], int *error, long long spin_limit, int hcn,
+                                          double *carry = nullptr) {
   constexpr int SLAB = kThreads * KPT;
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
@@ -615,7 +619,9 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   const int e0 = t * per < a.nblk ? t * per : a.nblk;
   const int e1 = e0 + per < a.nblk ? e0 + per : a.nblk;
   double loc = 0.0;
-  if constexpr (POLL) {
+  if constexpr (SOLO) {
+    // nothing to collect
+  } else if constexpr (POLL) {
     // The slab sums double as arrival flags: a slot holds -1 until its workgroup has finished the previous step
     // (and its p and history row have completed), so polling them is the synchronisation between steps, and the
     // successful poll already has the values.  Bounded: gives up after spin_limit rounds.
@@ -639,12 +645,16 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   } else {
     for (int e = e0; e < e1; ++e) loc += ld_dev(bs + e);
   }
-  double mass;
-  double inc = block_incl_scan(loc, sh.sm, &mass);
-  double excl = __shfl_up(inc, 1, kWave);          // exclusive prefix = inclusive prefix of thread t-1
-  if (lane == 0) {
-    excl = 0.0;
-    for (int k = 0; k < t / kWave; ++k) excl += sh.sm[k];
+  double mass, inc = 0.0, excl = 0.0;
+  if constexpr (SOLO) {
+    mass = *carry;
+  } else {
+    inc = block_incl_scan(loc, sh.sm, &mass);
+    excl = __shfl_up(inc, 1, kWave);               // exclusive prefix = inclusive prefix of thread t-1
+    if (lane == 0) {
+      excl = 0.0;
+      for (int k = 0; k < t / kWave; ++k) excl += sh.sm[k];
+    }
   }
   if (!(mass > 0.0)) return 0;                     // h(K,K) is reproduced exactly by the pivots so far
 
@@ -653,34 +663,38 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   int cand = INT_MAX;
   double cand_base = 0.0;
   int last_pos = -1;
-  {
-    double run = excl;
-    for (int e = e0; e < e1; ++e) {
-      const double v = ld_dev(bs + e), nxt = run + v;
-      if (nxt > target && cand == INT_MAX) { cand = e; cand_base = run; }
-      if (v > 0.0) last_pos = e;
-      run = nxt;
+  int bstar = 0;
+  double base = 0.0;
+  if constexpr (!SOLO) {
+    {
+      double run = excl;
+      for (int e = e0; e < e1; ++e) {
+        const double v = ld_dev(bs + e), nxt = run + v;
+        if (nxt > target && cand == INT_MAX) { cand = e; cand_base = run; }
+        if (v > 0.0) last_pos = e;
+        run = nxt;
+      }
     }
+    bstar = block_reduce<int>(cand, sh.smi, MinOp());
+    if (bstar == INT_MAX) {
+      // Rounding left no slab above u * mass (u within an ulp of 1): take the last index of positive mass.
+      bstar = block_reduce<int>(last_pos, sh.smi, MaxOp());
+      target = INFINITY;
+      if (t == 0) sh.s_base = 0.0;
+    } else if (cand == bstar) {
+      sh.s_base = cand_base;
+    }
+    __syncthreads();
+    base = sh.s_base;
+    bstar = bstar < 0 ? 0 : (bstar >= a.nblk ? a.nblk - 1 : bstar);   // only non-finite input can get here
   }
-  int bstar = block_reduce<int>(cand, sh.smi, MinOp());
-  if (bstar == INT_MAX) {
-    // Rounding left no slab above u * mass (u within an ulp of 1): take the last index of positive mass.
-    bstar = block_reduce<int>(last_pos, sh.smi, MaxOp());
-    target = INFINITY;
-    if (t == 0) sh.s_base = 0.0;
-  } else if (cand == bstar) {
-    sh.s_base = cand_base;
-  }
-  __syncthreads();
-  const double base = sh.s_base;
-  bstar = bstar < 0 ? 0 : (bstar >= a.nblk ? a.nblk - 1 : bstar);   // only non-finite input can get here
 
   // ---- 3. the index inside that slab ---------------------------------------------------------------
   const double *ps = pin + (size_t)bstar * SLAB;
   double pv[KPT];
   loc = 0.0;
 #pragma unroll
-  for (int k = 0; k < KPT; ++k) { pv[k] = ld_dev(ps + l_loc + k); loc += pv[k]; }
+  for (int k = 0; k < KPT; ++k) { pv[k] = SOLO ? pown[k] : ld_dev(ps + l_loc + k); loc += pv[k]; }
   double tot2;
   inc = block_incl_scan(loc, sh.sm, &tot2);
   excl = __shfl_up(inc, 1, kWave);
@@ -708,7 +722,8 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
 
   // ---- 4. broadcast data of the pivot: its history column g_j = F_j(s) and k_s - kbar ------------------
   const H *Fs = reinterpret_cast<const H *>(a.F) + ((size_t)pr * a.nblk + bstar) * a.r * SLAB + s_loc;
-  for (int j = t; j < i; j += kThreads) g[j] = (double)ld_dev(Fs + (size_t)j * SLAB);
+  for (int j = t; j < i; j += kThreads)
+    g[j] = SOLO && j < hcn ? (double)hc[(size_t)j * SLAB + s_loc] : (double)ld_dev(Fs + (size_t)j * SLAB);
   const int nc = a.dpad / kChunk;
   const T *Kp = reinterpret_cast<const T *>(a.Kp) + (size_t)pr * nc * a.npad * kChunk;
   double cbp = 0.0;
@@ -819,7 +834,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     if (l >= a.n) { pn = 0.0; f = 0.0; }
     st_dev(Fb + (size_t)i * SLAB + l_loc + k, (H)f);
     fkeep[k] = f;
-    st_dev(pout + l, pn);
+    if constexpr (!SOLO) st_dev(pout + l, pn);
     pown[k] = pn;
     psum += pn;
   }
@@ -828,9 +843,14 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
 #pragma unroll
     for (int k = 0; k < KPT; ++k) hc[(size_t)i * SLAB + l_loc + k] = (H)fkeep[k];
   }
-  if constexpr (POLL) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's p and history stores have completed
-  __syncthreads();
-  if (t == 0 && i + 1 < a.r) st_dev(bs_next + b, tot);       // publishes the sum and, with it, the whole step
+  if constexpr (SOLO) {
+    *carry = tot;
+    __syncthreads();                                         // the cached row is complete before the next step reads it
+  } else {
+    if constexpr (POLL) __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this thread's p and history stores have completed
+    __syncthreads();
+    if (t == 0 && i + 1 < a.r) st_dev(bs_next + b, tot);     // publishes the sum and, with it, the whole step
+  }
 
   // ---- 8. bookkeeping by the slab that owns the pivot -----------------------------------------------------
   if (b == bstar) {
@@ -882,7 +902,7 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 // bounded: if a limit is hit (it never should be) the error word is set and every workgroup leaves.  With
 // NC > 0 a thread keeps the packed features of its keys in registers for the whole loop, which removes the
 // O(n d) key stream from every step.
-template <typename T, int KPT, int NC, typename H>
+template <typename T, int KPT, int NC, typename H, bool SOLO = false>
 __global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
                                                                   int hcn) {
   extern __shared__ double dyn[];
@@ -901,8 +921,16 @@ __global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(
   load_key_regs<T, KPT, NC>(kr, reinterpret_cast<const T *>(a.Kp) + ((size_t)pr * nc * a.npad + l_glob) * kChunk,
                             a.npad);
   int i = 0, rc = 1;
+  double carry = 0.0;
+  if constexpr (SOLO) {
+    double s0 = 0.0;
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) s0 += pown[k];
+    carry = block_sum(s0, sh.sm);
+  }
   for (; i < a.r; ++i) {
-    rc = rpnys_step<T, KPT, NC, true, H>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
+    rc = rpnys_step<T, KPT, NC, !SOLO, H, SOLO>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn,
+                                                &carry);
     if (rc != 1) break;
   }
   if (rc == 0) {
@@ -1258,20 +1286,26 @@ LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
   if (!pl.persistent) return lp;
   const int nc = pl.dpad / kChunk;
   constexpr int regs_per_chunk = KPT * (sizeof(T) == 2 ? 2 : 4);
+  const bool solo = pl.nblk == 1;                             // one slab per problem: see rpnys_step
   const void *fn;
-  if (nc == 32 && 32 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H>;
-  else if (nc == 16 && 16 * regs_per_chunk <= 128) fn = (const void *)k_rpnys_persistent<T, KPT, 16, H>;
-  else fn = (const void *)k_rpnys_persistent<T, KPT, 0, H>;
+  if (nc == 32 && 32 * regs_per_chunk <= 128)
+    fn = solo ? (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H, true>
+              : (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H>;
+  else if (nc == 16 && 16 * regs_per_chunk <= 128)
+    fn = solo ? (const void *)k_rpnys_persistent<T, KPT, 16, H, true> : (const void *)k_rpnys_persistent<T, KPT, 16, H>;
+  else
+    fn = solo ? (const void *)k_rpnys_persistent<T, KPT, 0, H, true> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
   const int cus = compute_units();
   const int64_t wgs = (int64_t)pl.nblk * s.P;
-  const int need = (int)((wgs + cus - 1) / cus);             // workgroups a compute unit must hold
+  int need = (int)((wgs + cus - 1) / cus);                   // workgroups a compute unit must hold
   const size_t base = (size_t)((s.r + pl.dpad + 1) & ~1) * sizeof(double);
   int per_cu = 0;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess) return lp;
+  if (solo && per_cu >= 1 && need > per_cu) need = per_cu;    // no workgroup waits for another: any grid size will do
   if (per_cu < need) {
     // Keys in registers cost too many registers for this many workgroups per compute unit: the variant that
     // streams the keys every step is leaner and still saves the launches and their gaps.
-    fn = (const void *)k_rpnys_persistent<T, KPT, 0, H>;
+    fn = solo ? (const void *)k_rpnys_persistent<T, KPT, 0, H, true> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess || per_cu < need)
       return lp;
   }
