@@ -128,6 +128,31 @@ def test_seed_path_draws_the_documented_uniforms():
     assert not torch.equal(cs_seed.idx, wc.wildcat(Q, K, V, r=s.r, seed=1, return_coreset=True)[1].idx)
 
 
+def test_random_small_shapes_whole_path():
+    """Sixty seeded random combinations of storage type, head grouping, bin count, pivots per bin, keys per bin, query
+    count (decode-sized to several tiles) and widths through the whole path, each against the oracle: this is what
+    exercises the kernel variants that shapes select (single-slab loop, small Gram pass, decode / tiled / fp32 WtdAttn,
+    d_v = 256 ...) in combinations the named tests do not list."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 60:
+        cfg = int(rng.choice([2, 3, 3, 4, 6]))
+        d = int(rng.choice([64, 128]))
+        kv, group = int(rng.choice([1, 2, 3])), int(rng.choice([1, 2, 4]))
+        bins = int(rng.choice([1, 1, 2, 4, 8, 16]))
+        r = int(rng.choice([1, 2, 3, 4, 8, 12, 20])) * bins
+        n = int(rng.choice([16, 60, 128, 200, 256, 300, 512, 700, 1100])) * bins
+        m = int(rng.choice([1, 5, 40, 64, 130, 300, 700]))
+        dtype = str(rng.choice(["bf16", "f32"]))
+        dv = d if (cfg != 3 or rng.random() < 0.5) else int(rng.choice([64, 128, 256]))
+        if r > n or n > 6000:
+            continue
+        w = wl.make(cfg, q_heads=kv * group, kv_heads=kv, n=n, m_=m, d=d, dv_=dv, r=r, bins=bins, dtype=dtype)
+        out, cs = run_gpu(w)
+        check_against_oracle(w, out, cs)
+        done += 1
+
+
 # ---------------------------------------------------------------------------------- WtdAttn alone
 @pytest.mark.parametrize("dtype,n,m,d,dv", [("f32", 300, 77, 64, 64), ("bf16", 1000, 333, 64, 64),
                                             ("bf16", 513, 129, 128, 128), ("bf16", 96, 40, 64, 128),
