@@ -214,7 +214,9 @@ __global__ __launch_bounds__(kThreads) void k_pack_stats(const T *__restrict__ K
   double ksum[EPP];
 #pragma unroll
   for (int e = 0; e < EPP; ++e) ksum[e] = 0.0;
-  for (int64_t tile0 = key0; tile0 < key1; tile0 += tk) {
+  // Tiles that lie wholly in the padding (rows >= n) are not written: with small bins the padding up to a full
+  // slab is many times the data, and every reader of the packed copy skips rows >= n.
+  for (int64_t tile0 = key0; tile0 < key1 && tile0 < n; tile0 += tk) {
     for (int lr = rk; lr < tk; lr += rpp) {
       const int64_t row = tile0 + lr;
       uint4 v = make_uint4(0u, 0u, 0u, 0u);
@@ -329,16 +331,18 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm(const T *__restrict__ Kp, c
   double acc[KPT];
 #pragma unroll
   for (int k = 0; k < KPT; ++k) acc[k] = 0.0;
-  for (int c = 0; c < nc; ++c) {
-    float x[KPT][kChunk];
-    load_chunk<T, KPT>(Kp + (((size_t)pr * nc + c) * npad + l0) * kChunk, x);
+  if (l0 < n) {                                              // padding rows of the packed copy are not even written
+    for (int c = 0; c < nc; ++c) {
+      float x[KPT][kChunk];
+      load_chunk<T, KPT>(Kp + (((size_t)pr * nc + c) * npad + l0) * kChunk, x);
 #pragma unroll
-    for (int k = 0; k < KPT; ++k)
+      for (int k = 0; k < KPT; ++k)
 #pragma unroll
-      for (int e = 0; e < kChunk; ++e) {
-        const double df = (double)x[k][e] - skb[c * kChunk + e];
-        acc[k] = fma(df, df, acc[k]);
-      }
+        for (int e = 0; e < kChunk; ++e) {
+          const double df = (double)x[k][e] - skb[c * kChunk + e];
+          acc[k] = fma(df, df, acc[k]);
+        }
+    }
   }
   double mx = 0.0;
 #pragma unroll
@@ -521,11 +525,16 @@ struct KeyRegs {
   float x[NC > 0 ? NC : 1][KPT][kChunk / (sizeof(T) == 2 ? 2 : 1)];   // bf16 pairs stay packed in one 32-bit lane
 };
 template <typename T, int KPT, int NC>
-__device__ __forceinline__ void load_key_regs(KeyRegs<T, KPT, NC> &kr, const T *kp, int64_t npad) {
+__device__ __forceinline__ void load_key_regs(KeyRegs<T, KPT, NC> &kr, const T *kp, int64_t npad, bool exists) {
   if constexpr (NC > 0) {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-      if constexpr (sizeof(T) == 2) {
+      if (!exists) {                                           // a thread whose keys are all padding: nothing to read
+#pragma unroll
+        for (int k = 0; k < KPT; ++k)
+#pragma unroll
+          for (int e = 0; e < (int)(sizeof(kr.x[0][0]) / sizeof(float)); ++e) kr.x[c][k][e] = 0.0f;
+      } else if constexpr (sizeof(T) == 2) {
         const uint32_t *src = reinterpret_cast<const uint32_t *>(kp + (size_t)c * npad * kChunk);
 #pragma unroll
         for (int k = 0; k < KPT; ++k) {
@@ -806,8 +815,9 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     }
   } else {
     const T *kp = Kp + (size_t)l_glob * kChunk;
+    const int nc_mine = l_glob < a.n ? nc : 0;                // a thread whose keys are all padding reads nothing
 #pragma unroll 4
-    for (int c = 0; c < nc; ++c) {
+    for (int c = 0; c < nc_mine; ++c) {
       float x[KPT][kChunk];
       load_chunk<T, KPT>(kp + (size_t)c * a.npad * kChunk, x);
 #pragma unroll
@@ -919,7 +929,7 @@ __global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(
   }
   KeyRegs<T, KPT, NC> kr;
   load_key_regs<T, KPT, NC>(kr, reinterpret_cast<const T *>(a.Kp) + ((size_t)pr * nc * a.npad + l_glob) * kChunk,
-                            a.npad);
+                            a.npad, l_glob < a.n);
   int i = 0, rc = 1;
   double carry = 0.0;
   if constexpr (SOLO) {
