@@ -1253,6 +1253,44 @@ __global__ __launch_bounds__(kSolveCols * 32) void k_solve(const double *__restr
   }
 }
 
+// The same solve for small ranks (r <= kSolveSmall, i.e. binned problems with a handful of pivots each, of which there
+// are many): one thread per (problem, right-hand-side column) substitutes backwards through its own copy of the
+// column, in the order k_solve uses inside a panel (x_a = g_a * (1 / L_aa), then g_b -= L_ab x_a for b < a), so the
+// two kernels give the same bits.  grid ceil(P * (dv + 1) / 256).
+constexpr int kSolveSmall = 16;
+
+__global__ __launch_bounds__(kThreads) void k_solve_small(const double *__restrict__ L, const double *__restrict__ Gt,
+                                                          const int32_t *__restrict__ r_eff, int P, int r, int dv,
+                                                          float *__restrict__ v_s, float *__restrict__ w) {
+  const int dv1 = dv + 1;
+  const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (gid >= (int64_t)P * dv1) return;
+  const int pr = (int)(gid / dv1), c = (int)(gid % dv1);
+  const int re = min(r_eff[pr], r);
+  const double *Lp = L + (size_t)pr * r * r;
+  double g[kSolveSmall];
+#pragma unroll
+  for (int j = 0; j < kSolveSmall; ++j) g[j] = j < re ? Gt[((size_t)pr * dv1 + c) * r + j] : 0.0;
+#pragma unroll
+  for (int a = kSolveSmall - 1; a >= 0; --a) {
+    if (a < re) {
+      const double xa = g[a] * (1.0 / Lp[(size_t)a * r + a]);
+      g[a] = xa;
+#pragma unroll
+      for (int b = 0; b < kSolveSmall; ++b)
+        if (b < a) g[b] = fma(-Lp[(size_t)a * r + b], xa, g[b]);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kSolveSmall; ++j) {
+    if (j < r) {
+      const float val = j < re ? (float)g[j] : 0.0f;
+      if (c < dv) v_s[((size_t)pr * r + j) * dv + c] = val;
+      else w[(size_t)pr * r + j] = val;
+    }
+  }
+}
+
 // K_S = original key rows at the pivots (Alg. 2: recentred pivots plus the mean), zero in unused slots.  Pivot indices
 // were found relative to the bin; once the row is read, the slot's index is rewritten as an index into the head's
 // n * bins keys.  grid (r, P), n = keys per bin.
@@ -1460,12 +1498,18 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   hipLaunchKernelGGL(k_gram_reduce, dim3((s.r * dv1 + kThreads - 1) / kThreads, P), dim3(kThreads), 0, st, gpart, s.r,
                      dv1, pl.nchunk, Gt);
   LAUNCH_CHECK();
-  const size_t solve_lds = ((size_t)kSolveCols * s.r + kPanel * (kPanel + 1) + kSolveCols * kPanel) * sizeof(double);
-  if (solve_lds > 64 * 1024 &&
-      hipFuncSetAttribute((const void *)k_solve, hipFuncAttributeMaxDynamicSharedMemorySize, (int)solve_lds) != hipSuccess)
-    return WILDCAT_EHIP;
-  hipLaunchKernelGGL(k_solve, dim3((dv1 + kSolveCols - 1) / kSolveCols, P), dim3(kSolveCols * 32), solve_lds, st, L, Gt,
-                     out->r_eff, s.r, s.dv, out->v_s, out->w);
+  if (s.r <= kSolveSmall) {
+    const int64_t cols = (int64_t)P * dv1;
+    hipLaunchKernelGGL(k_solve_small, dim3((unsigned)((cols + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, L, Gt,
+                       out->r_eff, P, s.r, s.dv, out->v_s, out->w);
+  } else {
+    const size_t solve_lds = ((size_t)kSolveCols * s.r + kPanel * (kPanel + 1) + kSolveCols * kPanel) * sizeof(double);
+    if (solve_lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void *)k_solve, hipFuncAttributeMaxDynamicSharedMemorySize, (int)solve_lds) != hipSuccess)
+      return WILDCAT_EHIP;
+    hipLaunchKernelGGL(k_solve, dim3((dv1 + kSolveCols - 1) / kSolveCols, P), dim3(kSolveCols * 32), solve_lds, st, L, Gt,
+                       out->r_eff, s.r, s.dv, out->v_s, out->w);
+  }
   LAUNCH_CHECK();
   if (s.dtype == WILDCAT_BF16 && out->v_t && out->v_scale) {      // MFMA operand form of V_S for WtdAttn, per head
     const int rc = enqueue_pack_values(P / s.bins, s.r * s.bins, s.dv, out->v_s, out->v_t, out->v_scale, st);
