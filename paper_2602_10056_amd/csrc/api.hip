@@ -98,7 +98,9 @@ Plan make_plan(const Shape &s) {
   // Single-launch loop if all slabs can be resident (refined against real occupancy at launch).  The environment
   // variable WILDCAT_RPNYS_LOOP=steps forces one launch per step (a tuning and debugging switch).
   const char *mode = std::getenv("WILDCAT_RPNYS_LOOP");
-  p.persistent = s.r >= 2 && (int64_t)p.nblk * s.P <= 2 * 1024 && !(mode && std::strcmp(mode, "steps") == 0);
+  // A problem of one slab takes the single-launch form at any rank and any problem count (its workgroups never wait).
+  p.persistent = (p.nblk == 1 || (s.r >= 2 && (int64_t)p.nblk * s.P <= 2 * 1024)) &&
+                 !(mode && std::strcmp(mode, "steps") == 0);
   p.total = off;
   return p;
 }

@@ -31,6 +31,7 @@
 #include <climits>
 #include <cmath>
 #include <cstdlib>
+#include <cstring>
 
 #include "common.h"
 
@@ -368,17 +369,28 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm(const T *__restrict__ Kp, c
 // If R_K or R_Q is zero every kernel value is 1 whatever tau is; tau is then reported as +inf and
 // the loop runs with exponent scale 0.
 // --------------------------------------------------------------------------------------------
+// One thread evaluates this while its workgroup waits, so the chain of double-precision logarithms is kept short:
+// the start comes from a few single-precision rounds, and the iteration stops once a step is below 1e-9 relative --
+// Newton converges quadratically here (error_next <= 1.9 error^2 for w >= 0.2), so the value after that step is
+// exact to rounding.
 __device__ double lambert_w0(double z) {
+  float wf = log1pf((float)z);
+  const float lzf = logf((float)z);
+  for (int it = 0; it < 4; ++it) wf -= (wf + logf(wf) - lzf) / (1.0f + 1.0f / wf);
   const double lz = log(z);
-  double w = log1p(z);
+  double w = wf > 0.0f && wf < INFINITY ? (double)wf : log1p(z);
   for (int it = 0; it < 64; ++it) {
     const double wn = w - (w + log(w) - lz) / (1.0 + 1.0 / w);
-    const bool done = fabs(wn - w) <= 4e-16 * fabs(wn);
+    const bool done = fabs(wn - w) <= 1e-9 * fabs(wn);
     w = wn;
     if (done) break;
   }
   return w;
 }
+
+// rho_0 = sqrt(1 + exp(W0(2 / e^2) + 2)) = sqrt(1 + 2 / W0(2 / e^2))   (eq. (kernel-temperature)), W0(2 / e^2) =
+// 0.21771510575709011...
+constexpr double kRho0 = 0x1.988661e4d29bbp+1;               // 3.19160102532370412...
 
 // Evaluated by one thread of every workgroup of k_init_p (same inputs, same arithmetic, same value everywhere).
 __device__ void temperature(double rk2, double rq, double n, double beta, double *tau, double *beta_tau, double *rk_out) {
@@ -387,9 +399,8 @@ __device__ void temperature(double rk2, double rq, double n, double beta, double
     *tau = INFINITY;
     *beta_tau = 0.0;
   } else {
-    const double rho0 = sqrt(1.0 + exp(lambert_w0(2.0 * exp(-2.0)) + 2.0));
     const double b0 = log(n) / (beta * rq * rk) + 2.0;
-    const double rho = b0 / (2.0 * lambert_w0(b0 / (2.0 * rho0)));
+    const double rho = b0 / (2.0 * lambert_w0(b0 / (2.0 * kRho0)));
     *tau = sqrt(rho * rk / rq);
     *beta_tau = beta / (*tau * *tau);
   }
@@ -604,12 +615,13 @@ struct StepShared {
 // with what later steps read back).
 // SOLO: the problem has a single slab (small bins), so this workgroup is alone with it: the total mass is carried
 // from step to step in `carry`, the residual diagonal is searched in registers, and nothing is polled, published or
-// written for other workgroups (the history rows still go to memory: the Gram pass reads them).
+// written for other workgroups (the history rows still go to memory: the Gram pass reads them).  The step's uniform
+// and beta / tau^2 arrive as arguments (u_solo, bt_solo): the caller (k_rpnys_solo) has just computed them itself.
 template <typename T, int KPT, int NC, bool POLL, typename H, bool SOLO = false>
 __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int pr, double *g, double *ksc,
                                           StepShared &sh, const KeyRegs<T, KPT, NC> &kr, double (&pown)[KPT],
                                           const double (&flo)[KPT], int *error, long long spin_limit, int hcn,
-                                          double *carry = nullptr) {
+                                          double *carry = nullptr, double u_solo = 0.0, double bt_solo = 0.0) {
   constexpr int SLAB = kThreads * KPT;
   const int t = threadIdx.x;
   const int lane = t & (kWave - 1);
@@ -668,7 +680,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   if (!(mass > 0.0)) return 0;                     // h(K,K) is reproduced exactly by the pivots so far
 
   // ---- 2. the slab holding the draw: first slab whose inclusive prefix exceeds u * mass ----------------------
-  double target = a.u[(size_t)pr * a.r + i] * mass;
+  double target = (SOLO ? u_solo : a.u[(size_t)pr * a.r + i]) * mass;
   int cand = INT_MAX;
   double cand_base = 0.0;
   int last_pos = -1;
@@ -744,7 +756,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   }
   const double cb = block_sum(cbp, sh.sm);       // <kbar, k_s - kbar>; also publishes g, ksc, s_ps
   const double inv = 1.0 / sqrt(sh.s_ps);
-  const double beta_tau = a.scal[(size_t)pr * 8 + 2];
+  const double beta_tau = SOLO ? bt_solo : a.scal[(size_t)pr * 8 + 2];
 
   // ---- 5. history product  acc_l = sum_{j<i} F_j(l) g_j  (the O(n i) stream) ---------------------------
   // Rows are walked upwards on even steps and downwards on odd steps: the rows a step reads last are the
@@ -912,7 +924,7 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 // bounded: if a limit is hit (it never should be) the error word is set and every workgroup leaves.  With
 // NC > 0 a thread keeps the packed features of its keys in registers for the whole loop, which removes the
 // O(n d) key stream from every step.
-template <typename T, int KPT, int NC, typename H, bool SOLO = false>
+template <typename T, int KPT, int NC, typename H>
 __global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
                                                                   int hcn) {
   extern __shared__ double dyn[];
@@ -931,16 +943,8 @@ __global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(
   load_key_regs<T, KPT, NC>(kr, reinterpret_cast<const T *>(a.Kp) + ((size_t)pr * nc * a.npad + l_glob) * kChunk,
                             a.npad, l_glob < a.n);
   int i = 0, rc = 1;
-  double carry = 0.0;
-  if constexpr (SOLO) {
-    double s0 = 0.0;
-#pragma unroll
-    for (int k = 0; k < KPT; ++k) s0 += pown[k];
-    carry = block_sum(s0, sh.sm);
-  }
   for (; i < a.r; ++i) {
-    rc = rpnys_step<T, KPT, NC, !SOLO, H, SOLO>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn,
-                                                &carry);
+    rc = rpnys_step<T, KPT, NC, true, H>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
     if (rc != 1) break;
   }
   if (rc == 0) {
@@ -952,6 +956,306 @@ __global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(
       for (int k = 0; k < KPT; ++k) Fb[(size_t)j * SLAB + t * KPT + k] = (H)0;
     if (b == 0 && t == 0) a.r_eff[pr] = i;
   }
+}
+
+// Driver 3: problems of a single slab (small bins: the image-model layer shapes, many bins of a long sequence).  One
+// workgroup is alone with its problem, so the whole of Alg. 2's bin body up to the pivots runs here in one launch:
+// ||k_l - kbar||^2 and R_K (what k_sqnorm computes, in the same order), the temperature, p_l = exp(beta_tau ||.||^2)
+// and its floor (k_init_p), then the r steps in their SOLO form.  The residual diagonal, its floor and the total mass
+// live in registers throughout; only the history rows, L, idx, r_eff and tau leave the workgroup.  grid (1, P); any
+// number of workgroups may be resident (none waits for another).
+struct SoloInit {
+  const double *r_q;      // [P / bins]
+  const double *u;        // [P][r] uniforms, or null: drawn from `seed` by the library's counter-based generator
+  double *scal;           // [P][8]: 0 = R_K^2, 1 = tau, 2 = beta / tau^2, 3 = R_K
+  double *tau_out;        // [P]
+  unsigned long long seed;
+  double rank_tol, tau_n, beta;
+  int bins;
+};
+
+template <typename T, int KPT, int NC, typename H>
+__global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_solo(StepArgs a, SoloInit in, int hcn) {
+  extern __shared__ double dyn[];
+  __shared__ StepShared sh;
+  constexpr int SLAB = kThreads * KPT;
+  const int t = threadIdx.x, pr = blockIdx.y;
+  const int64_t l_glob = t * KPT;
+  const int nc = a.dpad / kChunk;
+  double *skb = dyn + a.r;                                   // the step's k_s - kbar buffer is free until step 0
+  if (t < a.dpad) skb[t] = a.kbar[(size_t)pr * a.dpad + t];
+  const T *kp = reinterpret_cast<const T *>(a.Kp) + ((size_t)pr * nc * a.npad + l_glob) * kChunk;
+  KeyRegs<T, KPT, NC> kr;
+  load_key_regs<T, KPT, NC>(kr, kp, a.npad, l_glob < a.n);
+  __syncthreads();
+
+  double sq[KPT];
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) sq[k] = 0.0;
+  if (l_glob < a.n) {
+    if constexpr (NC > 0) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        float x[KPT][kChunk];
+        key_chunk<T, KPT, NC>(kr, c, x);
+#pragma unroll
+        for (int k = 0; k < KPT; ++k)
+#pragma unroll
+          for (int e = 0; e < kChunk; ++e) {
+            const double df = (double)x[k][e] - skb[c * kChunk + e];
+            sq[k] = fma(df, df, sq[k]);
+          }
+      }
+    } else {
+      for (int c = 0; c < nc; ++c) {
+        float x[KPT][kChunk];
+        load_chunk<T, KPT>(kp + (size_t)c * a.npad * kChunk, x);
+#pragma unroll
+        for (int k = 0; k < KPT; ++k)
+#pragma unroll
+          for (int e = 0; e < kChunk; ++e) {
+            const double df = (double)x[k][e] - skb[c * kChunk + e];
+            sq[k] = fma(df, df, sq[k]);
+          }
+      }
+    }
+  }
+  double mx = 0.0;
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    if (l_glob + k >= a.n) sq[k] = 0.0;
+    mx = fmax(mx, sq[k]);
+  }
+  mx = block_reduce<double>(mx, sh.sm, MaxOp());
+  if (t == 0) {
+    double tau, bt, rk;
+    temperature(mx, in.r_q[pr / in.bins], in.tau_n, in.beta, &tau, &bt, &rk);
+    sh.s_base = bt;
+    in.scal[(size_t)pr * 8] = mx;
+    in.scal[(size_t)pr * 8 + 1] = tau;
+    in.scal[(size_t)pr * 8 + 2] = bt;
+    in.scal[(size_t)pr * 8 + 3] = rk;
+    in.tau_out[pr] = tau;
+  }
+  __syncthreads();
+  const double beta_tau = sh.s_base;
+  double pown[KPT], flo[KPT], s0 = 0.0;
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    const double v = (l_glob + k < a.n) ? exp(beta_tau * sq[k]) : 0.0;
+    pown[k] = v;
+    flo[k] = in.rank_tol * v;
+    s0 += v;
+  }
+  double carry = block_sum(s0, sh.sm);
+
+  int i = 0;
+  for (; i < a.r; ++i) {
+    const unsigned long long ctr = (unsigned long long)pr * a.r + i + 1ull;
+    const double ui = in.u ? in.u[(size_t)pr * a.r + i]
+                           : (double)(mix64(in.seed + ctr * 0x9E3779B97F4A7C15ull) >> 11) * 0x1.0p-53;
+    if (rpnys_step<T, KPT, NC, false, H, true>(a, i, 0, pr, dyn, dyn + a.r, sh, kr, pown, flo, nullptr, 0, hcn, &carry,
+                                               ui, beta_tau) != 1)
+      break;
+  }
+  // Slots the loop did not fill (residual mass exhausted at step i): zero history rows for the Gram pass, idx = -1.
+  H *Fb = reinterpret_cast<H *>(a.F) + (size_t)pr * a.r * SLAB;
+  for (int j = i; j < a.r; ++j)
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) Fb[(size_t)j * SLAB + t * KPT + k] = (H)0;
+  for (int j = i + t; j < a.r; j += kThreads) a.idx[(size_t)pr * a.r + j] = -1;
+  if (t == 0) a.r_eff[pr] = i;
+}
+
+// Driver 4: tiny problems (at most 128 keys and 16 pivots: the many-bin settings, where a layer has hundreds or
+// thousands of them).  One WAVE per problem, four problems per workgroup: a lane keeps its one or two keys as floats
+// in registers, the history rows of the problem sit in the wave's own piece of LDS, and every reduction, scan and
+// broadcast of the step is a cross-lane operation, so the loop has no workgroup barrier and no memory round trip at
+// all.  Same steps and the same arithmetic per key as the SOLO form above (sums over lanes associate differently:
+// rounding only).  grid ceil(P / 4); dynamic LDS 4 x (DP doubles + r x 64 KW history entries).
+__device__ __forceinline__ void wave_sync_lds() {            // LDS written by one lane is read by another lane next
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+__device__ __forceinline__ double lane_value(double v, int lane) {      // lane: the same in every lane
+  const long long b = __double_as_longlong(v);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, lane);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)b >> 32), lane);
+  return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+template <typename T, int KW, int DP, typename H>
+__global__ __launch_bounds__(kThreads) void k_rpnys_wave(StepArgs a, SoloInit in) {
+  extern __shared__ double dyn[];
+  constexpr int NCH = DP / kChunk, ROW = kWave * KW;
+  const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+  const int pr = blockIdx.x * (kThreads / kWave) + wv;
+  if (pr >= a.P) return;                                     // no workgroup barrier below
+  const int r = a.r;
+  const size_t per_wave = (size_t)DP * sizeof(double) + (((size_t)r * ROW * sizeof(H) + 7) & ~(size_t)7);
+  char *mine = reinterpret_cast<char *>(dyn) + wv * per_wave;
+  double *skb = reinterpret_cast<double *>(mine);
+  H *hist = reinterpret_cast<H *>(mine + (size_t)DP * sizeof(double));
+  for (int c = lane; c < DP; c += kWave) skb[c] = a.kbar[(size_t)pr * DP + c];
+  const int l0 = lane * KW;
+  float x[KW][DP];
+  {
+    const T *kp = reinterpret_cast<const T *>(a.Kp) + ((size_t)pr * NCH * a.npad + l0) * kChunk;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      float xc[KW][kChunk];
+      if (l0 < a.n) {
+        load_chunk<T, KW>(kp + (size_t)c * a.npad * kChunk, xc);
+      } else {
+#pragma unroll
+        for (int k = 0; k < KW; ++k)
+#pragma unroll
+          for (int e = 0; e < kChunk; ++e) xc[k][e] = 0.0f;
+      }
+#pragma unroll
+      for (int k = 0; k < KW; ++k)
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) x[k][c * kChunk + e] = xc[k][e];
+    }
+  }
+  wave_sync_lds();
+
+  // ---- ||k_l - kbar||^2, R_K, temperature, p_0 ---------------------------------------------------------------
+  double sq[KW], mx = 0.0;
+#pragma unroll
+  for (int k = 0; k < KW; ++k) sq[k] = 0.0;
+#pragma unroll
+  for (int c = 0; c < DP; ++c) {
+    const double kb = skb[c];
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      const double df = (double)x[k][c] - kb;
+      sq[k] = fma(df, df, sq[k]);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < KW; ++k) {
+    if (l0 + k >= a.n) sq[k] = 0.0;
+    mx = fmax(mx, sq[k]);
+  }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) mx = fmax(mx, __shfl_xor(mx, off, kWave));
+  double tau, beta_tau, rk;
+  temperature(mx, in.r_q[pr / in.bins], in.tau_n, in.beta, &tau, &beta_tau, &rk);   // every lane, same value
+  if (lane == 0) {
+    in.scal[(size_t)pr * 8] = mx;
+    in.scal[(size_t)pr * 8 + 1] = tau;
+    in.scal[(size_t)pr * 8 + 2] = beta_tau;
+    in.scal[(size_t)pr * 8 + 3] = rk;
+    in.tau_out[pr] = tau;
+  }
+  double p[KW], flo[KW], psum = 0.0;
+#pragma unroll
+  for (int k = 0; k < KW; ++k) {
+    p[k] = (l0 + k < a.n) ? exp(beta_tau * sq[k]) : 0.0;
+    flo[k] = in.rank_tol * p[k];
+    psum += p[k];
+  }
+  double mass = wave_sum(psum);
+
+  // ---- the r steps of Alg. 1 ---------------------------------------------------------------------------------
+  H *Fb = reinterpret_cast<H *>(a.F) + (size_t)pr * r * a.npad;            // one slab per problem: rows of npad entries
+  int i = 0;
+  for (; i < r; ++i) {
+    if (!(mass > 0.0)) break;
+    const unsigned long long ctr = (unsigned long long)pr * r + i + 1ull;
+    const double ui = in.u ? in.u[(size_t)pr * r + i]
+                           : (double)(mix64(in.seed + ctr * 0x9E3779B97F4A7C15ull) >> 11) * 0x1.0p-53;
+    const double target = ui * mass;
+    // the draw: first index whose inclusive prefix sum exceeds u * mass, else the last index of positive mass
+    double loc = 0.0;
+#pragma unroll
+    for (int k = 0; k < KW; ++k) loc += p[k];
+    double inc = loc;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const double up = __shfl_up(inc, off, kWave);
+      if (lane >= off) inc += up;
+    }
+    double run = __shfl_up(inc, 1, kWave);
+    if (lane == 0) run = 0.0;
+    int cand = INT_MAX, last_pos = -1;
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      const double nxt = run + p[k];
+      if (nxt > target && cand == INT_MAX) cand = l0 + k;
+      if (p[k] > 0.0) last_pos = l0 + k;
+      run = nxt;
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+      cand = min(cand, __shfl_xor(cand, off, kWave));
+      last_pos = max(last_pos, __shfl_xor(last_pos, off, kWave));
+    }
+    int s_loc = cand == INT_MAX ? last_pos : cand;
+    if (s_loc < 0) s_loc = 0;                                // non-finite input only
+    s_loc = __builtin_amdgcn_readfirstlane(s_loc);
+    const int owner = s_loc / KW;
+    const bool second = KW == 2 && (s_loc % KW) != 0;
+    const double p_s = lane_value(second ? p[KW - 1] : p[0], owner);
+    const double inv = 1.0 / sqrt(p_s);
+
+    // kernel column: <k_l - kbar, k_s - kbar> = <k_l, k_s - kbar> - <kbar, k_s - kbar>
+    double dot[KW], cb = 0.0;
+#pragma unroll
+    for (int k = 0; k < KW; ++k) dot[k] = 0.0;
+#pragma unroll
+    for (int c = 0; c < DP; ++c) {
+      const float xs = __int_as_float(
+          __builtin_amdgcn_readlane(__float_as_int(second ? x[KW - 1][c] : x[0][c]), owner));
+      const double kb = skb[c];
+      const double ks = (double)xs - kb;
+      cb = fma(kb, ks, cb);
+#pragma unroll
+      for (int k = 0; k < KW; ++k) dot[k] = fma((double)x[k][c], ks, dot[k]);
+    }
+    // history product  sum_{j<i} F_j(l) F_j(s)
+    double acc[KW];
+#pragma unroll
+    for (int k = 0; k < KW; ++k) acc[k] = 0.0;
+    for (int j = 0; j < i; ++j) {
+      const double gj = (double)hist[(size_t)j * ROW + s_loc];
+#pragma unroll
+      for (int k = 0; k < KW; ++k) acc[k] = fma((double)hist[(size_t)j * ROW + l0 + k], gj, acc[k]);
+    }
+    // new Cholesky row and residual diagonal
+    psum = 0.0;
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      const int l = l0 + k;
+      double f = (double)(H)((exp(beta_tau * (dot[k] - cb)) - acc[k]) * inv);
+      double pn = p[k] - f * f;
+      if (pn <= flo[k]) pn = 0.0;
+      if (l == s_loc) {
+        pn = 0.0;
+        a.L[((size_t)pr * r + i) * r + i] = f;
+        a.idx[(size_t)pr * r + i] = s_loc;
+      }
+      if (l >= a.n) { pn = 0.0; f = 0.0; }
+      Fb[(size_t)i * a.npad + l] = (H)f;
+      hist[(size_t)i * ROW + l] = (H)f;
+      p[k] = pn;
+      psum += pn;
+    }
+    if (lane < i) a.L[((size_t)pr * r + i) * r + lane] = (double)hist[(size_t)lane * ROW + s_loc];
+    wave_sync_lds();                                         // row i is in LDS before the next step reads it
+    mass = wave_sum(psum);
+  }
+  for (int j = i; j < r; ++j)
+#pragma unroll
+    for (int k = 0; k < KW; ++k) Fb[(size_t)j * a.npad + l0 + k] = (H)0;
+  for (int j = i + lane; j < r; j += kWave) a.idx[(size_t)pr * r + j] = -1;
+  if (lane == 0) a.r_eff[pr] = i;
 }
 
 // --------------------------------------------------------------------------------------------
@@ -1326,23 +1630,54 @@ struct LoopPlan {
   const void *fn;
   size_t lds;
   int hcn;
+  bool solo;              // fn is k_rpnys_solo or k_rpnys_wave (which also do the work of k_sqnorm and k_init_p)
+  bool wave;              // fn is k_rpnys_wave
 };
+
+constexpr int kWaveRank = 16;                                // k_rpnys_wave: at most this many pivots (lane j < i writes L)
+
+template <typename T, typename H>
+const void *wave_kernel(const Shape &s, int dpad) {
+  if (s.r > kWaveRank) return nullptr;
+  if (dpad == 64 && s.n <= 64) return (const void *)k_rpnys_wave<T, 1, 64, H>;
+  if (dpad == 64 && s.n <= 128) return (const void *)k_rpnys_wave<T, 2, 64, H>;
+  if (dpad == 128 && s.n <= 64) return (const void *)k_rpnys_wave<T, 1, 128, H>;
+  return nullptr;
+}
 
 template <typename T, int KPT, typename H>
 LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
-  LoopPlan lp = {nullptr, 0, 0};
+  LoopPlan lp = {nullptr, 0, 0, false, false};
   if (!pl.persistent) return lp;
+  // One wave per problem pays once the workgroup-per-problem form would need several rounds of workgroups: a wave
+  // alone takes about 6 us per step against 4 us for a workgroup, but sixteen times as many problems are in flight.
+  // WILDCAT_RPNYS_LOOP=wave selects it wherever it applies (a testing switch).
+  const char *mode = std::getenv("WILDCAT_RPNYS_LOOP");
+  if (pl.nblk == 1 && (s.P > 2 * compute_units() || (mode && std::strcmp(mode, "wave") == 0))) {
+    if (const void *wfn = wave_kernel<T, H>(s, pl.dpad)) {
+      const int kw = s.n <= 64 ? 1 : 2;
+      const size_t per_wave = (size_t)pl.dpad * sizeof(double) + (((size_t)s.r * kWave * kw * sizeof(H) + 7) & ~(size_t)7);
+      lp.lds = per_wave * (kThreads / kWave);
+      if (lp.lds <= 64 * 1024 ||
+          hipFuncSetAttribute(wfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lp.lds) == hipSuccess) {
+        lp.fn = wfn;
+        lp.solo = lp.wave = true;
+        return lp;
+      }
+      lp.lds = 0;
+    }
+  }
   const int nc = pl.dpad / kChunk;
   constexpr int regs_per_chunk = KPT * (sizeof(T) == 2 ? 2 : 4);
   const bool solo = pl.nblk == 1;                             // one slab per problem: see rpnys_step
   const void *fn;
   if (nc == 32 && 32 * regs_per_chunk <= 128)
-    fn = solo ? (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H, true>
+    fn = solo ? (const void *)k_rpnys_solo<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H>
               : (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H>;
   else if (nc == 16 && 16 * regs_per_chunk <= 128)
-    fn = solo ? (const void *)k_rpnys_persistent<T, KPT, 16, H, true> : (const void *)k_rpnys_persistent<T, KPT, 16, H>;
+    fn = solo ? (const void *)k_rpnys_solo<T, KPT, 16, H> : (const void *)k_rpnys_persistent<T, KPT, 16, H>;
   else
-    fn = solo ? (const void *)k_rpnys_persistent<T, KPT, 0, H, true> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
+    fn = solo ? (const void *)k_rpnys_solo<T, KPT, 0, H> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
   const int cus = compute_units();
   const int64_t wgs = (int64_t)pl.nblk * s.P;
   int need = (int)((wgs + cus - 1) / cus);                   // workgroups a compute unit must hold
@@ -1353,11 +1688,12 @@ LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
   if (per_cu < need) {
     // Keys in registers cost too many registers for this many workgroups per compute unit: the variant that
     // streams the keys every step is leaner and still saves the launches and their gaps.
-    fn = solo ? (const void *)k_rpnys_persistent<T, KPT, 0, H, true> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
+    fn = solo ? (const void *)k_rpnys_solo<T, KPT, 0, H> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess || per_cu < need)
       return lp;
   }
   lp.fn = fn;
+  lp.solo = solo;
   lp.lds = base;
   // History cache: optional, and only if the kernel stays resident with it.
   int dev = 0, lds_cu = 0;
@@ -1432,14 +1768,17 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   hipLaunchKernelGGL(k_col_final, dim3(P / s.bins), dim3(kFinalThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
                      nparts, s.bins, lpr, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
   LAUNCH_CHECK();
-  hipLaunchKernelGGL((k_sqnorm<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, Kp, kbar, s.n, pl.npad, pl.dpad, d0,
-                     (unsigned long long *)scal);
-  LAUNCH_CHECK();
-  hipLaunchKernelGGL((k_init_p<KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, s.n, pl.npad, pl.nblk, s.r, s.rank_tol,
-                     s.bins, (double)(s.tau_full_n ? s.n * s.bins : s.n), s.beta, o->r_q, scal, out->tau, d0, p, bsum,
-                     out->idx, out->r_eff, o->uniforms ? (double *)nullptr : u_gen, (unsigned long long)seed,
-                     (int *)(ws + pl.off_sync));
-  LAUNCH_CHECK();
+  const LoopPlan lp = persistent_kernel<T, KPT, H>(s, pl);
+  const double tau_n = (double)(s.tau_full_n ? s.n * s.bins : s.n);
+  if (!lp.solo) {
+    hipLaunchKernelGGL((k_sqnorm<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, Kp, kbar, s.n, pl.npad, pl.dpad, d0,
+                       (unsigned long long *)scal);
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL((k_init_p<KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, s.n, pl.npad, pl.nblk, s.r, s.rank_tol,
+                       s.bins, tau_n, s.beta, o->r_q, scal, out->tau, d0, p, bsum, out->idx, out->r_eff,
+                       o->uniforms ? (double *)nullptr : u_gen, (unsigned long long)seed, (int *)(ws + pl.off_sync));
+    LAUNCH_CHECK();
+  }
 
   StepArgs a;
   a.Kp = Kp; a.kbar = kbar; a.scal = scal; a.floor = d0; a.u = o->uniforms ? o->uniforms : u_gen;
@@ -1448,9 +1787,17 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
   const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
   bool done = false;
-  const LoopPlan lp = persistent_kernel<T, KPT, H>(s, pl);
   const void *fn = lp.fn;
-  if (fn) {
+  if (fn && lp.solo) {
+    SoloInit in;
+    in.r_q = o->r_q; in.u = o->uniforms; in.scal = scal; in.tau_out = out->tau; in.seed = (unsigned long long)seed;
+    in.rank_tol = s.rank_tol; in.tau_n = tau_n; in.beta = s.beta; in.bins = s.bins;
+    int hcn = lp.hcn;
+    void *args[] = {(void *)&a, (void *)&in, (void *)&hcn};
+    const dim3 grid = lp.wave ? dim3((P + kThreads / kWave - 1) / (kThreads / kWave)) : dim3(1, P);
+    if (hipLaunchKernel(fn, grid, dim3(kThreads), args, lp.lds, st) != hipSuccess) return WILDCAT_EHIP;
+    done = true;
+  } else if (fn) {
     int *err_word = (int *)(ws + pl.off_sync);
     long long spin_limit = 2000000;    // polls of about a microsecond each: seconds, far beyond any real step
     int hcn = lp.hcn;

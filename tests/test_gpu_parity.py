@@ -483,6 +483,76 @@ def test_binned_seed_path_and_loop_drivers(monkeypatch):
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("cfg,ov,kw", [
+    (8, dict(batch=3), {}),                                                        # 672 bins of 14 keys, 1 pivot each (fp32)
+    (6, dict(q_heads=4, kv_heads=4, n=160 * 64, r=160 * 4, bins=160, d=128), {}),  # 640 bins of 64 keys, d = 128, bf16
+    (6, dict(q_heads=4, kv_heads=4, n=130 * 100, r=130 * 16, bins=130), {}),       # 520 bins of 100 keys (two per lane), 16 pivots
+    (6, dict(q_heads=2, kv_heads=2, n=300 * 33, r=300 * 5, bins=300), dict(history="f32")),
+])
+def test_many_tiny_bins_take_the_wave_per_problem_loop(cfg, ov, kw):
+    """More than 512 problems of at most 128 keys and 16 pivots each: the selection loop runs one wave per problem
+    (k_rpnys_wave).  Every bin against the oracle."""
+    w = wl.make(cfg, **ov)
+    s = w["shape"]
+    assert s.problems * s.bins > 512 and s.n // s.bins <= 128 and s.r // s.bins <= 16
+    out, cs = run_gpu(w)
+    print(cfg, check_against_oracle(w, out, cs))
+    if kw:
+        check_fast_mode_against_default(run_gpu(w, **kw), (out, cs))
+
+
+def check_fast_mode_against_default(fast, default):
+    """fp32 history rows on a problem whose tie margins dwarf fp32 rounding: the float64 pivots, results equal to
+    fp32-history accuracy."""
+    (o32, c32), (o64, c64) = fast, default
+    assert torch.equal(c32.idx, c64.idx) and torch.equal(c32.r_eff, c64.r_eff)
+    for a, b in ((c32.w, c64.w), (c32.v_s, c64.v_s)):
+        assert float((a - b).abs().max()) <= 2e-3 * float(b.abs().max())
+    tol = 2e-3 if o64.dtype == torch.float32 else 2 ** -7          # bf16 outputs: one unit in the last place
+    assert float((o32.float() - o64.float()).abs().max()) <= tol * float(o64.float().abs().max())
+
+
+def test_wave_per_problem_loop_on_random_small_shapes(monkeypatch):
+    """WILDCAT_RPNYS_LOOP=wave selects the wave-per-problem loop wherever it applies, whatever the problem count:
+    forty seeded random shapes inside its range (ragged key counts, one and two keys per lane, both widths, both storage
+    types, both history types) against the oracle, then the two rank-exhaustion cases with few keys per problem."""
+    monkeypatch.setenv("WILDCAT_RPNYS_LOOP", "wave")
+    rng = np.random.default_rng(77)
+    done = 0
+    while done < 40:
+        d = int(rng.choice([64, 64, 128]))
+        bins = int(rng.choice([1, 2, 5, 16]))
+        nb = int(rng.choice([3, 14, 33, 64] if d == 128 else [3, 14, 33, 64, 65, 100, 128]))
+        rb = int(rng.choice([1, 2, 3, 7, 16]))
+        if rb > nb:
+            continue
+        kv, group = int(rng.choice([1, 3])), int(rng.choice([1, 2]))
+        dtype = str(rng.choice(["bf16", "f32"]))
+        kw = dict(history="f32") if rng.random() < 0.3 else {}
+        w = wl.make(6 if dtype == "bf16" else 3, q_heads=kv * group, kv_heads=kv, n=nb * bins, m_=int(rng.choice([1, 50, 200])),
+                    d=d, r=rb * bins, bins=bins, dtype=dtype)
+        out, cs = run_gpu(w)
+        check_against_oracle(w, out, cs)
+        if kw:
+            check_fast_mode_against_default(run_gpu(w, **kw), (out, cs))
+        done += 1
+    # rank exhaustion: 9 distinct keys among 100, 16 slots
+    rng = np.random.default_rng(12)
+    n, d, q, r = 100, 64, 9, 16
+    proto = wl.round_to_storage(rng.standard_normal((q, d)), "f32")
+    lab = np.concatenate([np.arange(q), rng.integers(0, q, n - q)])
+    rng.shuffle(lab)
+    K = proto[lab][None, None]
+    V = wl.round_to_storage(rng.standard_normal((1, 1, n, d)), "f32")
+    Q = wl.round_to_storage(rng.standard_normal((1, 1, 40, d)), "f32")
+    u = rng.random((1, r))
+    w = {"shape": wl.shape(1, n=n, r=r, m_=40), "Q": Q, "K": K, "V": V, "u": u}
+    out, cs = wc.wildcat(to_dev(Q, "f32"), to_dev(K, "f32"), to_dev(V, "f32"), r=r,
+                         uniforms=torch.from_numpy(u).to(dev()), return_coreset=True)
+    assert cs.r_eff.item() == q and np.all(cs.idx.cpu().numpy()[0, 0][q:] == -1)
+    check_against_oracle(w, out, cs)
+
+
 def test_binned_full_size_config6():
     """The binned benchmark shape at full size (n = 65536, 16 bins of 4096 keys, 4 pivots each), every head checked."""
     w = wl.make(6)
