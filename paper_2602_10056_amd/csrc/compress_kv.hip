@@ -373,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void k_sqnorm(const T *__restrict__ Kp, c
 // the start comes from a few single-precision rounds, and the iteration stops once a step is below 1e-9 relative --
 // Newton converges quadratically here (error_next <= 1.9 error^2 for w >= 0.2), so the value after that step is
 // exact to rounding.
-__device__ double lambert_w0(double z) {
+__device__ __forceinline__ double lambert_w0(double z) {
   float wf = log1pf((float)z);
   const float lzf = logf((float)z);
   for (int it = 0; it < 4; ++it) wf -= (wf + logf(wf) - lzf) / (1.0f + 1.0f / wf);
@@ -393,7 +393,7 @@ __device__ double lambert_w0(double z) {
 constexpr double kRho0 = 0x1.988661e4d29bbp+1;               // 3.19160102532370412...
 
 // Evaluated by one thread of every workgroup of k_init_p (same inputs, same arithmetic, same value everywhere).
-__device__ void temperature(double rk2, double rq, double n, double beta, double *tau, double *beta_tau, double *rk_out) {
+__device__ __forceinline__ void temperature(double rk2, double rq, double n, double beta, double *tau, double *beta_tau, double *rk_out) {
   const double rk = sqrt(rk2);
   if (!(rk > 0.0) || !(rq > 0.0)) {
     *tau = INFINITY;
@@ -1090,7 +1090,7 @@ __device__ __forceinline__ double lane_value(double v, int lane) {      // lane:
 }
 
 template <typename T, int KW, int DP, typename H>
-__global__ __launch_bounds__(kThreads) void k_rpnys_wave(StepArgs a, SoloInit in) {
+__global__ __launch_bounds__(kThreads, KW * DP <= 64 ? 2 : 1) void k_rpnys_wave(StepArgs a, SoloInit in) {
   extern __shared__ double dyn[];
   constexpr int NCH = DP / kChunk, ROW = kWave * KW;
   const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
@@ -1137,6 +1137,7 @@ __global__ __launch_bounds__(kThreads) void k_rpnys_wave(StepArgs a, SoloInit in
       const double df = (double)x[k][c] - kb;
       sq[k] = fma(df, df, sq[k]);
     }
+    if ((c & 7) == 7) __builtin_amdgcn_sched_barrier(0);
   }
 #pragma unroll
   for (int k = 0; k < KW; ++k) {
@@ -1168,6 +1169,14 @@ __global__ __launch_bounds__(kThreads) void k_rpnys_wave(StepArgs a, SoloInit in
   int i = 0;
   for (; i < r; ++i) {
     if (!(mass > 0.0)) break;
+    // The keys stay as floats: without this the compiler keeps their fp64 widenings (loop invariants of the fully
+    // unrolled products below) in registers as well, and spills.
+#pragma unroll
+    for (int k = 0; k < KW; ++k)
+#pragma unroll
+      for (int c = 0; c < DP; ++c) asm volatile("" : "+v"(x[k][c]));
+    const double *kbar_lds = skb;                            // likewise kbar: read from LDS every step, not kept
+    asm volatile("" : "+v"(kbar_lds));
     const unsigned long long ctr = (unsigned long long)pr * r + i + 1ull;
     const double ui = in.u ? in.u[(size_t)pr * r + i]
                            : (double)(mix64(in.seed + ctr * 0x9E3779B97F4A7C15ull) >> 11) * 0x1.0p-53;
@@ -1202,7 +1211,8 @@ __global__ __launch_bounds__(kThreads) void k_rpnys_wave(StepArgs a, SoloInit in
     s_loc = __builtin_amdgcn_readfirstlane(s_loc);
     const int owner = s_loc / KW;
     const bool second = KW == 2 && (s_loc % KW) != 0;
-    const double p_s = lane_value(second ? p[KW - 1] : p[0], owner);
+    const double p_s0 = lane_value(p[0], owner), p_s1 = lane_value(p[KW - 1], owner);
+    const double p_s = second ? p_s1 : p_s0;
     const double inv = 1.0 / sqrt(p_s);
 
     // kernel column: <k_l - kbar, k_s - kbar> = <k_l, k_s - kbar> - <kbar, k_s - kbar>
@@ -1211,13 +1221,18 @@ __global__ __launch_bounds__(kThreads) void k_rpnys_wave(StepArgs a, SoloInit in
     for (int k = 0; k < KW; ++k) dot[k] = 0.0;
 #pragma unroll
     for (int c = 0; c < DP; ++c) {
-      const float xs = __int_as_float(
-          __builtin_amdgcn_readlane(__float_as_int(second ? x[KW - 1][c] : x[0][c]), owner));
-      const double kb = skb[c];
+      // (both keys of the owner lane are fetched and one is kept: selecting before the fetch would index x dynamically)
+      float xs = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x[0][c]), owner));
+      if constexpr (KW == 2) {
+        const float xs1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x[KW - 1][c]), owner));
+        xs = second ? xs1 : xs;
+      }
+      const double kb = kbar_lds[c];
       const double ks = (double)xs - kb;
       cb = fma(kb, ks, cb);
 #pragma unroll
       for (int k = 0; k < KW; ++k) dot[k] = fma((double)x[k][c], ks, dot[k]);
+      if ((c & 7) == 7) __builtin_amdgcn_sched_barrier(0);  // eight features at a time: keeps the widened values few
     }
     // history product  sum_{j<i} F_j(l) F_j(s)
     double acc[KW];
@@ -1343,6 +1358,119 @@ __global__ __launch_bounds__(kThreads) void k_gram(const H *__restrict__ F, cons
     for (int c = 0; c < CW; ++c)
       if (col0 + tx + 16 * c < dv) dst[col0 + tx + 16 * c] = acc[q][c];
     if (tx == 0 && ct == 0) dst[dv] = rs[q];
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// The same Gram pass on the fp64 matrix cores (v_mfma_f64_16x16x4_f64), for value widths of 64, 128 and 256: the
+// pass is a dense fp64 contraction (2 n r (d_v + 1) flop against one read of F and V), bound by fp64 arithmetic,
+// and the matrix pipe sustains its rate without the LDS tiles and register blocking the vector form needs.
+// Lane (k = lane / 16, i = lane % 16) supplies A[i][k] = F_row(i)(key k) and B[k][j = i] = V(key k, column); the
+// result tile holds D[4 v + lane / 16][lane % 16] in element v.  Column tile c of a lane covers value column
+// NT (lane % 16) + c, so the NT values a lane needs from a key are adjacent in memory (one or two 16-byte loads) and
+// its NT results of a row are adjacent in the output.  A wavefront owns 16 RT rows of F and all 16 NT columns; a
+// workgroup 64 RT rows; the row sums (w = F 1) are added on the vector ALU from the same A operands.
+// grid (nchunk, ceil(r / (64 RT)), P); same partial-sum layout as k_gram.
+// --------------------------------------------------------------------------------------------
+typedef double dbl4 __attribute__((ext_vector_type(4)));
+
+template <typename T, int NT>
+struct ValueRun {                                            // NT adjacent values of one row, in storage form
+  static constexpr int WORDS = NT * (int)sizeof(T) / 4;
+  uint32_t w[WORDS];
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int e = 0; e < WORDS; ++e) w[e] = 0u;
+  }
+  __device__ __forceinline__ void load(const T *__restrict__ src) {
+    if constexpr (WORDS == 2) {
+      const uint2 v = *reinterpret_cast<const uint2 *>(src);
+      w[0] = v.x; w[1] = v.y;
+    } else {
+#pragma unroll
+      for (int q = 0; q < WORDS / 4; ++q) {
+        const uint4 v = reinterpret_cast<const uint4 *>(src)[q];
+        w[4 * q] = v.x; w[4 * q + 1] = v.y; w[4 * q + 2] = v.z; w[4 * q + 3] = v.w;
+      }
+    }
+  }
+  __device__ __forceinline__ double get(int e) const {
+    if constexpr (sizeof(T) == 4) return (double)__uint_as_float(w[e]);
+    else return (double)__uint_as_float((e & 1) ? (w[e / 2] & 0xffff0000u) : (w[e / 2] << 16));
+  }
+};
+
+template <typename T, int NT, typename H>
+__global__ __launch_bounds__(kThreads) void k_gram_mfma(const H *__restrict__ F, const T *__restrict__ V, int64_t n,
+                                                        int nblk, int slab, int r, int slabs_per_chunk, int nchunk,
+                                                        double *__restrict__ gpart) {
+  constexpr int RT = NT <= 8 ? 2 : 1;                        // row tiles per wavefront: 16 RT x NT x 8 accumulator registers
+  constexpr int U = 4;                                       // MFMA depth steps (4 keys each) in flight
+  constexpr int dv = 16 * NT;
+  const int t = threadIdx.x, lane = t & (kWave - 1), wv = t / kWave;
+  const int ch = blockIdx.x, pr = blockIdx.z;
+  const int li = lane & 15, lk = lane >> 4;
+  const int row_base = blockIdx.y * (64 * RT) + wv * (16 * RT);
+  dbl4 acc[RT][NT];
+  double rs[RT];
+  bool rok[RT];
+  size_t roff[RT];
+#pragma unroll
+  for (int q = 0; q < RT; ++q) {
+    const int row = row_base + 16 * q + li;
+    rok[q] = row < r;
+    roff[q] = (size_t)(rok[q] ? row : 0) * slab;
+    rs[q] = 0.0;
+#pragma unroll
+    for (int c = 0; c < NT; ++c) acc[q][c] = dbl4{0.0, 0.0, 0.0, 0.0};
+  }
+  const int sb0 = ch * slabs_per_chunk;
+  const int sb1 = sb0 + slabs_per_chunk < nblk ? sb0 + slabs_per_chunk : nblk;
+  for (int sb = sb0; sb < sb1; ++sb) {
+    const int64_t l0 = (int64_t)sb * slab;
+    if (l0 >= n) break;
+    const int kend = n - l0 < slab ? (int)(n - l0) : slab;
+    const H *Fs = F + ((size_t)pr * nblk + sb) * r * slab;
+    const T *Vs = V + ((size_t)pr * n + l0) * dv + NT * li;
+    for (int k0 = 0; k0 < kend; k0 += 4 * U) {
+      double a[U][RT];
+      ValueRun<T, NT> b[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int key = k0 + 4 * u + lk;
+        const bool kok = key < kend;
+#pragma unroll
+        for (int q = 0; q < RT; ++q) a[u][q] = (kok && rok[q]) ? (double)Fs[roff[q] + key] : 0.0;
+        if (kok) b[u].load(Vs + (size_t)key * dv);
+        else b[u].zero();
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int q = 0; q < RT; ++q) rs[q] += a[u][q];
+#pragma unroll
+        for (int c = 0; c < NT; ++c) {
+          const double bv = b[u].get(c);
+#pragma unroll
+          for (int q = 0; q < RT; ++q) acc[q][c] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u][q], bv, acc[q][c], 0, 0, 0);
+        }
+      }
+    }
+  }
+  constexpr int dv1 = dv + 1;
+  double *part = gpart + ((size_t)pr * nchunk + ch) * r * dv1;
+#pragma unroll
+  for (int q = 0; q < RT; ++q) {
+    rs[q] += __shfl_xor(rs[q], 16, kWave);
+    rs[q] += __shfl_xor(rs[q], 32, kWave);
+    if (lk == 0 && rok[q]) part[(size_t)(row_base + 16 * q + li) * dv1 + dv] = rs[q];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int arow = row_base + 16 * q + 4 * v + lk;
+      if (arow >= r) continue;
+#pragma unroll
+      for (int c = 0; c < NT; ++c) part[(size_t)arow * dv1 + NT * li + c] = acc[q][c][v];
+    }
   }
 }
 
@@ -1832,6 +1960,16 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     else
       hipLaunchKernelGGL((k_gram_small<T, 16, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
                          tpr, pl.slabs_per_chunk, pl.nchunk, gpart);
+  } else if (s.dv == 64 || s.dv == 128) {
+    if (s.dv == 64)
+      hipLaunchKernelGGL((k_gram_mfma<T, 4, H>), dim3(pl.nchunk, rtiles, P), dim3(kThreads), 0, st, F, V, s.n, pl.nblk,
+                         pl.slab, s.r, pl.slabs_per_chunk, pl.nchunk, gpart);
+    else
+      hipLaunchKernelGGL((k_gram_mfma<T, 8, H>), dim3(pl.nchunk, rtiles, P), dim3(kThreads), 0, st, F, V, s.n, pl.nblk,
+                         pl.slab, s.r, pl.slabs_per_chunk, pl.nchunk, gpart);
+  } else if (s.dv == 256) {
+    hipLaunchKernelGGL((k_gram_mfma<T, 16, H>), dim3(pl.nchunk, (s.r + 63) / 64, P), dim3(kThreads), 0, st, F, V, s.n,
+                       pl.nblk, pl.slab, s.r, pl.slabs_per_chunk, pl.nchunk, gpart);
   } else if (s.dv <= 64) {
     hipLaunchKernelGGL((k_gram<T, 4, H>), dim3(pl.nchunk, rtiles, P), dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab,
                        s.r, s.dv, pl.slabs_per_chunk, pl.nchunk, 1, gpart);
