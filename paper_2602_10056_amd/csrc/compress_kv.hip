@@ -1401,11 +1401,11 @@ struct ValueRun {                                            // NT adjacent valu
 };
 
 template <typename T, int NT, typename H>
-__global__ __launch_bounds__(kThreads) void k_gram_mfma(const H *__restrict__ F, const T *__restrict__ V, int64_t n,
+__global__ __launch_bounds__(kThreads, 2) void k_gram_mfma(const H *__restrict__ F, const T *__restrict__ V, int64_t n,
                                                         int nblk, int slab, int r, int slabs_per_chunk, int nchunk,
                                                         double *__restrict__ gpart) {
   constexpr int RT = NT <= 8 ? 2 : 1;                        // row tiles per wavefront: 16 RT x NT x 8 accumulator registers
-  constexpr int U = 4;                                       // MFMA depth steps (4 keys each) in flight
+  constexpr int U = (sizeof(T) == 4 && NT >= 8) ? 2 : 4;     // MFMA depth steps (4 keys each) per fetch, two fetches in flight
   constexpr int dv = 16 * NT;
   const int t = threadIdx.x, lane = t & (kWave - 1), wv = t / kWave;
   const int ch = blockIdx.x, pr = blockIdx.z;
@@ -1424,37 +1424,49 @@ __global__ __launch_bounds__(kThreads) void k_gram_mfma(const H *__restrict__ F,
 #pragma unroll
     for (int c = 0; c < NT; ++c) acc[q][c] = dbl4{0.0, 0.0, 0.0, 0.0};
   }
+  // The chunk's keys [lbeg, lend) are walked in groups of 4 U (8 or 16; slabs are multiples of 16 keys, so a group lies in
+  // one slab); the operands of the next group are fetched before the products of the current one are issued.
   const int sb0 = ch * slabs_per_chunk;
   const int sb1 = sb0 + slabs_per_chunk < nblk ? sb0 + slabs_per_chunk : nblk;
-  for (int sb = sb0; sb < sb1; ++sb) {
-    const int64_t l0 = (int64_t)sb * slab;
-    if (l0 >= n) break;
-    const int kend = n - l0 < slab ? (int)(n - l0) : slab;
-    const H *Fs = F + ((size_t)pr * nblk + sb) * r * slab;
-    const T *Vs = V + ((size_t)pr * n + l0) * dv + NT * li;
-    for (int k0 = 0; k0 < kend; k0 += 4 * U) {
-      double a[U][RT];
-      ValueRun<T, NT> b[U];
+  const int64_t lbeg = (int64_t)sb0 * slab;
+  const int64_t lend = (int64_t)sb1 * slab < n ? (int64_t)sb1 * slab : n;
+  const H *Fp = F + (size_t)pr * nblk * r * slab;
+  const T *Vp = V + (size_t)pr * n * dv + NT * li;
+  auto fetch = [&](int64_t lg, double (&a)[U][RT], ValueRun<T, NT> (&b)[U]) {
+    const int64_t sb = lg / slab;                            // uniform
+    const H *Fs = Fp + (size_t)sb * r * slab + (lg - sb * slab);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int key = k0 + 4 * u + lk;
-        const bool kok = key < kend;
+    for (int u = 0; u < U; ++u) {
+      const int64_t l = lg + 4 * u + lk;
+      const bool kok = l < lend;
 #pragma unroll
-        for (int q = 0; q < RT; ++q) a[u][q] = (kok && rok[q]) ? (double)Fs[roff[q] + key] : 0.0;
-        if (kok) b[u].load(Vs + (size_t)key * dv);
-        else b[u].zero();
+      for (int q = 0; q < RT; ++q) a[u][q] = (kok && rok[q]) ? (double)Fs[roff[q] + 4 * u + lk] : 0.0;
+      if (kok) b[u].load(Vp + (size_t)l * dv);
+      else b[u].zero();
+    }
+  };
+  auto multiply = [&](const double (&a)[U][RT], const ValueRun<T, NT> (&b)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int q = 0; q < RT; ++q) rs[q] += a[u][q];
+#pragma unroll
+      for (int c = 0; c < NT; ++c) {
+        const double bv = b[u].get(c);
+#pragma unroll
+        for (int q = 0; q < RT; ++q) acc[q][c] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u][q], bv, acc[q][c], 0, 0, 0);
       }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int q = 0; q < RT; ++q) rs[q] += a[u][q];
-#pragma unroll
-        for (int c = 0; c < NT; ++c) {
-          const double bv = b[u].get(c);
-#pragma unroll
-          for (int q = 0; q < RT; ++q) acc[q][c] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u][q], bv, acc[q][c], 0, 0, 0);
-        }
-      }
+    }
+  };
+  if (lbeg < lend) {
+    double a0[U][RT], a1[U][RT];
+    ValueRun<T, NT> b0[U], b1[U];
+    fetch(lbeg, a0, b0);
+    for (int64_t lg = lbeg; lg < lend; lg += 8 * U) {
+      fetch(lg + 4 * U, a1, b1);                             // past lend: zeros, nothing read
+      multiply(a0, b0);
+      fetch(lg + 8 * U, a0, b0);
+      if (lg + 4 * U < lend) multiply(a1, b1);
     }
   }
   constexpr int dv1 = dv + 1;
@@ -1651,8 +1663,12 @@ __global__ __launch_bounds__(kSolveCols * 32) void k_solve(const double *__restr
     if (grp < ncol) {                                  // 1. solve inside the panel: x_a = g_a / L_aa, g_b -= L_ab x_a
       double gb = q < np ? gc[(size_t)grp * r + j0 + q] : 0.0;
       double xb = 0.0;
-      for (int a = np - 1; a >= 0; --a) {
-        const double xa = __shfl(gb, a, 32) * ld[a * (kPanel + 1) + a];
+      const bool upper = (t & 32) != 0;                 // this column's 32 lanes are the upper half of their wavefront
+#pragma unroll
+      for (int a = kPanel - 1; a >= 0; --a) {
+        if (a >= np) continue;                            // uniform: only the topmost panel is short
+        const double glo = lane_value(gb, a), ghi = lane_value(gb, a + 32);
+        const double xa = (upper ? ghi : glo) * ld[a * (kPanel + 1) + a];
         if (q == a) xb = xa;
         if (q < a) gb = fma(-ld[a * (kPanel + 1) + q], xa, gb);
       }
@@ -1666,6 +1682,7 @@ __global__ __launch_bounds__(kSolveCols * 32) void k_solve(const double *__restr
       double upd[kSolveCols];
 #pragma unroll
       for (int c = 0; c < kSolveCols; ++c) upd[c] = 0.0;
+#pragma unroll 8
       for (int a = 0; a < np; ++a) {
         const double lv = Lp[(size_t)(j0 + a) * r + k];
 #pragma unroll
