@@ -200,8 +200,8 @@ __global__ __launch_bounds__(kThreads) void k_pack_stats(const T *__restrict__ K
                                                          float *__restrict__ vminpart, float *__restrict__ vmaxpart) {
   constexpr int EPP = Piece<T>::N;                       // elements per 16-byte piece
   extern __shared__ __attribute__((aligned(16))) char tile[];   // tk rows of (d * sizeof(T) + 8) bytes
-  __shared__ double sks[kThreads][EPP];
-  __shared__ float smn[kThreads][EPP], smx[kThreads][EPP];
+  __shared__ double sks[kThreads / kWave][kMaxWidth];           // per wavefront and column
+  __shared__ float smn[kThreads / kWave][kMaxWidth], smx[kThreads / kWave][kMaxWidth];
   const int t = threadIdx.x, blk = blockIdx.x, pr = blockIdx.y;
   const int ppr = d / EPP, ppv = dv / EPP;               // pieces per K row / V row (powers of two <= 64)
   const int rowb = d * (int)sizeof(T) + 8;
@@ -261,23 +261,36 @@ __global__ __launch_bounds__(kThreads) void k_pack_stats(const T *__restrict__ K
     for (int e = 0; e < EPP; ++e) { mn[e] = fminf(mn[e], x[e]); mx[e] = fmaxf(mx[e], x[e]); }
   }
 
-  // ---- combine the threads that share a piece column, in row-group order ----------------------------------------
+  // ---- combine the threads that share a piece column: the lanes of a wavefront by a butterfly over the lanes that
+  // differ in the row group only (a fixed order), then the four wavefronts in turn ----------------------------------
+  const int lane = t & (kWave - 1), wv = t / kWave;
+  for (int off = ppr; off < kWave; off <<= 1)
 #pragma unroll
-  for (int e = 0; e < EPP; ++e) { sks[t][e] = ksum[e]; smn[t][e] = mn[e]; smx[t][e] = mx[e]; }
+    for (int e = 0; e < EPP; ++e) ksum[e] += __shfl_xor(ksum[e], off, kWave);
+  for (int off = ppv; off < kWave; off <<= 1)
+#pragma unroll
+    for (int e = 0; e < EPP; ++e) {
+      mn[e] = fminf(mn[e], __shfl_xor(mn[e], off, kWave));
+      mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], off, kWave));
+    }
+  if (lane < ppr)
+#pragma unroll
+    for (int e = 0; e < EPP; ++e) sks[wv][lane * EPP + e] = ksum[e];
+  if (lane < ppv)
+#pragma unroll
+    for (int e = 0; e < EPP; ++e) { smn[wv][lane * EPP + e] = mn[e]; smx[wv][lane * EPP + e] = mx[e]; }
   __syncthreads();
   const size_t slot = (size_t)pr * nb + blk;
   if (t < d) {
-    const int j = t / EPP, e = t % EPP;
     double acc = 0.0;
-    for (int q = 0; q < rpp; ++q) acc += sks[q * ppr + j][e];
+    for (int q = 0; q < kThreads / kWave; ++q) acc += sks[q][t];
     mpart[slot * d + t] = acc;
   }
   if (t < dv) {
-    const int j = t / EPP, e = t % EPP;
     float lo = INFINITY, hi = -INFINITY;
-    for (int q = 0; q < rpv; ++q) {
-      lo = fminf(lo, smn[q * ppv + j][e]);
-      hi = fmaxf(hi, smx[q * ppv + j][e]);
+    for (int q = 0; q < kThreads / kWave; ++q) {
+      lo = fminf(lo, smn[q][t]);
+      hi = fmaxf(hi, smx[q][t]);
     }
     vminpart[slot * dv + t] = lo;
     vmaxpart[slot * dv + t] = hi;
