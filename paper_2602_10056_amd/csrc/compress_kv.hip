@@ -1718,12 +1718,13 @@ __global__ __launch_bounds__(kSolveCols * 32) void k_solve(const double *__restr
 // The same solve for small ranks (r <= kSolveSmall, i.e. binned problems with a handful of pivots each, of which there
 // are many): one thread per (problem, right-hand-side column) substitutes backwards through its own copy of the
 // column, in the order k_solve uses inside a panel (x_a = g_a * (1 / L_aa), then g_b -= L_ab x_a for b < a), so the
-// two kernels give the same bits.  grid ceil(P * (dv + 1) / 256).
+// two kernels give the same bits.  The right-hand side is summed here from the Gram pass's partial sums, in chunk order
+// as k_gram_reduce does (adjacent threads read adjacent columns), which saves that launch.  grid ceil(P * (dv + 1) / 256).
 constexpr int kSolveSmall = 16;
 
-__global__ __launch_bounds__(kThreads) void k_solve_small(const double *__restrict__ L, const double *__restrict__ Gt,
-                                                          const int32_t *__restrict__ r_eff, int P, int r, int dv,
-                                                          float *__restrict__ v_s, float *__restrict__ w) {
+__global__ __launch_bounds__(kThreads) void k_solve_small(const double *__restrict__ L, const double *__restrict__ gpart,
+                                                          int nchunk, const int32_t *__restrict__ r_eff, int P, int r,
+                                                          int dv, float *__restrict__ v_s, float *__restrict__ w) {
   const int dv1 = dv + 1;
   const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (gid >= (int64_t)P * dv1) return;
@@ -1732,7 +1733,11 @@ __global__ __launch_bounds__(kThreads) void k_solve_small(const double *__restri
   const double *Lp = L + (size_t)pr * r * r;
   double g[kSolveSmall];
 #pragma unroll
-  for (int j = 0; j < kSolveSmall; ++j) g[j] = j < re ? Gt[((size_t)pr * dv1 + c) * r + j] : 0.0;
+  for (int j = 0; j < kSolveSmall; ++j) {
+    g[j] = 0.0;
+    if (j < re)
+      for (int ch = 0; ch < nchunk; ++ch) g[j] += gpart[(((size_t)pr * nchunk + ch) * r + j) * dv1 + c];
+  }
 #pragma unroll
   for (int a = kSolveSmall - 1; a >= 0; --a) {
     if (a < re) {
@@ -2010,13 +2015,14 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   }
   LAUNCH_CHECK();
   const int dv1 = s.dv + 1;
-  hipLaunchKernelGGL(k_gram_reduce, dim3((s.r * dv1 + kThreads - 1) / kThreads, P), dim3(kThreads), 0, st, gpart, s.r,
+  if (s.r > kSolveSmall)
+    hipLaunchKernelGGL(k_gram_reduce, dim3((s.r * dv1 + kThreads - 1) / kThreads, P), dim3(kThreads), 0, st, gpart, s.r,
                      dv1, pl.nchunk, Gt);
   LAUNCH_CHECK();
   if (s.r <= kSolveSmall) {
     const int64_t cols = (int64_t)P * dv1;
-    hipLaunchKernelGGL(k_solve_small, dim3((unsigned)((cols + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, L, Gt,
-                       out->r_eff, P, s.r, s.dv, out->v_s, out->w);
+    hipLaunchKernelGGL(k_solve_small, dim3((unsigned)((cols + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, L, gpart,
+                       pl.nchunk, out->r_eff, P, s.r, s.dv, out->v_s, out->w);
   } else {
     const size_t solve_lds = ((size_t)kSolveCols * s.r + kPanel * (kPanel + 1) + kSolveCols * kPanel) * sizeof(double);
     if (solve_lds > 64 * 1024 &&
