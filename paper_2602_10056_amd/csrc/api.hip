@@ -78,6 +78,20 @@ Plan make_plan(const Shape &s) {
   if (want > p.nblk) want = p.nblk;
   p.slabs_per_chunk = (p.nblk + want - 1) / want;
   p.nchunk = (p.nblk + p.slabs_per_chunk - 1) / p.slabs_per_chunk;
+  p.chunk_keys = (int64_t)p.slabs_per_chunk * p.slab;
+  p.gram_cols = p.nblk == 1 && s.r <= 16 && s.n <= 256;
+  if (p.gram_cols) {
+    // Small bins of small rank (k_gram_cols: a thread per value column, no sums across threads): the bin is cut into
+    // pieces of at least 16 keys, so that a few problems still spread over the device and no thread walks through
+    // many keys; a workgroup takes 256 / (columns rounded up to a power of two >= 64) consecutive pieces.
+    int tp = 64;
+    while (tp < s.dv) tp <<= 1;
+    const int pieces = want * (kThreads / tp);
+    int64_t ck = (s.n + pieces - 1) / pieces;
+    ck = (ck + 15) / 16 * 16;
+    p.chunk_keys = ck;
+    p.nchunk = (int)((s.n + ck - 1) / ck);
+  }
 
   const size_t es = s.dtype == WILDCAT_BF16 ? 2 : 4;
   const size_t P = (size_t)s.P, n = (size_t)p.npad, r = (size_t)s.r, dv1 = (size_t)s.dv + 1;

@@ -51,8 +51,10 @@ struct Plan {
   int64_t npad;     // nblk * slab
   int dpad;         // d rounded up to a multiple of kChunk
   int nb0;          // row blocks of the column-statistics pass
-  int nchunk;       // n-chunks of the Gram pass (each a whole number of slabs)
+  int nchunk;       // n-chunks of the Gram pass
   int slabs_per_chunk;
+  int64_t chunk_keys;  // keys per chunk: slabs_per_chunk * slab, or a piece of the bin (gram_cols)
+  bool gram_cols;      // small bins of small rank: the Gram pass runs as k_gram_cols
   size_t off_kbar, off_kp, off_d0, off_p, off_bsum, off_scal, off_F, off_L, off_gpart, off_g,
       off_mpart, off_vminpart, off_vmaxpart, off_u, off_sync;
   bool persistent;  // try the single-launch selection loop (all slabs of all problems resident at once)

@@ -1542,7 +1542,7 @@ template <> struct Value4<bf16_t> {
 template <typename T, int R, typename H>
 __global__ __launch_bounds__(kThreads) void k_gram_small(const H *__restrict__ F, const T *__restrict__ V,
                                                          int64_t n, int nblk, int slab, int r, int dv, int tpr,
-                                                         int slabs_per_chunk, int nchunk,
+                                                         int64_t chunk_keys, int nchunk,
                                                          double *__restrict__ gpart) {
   __shared__ double red[kThreads / kWave][kWave][5];
   const int t = threadIdx.x, ch = blockIdx.x, pr = blockIdx.z;
@@ -1558,15 +1558,17 @@ __global__ __launch_bounds__(kThreads) void k_gram_small(const H *__restrict__ F
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[j][c] = 0.0;
   }
-  const int sb0 = ch * slabs_per_chunk;
-  const int sb1 = sb0 + slabs_per_chunk < nblk ? sb0 + slabs_per_chunk : nblk;
+  // The chunk's keys [lbeg, lend): whole slabs, or a piece of the only slab.
+  const int64_t lbeg = (int64_t)ch * chunk_keys;
+  const int64_t lend = lbeg + chunk_keys < n ? lbeg + chunk_keys : n;
   const T *Vp = V + (size_t)pr * n * dv;
-  for (int sb = sb0; sb < sb1; ++sb) {
+  for (int sb = (int)(lbeg / slab); (int64_t)sb * slab < lend; ++sb) {
     const H *Fslab = F + ((size_t)pr * nblk + sb) * r * slab;
     constexpr int U = R <= 4 ? 4 : (R <= 8 ? 2 : 1);             // keys in flight per thread
-    const int64_t left = n - (int64_t)sb * slab;                  // keys of this slab that exist (F is zero beyond them)
-    const int kend = left < slab ? (left > 0 ? (int)left : 0) : slab;
-    for (int k0 = 0; k0 < kend; k0 += U * kgs) {
+    const int64_t s0 = (int64_t)sb * slab;
+    const int kbeg = lbeg > s0 ? (int)(lbeg - s0) : 0;            // F is zero beyond n, V does not exist there
+    const int kend = lend - s0 < slab ? (int)(lend - s0) : slab;
+    for (int k0 = kbeg; k0 < kend; k0 += U * kgs) {
       Value4<T> raw[U];
       double f[U][R];
       bool ok[U];
@@ -1574,7 +1576,7 @@ __global__ __launch_bounds__(kThreads) void k_gram_small(const H *__restrict__ F
       for (int q = 0; q < U; ++q) {
         const int l_loc = k0 + q * kgs + kg;
         const int64_t l = (int64_t)sb * slab + l_loc;
-        ok[q] = active && l_loc < slab && l < n;                  // F is zero beyond n, V does not exist there
+        ok[q] = active && l_loc < kend;
         const int l_safe = ok[q] ? l_loc : 0;
         raw[q].load(Vp + (size_t)(ok[q] ? l : 0) * dv, active ? col : 0, dv, vec);
 #pragma unroll
@@ -1617,6 +1619,66 @@ __global__ __launch_bounds__(kThreads) void k_gram_small(const H *__restrict__ F
       for (int c = 0; c < 4; ++c)
         if (col + c < dv) dst[col + c] = tot[c];
       if (lane == 0) dst[dv] = tot[4];
+    }
+  }
+}
+
+// Gram pass for small bins of small rank (one slab, at most 256 keys, r <= R <= 16: the image-model layer shapes and
+// the many-bin settings).  There a problem is a few dozen keys, and what k_gram_small spends on adding up the partial
+// sums of its threads exceeds the work.  Here a thread owns one value column of one piece of the bin's keys and all R
+// rows of F: its R sums need no other thread; the row sums (w = F 1) are formed by every thread and written by the
+// first.  tp threads (a power of two >= 64, >= d_v) cover a value row; a workgroup takes 256 / tp consecutive pieces,
+// i.e. one run of keys, whose part of F it first copies to LDS with one coalesced pass: every lane of a wavefront
+// needs the same entry of F, which LDS hands out as a broadcast, while as a per-lane load of one address it costs the
+// memory pipeline some fifty clocks (and as a scalar load a round trip per handful of entries).
+// grid (ceil(nchunk / (256 / tp)), 1, P); dynamic LDS R * (256 / tp) * chunk_keys doubles; same partial-sum layout as
+// k_gram (one partial per piece).
+template <typename T, int R, typename H>
+__global__ __launch_bounds__(kThreads) void k_gram_cols(const H *__restrict__ F, const T *__restrict__ V, int64_t n,
+                                                        int slab, int r, int dv, int tp, int chunk_keys, int nchunk,
+                                                        double *__restrict__ gpart) {
+  extern __shared__ double fs[];                              // [R][run]: rows of F over this workgroup's run of keys
+  const int t = threadIdx.x, pr = blockIdx.z;
+  const int sub = kThreads / tp, run = sub * chunk_keys;
+  const int64_t run0 = (int64_t)blockIdx.x * run;
+  const H *Fp = F + (size_t)pr * r * slab;                   // one slab per problem
+  for (int e = t; e < R * run; e += kThreads) {
+    const int j = e / run, k = e % run;
+    fs[e] = (j < r && run0 + k < n) ? (double)Fp[(size_t)j * slab + run0 + k] : 0.0;
+  }
+  __syncthreads();
+  const int c = t % tp, q = t / tp, ch = blockIdx.x * sub + q;
+  if (ch >= nchunk) return;
+  const bool active = c < dv;
+  const int64_t lbeg = run0 + (int64_t)q * chunk_keys;
+  const int kcount = lbeg + chunk_keys < n ? chunk_keys : (int)(n - lbeg);      // >= 1: ch < nchunk
+  const T *Vp = V + ((size_t)pr * n + lbeg) * dv + (active ? c : 0);
+  const double *fq = fs + q * chunk_keys;
+  double acc[R], rs[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) acc[j] = rs[j] = 0.0;
+  for (int k0 = 0; k0 < kcount; k0 += 8) {                    // eight keys per round; chunk_keys is a multiple of 16
+    float v[8];                                               // and F is zero in LDS past the end of the bin
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = to_float(Vp[(size_t)(k0 + u < kcount ? k0 + u : kcount - 1) * dv]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const double vd = (double)v[u];
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        const double f = fq[j * run + k0 + u];
+        acc[j] = fma(f, vd, acc[j]);
+        rs[j] += f;
+      }
+    }
+  }
+  const int dv1 = dv + 1;
+  double *dst = gpart + ((size_t)pr * nchunk + ch) * r * dv1;
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    if (j < r) {
+      if (active) dst[(size_t)j * dv1 + c] = acc[j];          // (an inactive thread read column 0: harmless, not stored)
+      if (c == 0) dst[(size_t)j * dv1 + dv] = rs[j];
     }
   }
 }
@@ -1733,10 +1795,12 @@ __global__ __launch_bounds__(kThreads) void k_solve_small(const double *__restri
   const double *Lp = L + (size_t)pr * r * r;
   double g[kSolveSmall];
 #pragma unroll
-  for (int j = 0; j < kSolveSmall; ++j) {
-    g[j] = 0.0;
-    if (j < re)
-      for (int ch = 0; ch < nchunk; ++ch) g[j] += gpart[(((size_t)pr * nchunk + ch) * r + j) * dv1 + c];
+  for (int j = 0; j < kSolveSmall; ++j) g[j] = 0.0;
+  for (int ch = 0; ch < nchunk; ++ch) {                       // chunk order per entry; the rows' loads are independent
+    const double *gp = gpart + ((size_t)pr * nchunk + ch) * r * dv1 + c;
+#pragma unroll
+    for (int j = 0; j < kSolveSmall; ++j)
+      if (j < re) g[j] += gp[(size_t)j * dv1];
   }
 #pragma unroll
   for (int a = kSolveSmall - 1; a >= 0; --a) {
@@ -1982,19 +2046,34 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   if (o->ev_loop_end && hipEventRecord((hipEvent_t)o->ev_loop_end, st) != hipSuccess) return WILDCAT_EHIP;
 
   const int rtiles = (s.r + kGramRows - 1) / kGramRows;
-  if (s.r <= 16) {
+  if (pl.gram_cols) {
+    int tp = 64;
+    while (tp < s.dv) tp <<= 1;
+    const int sub = kThreads / tp;
+    const dim3 grid((pl.nchunk + sub - 1) / sub, 1, P);
+    const size_t run = (size_t)sub * pl.chunk_keys;            // <= 320 keys (n <= 256): at most 41 KB of LDS
+    if (s.r <= 4)
+      hipLaunchKernelGGL((k_gram_cols<T, 4, H>), grid, dim3(kThreads), (size_t)4 * run * sizeof(double), st, F, V, s.n,
+                         pl.slab, s.r, s.dv, tp, (int)pl.chunk_keys, pl.nchunk, gpart);
+    else if (s.r <= 8)
+      hipLaunchKernelGGL((k_gram_cols<T, 8, H>), grid, dim3(kThreads), (size_t)8 * run * sizeof(double), st, F, V, s.n,
+                         pl.slab, s.r, s.dv, tp, (int)pl.chunk_keys, pl.nchunk, gpart);
+    else
+      hipLaunchKernelGGL((k_gram_cols<T, 16, H>), grid, dim3(kThreads), (size_t)16 * run * sizeof(double), st, F, V, s.n,
+                         pl.slab, s.r, s.dv, tp, (int)pl.chunk_keys, pl.nchunk, gpart);
+  } else if (s.r <= 16) {
     int tpr = 1;
     while (tpr * 4 < s.dv) tpr <<= 1;                        // threads per value row (<= 64: dv <= kMaxWidth)
     const dim3 grid(pl.nchunk, 1, P);
     if (s.r <= 4)
       hipLaunchKernelGGL((k_gram_small<T, 4, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
-                         pl.slabs_per_chunk, pl.nchunk, gpart);
+                         pl.chunk_keys, pl.nchunk, gpart);
     else if (s.r <= 8)
       hipLaunchKernelGGL((k_gram_small<T, 8, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
-                         pl.slabs_per_chunk, pl.nchunk, gpart);
+                         pl.chunk_keys, pl.nchunk, gpart);
     else
       hipLaunchKernelGGL((k_gram_small<T, 16, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv,
-                         tpr, pl.slabs_per_chunk, pl.nchunk, gpart);
+                         tpr, pl.chunk_keys, pl.nchunk, gpart);
   } else if (s.dv == 64 || s.dv == 128) {
     if (s.dv == 64)
       hipLaunchKernelGGL((k_gram_mfma<T, 4, H>), dim3(pl.nchunk, rtiles, P), dim3(kThreads), 0, st, F, V, s.n, pl.nblk,
