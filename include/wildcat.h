@@ -188,9 +188,13 @@ int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *out, int64_
                      int32_t d, int32_t r, const wildcat_opts *opts);
 
 /* HOST (queries the current device).  1 if wildcat_compress_kv will run the RPNys selection loop
- * (Alg. 1) of this shape as one persistent launch -- all key slabs of all problems (bins) resident
- * on the device at once, synchronising through memory -- and 0 if it will issue one launch per
- * step; negative wildcat_status for invalid arguments.  For profiling and reporting only. */
+ * (Alg. 1) of this shape as one launch for all steps -- either all key slabs of all problems (bins)
+ * resident on the device at once, the workgroups of a problem synchronising through memory, or,
+ * for problems of a single slab, one workgroup (one wavefront, if the problems are tiny and many)
+ * alone with its problem -- and 0 if it will issue one launch per step; negative wildcat_status for
+ * invalid arguments.  For profiling and reporting only.  The environment variable
+ * WILDCAT_RPNYS_LOOP overrides the choice: "steps" forces one launch per step, "wave" the
+ * wavefront-per-problem form wherever the shape allows it (switches for tuning and testing). */
 int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts);
 
 /* Rewrites cs->v_t and cs->v_scale from cs->v_s (device buffers, see wildcat_coreset) for a coreset
