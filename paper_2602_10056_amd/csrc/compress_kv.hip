@@ -648,6 +648,27 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   const int l_loc = t * KPT;
   const int64_t l_glob = (int64_t)b * SLAB + l_loc;
 
+  // ---- 0. (single-launch loop) the first history rows of section 5 are requested now: which rows a step reads does
+  // not depend on the pivot, only their weights g do, so these loads fly while the pivot is searched and a workgroup
+  // keeps its share of the memory system busy during the part of the step that moves no data. ------------------------
+  // Rows in flight per thread: eight 16-byte loads with two keys per thread, twelve narrower ones with one key
+  // (those workgroups are small and few, and eight 8-byte loads each would not keep the memory system busy).
+  constexpr int U = KPT == 1 ? 12 : 8;
+  constexpr bool EARLY = POLL && !SOLO;
+  HistVec<KPT, H> early[EARLY ? U : 1];
+  bool have_early = false;
+  if constexpr (EARLY) {
+    const int nc0 = i < hcn ? i : hcn;
+    if (i - nc0 >= U) {
+      const bool down0 = (i & 1) != 0;
+      const ptrdiff_t fstep0 = down0 ? -(ptrdiff_t)SLAB : (ptrdiff_t)SLAB;
+      const H *fp0 = Fb + l_loc + (size_t)(down0 ? i - 1 : nc0) * SLAB;
+#pragma unroll
+      for (int q = 0; q < U; ++q) early[q].load(fp0 + q * fstep0);
+      have_early = true;
+    }
+  }
+
   // ---- 1. total mass = sum p (from the per-slab sums, in slab order) ----------------------------
   const int per = (a.nblk + kThreads - 1) / kThreads;
   const int e0 = t * per < a.nblk ? t * per : a.nblk;
@@ -794,10 +815,20 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     const int gstep = down ? -1 : 1;
     const H *fp = Fb + l_loc + (size_t)(down ? i - 1 : nc_rows) * SLAB;
     const double *gp = g + (down ? i - 1 : nc_rows);
-    // Rows in flight per thread: eight 16-byte loads with two keys per thread, twelve narrower ones with one key
-    // (those workgroups are small and few, and eight 8-byte loads each would not keep the memory system busy).
-    constexpr int U = KPT == 1 ? 12 : 8;
     int j = 0;
+    if constexpr (EARLY) {
+      if (have_early) {                                       // the batch requested in section 0
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+          const double gj = gp[q * gstep];
+#pragma unroll
+          for (int k = 0; k < KPT; ++k) acc[k] = fma((double)early[q].v[k], gj, acc[k]);
+        }
+        fp += U * fstep;
+        gp += U * gstep;
+        j = U;
+      }
+    }
     for (; j + U <= nh; j += U) {
       HistVec<KPT, H> h[U];
 #pragma unroll
