@@ -553,6 +553,22 @@ def test_wave_per_problem_loop_on_random_small_shapes(monkeypatch):
     check_against_oracle(w, out, cs)
 
 
+@pytest.mark.parametrize("ov", [
+    dict(q_heads=2, kv_heads=2, n=70 * 4, m_=33, d=48, dv_=80, r=3 * 4, bins=4, dtype="bf16"),
+    dict(q_heads=2, kv_heads=1, n=130, m_=20, d=40, dv_=72, r=9, bins=1, dtype="f32"),
+    dict(q_heads=1, kv_heads=1, n=200 * 3, m_=64, d=56, dv_=136, r=16 * 3, bins=3, dtype="f32"),
+    dict(q_heads=2, kv_heads=2, n=1000, m_=100, d=72, dv_=200, r=40, bins=1, dtype="bf16"),
+    dict(q_heads=4, kv_heads=4, n=16 * 40, m_=70, d=64, dv_=256, r=3 * 40, bins=40, dtype="bf16"),
+])
+def test_odd_widths_whole_path(ov):
+    """Key and value widths that are no power of two and not equal (no MFMA kernel covers them: the generic column
+    statistics, Gram and WtdAttn kernels run), with and without bins, both storage types, both history types."""
+    w = wl.make(3, **ov)
+    out, cs = run_gpu(w)
+    print(check_against_oracle(w, out, cs))
+    check_fast_mode_against_default(run_gpu(w, history="f32"), (out, cs))
+
+
 def test_binned_full_size_config6():
     """The binned benchmark shape at full size (n = 65536, 16 bins of 4096 keys, 4 pivots each), every head checked."""
     w = wl.make(6)
