@@ -123,6 +123,47 @@ def test_temperature_closed_form_and_bounds(beta, RQ, RK, n):
     assert max(wo.RHO0, 0.8 * rho) - 1e-6 <= rho_b <= rho + 1e-6
 
 
+def test_temperature_worked_values():
+    """eq. (kernel-temperature) on two inputs worked outside the oracle (tests/golden/temperature_worked_values.txt):
+    catches a dropped "+2", a swapped radius or a misplaced factor that a restated formula would repeat."""
+    with open(os.path.join(GOLD, "temperature_worked_values.txt")) as f:
+        rows = [[float(x) for x in line.split()] for line in f if line.strip() and not line.startswith("#")]
+    assert len(rows) == 2
+    for beta, RQ, RK, n, b0_ref, rho_ref, tau_ref in rows:
+        tau, rho, b0 = wo.temperature(beta, RQ, RK, int(n))
+        assert b0 == pytest.approx(b0_ref, rel=2e-5)
+        assert rho == pytest.approx(rho_ref, rel=2e-5)
+        assert tau == pytest.approx(tau_ref, rel=2e-5)
+
+
+def test_temperature_special_cases_and_scaling_laws():
+    """Facts eq. (kernel-temperature) fixes without evaluating it the way the oracle does."""
+    # n = 1: log n = 0, so b_0 = 2 whatever beta and the radii are, and rho = 1 / W0(1 / rho_0).
+    tau, rho, b0 = wo.temperature(0.37, 2.5, 0.75, 1)
+    assert b0 == 2.0
+    assert rho * scipy.special.lambertw(1.0 / wo.RHO0).real == pytest.approx(1.0, rel=1e-12)
+    # W0(e) = 1: inputs with b_0 = 2 e rho_0 give rho = e rho_0 (= rho_0 exp(1)) and tau^2 = e rho_0 R_K / R_Q.
+    RQ, RK, n = 3.0, 0.5, 4096
+    beta = math.log(n) / ((2.0 * math.e * wo.RHO0 - 2.0) * RQ * RK)
+    tau, rho, b0 = wo.temperature(beta, RQ, RK, n)
+    assert rho == pytest.approx(math.e * wo.RHO0, rel=1e-12)
+    assert tau * tau == pytest.approx(math.e * wo.RHO0 * RK / RQ, rel=1e-12)
+    # b_0 and rho depend on the radii through the product R_Q R_K only; tau carries the ratio: moving a factor c
+    # from the keys to the queries (R_Q c, R_K / c) divides tau by c -- the asymmetric roles of Sec. 2.4.  A
+    # temperature with the radii swapped would multiply by c instead.
+    t1, r1, b1 = wo.temperature(0.2, 4.0, 6.0, 500)
+    t2, r2, b2 = wo.temperature(0.2, 4.0 * 3.0, 6.0 / 3.0, 500)
+    assert b2 == pytest.approx(b1, rel=1e-14) and r2 == pytest.approx(r1, rel=1e-13)
+    assert t2 == pytest.approx(t1 / 3.0, rel=1e-13)
+    # rho >= rho_0 always (Corollary "Bounds on optimal rho"), with equality approached as log n / (beta R_Q R_K) -> 0
+    # only up to the "+2": at b_0 = 2 the value is 1 / W0(1 / rho_0) > rho_0.
+    assert wo.temperature(1.0, 50.0, 50.0, 2)[1] >= wo.RHO0
+    # rescaled radii: the product of the rescaled radii tau R_Q and R_K / tau is unchanged, their ratio is rho
+    tau, rho, _ = wo.temperature(0.11, 7.0, 2.0, 10000)
+    assert (tau * 7.0) * (2.0 / tau) == pytest.approx(14.0, rel=1e-14)
+    assert (tau * 7.0) / (2.0 / tau) == pytest.approx(rho, rel=1e-12)
+
+
 def test_temperature_rescaling_leaves_attention_matrix_unchanged():
     """(Q, K) -> (tau Q, K / tau) leaves A, hence eq. (1), unchanged (Sec. 2.4)."""
     rng = np.random.default_rng(3)
