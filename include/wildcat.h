@@ -22,16 +22,33 @@
  *     head h attends to kv head h / (q_heads / kv_heads).
  *   - Unless marked HOST, every pointer is a DEVICE pointer on the current HIP
  *     device.  The caller owns every buffer, including the workspace; the
- *     library allocates and frees nothing and keeps no state between calls.
+ *     library allocates and frees nothing, reads no environment variable and
+ *     keeps no state between calls: every decision is a function of the
+ *     arguments and of the current device's attributes, queried anew.
  *   - All work is enqueued on opts->stream (NULL = the null stream).  No entry
  *     point synchronises with the host; results are valid once the stream has
  *     reached the end of the enqueued work.
  *   - Every function returning int returns WILDCAT_OK (0) or a negative
  *     wildcat_status.  Arguments are validated on the host before anything is
- *     launched; on error nothing has been enqueued.  No exception crosses the
- *     boundary.  Non-finite inputs give unspecified (but memory-safe) results.
+ *     launched: WILDCAT_EINVAL, WILDCAT_EWORKSPACE and WILDCAT_EUNSUPPORTED mean
+ *     that nothing has been enqueued.  WILDCAT_EHIP (a launch or runtime call
+ *     failed) may leave the kernels launched before the failure enqueued; the
+ *     outputs are then unspecified.  No exception crosses the boundary.
+ *     Non-finite inputs give unspecified (but memory-safe) results.
  *   - Calls that share a workspace or output buffers must be ordered by the
  *     caller (same stream, or events).
+ *   - Sharing the device.  When wildcat_rpnys_single_launch() reports 1 for a
+ *     shape with more than one slab of keys per problem, the selection loop of
+ *     wildcat_compress_kv runs as launches whose workgroups wait for one
+ *     another and therefore must all be resident at once.  The grid is sized
+ *     for an otherwise idle device: such a call must not overlap other GPU
+ *     work on the same device (another stream's kernels, a second
+ *     wildcat_compress_kv), or its workgroups may hold part of the device while
+ *     waiting for workgroups that cannot start.  The waits are bounded
+ *     (opts->wait_limit): they then give up and the call reports r_eff = -1
+ *     instead of hanging, but only after seconds.  A caller who shares the
+ *     device sets opts->loop_driver = WILDCAT_LOOP_STEPS, which has no such
+ *     requirement.  Every other kernel of the library may overlap anything.
  *   - The library depends on the HIP runtime (libamdhip64) and must use the
  *     same copy of it as the code that allocated the buffers and created the
  *     stream: a host program that ships its own runtime loads that first and
@@ -58,6 +75,17 @@ typedef enum { WILDCAT_F32 = 0, WILDCAT_BF16 = 1 } wildcat_dtype;
  * pivots are still drawn from (that) residual by the same inverse-CDF rule, yet at large n some
  * differ from the float64 reference's.  Sums and the residual diagonal itself stay float64. */
 typedef enum { WILDCAT_HISTORY_F64 = 0, WILDCAT_HISTORY_F32 = 1 } wildcat_history;
+
+/* How wildcat_compress_kv launches the selection loop (Alg. 1).
+ * WILDCAT_LOOP_AUTO: all steps in one launch per group of problems wherever the workgroups of a group can be
+ *   resident on the device at once (see "Sharing the device" above), else one launch per step.
+ * WILDCAT_LOOP_STEPS: always one launch per step; safe on a shared device, slower (the keys are re-read every
+ *   step and every step pays a launch).
+ * WILDCAT_LOOP_WAVE: like AUTO, but problems small enough for the wavefront-per-problem form (at most 128 keys --
+ *   64 at d = 128 -- and 16 pivots per bin) take it whatever their number (AUTO takes it only when there are many);
+ *   a tuning and testing switch.
+ * All three draw the same pivots; results differ in the rounding of float64 sums only. */
+typedef enum { WILDCAT_LOOP_AUTO = 0, WILDCAT_LOOP_STEPS = 1, WILDCAT_LOOP_WAVE = 2 } wildcat_loop;
 
 typedef enum {
   WILDCAT_OK = 0,
@@ -98,13 +126,19 @@ typedef struct {
                      /* 1 -> the full length n (Alg. 2 as printed)                     */
   int32_t history;   /* wildcat_history: precision in which the selection loop keeps   */
                      /* its history (the partial Cholesky rows it re-reads every step) */
-  int32_t reserved1;
+  int32_t loop_driver; /* wildcat_loop: launch form of the selection loop                */
   void *stream;      /* hipStream_t                                                 */
   void *ev_loop_begin; /* optional hipEvent_t pair that wildcat_compress_kv records  */
   void *ev_loop_end; /* on the stream right before the first and right after the    */
                      /* last launch of the RPNys selection loop (for profiling)     */
   void *workspace;   /* device scratch, 256-byte aligned, of at least               */
   size_t workspace_bytes; /* wildcat_workspace_bytes(...) bytes                     */
+  int64_t wait_limit; /* polls (about a microsecond each) after which a workgroup of the  */
+                     /* resident selection loop stops waiting for another one; 0 ->      */
+                     /* 2000000.  Negative: a hook for testing the give-up path -- every */
+                     /* workgroup but the first of each problem leaves at once, the      */
+                     /* first gives up at its first unanswered poll, and the call        */
+                     /* reports r_eff = -1 (all kernels still end normally).             */
 } wildcat_opts;
 
 /* The compressed cache: output of CompressKV, input of WtdAttn.  All buffers are
@@ -113,9 +147,11 @@ typedef struct {
   int32_t *idx;   /* [P, r]  pivot index into the n keys, bin by bin in selection   */
                   /*         order; -1 in unused slots (a bin's rank was exhausted  */
                   /*         before its r/B pivots)                                 */
-  int32_t *r_eff; /* [P, B]  number of pivots drawn in each bin (-1: internal wait      */
-                  /*         timed out, the call's outputs are invalid; never       */
-                  /*         expected)                                              */
+  int32_t *r_eff; /* [P, B]  number of pivots drawn in each bin (-1 in every entry: a    */
+                  /*         wait inside the resident loop ran out, see "Sharing    */
+                  /*         the device"; idx, k_s, v_s, w are then zero / -1 or    */
+                  /*         unspecified, and wildcat_wtd_attn on them is memory-   */
+                  /*         safe but meaningless)                                  */
   void *k_s;      /* [P, r, d]  storage dtype: original (un-recentred) key rows     */
   float *v_s;     /* [P, r, dv] W V                                                 */
   float *w;       /* [P, r]     W 1                                                 */
@@ -188,14 +224,27 @@ int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *out, int64_
                      int32_t d, int32_t r, const wildcat_opts *opts);
 
 /* HOST (queries the current device).  1 if wildcat_compress_kv will run the RPNys selection loop
- * (Alg. 1) of this shape as one launch for all steps -- either all key slabs of all problems (bins)
- * resident on the device at once, the workgroups of a problem synchronising through memory, or,
- * for problems of a single slab, one workgroup (one wavefront, if the problems are tiny and many)
- * alone with its problem -- and 0 if it will issue one launch per step; negative wildcat_status for
- * invalid arguments.  For profiling and reporting only.  The environment variable
- * WILDCAT_RPNYS_LOOP overrides the choice: "steps" forces one launch per step, "wave" the
- * wavefront-per-problem form wherever the shape allows it (switches for tuning and testing). */
+ * (Alg. 1) of this shape with all steps inside one launch per group of problems -- either the key slabs of
+ * the group's problems (bins) resident on the device at once, the workgroups of a problem synchronising
+ * through memory, or, for problems of a single slab, one workgroup (one wavefront, if the problems are tiny
+ * and many) alone with its problem -- and 0 if it will issue one launch per step; negative wildcat_status
+ * for invalid arguments.  opts->loop_driver is honoured.  For profiling, reporting and the rule under
+ * "Sharing the device". */
 int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts);
+
+/* HOST.  The launch form of the selection loop for a shape, as eight integers:
+ *   out[0] driver: 0 one launch per step, 1 resident launches (slabs of a problem poll each other),
+ *          2 one workgroup alone with each single-slab problem, 3 one wavefront per tiny problem
+ *   out[1] keys per thread (1 or 2)       out[2] slabs (workgroups) per problem
+ *   out[3] problems (bins) per launch     out[4] launches for all problems (driver 0: per step)
+ *   out[5] 1 if the keys stay in registers for the whole loop, 0 if they are re-read every step
+ *   out[6] workgroups a compute unit must hold during a launch     out[7] 0
+ * With compute_units > 0 nothing touches a device: the plan is the one for a device with that many compute
+ * units that can hold occ_resident_keys (0: cannot) resp. occ_streamed_keys workgroups of the loop kernel per
+ * compute unit with the keys in registers resp. streamed.  With compute_units <= 0 the three figures are those
+ * of the current device, and the plan is the one wildcat_compress_kv will use there. */
+int wildcat_loop_plan(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts, int32_t compute_units,
+                      int32_t occ_resident_keys, int32_t occ_streamed_keys, int32_t out[8]);
 
 /* Rewrites cs->v_t and cs->v_scale from cs->v_s (device buffers, see wildcat_coreset) for a coreset
  * of r rows and value width dv; batch and kv_heads are read from opts, whose dtype must

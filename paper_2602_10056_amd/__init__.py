@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libwildcat.so")
 WILDCAT_F32, WILDCAT_BF16 = 0, 1
 EXPORTS = ("wildcat_version", "wildcat_strerror", "wildcat_workspace_bytes", "wildcat_draw_uniforms",
            "wildcat_query_radius", "wildcat_compress_kv", "wildcat_wtd_attn", "wildcat_pack_values",
-           "wildcat_rpnys_single_launch")
+           "wildcat_rpnys_single_launch", "wildcat_loop_plan")
 
 
 class WildcatError(RuntimeError):
@@ -31,9 +31,10 @@ class _Opts(ctypes.Structure):
         ("beta", ctypes.c_double), ("rank_tol", ctypes.c_double),
         ("r_q", ctypes.c_void_p), ("uniforms", ctypes.c_void_p),
         ("bins", ctypes.c_int32), ("tau_length", ctypes.c_int32),
-        ("history", ctypes.c_int32), ("reserved1", ctypes.c_int32),
+        ("history", ctypes.c_int32), ("loop_driver", ctypes.c_int32),
         ("stream", ctypes.c_void_p), ("ev_loop_begin", ctypes.c_void_p), ("ev_loop_end", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("wait_limit", ctypes.c_int64),
     ]
 
 
@@ -83,6 +84,9 @@ def load_library(force: bool = False):
                                      ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
     lib.wildcat_rpnys_single_launch.restype = ctypes.c_int
     lib.wildcat_rpnys_single_launch.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
+    lib.wildcat_loop_plan.restype = ctypes.c_int
+    lib.wildcat_loop_plan.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts),
+                                      ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     lib.wildcat_pack_values.restype = ctypes.c_int
     lib.wildcat_pack_values.argtypes = [ctypes.POINTER(_Coreset), ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(_Opts)]
     _lib = lib
@@ -167,22 +171,49 @@ def _history_code(history):
     return int(history == "f32")
 
 
-def workspace_bytes(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1, history="f64"):
+_LOOPS = {"auto": 0, "steps": 1, "wave": 2}
+
+
+def _loop_code(loop):
+    if loop not in _LOOPS:
+        raise WildcatError("loop is 'auto', 'steps' or 'wave'")
+    return _LOOPS[loop]
+
+
+def _shape_opts(batch, kv_heads, dv, dtype, bins, history, loop):
     o = _Opts()
     o.batch, o.kv_heads, o.dv, o.dtype, o.bins = batch, kv_heads, dv, dtype, bins
-    o.history = _history_code(history)
+    o.history, o.loop_driver = _history_code(history), _loop_code(loop)
+    return o
+
+
+def workspace_bytes(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1, history="f64"):
+    o = _shape_opts(batch, kv_heads, dv, dtype, bins, history, "auto")
     return load_library().wildcat_workspace_bytes(n, d, r, ctypes.byref(o))
 
 
-def rpnys_single_launch(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1, history="f64"):
-    """True if compress_kv runs the selection loop of this shape as one persistent launch (needs a GPU)."""
-    o = _Opts()
-    o.batch, o.kv_heads, o.dv, o.dtype, o.bins = batch, kv_heads, dv, dtype, bins
-    o.history = _history_code(history)
+def rpnys_single_launch(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1, history="f64", loop="auto"):
+    """True if compress_kv runs the selection loop of this shape with all steps inside a launch (needs a GPU)."""
+    o = _shape_opts(batch, kv_heads, dv, dtype, bins, history, loop)
     rc = load_library().wildcat_rpnys_single_launch(n, d, r, ctypes.byref(o))
     if rc < 0:
         _check(rc, "wildcat_rpnys_single_launch")
     return bool(rc)
+
+
+LOOP_PLAN_FIELDS = ("driver", "keys_per_thread", "slabs", "problems_per_launch", "launches", "keys_in_registers",
+                    "workgroups_per_cu", "reserved")
+
+
+def loop_plan(n, d, r, batch=1, kv_heads=1, dv=0, dtype=WILDCAT_BF16, bins=1, history="f64", loop="auto",
+              compute_units=0, occ_resident_keys=0, occ_streamed_keys=0):
+    """wildcat_loop_plan as a dict (see include/wildcat.h).  compute_units = 0: the current device (needs a GPU);
+    > 0: pure host logic for a device with the given capacities."""
+    o = _shape_opts(batch, kv_heads, dv, dtype, bins, history, loop)
+    out = (ctypes.c_int32 * 8)()
+    _check(load_library().wildcat_loop_plan(n, d, r, ctypes.byref(o), compute_units, occ_resident_keys,
+                                            occ_streamed_keys, out), "wildcat_loop_plan")
+    return dict(zip(LOOP_PLAN_FIELDS, (int(x) for x in out)))
 
 
 def query_radius(Q, kv_heads=None, workspace=None):
@@ -200,12 +231,13 @@ def query_radius(Q, kv_heads=None, workspace=None):
 
 
 def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, loop_events=None,
-                bins=1, temperature_n="bin", history="f64"):
+                bins=1, temperature_n="bin", history="f64", loop="auto", wait_limit=0):
     """CompressKV (Alg. 2).  K: [B, Hkv, n, d], V: [B, Hkv, n, dv]; r_q: float64 [B, Hkv] on the device;
     uniforms: optional float64 [B*Hkv, r] on the device (else drawn from `seed`); loop_events: optional pair
     of raw hipEvent_t handles recorded around the RPNys loop; bins: B of Alg. 2 (must divide n and r);
     temperature_n: "bin" (length n/B in the temperature) or "full" (n); history: "f64" (pivots identical to a
-    float64 reference) or "f32" (fast mode, see wildcat_history in include/wildcat.h).  Returns a Coreset."""
+    float64 reference) or "f32" (fast mode, see wildcat_history in include/wildcat.h); loop: "auto", "steps" or
+    "wave" (wildcat_loop); wait_limit: see wildcat_opts.  Returns a Coreset."""
     import torch
     _need(K, "K", 4)
     _need(V, "V", 4)
@@ -244,6 +276,7 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
     )
     o = _opts(B, H, H, n, dv, code, beta, rank_tol, r_q.contiguous(), uniforms, workspace)
     o.bins, o.tau_length, o.history = bins, int(temperature_n == "full"), _history_code(history)
+    o.loop_driver, o.wait_limit = _loop_code(loop), int(wait_limit)
     if loop_events is not None:
         o.ev_loop_begin, o.ev_loop_end = loop_events
     c = cs.c_struct()
@@ -285,7 +318,7 @@ def wtd_attn(Q, cs: Coreset, beta=None, out=None):
 
 
 def wildcat(Q, K, V, r, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, return_coreset=False,
-            bins=1, temperature_n="bin", history="f64"):
+            bins=1, temperature_n="bin", history="f64", loop="auto", wait_limit=0):
     """WildCat (Alg. 4): query radius, CompressKV, WtdAttn."""
     if workspace is None:
         import torch
@@ -297,6 +330,6 @@ def wildcat(Q, K, V, r, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspac
         workspace = torch.empty(need, dtype=torch.uint8, device=K.device)
     r_q = query_radius(Q, K.shape[1], workspace=workspace)
     cs = compress_kv(K, V, r, r_q, seed=seed, uniforms=uniforms, beta=beta, rank_tol=rank_tol, workspace=workspace,
-                     bins=bins, temperature_n=temperature_n, history=history)
+                     bins=bins, temperature_n=temperature_n, history=history, loop=loop, wait_limit=wait_limit)
     out = wtd_attn(Q, cs, beta=beta)
     return (out, cs) if return_coreset else out

@@ -1,7 +1,6 @@
 // Host-side pieces of the C ABI that launch nothing: option resolution, the workspace plan,
 // the documented uniform stream and error strings.
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 
 #include "common.h"
@@ -38,6 +37,9 @@ int resolve_shape(int64_t n, int64_t m_arg, int32_t d, int32_t r, const wildcat_
   s->tau_full_n = o->tau_length;
   if (o->history != WILDCAT_HISTORY_F64 && o->history != WILDCAT_HISTORY_F32) return WILDCAT_EINVAL;
   s->history_f32 = o->history == WILDCAT_HISTORY_F32;
+  if (o->loop_driver < WILDCAT_LOOP_AUTO || o->loop_driver > WILDCAT_LOOP_WAVE) return WILDCAT_EINVAL;
+  s->loop_driver = o->loop_driver;
+  s->wait_limit = o->wait_limit == 0 ? 2000000ll : (long long)o->wait_limit;
   if ((int64_t)s->P * s->bins > (1 << 20)) return WILDCAT_EINVAL;
   if (d > kMaxWidth || s->dv > kMaxWidth) return WILDCAT_EUNSUPPORTED;
   s->stream = (hipStream_t)o->stream;
@@ -45,15 +47,59 @@ int resolve_shape(int64_t n, int64_t m_arg, int32_t d, int32_t r, const wildcat_
 }
 
 int compute_units() {
-  static int cached[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (!cached[dev]) {
-    int n = 0;
-    cached[dev] =
-        (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  return (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+}
+
+bool keys_fit_registers(int dtype, int kpt, int dpad) {
+  // 32-bit registers per chunk of four features: bf16 pairs stay packed; at most 128 registers for the keys
+  const int nc = dpad / kChunk, regs_per_chunk = kpt * (dtype == WILDCAT_BF16 ? 2 : 4);
+  return (nc == 32 || nc == 16) && nc * regs_per_chunk <= 128;
+}
+
+bool wave_loop_covers(const Shape &s, int dpad) {
+  return s.r <= 16 && ((dpad == 64 && s.n <= 128) || (dpad == 128 && s.n <= 64));
+}
+
+LoopChoice choose_loop(const Shape &s, const Plan &pl, const DeviceCaps &caps, bool allow_wave) {
+  const LoopChoice steps = {kLoopSteps, 0, s.P, 1, 0};
+  if (!pl.persistent || s.loop_driver == WILDCAT_LOOP_STEPS || caps.cus < 1) return steps;
+  const int occ_regs = keys_fit_registers(s.dtype, pl.kpt, pl.dpad) ? caps.occ_regs : 0;
+  if (pl.nblk == 1) {
+    // One slab per problem: no workgroup waits for another, so any number of them may be queued in one launch.
+    // One wave per problem pays once the workgroup-per-problem form would need several rounds of workgroups: a
+    // wave alone takes about 6 us per step against 4 us for a workgroup, but sixteen times as many are in flight.
+    if (allow_wave && wave_loop_covers(s, pl.dpad) && (s.P > 2 * caps.cus || s.loop_driver == WILDCAT_LOOP_WAVE))
+      return LoopChoice{kLoopWave, 1, s.P, 1, 1};
+    const int rounds = (s.P + caps.cus - 1) / caps.cus;
+    if (occ_regs >= 1) return LoopChoice{kLoopSolo, 1, s.P, 1, rounds < occ_regs ? rounds : occ_regs};
+    if (caps.occ_stream >= 1) return LoopChoice{kLoopSolo, 0, s.P, 1, rounds < caps.occ_stream ? rounds : caps.occ_stream};
+    return steps;
   }
-  return cached[dev];
+  // Several slabs per problem: the workgroups of a launch poll each other and must all be resident.  The problems
+  // are independent, so they may be split into groups that run one after the other (A: few enough per launch that
+  // the keys stay in registers; B: as many as fit with the keys streamed every step).  Per step, A pays the
+  // latency of a step once per group, B pays one more read of all keys: take the cheaper (7 us of step latency,
+  // 6.5 TB/s of streaming rate: what the loop measures on this device).
+  const int64_t cap_a = (int64_t)caps.cus * occ_regs, cap_b = (int64_t)caps.cus * caps.occ_stream;
+  auto plan = [&](int64_t cap, int regs) {
+    LoopChoice c = steps;
+    const int64_t fit = cap / pl.nblk;                         // problems that fit at once
+    if (fit < 1) return c;
+    c.kind = kLoopResident;
+    c.keys_in_regs = regs;
+    c.launches = (int)((s.P + fit - 1) / fit);
+    c.group = (s.P + c.launches - 1) / c.launches;             // balanced groups
+    c.need = (int)(((int64_t)c.group * pl.nblk + caps.cus - 1) / caps.cus);
+    return c;
+  };
+  const LoopChoice a = plan(cap_a, 1), b = plan(cap_b, 0);
+  if (a.kind == kLoopSteps) return b;                          // (b may be kLoopSteps too)
+  if (b.kind == kLoopSteps || a.launches <= b.launches) return a;
+  const double es = s.dtype == WILDCAT_BF16 ? 2.0 : 4.0;
+  const double key_read_us = (double)s.P * (double)s.n * s.d * es / 6.5e6;
+  return (a.launches - b.launches) * 7.0 < key_read_us ? a : b;
 }
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -112,12 +158,9 @@ Plan make_plan(const Shape &s) {
   p.off_vmaxpart = take(P * p.nb0 * (size_t)s.dv * 4);
   p.off_u = take(P * r * 8);
   p.off_sync = take(4);
-  // Single-launch loop if all slabs can be resident (refined against real occupancy at launch).  The environment
-  // variable WILDCAT_RPNYS_LOOP=steps forces one launch per step (a tuning and debugging switch).
-  const char *mode = std::getenv("WILDCAT_RPNYS_LOOP");
-  // A problem of one slab takes the single-launch form at any rank and any problem count (its workgroups never wait).
-  p.persistent = (p.nblk == 1 || (s.r >= 2 && (int64_t)p.nblk * s.P <= 2 * 1024)) &&
-                 !(mode && std::strcmp(mode, "steps") == 0);
+  // Resident launches are an option for every loop of at least two steps (how many problems share a launch is
+  // decided against the device, see choose_loop); a problem of one slab takes its single-launch form at any rank.
+  p.persistent = p.nblk == 1 || s.r >= 2;
   p.total = off;
   return p;
 }

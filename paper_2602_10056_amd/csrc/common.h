@@ -23,6 +23,8 @@ struct Shape {
   int bins;          // B of Alg. 2 (>= 1)
   int tau_full_n;    // temperature from the full length n instead of the bin length n / B
   int history_f32;   // history rows of the selection loop in fp32 (fast mode) instead of fp64
+  int loop_driver;   // wildcat_loop: how the selection loop is launched
+  long long wait_limit;  // polls before a wait inside the resident loop gives up (> 0), or the test hook (< 0)
   double beta, rank_tol;
   hipStream_t stream;
 };
@@ -57,12 +59,39 @@ struct Plan {
   bool gram_cols;      // small bins of small rank: the Gram pass runs as k_gram_cols
   size_t off_kbar, off_kp, off_d0, off_p, off_bsum, off_scal, off_F, off_L, off_gpart, off_g,
       off_mpart, off_vminpart, off_vmaxpart, off_u, off_sync;
-  bool persistent;  // try the single-launch selection loop (all slabs of all problems resident at once)
+  bool persistent;  // the selection loop may run as resident launches (see choose_loop); false: one launch per step
   size_t total;
 };
 Plan make_plan(const Shape &s);
 
-// Number of compute units of the current device (queried once per process and device).
+// ---- how the selection loop (Alg. 1) of a shape is launched ------------------------------------------------
+enum LoopKind {
+  kLoopSteps = 0,     // one launch per step: the kernel boundary synchronises the slabs of a problem
+  kLoopResident = 1,  // all steps in one launch per group of problems; the slabs of a problem poll each other
+  kLoopSolo = 2,      // problems of one slab: one workgroup alone with its problem, one launch, nothing polled
+  kLoopWave = 3       // tiny problems: one wavefront per problem, one launch
+};
+struct DeviceCaps {
+  int cus;         // compute units
+  int occ_regs;    // workgroups of the loop kernel a compute unit holds with the keys kept in registers (0: none)
+  int occ_stream;  // ... with the keys streamed from memory every step
+};
+struct LoopChoice {
+  int kind;          // LoopKind
+  int keys_in_regs;  // the keys stay in registers for the whole loop
+  int group;         // problems per launch
+  int launches;      // launches for all problems (kLoopSteps: per step)
+  int need;          // workgroups a compute unit must hold during a launch
+};
+// Pure host logic (no device is touched): the launch form of the loop for shape `s` (the bin view) on a device with
+// the given capacities.
+LoopChoice choose_loop(const Shape &s, const Plan &pl, const DeviceCaps &caps, bool allow_wave = true);
+// Whether a loop kernel that keeps the packed keys in registers exists for this storage type, keys per thread and
+// padded width; whether the wavefront-per-problem loop covers this shape.
+bool keys_fit_registers(int dtype, int kpt, int dpad);
+bool wave_loop_covers(const Shape &s, int dpad);
+
+// Number of compute units of the current device.
 int compute_units();
 
 // Writes the packed half-precision values v_t and their scale v_scale (see wildcat_coreset) from v_s [P, r, dv].

@@ -30,8 +30,6 @@
 // one launch per step otherwise (see rpnys_step and its two drivers).
 #include <climits>
 #include <cmath>
-#include <cstdlib>
-#include <cstring>
 
 #include "common.h"
 
@@ -506,6 +504,8 @@ struct StepArgs {
   int32_t *idx, *r_eff;
   int64_t n, npad;
   int P, nblk, r, dpad;
+  int pr0;                // first problem of this launch (resident loop: the problems run in groups)
+  int absent;             // test hook of the give-up path: every workgroup but slab 0 of a problem leaves at once
 };
 
 // History loads are streaming: each entry is read once per step and the working set (hundreds of MB)
@@ -793,12 +793,13 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   const double beta_tau = SOLO ? bt_solo : a.scal[(size_t)pr * 8 + 2];
 
   // ---- 5. history product  acc_l = sum_{j<i} F_j(l) g_j  (the O(n i) stream) ---------------------------
-  // Rows are walked upwards on even steps and downwards on odd steps: the rows a step reads last are the
-  // rows the next step reads first, so whatever part of the history the memory-side cache still holds is
-  // reused before it is evicted.  (The order is fixed per step, so results stay reproducible.)
-  // The first hcn rows of this slab's history are also kept in LDS (`hc`, persistent driver only): they are the rows
-  // every later step needs, so caching them removes about 2 hcn / r of the stream.  Cached rows are added first, in
-  // ascending order; the direction of the walk alternates over the remaining rows only.
+  // Rows are added in ascending order on even steps and in descending order on odd steps: the rows a step reads
+  // last from memory are the rows the next step reads first, so whatever part of the history the memory-side
+  // cache still holds is reused before it is evicted.  The order is fixed per step and does not depend on how
+  // the loop is launched, so every launch form gives the same bits.
+  // The first hcn rows of this slab's history are also kept in LDS (`hc`, single-launch forms only): they are
+  // the rows every later step needs, so serving them from LDS removes about 2 hcn / r of the stream.  They take
+  // their place in the same order: first on even steps, last on odd ones.
   double acc[KPT];
 #pragma unroll
   for (int k = 0; k < KPT; ++k) acc[k] = 0.0;
@@ -806,10 +807,12 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     const bool down = (i & 1) != 0;
     const int nc_rows = i < hcn ? i : hcn;                   // rows [0, nc_rows) come from LDS
     const int nh = i - nc_rows;                              // rows [nc_rows, i) from memory
-    for (int j = 0; j < nc_rows; ++j) {                       // cached rows, always first and upwards
-      const double gj = g[j];
+    if (!down) {
+      for (int j = 0; j < nc_rows; ++j) {
+        const double gj = g[j];
 #pragma unroll
-      for (int k = 0; k < KPT; ++k) acc[k] = fma((double)hc[(size_t)j * SLAB + l_loc + k], gj, acc[k]);
+        for (int k = 0; k < KPT; ++k) acc[k] = fma((double)hc[(size_t)j * SLAB + l_loc + k], gj, acc[k]);
+      }
     }
     const ptrdiff_t fstep = down ? -(ptrdiff_t)SLAB : (ptrdiff_t)SLAB;
     const int gstep = down ? -1 : 1;
@@ -850,6 +853,13 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
       for (int k = 0; k < KPT; ++k) acc[k] = fma((double)h.v[k], gj, acc[k]);
       fp += fstep;
       gp += gstep;
+    }
+    if (down) {
+      for (int j2 = nc_rows - 1; j2 >= 0; --j2) {
+        const double gj = g[j2];
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) acc[k] = fma((double)hc[(size_t)j2 * SLAB + l_loc + k], gj, acc[k]);
+      }
     }
   }
 
@@ -961,8 +971,8 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
   }
 }
 
-// Driver 2: the whole loop in one launch.  Requires all nblk * P workgroups to fit on the device at once (the
-// host checks the grid against the kernel's occupancy).  The workgroups of one problem synchronise after every step through
+// Driver 2: the whole loop in one launch for the problems a.pr0 .. a.pr0 + gridDim.y - 1.  Requires all
+// nblk * gridDim.y workgroups to fit on the device at once (the host sizes the groups against the kernel's occupancy).  The workgroups of one problem synchronise after every step through
 // the slab sums themselves (see POLL above); the values that cross workgroups (p, slab sums, history rows) are
 // stored and loaded device-coherently (st_dev / ld_dev), so no cache-wide fence is needed.  Every wait is
 // bounded: if a limit is hit (it never should be) the error word is set and every workgroup leaves.  With
@@ -974,7 +984,8 @@ __global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(
   extern __shared__ double dyn[];
   __shared__ StepShared sh;
   constexpr int SLAB = kThreads * KPT;
-  const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
+  const int t = threadIdx.x, b = blockIdx.x, pr = a.pr0 + blockIdx.y;
+  if (a.absent && b > 0) return;                             // (test hook) as if this workgroup never became resident
   const int64_t l_glob = (int64_t)b * SLAB + t * KPT;
   const int nc = a.dpad / kChunk;
   double pown[KPT], flo[KPT];
@@ -1881,15 +1892,14 @@ __global__ void k_check_sync(const int *error, int P, int32_t *r_eff) {
     if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP; \
   } while (0)
 
-// The single-launch selection loop for this shape (fn = null if its workgroups cannot all be resident at once; then
-// the loop runs as one launch per step), its dynamic LDS size and the number of history rows cached in LDS: whatever
-// LDS the compute unit has left once every workgroup it must hold has its share.
+// The launch form of the selection loop for this shape on the current device: the kernel (null: one launch per
+// step), its dynamic LDS size and the number of history rows cached in LDS -- whatever LDS the compute unit has left
+// once every workgroup it must hold has its share.
 struct LoopPlan {
+  LoopChoice c;
   const void *fn;
   size_t lds;
   int hcn;
-  bool solo;              // fn is k_rpnys_solo or k_rpnys_wave (which also do the work of k_sqnorm and k_init_p)
-  bool wave;              // fn is k_rpnys_wave
 };
 
 constexpr int kWaveRank = 16;                                // k_rpnys_wave: at most this many pivots (lane j < i writes L)
@@ -1903,57 +1913,68 @@ const void *wave_kernel(const Shape &s, int dpad) {
   return nullptr;
 }
 
+// The workgroup-per-slab loop kernel: `solo` = problems of one slab, `regs` = keys kept in registers (only where
+// keys_fit_registers says so), nc = chunks of four features.
 template <typename T, int KPT, typename H>
-LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
-  LoopPlan lp = {nullptr, 0, 0, false, false};
-  if (!pl.persistent) return lp;
-  // One wave per problem pays once the workgroup-per-problem form would need several rounds of workgroups: a wave
-  // alone takes about 6 us per step against 4 us for a workgroup, but sixteen times as many problems are in flight.
-  // WILDCAT_RPNYS_LOOP=wave selects it wherever it applies (a testing switch).
-  const char *mode = std::getenv("WILDCAT_RPNYS_LOOP");
-  if (pl.nblk == 1 && (s.P > 2 * compute_units() || (mode && std::strcmp(mode, "wave") == 0))) {
-    if (const void *wfn = wave_kernel<T, H>(s, pl.dpad)) {
-      const int kw = s.n <= 64 ? 1 : 2;
-      const size_t per_wave = (size_t)pl.dpad * sizeof(double) + (((size_t)s.r * kWave * kw * sizeof(H) + 7) & ~(size_t)7);
-      lp.lds = per_wave * (kThreads / kWave);
-      if (lp.lds <= 64 * 1024 ||
-          hipFuncSetAttribute(wfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lp.lds) == hipSuccess) {
-        lp.fn = wfn;
-        lp.solo = lp.wave = true;
-        return lp;
-      }
-      lp.lds = 0;
-    }
-  }
-  const int nc = pl.dpad / kChunk;
+const void *loop_kernel(bool solo, bool regs, int nc) {
   constexpr int regs_per_chunk = KPT * (sizeof(T) == 2 ? 2 : 4);
-  const bool solo = pl.nblk == 1;                             // one slab per problem: see rpnys_step
-  const void *fn;
-  if (nc == 32 && 32 * regs_per_chunk <= 128)
-    fn = solo ? (const void *)k_rpnys_solo<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H>
-              : (const void *)k_rpnys_persistent<T, KPT, (32 * regs_per_chunk <= 128 ? 32 : 0), H>;
-  else if (nc == 16 && 16 * regs_per_chunk <= 128)
-    fn = solo ? (const void *)k_rpnys_solo<T, KPT, 16, H> : (const void *)k_rpnys_persistent<T, KPT, 16, H>;
-  else
-    fn = solo ? (const void *)k_rpnys_solo<T, KPT, 0, H> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
-  const int cus = compute_units();
-  const int64_t wgs = (int64_t)pl.nblk * s.P;
-  int need = (int)((wgs + cus - 1) / cus);                   // workgroups a compute unit must hold
-  const size_t base = (size_t)((s.r + pl.dpad + 1) & ~1) * sizeof(double);
-  int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess) return lp;
-  if (solo && per_cu >= 1 && need > per_cu) need = per_cu;    // no workgroup waits for another: any grid size will do
-  if (per_cu < need) {
-    // Keys in registers cost too many registers for this many workgroups per compute unit: the variant that
-    // streams the keys every step is leaner and still saves the launches and their gaps.
-    fn = solo ? (const void *)k_rpnys_solo<T, KPT, 0, H> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, base) != hipSuccess || per_cu < need)
-      return lp;
+  if constexpr (32 * regs_per_chunk <= 128) {
+    if (regs && nc == 32)
+      return solo ? (const void *)k_rpnys_solo<T, KPT, 32, H> : (const void *)k_rpnys_persistent<T, KPT, 32, H>;
   }
-  lp.fn = fn;
-  lp.solo = solo;
-  lp.lds = base;
+  if constexpr (16 * regs_per_chunk <= 128) {
+    if (regs && nc == 16)
+      return solo ? (const void *)k_rpnys_solo<T, KPT, 16, H> : (const void *)k_rpnys_persistent<T, KPT, 16, H>;
+  }
+  return solo ? (const void *)k_rpnys_solo<T, KPT, 0, H> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
+}
+
+inline size_t loop_base_lds(const Shape &s, const Plan &pl) { return (size_t)((s.r + pl.dpad + 1) & ~1) * sizeof(double); }
+
+template <typename T, int KPT, typename H>
+int device_caps(const Shape &s, const Plan &pl, DeviceCaps *caps) {
+  const int nc = pl.dpad / kChunk;
+  const bool solo = pl.nblk == 1;
+  const size_t base = loop_base_lds(s, pl);
+  caps->cus = compute_units();
+  caps->occ_regs = caps->occ_stream = 0;
+  if (keys_fit_registers(s.dtype, pl.kpt, pl.dpad) &&
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_regs, loop_kernel<T, KPT, H>(solo, true, nc), kThreads,
+                                                   base) != hipSuccess)
+    caps->occ_regs = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_stream, loop_kernel<T, KPT, H>(solo, false, nc), kThreads,
+                                                   base) != hipSuccess)
+    caps->occ_stream = 0;
+  (void)hipGetLastError();                                   // a failed query must not be reported by a later launch check
+  return WILDCAT_OK;
+}
+
+template <typename T, int KPT, typename H>
+LoopPlan plan_loop(const Shape &s, const Plan &pl) {
+  LoopPlan lp = {{kLoopSteps, 0, s.P, 1, 0}, nullptr, 0, 0};
+  if (!pl.persistent || s.loop_driver == WILDCAT_LOOP_STEPS) return lp;
+  DeviceCaps caps;
+  device_caps<T, KPT, H>(s, pl, &caps);
+  LoopChoice c = choose_loop(s, pl, caps);
+  if (c.kind == kLoopWave) {
+    const void *wfn = wave_kernel<T, H>(s, pl.dpad);
+    const int kw = s.n <= 64 ? 1 : 2;
+    const size_t per_wave = (size_t)pl.dpad * sizeof(double) + (((size_t)s.r * kWave * kw * sizeof(H) + 7) & ~(size_t)7);
+    const size_t lds = per_wave * (kThreads / kWave);
+    if (wfn && (lds <= 64 * 1024 ||
+                hipFuncSetAttribute(wfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess)) {
+      lp.c = c; lp.fn = wfn; lp.lds = lds;
+      return lp;
+    }
+    c = choose_loop(s, pl, caps, false);                     // the wave form cannot run here: a workgroup per problem
+  }
+  if (c.kind == kLoopSteps) return lp;
+  const bool solo = c.kind == kLoopSolo;
+  const void *fn = loop_kernel<T, KPT, H>(solo, c.keys_in_regs != 0, pl.dpad / kChunk);
+  const size_t base = loop_base_lds(s, pl);
+  lp.c = c; lp.fn = fn; lp.lds = base;
   // History cache: optional, and only if the kernel stays resident with it.
+  const int need = c.need > 0 ? c.need : 1;
   int dev = 0, lds_cu = 0;
   if (hipGetDevice(&dev) == hipSuccess &&
       hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) == hipSuccess && lds_cu > 0) {
@@ -1972,6 +1993,7 @@ LoopPlan persistent_kernel(const Shape &s, const Plan &pl) {
       }
     }
   }
+  (void)hipGetLastError();
   return lp;
 }
 
@@ -2026,9 +2048,10 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   hipLaunchKernelGGL(k_col_final, dim3(P / s.bins), dim3(kFinalThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
                      nparts, s.bins, lpr, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
   LAUNCH_CHECK();
-  const LoopPlan lp = persistent_kernel<T, KPT, H>(s, pl);
+  const LoopPlan lp = plan_loop<T, KPT, H>(s, pl);
+  const bool one_slab_form = lp.c.kind == kLoopSolo || lp.c.kind == kLoopWave;   // these also do the work of k_sqnorm, k_init_p
   const double tau_n = (double)(s.tau_full_n ? s.n * s.bins : s.n);
-  if (!lp.solo) {
+  if (!one_slab_form) {
     hipLaunchKernelGGL((k_sqnorm<T, KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, Kp, kbar, s.n, pl.npad, pl.dpad, d0,
                        (unsigned long long *)scal);
     LAUNCH_CHECK();
@@ -2042,28 +2065,36 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   a.Kp = Kp; a.kbar = kbar; a.scal = scal; a.floor = d0; a.u = o->uniforms ? o->uniforms : u_gen;
   a.p = p; a.bsum = bsum; a.F = F; a.L = L; a.idx = out->idx; a.r_eff = out->r_eff;
   a.n = s.n; a.npad = pl.npad; a.P = P; a.nblk = pl.nblk; a.r = s.r; a.dpad = pl.dpad;
+  a.pr0 = 0; a.absent = 0;
   if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
   const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
   bool done = false;
   const void *fn = lp.fn;
-  if (fn && lp.solo) {
+  if (fn && one_slab_form) {
     SoloInit in;
     in.r_q = o->r_q; in.u = o->uniforms; in.scal = scal; in.tau_out = out->tau; in.seed = (unsigned long long)seed;
     in.rank_tol = s.rank_tol; in.tau_n = tau_n; in.beta = s.beta; in.bins = s.bins;
     int hcn = lp.hcn;
     void *args[] = {(void *)&a, (void *)&in, (void *)&hcn};
-    const dim3 grid = lp.wave ? dim3((P + kThreads / kWave - 1) / (kThreads / kWave)) : dim3(1, P);
+    const dim3 grid = lp.c.kind == kLoopWave ? dim3((P + kThreads / kWave - 1) / (kThreads / kWave)) : dim3(1, P);
     if (hipLaunchKernel(fn, grid, dim3(kThreads), args, lp.lds, st) != hipSuccess) return WILDCAT_EHIP;
     done = true;
   } else if (fn) {
     int *err_word = (int *)(ws + pl.off_sync);
-    long long spin_limit = 2000000;    // polls of about a microsecond each: seconds, far beyond any real step
+    long long spin_limit = s.wait_limit > 0 ? s.wait_limit : 0;   // polls of about a microsecond each
+    a.absent = s.wait_limit < 0;
     int hcn = lp.hcn;
-    void *args[] = {(void *)&a, (void *)&err_word, (void *)&spin_limit, (void *)&hcn};
-    // An ordinary launch: the grid was checked against the device's capacity (persistent_kernel), so on an idle
-    // device every workgroup is resident at once; if other work holds compute units, the late workgroups start
-    // when it ends and the resident ones poll meanwhile (bounded).
-    if (hipLaunchKernel(fn, dim3(pl.nblk, P), dim3(kThreads), args, lp.lds, st) != hipSuccess) return WILDCAT_EHIP;
+    // Ordinary launches, one per group of problems, back to back on the stream: a group was sized against the
+    // device's capacity (choose_loop), so on an otherwise idle device every workgroup of a launch is resident at
+    // once; if other work holds compute units, the late workgroups start when it ends and the resident ones poll
+    // meanwhile (bounded).
+    for (int g0 = 0; g0 < P; g0 += lp.c.group) {
+      a.pr0 = g0;
+      const int gp = P - g0 < lp.c.group ? P - g0 : lp.c.group;
+      void *args[] = {(void *)&a, (void *)&err_word, (void *)&spin_limit, (void *)&hcn};
+      if (hipLaunchKernel(fn, dim3(pl.nblk, gp), dim3(kThreads), args, lp.lds, st) != hipSuccess) return WILDCAT_EHIP;
+    }
+    a.pr0 = 0;
     hipLaunchKernelGGL(k_check_sync, dim3(1), dim3(64), 0, st, err_word, P, out->r_eff);
     LAUNCH_CHECK();
     done = true;
@@ -2168,13 +2199,25 @@ int dispatch_compress(const Shape &s, const Plan &pl, const void *K, const void 
                        : dispatch_kpt<float, double>(s, pl, K, V, o, seed, out);
 }
 template <typename T, typename H>
-bool single_launch_kpt(const Shape &s, const Plan &pl) {
-  return (pl.kpt == 2 ? persistent_kernel<T, 2, H>(s, pl).fn : persistent_kernel<T, 1, H>(s, pl).fn) != nullptr;
+LoopChoice loop_choice_kpt(const Shape &s, const Plan &pl) {
+  return pl.kpt == 2 ? plan_loop<T, 2, H>(s, pl).c : plan_loop<T, 1, H>(s, pl).c;
 }
-bool dispatch_single_launch(const Shape &s, const Plan &pl) {
+LoopChoice dispatch_loop_choice(const Shape &s, const Plan &pl) {
   if (s.dtype == WILDCAT_BF16)
-    return s.history_f32 ? single_launch_kpt<bf16_t, float>(s, pl) : single_launch_kpt<bf16_t, double>(s, pl);
-  return s.history_f32 ? single_launch_kpt<float, float>(s, pl) : single_launch_kpt<float, double>(s, pl);
+    return s.history_f32 ? loop_choice_kpt<bf16_t, float>(s, pl) : loop_choice_kpt<bf16_t, double>(s, pl);
+  return s.history_f32 ? loop_choice_kpt<float, float>(s, pl) : loop_choice_kpt<float, double>(s, pl);
+}
+
+// Validation shared by the entry points that take a CompressKV shape; on success *s is the bin view.
+int compress_shape(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts, Shape *s) {
+  Shape whole;
+  const int rc = resolve_shape(n, 0, d, r, opts, &whole);
+  if (rc != WILDCAT_OK) return rc;
+  if (!bins_divide(whole)) return WILDCAT_EINVAL;
+  *s = bin_view(whole);
+  if (s->r > kMaxRank) return WILDCAT_EUNSUPPORTED;
+  if (s->P > 65535 || (int64_t)s->P * s->r > INT32_MAX) return WILDCAT_EUNSUPPORTED;   // problems index grid.y / grid.z
+  return WILDCAT_OK;
 }
 
 }  // namespace
@@ -2185,13 +2228,9 @@ using namespace wildcat;
 extern "C" int wildcat_compress_kv(const void *K, const void *V, int64_t n, int32_t d, int32_t r, uint64_t seed,
                                    const wildcat_opts *opts, wildcat_coreset *out) {
   if (!K || !V || !opts || !out) return WILDCAT_EINVAL;
-  Shape whole;
-  int rc = resolve_shape(n, 0, d, r, opts, &whole);
+  Shape s;
+  const int rc = compress_shape(n, d, r, opts, &s);
   if (rc != WILDCAT_OK) return rc;
-  if (!bins_divide(whole)) return WILDCAT_EINVAL;
-  const Shape s = bin_view(whole);
-  if (s.r > kMaxRank) return WILDCAT_EUNSUPPORTED;
-  if (s.P > 65535 || (int64_t)s.P * s.r > INT32_MAX) return WILDCAT_EUNSUPPORTED;   // problems index grid.y / grid.z
   if (!opts->r_q) return WILDCAT_EINVAL;
   if (!out->idx || !out->r_eff || !out->k_s || !out->v_s || !out->w || !out->v_min || !out->v_max || !out->tau)
     return WILDCAT_EINVAL;
@@ -2202,12 +2241,28 @@ extern "C" int wildcat_compress_kv(const void *K, const void *V, int64_t n, int3
 }
 
 extern "C" int wildcat_rpnys_single_launch(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts) {
-  Shape whole;
-  int rc = resolve_shape(n, 0, d, r, opts, &whole);
+  Shape s;
+  const int rc = compress_shape(n, d, r, opts, &s);
   if (rc != WILDCAT_OK) return rc;
-  if (!bins_divide(whole)) return WILDCAT_EINVAL;
-  const Shape s = bin_view(whole);
-  if (s.r > kMaxRank) return WILDCAT_EUNSUPPORTED;
+  return dispatch_loop_choice(s, make_plan(s)).kind != kLoopSteps ? 1 : 0;
+}
+
+extern "C" int wildcat_loop_plan(int64_t n, int32_t d, int32_t r, const wildcat_opts *opts, int32_t cus,
+                                 int32_t occ_resident_keys, int32_t occ_streamed_keys, int32_t out[8]) {
+  if (!out) return WILDCAT_EINVAL;
+  Shape s;
+  const int rc = compress_shape(n, d, r, opts, &s);
+  if (rc != WILDCAT_OK) return rc;
   const Plan pl = make_plan(s);
-  return dispatch_single_launch(s, pl) ? 1 : 0;
+  LoopChoice c;
+  if (cus > 0) {
+    if (occ_resident_keys < 0 || occ_streamed_keys < 0) return WILDCAT_EINVAL;
+    const DeviceCaps caps = {cus, occ_resident_keys, occ_streamed_keys};
+    c = choose_loop(s, pl, caps);
+  } else {
+    c = dispatch_loop_choice(s, pl);
+  }
+  out[0] = c.kind; out[1] = pl.kpt; out[2] = pl.nblk; out[3] = c.group; out[4] = c.kind == kLoopSteps ? 1 : c.launches;
+  out[5] = c.keys_in_regs; out[6] = c.need; out[7] = 0;
+  return WILDCAT_OK;
 }

@@ -5,11 +5,15 @@
 // maximum keeps exp() in range.  Any positive per-row factor cancels in Alg. 3's ratio and leaves the
 // sign of the normaliser (A w) unchanged, so the max shift does not alter the "> 0" guard.
 //
-// Two kernels:
-//   k_wtd_attn_mfma2  bf16 storage with packed values (coreset fields v_t, v_scale), d and dv of 64 or 128:
-//                     transposed tiles on v_mfma_f32_32x32x16, pipelined through LDS.
-//   k_wtd_attn_simple any storage type / width, fp32 arithmetic on the vector ALU (the fp32 path, and bf16
-//                     shapes the MFMA kernel does not cover).
+// Kernels:
+//   k_wtd_attn_mfma2    bf16 storage with packed values (coreset fields v_t, v_scale), d and dv of 64 or 128 (and
+//                       64 / 256): transposed tiles on v_mfma_f32_32x32x16, pipelined through LDS.
+//   k_wtd_attn_decode   the same arithmetic at decode shape (few queries per head): the key tiles are dealt out to
+//                       the waves of a workgroup, operands straight from memory.
+//   k_wtd_attn_mfma_f32 fp32 storage (d / dv of 64 / 64, 64 / 256, 128 / 128) on v_mfma_f32_32x32x2_f32.
+//   k_wtd_attn_simple   any storage type / width, fp32 arithmetic on the vector ALU (what the MFMA kernels do
+//                       not cover).
+//   k_qnorm_max(_vec), k_radius_final   the query radius R_Q;   k_value_scale, k_pack_values   the packed values.
 #include <climits>
 #include <cmath>
 
@@ -1087,12 +1091,9 @@ int launch_mfma2(const Shape &s, const void *Q, const wildcat_coreset *cs, void 
   if (total > INT32_MAX) return WILDCAT_EUNSUPPORTED;
   // Persistent grid: as many workgroups as fit on the device at once (two per compute unit by the launch bounds,
   // three where the registers of the narrower instantiations allow it).
-  static int per_cu = 0;
-  if (per_cu == 0) {
-    int occ = 0;
-    per_cu = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void *)k_wtd_attn_mfma2<D, DV, NW>, NW * 64,
-                                                           0) == hipSuccess && occ >= 1) ? occ : 8 / NW;
-  }
+  int occ = 0;
+  const int per_cu = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void *)k_wtd_attn_mfma2<D, DV, NW>,
+                                                                   NW * 64, 0) == hipSuccess && occ >= 1) ? occ : 8 / NW;
   const int64_t resident = (int64_t)compute_units() * per_cu;
   const unsigned grid = (unsigned)(total < resident ? total : resident);
   hipLaunchKernelGGL((k_wtd_attn_mfma2<D, DV, NW>), dim3(grid), dim3(NW * 64), 0, s.stream, (const bf16_t *)Q,

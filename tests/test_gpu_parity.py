@@ -237,8 +237,12 @@ def test_wtd_attn_guard_clip_and_oracle_coreset(dtype, d, m):
     np.testing.assert_array_equal(out[bad], np.tile(np.clip(0.0, vmin[0, 0], vmax[0, 0]), (bad.sum(), 1)))
     assert np.all(out >= vmin[0, 0]) and np.all(out <= vmax[0, 0])
     # where the normaliser is well away from zero the clipped values agree with the oracle
+    # (the bars of the whole path, relative to the max-norm of the oracle's rows: the sums of these rows cancel by at
+    # most a factor of five)
     good = np.abs(den) > 0.2 * np.abs(A).sum(1)
-    assert np.abs(out[good] - ref[good]).max() <= (3e-2 if dtype == "bf16" else 1e-4)
+    err = np.abs(out[good] - ref[good]).max() / np.abs(ref[good]).max()
+    print(dtype, d, m, "guard test: relative error on well-conditioned rows", err)
+    assert err <= TOL_OUT[dtype]
 
 
 def test_query_radius_grouped():
@@ -255,7 +259,7 @@ def test_query_radius_grouped():
 
 
 # ---------------------------------------------------------------------------------- degenerate inputs
-def test_rank_exhaustion_with_duplicate_keys():
+def test_rank_exhaustion_with_duplicate_keys(loop="auto", rank_tol=0.0, oracle_rank_tol=1e-10):
     """Keys drawn from q distinct vectors: the kernel matrix has rank q; the loop stops after q pivots, the
     remaining slots are empty and the result equals exact attention."""
     rng = np.random.default_rng(11)
@@ -269,12 +273,12 @@ def test_rank_exhaustion_with_duplicate_keys():
     u = rng.random((1, r))
     w = {"shape": wl.shape(1, n=n, r=r), "Q": Q, "K": K, "V": V, "u": u}
     out, cs = wc.wildcat(to_dev(Q, "f32"), to_dev(K, "f32"), to_dev(V, "f32"), r=r,
-                         uniforms=torch.from_numpy(u).to(dev()), return_coreset=True)
+                         uniforms=torch.from_numpy(u).to(dev()), return_coreset=True, loop=loop, rank_tol=rank_tol)
     assert cs.r_eff.item() == q
     idx = cs.idx.cpu().numpy()[0, 0]
     assert sorted(lab[idx[:q]].tolist()) == list(range(q)) and np.all(idx[q:] == -1)
     assert torch.all(cs.w[0, 0, q:] == 0) and torch.all(cs.v_s[0, 0, q:] == 0) and torch.all(cs.k_s[0, 0, q:] == 0)
-    check_against_oracle(w, out, cs)
+    check_against_oracle(w, out, cs, rank_tol=oracle_rank_tol)
     ref = wo.exact_attention(Q[0, 0].astype(np.float64), K[0, 0].astype(np.float64), V[0, 0].astype(np.float64),
                              1 / np.sqrt(d))
     assert relmax(out.cpu().numpy()[0, 0], ref) <= 1e-5
@@ -352,28 +356,110 @@ def test_full_size_config3():
     print(_full_size(3, heads=[0, 9], prefix_r=64))
 
 
-def test_both_loop_drivers_agree(monkeypatch):
-    """The persistent single-launch loop and the one-launch-per-step loop run the same step function.  The persistent
-    one adds the history rows it keeps in LDS first, so the two differ in the rounding of fp64 sums: identical
-    pivots, weights and values equal to fp32 rounding noise; both equal the oracle."""
+def test_both_loop_drivers_agree():
+    """The resident single-launch loop and the one-launch-per-step loop run the same step function and add the history
+    rows in the same order (the rows the resident loop keeps in LDS take their place in that order), so the two give
+    the same bits; both equal the oracle."""
     w = wl.make(4, q_heads=4, kv_heads=2, n=4096, r=160)
     s = w["shape"]
     assert wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads) is True
     o1, c1 = run_gpu(w)
-    monkeypatch.setenv("WILDCAT_RPNYS_LOOP", "steps")
-    assert wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads) is False
-    o2, c2 = run_gpu(w)
-    monkeypatch.delenv("WILDCAT_RPNYS_LOOP")
-    assert torch.equal(c1.idx, c2.idx) and torch.equal(c1.r_eff, c2.r_eff) and torch.equal(c1.k_s, c2.k_s)
-    for a, b in ((c1.w, c2.w), (c1.v_s, c2.v_s)):
-        assert float((a - b).abs().max()) <= 1e-6 * float(b.abs().max())
+    assert wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, loop="steps") is False
+    o2, c2 = run_gpu(w, loop="steps")
+    for a, b in ((c1.idx, c2.idx), (c1.r_eff, c2.r_eff), (c1.k_s, c2.k_s), (c1.w, c2.w), (c1.v_s, c2.v_s), (o1, o2)):
+        assert torch.equal(a, b)
     check_against_oracle(w, o1, c1)
     check_against_oracle(w, o2, c2)
 
 
-def test_rank_exhaustion_per_step_driver(monkeypatch):
-    monkeypatch.setenv("WILDCAT_RPNYS_LOOP", "steps")
-    test_rank_exhaustion_with_duplicate_keys()
+def test_problems_in_groups_equal_one_launch_per_step():
+    """Long contexts: the problems of a call are independent, so when their slabs cannot all be resident at once with
+    the keys in registers the resident loop runs them in groups, one launch per group.  On a shape that this device
+    splits into groups the result has the same bits as the loop with one launch per step (which has no groups), and
+    the pivots are the oracle's (a short run: pivots of an r'-run are the first r' of any longer run)."""
+    w = wl.make(4, q_heads=4, kv_heads=4, n=131072, r=24)
+    s = w["shape"]
+    plan = wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv)
+    print("loop plan", plan)
+    assert plan["driver"] == 1 and plan["launches"] >= 2 and plan["keys_in_registers"] == 1, plan
+    assert plan["problems_per_launch"] * plan["launches"] >= s.kv_heads
+    o1, c1 = run_gpu(w)
+    o2, c2 = run_gpu(w, loop="steps")
+    for a, b in ((c1.idx, c2.idx), (c1.r_eff, c2.r_eff), (c1.k_s, c2.k_s), (c1.w, c2.w), (c1.v_s, c2.v_s), (o1, o2)):
+        assert torch.equal(a, b)
+    idx = c1.idx.cpu().numpy()
+    for h in (0, 3):                                           # first and last group
+        Kh, Vh = w["K"][0, h].astype(np.float64), w["V"][0, h].astype(np.float64)
+        RQ = float(np.sqrt((w["Q"][0, h].astype(np.float64) ** 2).sum(-1).max()))
+        ocs = wo.compress_kv(Kh, Vh, RQ, s.beta, s.r, w["u"][h])
+        np.testing.assert_array_equal(idx[0, h], ocs.idx)
+        assert relmax(c1.w[0, h].cpu().numpy().astype(np.float64), ocs.w) <= TOL_COMPRESSED
+        assert relmax(c1.v_s[0, h].cpu().numpy().astype(np.float64), ocs.V_S) <= TOL_COMPRESSED
+
+
+def test_bounded_wait_gives_up_and_reports_it():
+    """The give-up path of the resident loop, forced from the host (wait_limit < 0: every workgroup but the first of a
+    problem leaves at once, the first stops at its first unanswered poll): every kernel ends normally, r_eff = -1
+    everywhere, WtdAttn on the result is memory-safe, and the next ordinary call is unaffected."""
+    w = wl.make(4, q_heads=4, kv_heads=2, n=4096, r=64)
+    s = w["shape"]
+    assert wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv)["driver"] == 1
+    out, cs = run_gpu(w, wait_limit=-1)
+    assert torch.all(cs.r_eff == -1)
+    assert out.shape == (s.batch, s.q_heads, s.m, s.dv)
+    out2, cs2 = run_gpu(w)
+    assert torch.all(cs2.r_eff == s.r)
+    check_against_oracle(w, out2, cs2)
+
+
+# ---------------------------------------------------------------------------------- rank tolerance (Alg. 1, last lines)
+def _near_duplicate_keys(bins):
+    """Keys = 9 prototypes plus noise whose size varies from key to key over 2.5 decades: after a prototype is
+    drawn, the residual of its near-copies sits between 1e-8 and 1e-3 of its initial value, so every rank_tol in
+    that range zeroes a different set of keys and changes the later draws."""
+    rng = np.random.default_rng(21)
+    n, d, q, r = 500, 64, 9, 24                                # two slabs as one problem, one slab per bin with two bins
+    proto = rng.standard_normal((q, d))
+    lab = np.concatenate([np.arange(q), rng.integers(0, q, n - q)])
+    rng.shuffle(lab)
+    scale = 10.0 ** rng.uniform(-4, -1.5, (n, 1))
+    K = wl.round_to_storage((proto[lab] + scale * rng.standard_normal((n, d)))[None, None], "f32")
+    V = wl.round_to_storage(rng.standard_normal((1, 1, n, d)), "f32")
+    Q = wl.round_to_storage(rng.standard_normal((1, 1, 128, d)), "f32")
+    u = rng.random((1, r))
+    return {"shape": wl.shape(1, n=n, r=r, m_=128, bins=bins), "Q": Q, "K": K, "V": V, "u": u}
+
+
+@pytest.mark.parametrize("loop", ["auto", "steps"])
+@pytest.mark.parametrize("bins", [1, 2])
+def test_rank_tolerance_settings_on_near_duplicate_keys(bins, loop):
+    """opts.rank_tol: negative = Alg. 1 as printed (p_s <- 0 and the bare clamp max(p, 0); oracle rank_tol = 0), and
+    custom values; each against the oracle run with the same setting, pivots bit-exact; the settings do differ."""
+    w = _near_duplicate_keys(bins)
+    seen = {}
+    for lib_tol, oracle_tol in ((-1.0, 0.0), (1e-6, 1e-6), (1e-4, 1e-4), (1e-3, 1e-3)):
+        out, cs = run_gpu(w, rank_tol=lib_tol, loop=loop)
+        check_against_oracle(w, out, cs, rank_tol=oracle_tol)
+        seen[lib_tol] = cs.idx.cpu().numpy().copy()
+    assert not np.array_equal(seen[1e-6], seen[1e-4]) and not np.array_equal(seen[1e-4], seen[1e-3])
+
+
+@pytest.mark.parametrize("lib_tol,oracle_tol", [(-1.0, 0.0), (1e-6, 1e-6)])
+def test_rank_tolerance_settings_shrunk_config3(lib_tol, oracle_tol):
+    w = wl.make(3, q_heads=2, kv_heads=2, n=4096, r=256)
+    out, cs = run_gpu(w, rank_tol=lib_tol)
+    print(check_against_oracle(w, out, cs, rank_tol=oracle_tol))
+
+
+def test_rank_tolerance_custom_value_with_exact_duplicates():
+    """Exact duplicates need a positive tolerance on both sides (with the bare clamp the residual of a pivot's copies
+    is rounding noise of either sign, and which of them survives is not defined): a custom value, all loop forms."""
+    for loop in ("auto", "steps"):
+        test_rank_exhaustion_with_duplicate_keys(loop=loop, rank_tol=1e-6, oracle_rank_tol=1e-6)
+
+
+def test_rank_exhaustion_per_step_driver():
+    test_rank_exhaustion_with_duplicate_keys(loop="steps")
 
 
 def test_pack_values_matches_compress_output():
@@ -468,7 +554,7 @@ def test_binned_rank_exhaustion_leaves_holes_that_add_nothing():
     assert relmax(out[0, 0].cpu().numpy().astype(np.float64), ref) < 1e-4
 
 
-def test_binned_seed_path_and_loop_drivers(monkeypatch):
+def test_binned_seed_path_and_loop_drivers():
     """Bin b of problem p consumes elements p r + b r/B .. of the documented uniform stream; both loop drivers agree."""
     w = wl.make(6, q_heads=2, kv_heads=2, n=2048)
     s = w["shape"]
@@ -477,8 +563,7 @@ def test_binned_seed_path_and_loop_drivers(monkeypatch):
     o_seed, c_seed = wc.wildcat(Q, K, V, r=s.r, seed=5, return_coreset=True, bins=s.bins)
     o_u, c_u = wc.wildcat(Q, K, V, r=s.r, uniforms=u, return_coreset=True, bins=s.bins)
     assert torch.equal(c_seed.idx, c_u.idx) and torch.equal(o_seed, o_u)
-    monkeypatch.setenv("WILDCAT_RPNYS_LOOP", "steps")
-    o_st, c_st = wc.wildcat(Q, K, V, r=s.r, uniforms=u, return_coreset=True, bins=s.bins)
+    o_st, c_st = wc.wildcat(Q, K, V, r=s.r, uniforms=u, return_coreset=True, bins=s.bins, loop="steps")
     for a, b in ((o_u, o_st), (c_u.idx, c_st.idx), (c_u.w, c_st.w), (c_u.v_s, c_st.v_s), (c_u.tau, c_st.tau)):
         assert torch.equal(a, b)
 
@@ -507,16 +592,15 @@ def check_fast_mode_against_default(fast, default):
     (o32, c32), (o64, c64) = fast, default
     assert torch.equal(c32.idx, c64.idx) and torch.equal(c32.r_eff, c64.r_eff)
     for a, b in ((c32.w, c64.w), (c32.v_s, c64.v_s)):
-        assert float((a - b).abs().max()) <= 2e-3 * float(b.abs().max())
-    tol = 2e-3 if o64.dtype == torch.float32 else 2 ** -7          # bf16 outputs: one unit in the last place
+        assert float((a - b).abs().max()) <= 1e-4 * float(b.abs().max())
+    tol = 1e-4 if o64.dtype == torch.float32 else 2 ** -7          # bf16 outputs: one unit in the last place
     assert float((o32.float() - o64.float()).abs().max()) <= tol * float(o64.float().abs().max())
 
 
-def test_wave_per_problem_loop_on_random_small_shapes(monkeypatch):
-    """WILDCAT_RPNYS_LOOP=wave selects the wave-per-problem loop wherever it applies, whatever the problem count:
+def test_wave_per_problem_loop_on_random_small_shapes():
+    """loop="wave" (WILDCAT_LOOP_WAVE) selects the wave-per-problem loop wherever it applies, whatever the problem count:
     forty seeded random shapes inside its range (ragged key counts, one and two keys per lane, both widths, both storage
     types, both history types) against the oracle, then the two rank-exhaustion cases with few keys per problem."""
-    monkeypatch.setenv("WILDCAT_RPNYS_LOOP", "wave")
     rng = np.random.default_rng(77)
     done = 0
     while done < 40:
@@ -531,10 +615,13 @@ def test_wave_per_problem_loop_on_random_small_shapes(monkeypatch):
         kw = dict(history="f32") if rng.random() < 0.3 else {}
         w = wl.make(6 if dtype == "bf16" else 3, q_heads=kv * group, kv_heads=kv, n=nb * bins, m_=int(rng.choice([1, 50, 200])),
                     d=d, r=rb * bins, bins=bins, dtype=dtype)
-        out, cs = run_gpu(w)
+        s = w["shape"]
+        assert wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if dtype == "bf16" else 0, bins,
+                            loop="wave")["driver"] == 3
+        out, cs = run_gpu(w, loop="wave")
         check_against_oracle(w, out, cs)
         if kw:
-            check_fast_mode_against_default(run_gpu(w, **kw), (out, cs))
+            check_fast_mode_against_default(run_gpu(w, loop="wave", **kw), (out, cs))
         done += 1
     # rank exhaustion: 9 distinct keys among 100, 16 slots
     rng = np.random.default_rng(12)
@@ -548,7 +635,7 @@ def test_wave_per_problem_loop_on_random_small_shapes(monkeypatch):
     u = rng.random((1, r))
     w = {"shape": wl.shape(1, n=n, r=r, m_=40), "Q": Q, "K": K, "V": V, "u": u}
     out, cs = wc.wildcat(to_dev(Q, "f32"), to_dev(K, "f32"), to_dev(V, "f32"), r=r,
-                         uniforms=torch.from_numpy(u).to(dev()), return_coreset=True)
+                         uniforms=torch.from_numpy(u).to(dev()), return_coreset=True, loop="wave")
     assert cs.r_eff.item() == q and np.all(cs.idx.cpu().numpy()[0, 0][q:] == -1)
     check_against_oracle(w, out, cs)
 
@@ -679,9 +766,11 @@ def test_fp32_history_small_problem_matches_the_oracle_exactly():
     ref, ocs, _ = wo.wildcat(w["Q"][0, 0].astype(np.float64), w["K"][0, 0].astype(np.float64),
                              w["V"][0, 0].astype(np.float64), s.beta, s.r, w["u"][0], return_coreset=True)
     np.testing.assert_array_equal(cs.idx[0, 0].cpu().numpy(), ocs.idx)
-    assert relmax(cs.w[0, 0].cpu().numpy().astype(np.float64), ocs.w) < 1e-3
-    assert relmax(cs.v_s[0, 0].cpu().numpy().astype(np.float64), ocs.V_S) < 1e-3
-    assert relmax(out[0, 0].cpu().numpy().astype(np.float64), ref) < 1e-3
+    errs = (relmax(cs.w[0, 0].cpu().numpy().astype(np.float64), ocs.w),
+            relmax(cs.v_s[0, 0].cpu().numpy().astype(np.float64), ocs.V_S),
+            relmax(out[0, 0].cpu().numpy().astype(np.float64), ref))
+    print("fp32 history, cfg 1: w, V_S, out", errs)
+    assert max(errs) < 1e-4
 
 
 @pytest.mark.parametrize("cfg,ov", [(4, dict(q_heads=4, kv_heads=2, n=4096, r=192)),
@@ -720,8 +809,11 @@ def test_fp32_history_is_a_valid_nystrom_compression(cfg, ov):
             Wfull_w[b * rb:(b + 1) * rb] = Wb.sum(axis=1)
         ev = relmax(cs32.v_s[0, h].cpu().numpy().astype(np.float64), Wfull_vs)
         ew = relmax(cs32.w[0, h].cpu().numpy().astype(np.float64), Wfull_w)
-        print(cfg, h, "v_s", ev, "w", ew)
-        assert ev < 2e-2 and ew < 2e-2
+        same = np.array_equal(idx, ocs.idx)
+        print(cfg, h, "v_s", ev, "w", ew, "pivots equal the oracle's:", same)
+        # with the oracle's pivots the compression is the oracle's up to the fp32 rounding of the history rows; with
+        # other pivots (a near-tie went the other way) it is a different, equally valid one, checked more loosely
+        assert ev < (1e-4 if same else 2e-2) and ew < (1e-4 if same else 2e-2)
         for g in range(s.group):                                                                     # (d)
             ex = wo.exact_attention(Qg[g], K, V, s.beta)
             e32 = relmax(out32[0, h * s.group + g].float().cpu().numpy().astype(np.float64), ex)

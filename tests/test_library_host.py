@@ -123,3 +123,67 @@ def test_library_shares_the_hip_runtime_of_torch():
     out = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
     assert out.returncode == 0, out.stderr
     assert out.stdout.strip().splitlines()[-1] == "1"
+
+
+# ---------------------------------------------------------------------------------- launch form of the selection loop
+MI355X = dict(compute_units=256, occ_resident_keys=2, occ_streamed_keys=4)   # what the loop kernels reach on that device
+
+
+def test_loop_plan_headline_and_long_context_shapes():
+    """Pure host logic (no device is touched when compute_units > 0): which launch form the selection loop takes."""
+    # headline shape: 8 problems x 64 slabs of 512 keys = 512 workgroups = 2 per compute unit, keys in registers
+    p = wc.loop_plan(32768, 128, 512, kv_heads=8, **MI355X)
+    assert p == dict(driver=1, keys_per_thread=2, slabs=64, problems_per_launch=8, launches=1, keys_in_registers=1,
+                     workgroups_per_cu=2, reserved=0)
+    # twice / four times the length: the problems run in groups that keep the keys in registers
+    p = wc.loop_plan(65536, 128, 512, kv_heads=8, **MI355X)
+    assert (p["driver"], p["problems_per_launch"], p["launches"], p["keys_in_registers"]) == (1, 4, 2, 1)
+    p = wc.loop_plan(131072, 128, 1024, kv_heads=8, **MI355X)
+    assert (p["driver"], p["problems_per_launch"], p["launches"], p["keys_in_registers"]) == (1, 2, 4, 1)
+    assert p["workgroups_per_cu"] == 2
+    # uneven split: 3 problems per launch would be 3 + 3 + 2; balanced groups of at most 3
+    p = wc.loop_plan(131072 // 2 * 3 // 3, 128, 64, kv_heads=7, **MI355X)
+    assert p["problems_per_launch"] * p["launches"] >= 7 and p["problems_per_launch"] * 128 <= 512
+    # one problem whose slabs exceed even the streamed-keys capacity: one launch per step
+    p = wc.loop_plan(1 << 20, 128, 64, kv_heads=1, **MI355X)
+    assert p["slabs"] == 2048 and p["driver"] == 0 and p["launches"] == 1
+    # ... and one that fits only with streamed keys
+    p = wc.loop_plan(1 << 19, 128, 64, kv_heads=1, **MI355X)
+    assert (p["driver"], p["keys_in_registers"], p["launches"]) == (1, 0, 1)
+
+
+def test_loop_plan_honours_the_loop_driver_option_and_small_shapes():
+    # the caller's opt-out for shared devices
+    p = wc.loop_plan(32768, 128, 512, kv_heads=8, loop="steps", **MI355X)
+    assert p["driver"] == 0
+    # a single step needs no loop at all unless the problem is one slab
+    assert wc.loop_plan(32768, 128, 1, kv_heads=8, **MI355X)["driver"] == 0
+    assert wc.loop_plan(200, 64, 1, kv_heads=8, **MI355X)["driver"] == 2
+    # one slab per problem: a workgroup alone with its problem, any number of problems in one launch
+    p = wc.loop_plan(4096, 64, 64, kv_heads=8, bins=16, dtype=wc.WILDCAT_BF16, **MI355X)
+    assert p["slabs"] == 1 and p["driver"] == 2 and p["launches"] == 1 and p["problems_per_launch"] == 128
+    # many tiny problems: a wavefront per problem; few of them: only on request
+    assert wc.loop_plan(3136, 64, 224, batch=8, bins=224, dtype=wc.WILDCAT_F32, **MI355X)["driver"] == 3
+    assert wc.loop_plan(3136, 64, 224, batch=1, bins=224, dtype=wc.WILDCAT_F32, **MI355X)["driver"] == 2
+    assert wc.loop_plan(3136, 64, 224, batch=1, bins=224, dtype=wc.WILDCAT_F32, loop="wave", **MI355X)["driver"] == 3
+    assert wc.loop_plan(4096, 64, 64, kv_heads=8, bins=16, loop="wave", **MI355X)["driver"] == 2   # 256 keys: too many for a wave
+    # a device that cannot hold a single workgroup of the loop kernel
+    assert wc.loop_plan(32768, 128, 512, kv_heads=8, compute_units=256, occ_resident_keys=0,
+                        occ_streamed_keys=0)["driver"] == 0
+    # widths whose keys do not fit the registers fall back to streamed keys: fp32 storage, d = 128, two keys per thread
+    p = wc.loop_plan(32768, 128, 64, kv_heads=8, dtype=wc.WILDCAT_F32, **MI355X)
+    assert p["driver"] == 1 and p["keys_in_registers"] == 0
+
+
+def test_loop_plan_rejects_bad_arguments():
+    lib = wc.load_library()
+    o = wc._Opts()
+    out = (ctypes.c_int32 * 8)()
+    assert lib.wildcat_loop_plan(128, 64, 16, ctypes.byref(o), 256, 2, 4, None) == -1
+    assert lib.wildcat_loop_plan(128, 64, 129, ctypes.byref(o), 256, 2, 4, out) == -1      # r > n
+    assert lib.wildcat_loop_plan(128, 64, 16, ctypes.byref(o), 256, -1, 4, out) == -1
+    o.loop_driver = 3
+    assert lib.wildcat_loop_plan(128, 64, 16, ctypes.byref(o), 256, 2, 4, out) == -1       # unknown driver
+    o.loop_driver = 0
+    o.bins = 3
+    assert lib.wildcat_loop_plan(128, 64, 16, ctypes.byref(o), 256, 2, 4, out) == -1
