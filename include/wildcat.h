@@ -24,7 +24,8 @@
  *     device.  The caller owns every buffer, including the workspace; the
  *     library allocates and frees nothing, reads no environment variable and
  *     keeps no state between calls: every decision is a function of the
- *     arguments and of the current device's attributes, queried anew.
+ *     arguments and of the current device's attributes, queried anew.  (One
+ *     exception, stated there: wildcat_query_radius_static.)
  *   - All work is enqueued on opts->stream (NULL = the null stream).  No entry
  *     point synchronises with the host; results are valid once the stream has
  *     reached the end of the enqueued work.
@@ -92,7 +93,9 @@ typedef enum {
   WILDCAT_EINVAL = -1,      /* null pointer, bad shape / dtype / option            */
   WILDCAT_EWORKSPACE = -2,  /* workspace missing, misaligned or too small          */
   WILDCAT_EHIP = -3,        /* a HIP runtime call or kernel launch failed          */
-  WILDCAT_EUNSUPPORTED = -4 /* valid request that this build does not implement    */
+  WILDCAT_EUNSUPPORTED = -4, /* valid request that this build does not implement   */
+  WILDCAT_ETOOLARGE = -5    /* shape beyond the fixed size of the library's own    */
+                            /* scratch (wildcat_query_radius_static only)          */
 } wildcat_status;
 
 /* Options.  A zero-filled struct selects the paper's defaults. */
@@ -198,6 +201,19 @@ int wildcat_draw_uniforms(uint64_t seed, int64_t count, double *host_out);
  * is several times faster than the atomic updates of r_q_out used otherwise.  Same result. */
 int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts,
                          double *r_q_out);
+
+/* The same result as wildcat_query_radius for callers that can neither allocate device memory nor offer a
+ * workspace at this point -- code running under HIP graph capture, tight serving loops that compute R_Q for
+ * new queries, harnesses that forbid allocation: the per-workgroup maxima go to a 64 KB array of device memory
+ * that is part of the library's code object (each device the library runs on holds one copy until the process
+ * ends; its address is looked up on the first call on a device and kept -- the one piece of state the library
+ * has).  Allocates nothing, synchronises nothing, ignores opts->workspace.  Limit: batch * q_heads <= 4096, else
+ * WILDCAT_ETOOLARGE and nothing is enqueued.  Nothing in the array needs clearing between calls (every entry a
+ * call reads it has written itself), but all calls on a device share it: calls that may overlap on one device
+ * (different streams) race and must be ordered by the caller.  Row widths that are not a power-of-two number
+ * (<= 64) of 16-byte pieces take the atomic path of wildcat_query_radius, which uses no scratch at all. */
+int wildcat_query_radius_static(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts,
+                                double *r_q_out);
 
 /* CompressKV (Alg. 2) together with the value range of Alg. 4:
  *   kbar = row mean of K;  then for each of the B = opts->bins bins of rows:

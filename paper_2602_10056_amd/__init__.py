@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libwildcat.so")
 WILDCAT_F32, WILDCAT_BF16 = 0, 1
 EXPORTS = ("wildcat_version", "wildcat_strerror", "wildcat_workspace_bytes", "wildcat_draw_uniforms",
            "wildcat_query_radius", "wildcat_compress_kv", "wildcat_wtd_attn", "wildcat_pack_values",
-           "wildcat_rpnys_single_launch", "wildcat_loop_plan")
+           "wildcat_rpnys_single_launch", "wildcat_loop_plan", "wildcat_query_radius_static")
 
 
 class WildcatError(RuntimeError):
@@ -75,6 +75,8 @@ def load_library(force: bool = False):
     lib.wildcat_query_radius.restype = ctypes.c_int
     lib.wildcat_query_radius.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(_Opts),
                                          ctypes.c_void_p]
+    lib.wildcat_query_radius_static.restype = ctypes.c_int
+    lib.wildcat_query_radius_static.argtypes = lib.wildcat_query_radius.argtypes
     lib.wildcat_compress_kv.restype = ctypes.c_int
     lib.wildcat_compress_kv.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
                                         ctypes.c_int32, ctypes.c_uint64, ctypes.POINTER(_Opts),
@@ -227,6 +229,21 @@ def query_radius(Q, kv_heads=None, workspace=None):
     o = _opts(B, Hq, kv_heads, m, 0, _dtype_code(Q), None, workspace=workspace)
     _check(load_library().wildcat_query_radius(Q.data_ptr(), m, d, ctypes.byref(o), out.data_ptr()),
            "wildcat_query_radius")
+    return out
+
+
+def query_radius_static(Q, kv_heads=None, out=None):
+    """wildcat_query_radius_static: R_Q with the library's own scratch (no workspace; see include/wildcat.h).  `out`:
+    optional float64 [B, Hkv] device tensor to write into (then nothing at all is allocated here either)."""
+    import torch
+    _need(Q, "Q", 4)
+    B, Hq, m, d = Q.shape
+    kv_heads = kv_heads or Hq
+    if out is None:
+        out = torch.empty((B, kv_heads), dtype=torch.float64, device=Q.device)
+    o = _opts(B, Hq, kv_heads, m, 0, _dtype_code(Q), None)
+    _check(load_library().wildcat_query_radius_static(Q.data_ptr(), m, d, ctypes.byref(o), out.data_ptr()),
+           "wildcat_query_radius_static")
     return out
 
 

@@ -178,6 +178,7 @@ extern "C" const char *wildcat_strerror(int status) {
     case WILDCAT_EWORKSPACE: return "workspace missing, misaligned or too small";
     case WILDCAT_EHIP: return "HIP runtime call or kernel launch failed";
     case WILDCAT_EUNSUPPORTED: return "request not supported by this build";
+    case WILDCAT_ETOOLARGE: return "shape exceeds the fixed size of the library's own scratch memory";
     default: return "unknown status";
   }
 }

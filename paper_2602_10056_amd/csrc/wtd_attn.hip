@@ -14,6 +14,7 @@
 //   k_wtd_attn_simple   any storage type / width, fp32 arithmetic on the vector ALU (what the MFMA kernels do
 //                       not cover).
 //   k_qnorm_max(_vec), k_radius_final   the query radius R_Q;   k_value_scale, k_pack_values   the packed values.
+#include <atomic>
 #include <climits>
 #include <cmath>
 
@@ -1127,7 +1128,37 @@ int enqueue_pack_values(int P, int r, int dv, const float *v_s, void *v_t, float
 
 using namespace wildcat;
 
-extern "C" int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts, double *r_q_out) {
+// ---- scratch that belongs to the library (wildcat_query_radius_static) ------------------------------------------
+// Per-workgroup maxima of squared norms for callers that cannot hand over a workspace.  Every device the library
+// runs on holds its own copy of this array, at its own address, until the process ends.  In host code the name
+// below is only a handle for hipGetSymbolAddress; the address the kernels get is looked up once per device.
+constexpr int kStaticHeads = 4096;                           // largest batch * q_heads the static entry point takes
+constexpr int kStaticPartials = 4096 + kStaticHeads;         // doubles: 64 KB
+static __device__ __align__(256) double scratch[kStaticPartials];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<double *> scratch_ptr[kMaxDevices];       // per device; racing first calls store the same value
+
+static int static_scratch(double **ptr) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return WILDCAT_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return WILDCAT_EUNSUPPORTED;
+  double *p = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void *sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return WILDCAT_EHIP;
+    p = static_cast<double *>(sym);
+    scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return WILDCAT_OK;
+}
+
+// Shared body of the two query-radius entry points.  `partial` (may be null): device memory for one double per
+// workgroup, `partial_doubles` of them; `own_scratch`: the buffer is the library's (then a shape that does not fit
+// is an error instead of a reason to fall back to atomics).
+static int query_radius_impl(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts, double *r_q_out,
+                             double *partial_buf, size_t partial_doubles, bool own_scratch) {
   if (!Q || !r_q_out || m < 1) return WILDCAT_EINVAL;
   Shape s;
   int rc = resolve_shape(m, m, d, 1, opts, &s);
@@ -1137,12 +1168,13 @@ extern "C" int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const w
   const bool vec = pieces >= 1 && pieces <= kWave && (pieces & (pieces - 1)) == 0;
   const int rows_per_pass = vec ? kThreads / pieces : kThreads;
   int64_t blocks = (m + rows_per_pass - 1) / rows_per_pass;
-  const int64_t cap = (4096 + s.batch * s.q_heads - 1) / (s.batch * s.q_heads);
+  const int64_t heads = (int64_t)s.batch * s.q_heads;
+  const int64_t cap = (4096 + heads - 1) / heads;
   if (blocks > cap) blocks = cap;
   // Optional scratch (see wildcat_query_radius in wildcat.h): one double per workgroup.
-  const size_t scratch = (size_t)s.batch * s.q_heads * blocks * sizeof(double);
-  double *partial = (vec && opts && opts->workspace && !((uintptr_t)opts->workspace & 255) &&
-                     opts->workspace_bytes >= scratch) ? (double *)opts->workspace : nullptr;
+  const size_t want = (size_t)heads * blocks;
+  if (own_scratch && (heads > kStaticHeads || want > partial_doubles)) return WILDCAT_ETOOLARGE;
+  double *partial = (vec && partial_buf && partial_doubles >= want) ? partial_buf : nullptr;
   if (!partial) {
     hipLaunchKernelGGL(k_zero_u64, dim3((s.P + 255) / 256), dim3(256), 0, s.stream, (unsigned long long *)r_q_out, s.P);
     if (hipGetLastError() != hipSuccess) return WILDCAT_EHIP;
@@ -1170,6 +1202,24 @@ extern "C" int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const w
                          s.group, (unsigned long long *)r_q_out);
   }
   return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
+}
+
+extern "C" int wildcat_query_radius(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts, double *r_q_out) {
+  double *buf = nullptr;
+  size_t doubles = 0;
+  if (opts && opts->workspace && !((uintptr_t)opts->workspace & 255)) {
+    buf = (double *)opts->workspace;
+    doubles = opts->workspace_bytes / sizeof(double);
+  }
+  return query_radius_impl(Q, m, d, opts, r_q_out, buf, doubles, false);
+}
+
+extern "C" int wildcat_query_radius_static(const void *Q, int64_t m, int32_t d, const wildcat_opts *opts,
+                                           double *r_q_out) {
+  double *buf = nullptr;
+  const int rc = static_scratch(&buf);
+  if (rc != WILDCAT_OK) return rc;
+  return query_radius_impl(Q, m, d, opts, r_q_out, buf, (size_t)kStaticPartials, true);
 }
 
 extern "C" int wildcat_wtd_attn(const void *Q, const wildcat_coreset *cs, void *out, int64_t m, int32_t d, int32_t r,
