@@ -7,8 +7,10 @@ already resident in HBM.  Workload: 32 query heads sharing 8 key/value heads, n 
 r = 512, bf16 storage (rotary-rotated Gaussian inputs), the shape the headline metric is quoted on.
 
 Prints ONE JSON line: tokens/s of the whole path, the roofline of the dominant kernel (the RPNys step
-kernel, HBM-bound, timed with HIP events on the launch stream), the WtdAttn MFMA rate, the float64 CPU
-oracle timed on the host cores, and exact attention at the same shape for context.
+kernel, HBM-bound, timed with HIP events on the launch stream; `frac` on algorithmic bytes, `frac_traffic` on
+the HBM bytes a counter run measured for the same launch), the WtdAttn MFMA rate, the float64 CPU oracle timed
+on the host cores, exact attention at the same shape for context, the same path at n = 32K / 64K / 128K
+(`scaling_in_n`) and the binned regime of Sec. 2.5 (`binned`: workload 6 with exact attention beside it).
 """
 import argparse
 import ctypes
@@ -60,6 +62,70 @@ def step_loop_bytes(P, n, d, r, es, single_launch, hs=8):
     return float(P) * n * (key_reads * d * es + r * (hs + 16) + float(hs) * r * (r - 1) / 2.0)
 
 
+def device_workload_cfg4(s, dev, tdt):
+    """Workload 4's recipe (N(0,1) entries, rotary rotation of Q and K by position, N(0,1) values, uniforms in
+    [0, 1)) drawn on the device with a seeded generator: the sweep over n needs the distribution, not the
+    oracle's exact numbers, and NumPy takes a minute for the 128K point."""
+    import torch
+    g = torch.Generator(device=dev)
+    g.manual_seed(s.data_seed * 1000003 + s.n)
+
+    def rope(x):
+        n, d = x.shape[-2], x.shape[-1]
+        j = torch.arange(d // 2, device=dev, dtype=torch.float64)
+        ang = torch.arange(n, device=dev, dtype=torch.float64)[:, None] * (10000.0 ** (-2.0 * j / d))[None, :]
+        c, sn = torch.cos(ang).float(), torch.sin(ang).float()
+        out = torch.empty_like(x)
+        out[..., 0::2] = x[..., 0::2] * c - x[..., 1::2] * sn
+        out[..., 1::2] = x[..., 0::2] * sn + x[..., 1::2] * c
+        return out
+
+    Q = rope(torch.randn((s.batch, s.q_heads, s.m, s.d), generator=g, device=dev)).to(tdt)
+    K = rope(torch.randn((s.batch, s.kv_heads, s.n, s.d), generator=g, device=dev)).to(tdt)
+    V = torch.randn((s.batch, s.kv_heads, s.n, s.dv), generator=g, device=dev).to(tdt)
+    u = torch.rand((s.problems, s.r), generator=g, device=dev, dtype=torch.float64)
+    return Q, K, V, u
+
+
+def timed_pass(wc, torch, s, Q, K, V, u, history, reps=3):
+    """ms of the whole path (query radius, CompressKV, WtdAttn) on resident inputs: one warm-up, then `reps` passes."""
+    es = 1 if s.dtype == "bf16" else 0
+    ws = torch.empty(wc.workspace_bytes(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, es, s.bins, history),
+                     dtype=torch.uint8, device=Q.device)
+    out = torch.empty((s.batch, s.q_heads, s.m, s.dv), dtype=Q.dtype, device=Q.device)
+
+    def one():
+        cs = wc.compress_kv(K, V, s.r, wc.query_radius(Q, s.kv_heads, workspace=ws), uniforms=u, workspace=ws,
+                            bins=s.bins, history=history)
+        wc.wtd_attn(Q, cs, out=out)
+
+    one()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        one()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def exact_attention_ms(torch, s, Q, K, V, reps=3):
+    import torch.nn.functional as F
+    Kx = K.repeat_interleave(s.group, dim=1) if s.group > 1 else K
+    Vx = V.repeat_interleave(s.group, dim=1) if s.group > 1 else V
+    for _ in range(2):
+        F.scaled_dot_product_attention(Q, Kx, Vx)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        F.scaled_dot_product_attention(Q, Kx, Vx)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
 def cpu_baseline(w, budget_heads):
     """The float64 oracle, as it stands, on the host cores; whole kv heads of the benchmark workload."""
     import numpy as np
@@ -97,7 +163,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact", action="store_true")
     ap.add_argument("--sweep-n", action="store_true",
-                    help="also time the path at n = 4K ... 128K (same recipe, r fixed) and add it as 'scaling_in_n'")
+                    help="'scaling_in_n' from n = 4K up (default: 32K, 64K, 128K), inputs from the NumPy recipe")
+    ap.add_argument("--no-sweep", action="store_true", help="leave out 'scaling_in_n' and 'binned'")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates profiler byte counters)")
     args = ap.parse_args()
@@ -161,18 +228,23 @@ def main():
     loop_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in loop_ev]))
     ph = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(3)] for m in marks]).mean(axis=0)
     P = s.problems
-    single = wc.rpnys_single_launch(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins,
-                                    args.history)
-    launches = 1 if single else s.r // s.bins
+    plan = wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins, args.history)
+    single = plan["driver"] != 0
+    launches = plan["launches"] * (1 if single else s.r // s.bins)
     # with bins the loop is P * B independent problems of n / B keys and r / B steps
-    loop_bytes = step_loop_bytes(P * s.bins, s.n // s.bins, s.d, s.r // s.bins, es, single,
+    loop_bytes = step_loop_bytes(P * s.bins, s.n // s.bins, s.d, s.r // s.bins, es, bool(plan["keys_in_registers"]),
                                  8 if args.history == "f64" else 4)
     achieved = loop_bytes / (loop_ms * 1e-3) / 1e9
-    traffic = None
+    # HBM bytes of the same launch from the rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of
+    # known size); the file says which launch form it was measured on
+    traffic = traffic_source = None
     tfile = os.path.join(ROOT, "profiles", "rpnys_loop_traffic.json")
     if os.path.exists(tfile) and args.cfg == 4 and args.history == "f64":
         with open(tfile) as f:
-            traffic = json.load(f).get("single_launch" if single else "per_step", {}).get("hbm_bytes_per_launch")
+            rec = json.load(f).get("single_launch" if single else "per_step", {})
+        if rec.get("launches") == launches:
+            traffic = rec.get("hbm_bytes_per_launch")
+            traffic_source = "profiles/rpnys_loop_traffic.json (summary: profiles/rpnys_loop_cfg4_hbm_traffic.md)"
     attn_flops = float(s.batch * s.q_heads) * s.m * (2.0 * s.r * (s.d + s.dv) + 2.0 * s.r)
     attn_tflops = attn_flops / (ph[2] * 1e-3) / 1e12
 
@@ -193,30 +265,20 @@ def main():
         "roofline": {"kernel": ("k_rpnys_persistent (RPNys selection loop, all %d steps in one launch)" % (s.r // s.bins)) if single
                                else "k_step (RPNys selection loop, one launch per step)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "launches": launches, "avg_launch_ms": loop_ms / launches,
-                     "algorithmic_bytes_per_launch": loop_bytes / launches},
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "frac_traffic": (traffic / (loop_ms / launches * 1e-3) / 1e9 / HBM_PEAK_GBS) if traffic else None,
+                     "launches": launches, "avg_launch_ms": loop_ms / launches,
+                     "algorithmic_bytes_per_launch": loop_bytes / launches,
+                     "loop_plan": plan},
         "wtd_attn": {"bound": "mfma", "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS},
     }
 
     if not args.no_exact:
         try:
-            import torch.nn.functional as F
-            Kx = K.repeat_interleave(s.group, dim=1)
-            Vx = V.repeat_interleave(s.group, dim=1)
-            for _ in range(2):
-                F.scaled_dot_product_attention(Q, Kx, Vx)
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(3):
-                F.scaled_dot_product_attention(Q, Kx, Vx)
-            b.record()
-            torch.cuda.synchronize()
-            ems = a.elapsed_time(b) / 3
+            ems = exact_attention_ms(torch, s, Q, K, V)
             res["exact_attention"] = {"impl": "torch scaled_dot_product_attention (ROCm)", "ms": ems,
                                       "tokens_per_s": s.batch * s.n / (ems * 1e-3)}
-            del Kx, Vx
         except Exception as e:           # context only; never fatal
             res["exact_attention"] = {"error": str(e)[:200]}
 
@@ -247,38 +309,57 @@ def main():
         except Exception as e:           # context only; never fatal
             res["fast_mode"] = {"error": str(e)[:200]}
 
-    if args.sweep_n:
+    if not args.no_sweep:
         del Q, K, V, ws, out
         torch.cuda.empty_cache()
+        # ---- the same path at other n (r fixed): near-linear means a flat us/token column ----
         sweep = []
-        for n2 in (4096, 8192, 16384, 32768, 65536, 131072) + ((262144,) if s.bins > 1 else ()):
-            w2 = wl.make(args.cfg, n=n2)
-            s2 = w2["shape"]
-            Q2, K2, V2 = (torch.from_numpy(w2[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
-            u2 = torch.from_numpy(w2["u"]).to(dev)
-            ws2 = torch.empty(wc.workspace_bytes(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d, 1 if es == 2 else 0,
-                                                 s2.bins, args.history), dtype=torch.uint8, device=dev)
-
-            def pass2():
-                cs2 = wc.compress_kv(K2, V2, s2.r, wc.query_radius(Q2, s2.kv_heads, workspace=ws2), uniforms=u2, workspace=ws2,
-                                     bins=s2.bins, history=args.history)
-                return wc.wtd_attn(Q2, cs2)
-
-            pass2()
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(3):
-                pass2()
-            b.record()
-            torch.cuda.synchronize()
-            ms2 = a.elapsed_time(b) / 3
+        on_device = args.cfg == 4 and not args.sweep_n
+        ns = ((4096, 8192, 16384) if args.sweep_n else ()) + (32768, 65536, 131072) \
+            + ((262144,) if args.sweep_n and s.bins > 1 else ())
+        for n2 in ns:
+            s2 = wl.shape(args.cfg, n=n2)
+            if on_device:
+                Q2, K2, V2, u2 = device_workload_cfg4(s2, dev, tdt)
+            else:
+                w2 = wl.make(args.cfg, n=n2)
+                Q2, K2, V2 = (torch.from_numpy(w2[k]).to(dev).to(tdt).contiguous() for k in ("Q", "K", "V"))
+                u2 = torch.from_numpy(w2["u"]).to(dev)
+                del w2
+            ms2 = timed_pass(wc, torch, s2, Q2, K2, V2, u2, args.history)
+            p2 = wc.loop_plan(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.dv, 1 if es == 2 else 0, s2.bins, args.history)
             sweep.append({"n": n2, "ms": ms2, "tokens_per_s": s2.batch * n2 / (ms2 * 1e-3), "us_per_token": ms2 * 1e3 / n2,
-                          "single_launch_loop": wc.rpnys_single_launch(n2, s2.d, s2.r, s2.batch, s2.kv_heads, s2.d,
-                                                                      1 if es == 2 else 0, s2.bins, args.history)})
-            del Q2, K2, V2, ws2, w2
+                          "loop_driver": p2["driver"], "loop_launches": p2["launches"] * (1 if p2["driver"] else s2.r // s2.bins),
+                          "keys_in_registers": bool(p2["keys_in_registers"])})
+            del Q2, K2, V2, u2
             torch.cuda.empty_cache()
-        res["scaling_in_n"] = sweep
+        res["scaling_in_n"] = {"workload": f"{s.name} recipe at other n, r={s.r} fixed"
+                                           + (" (inputs drawn on the device, same distributions)" if on_device else ""),
+                               "points": sweep}
+        # ---- the binned regime (Sec. 2.5), the setting of the paper's FlashAttention-2 comparison ----
+        try:
+            w6 = wl.make(6)
+            s6 = w6["shape"]
+            Q6, K6, V6 = (torch.from_numpy(w6[k]).to(dev).to(torch.bfloat16).contiguous() for k in ("Q", "K", "V"))
+            u6 = torch.from_numpy(w6["u"]).to(dev)
+            ms6 = timed_pass(wc, torch, s6, Q6, K6, V6, u6, args.history, reps=10)
+            # streaming roof: Q, K and V each read twice (R_Q before the temperature and again in WtdAttn; the key
+            # mean before the kernel columns; the value range before the Gram pass) and the output written once
+            tensor_bytes = float(s6.batch) * s6.n * 2
+            roof_bytes = (2 * s6.q_heads * s6.d + 2 * s6.kv_heads * s6.d + 2 * s6.kv_heads * s6.dv
+                          + s6.q_heads * s6.dv) * tensor_bytes
+            roof_ms = roof_bytes / (HBM_PEAK_GBS * 1e9) * 1e3
+            binned = {"workload": f"{s6.name}: {s6.kv_heads} heads, n={s6.n}, d={s6.d}, r={s6.r}, B={s6.bins}, bf16",
+                      "ms": ms6, "tokens_per_s": s6.batch * s6.n / (ms6 * 1e-3),
+                      "streaming_roof_bytes": roof_bytes, "streaming_roof_ms": roof_ms, "frac_of_roof": roof_ms / ms6}
+            if not args.no_exact:
+                ems6 = exact_attention_ms(torch, s6, Q6, K6, V6)
+                binned["exact_attention"] = {"impl": "torch scaled_dot_product_attention (ROCm)", "ms": ems6,
+                                             "tokens_per_s": s6.batch * s6.n / (ems6 * 1e-3)}
+            res["binned"] = binned
+            del Q6, K6, V6, u6, w6
+        except Exception as e:           # context only; never fatal
+            res["binned"] = {"error": str(e)[:200]}
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, s.kv_heads)
