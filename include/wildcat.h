@@ -112,10 +112,11 @@ typedef struct {
                      /* numerically in the span of the coreset).  0 -> 1e-10;       */
                      /* negative -> bare clamp max(p, 0).  See Alg. 1, last two     */
                      /* lines of the loop ("for numerical stability").              */
-  const double *r_q; /* [P] query radius R_Q per problem (input of Alg. 2).         */
+  const double *r_q; /* DEVICE [P] query radius R_Q per problem (input of Alg. 2).  */
                      /* Required by wildcat_compress_kv; fill it with               */
                      /* wildcat_query_radius or pass your own bound.                */
-  const double *uniforms; /* [P, r] pivot uniforms in [0,1), one per RPNys step,    */
+  const double *uniforms; /* DEVICE [P, r] pivot uniforms in [0,1), one per RPNys   */
+                     /* step (a device pointer, like every array of this struct),   */
                      /* or NULL: then u[p, i] is element p*r+i of the stream        */
                      /* wildcat_draw_uniforms(seed, ...) documents.                 */
   int32_t bins;      /* B of Alg. 2 (Sec. 2.5); 0 -> 1.  Bin b is the contiguous block  */
