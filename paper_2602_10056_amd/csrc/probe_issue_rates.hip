@@ -2,7 +2,7 @@
 // issue vector, transcendental, scalar and MFMA instructions, alone and in fixed mixes (no memory traffic).  The
 // WtdAttn kernel's instruction budget per MFMA is derived from these figures.  Every loop is a fixed number of
 // iterations over registers; the only memory written is one clock count per wave.
-//   hipcc --offload-arch=gfx950 -O3 paper_2602_10056_amd/csrc/probe_issue_rates.hip -o probe_issue_rates
+//   hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops paper_2602_10056_amd/csrc/probe_issue_rates.hip -o probe_issue_rates
 // Output per line: s_memtime ticks (core clocks) per unit of ONE wave, and wall time per unit over the launch.
 #include <hip/hip_runtime.h>
 #include <cstdio>
