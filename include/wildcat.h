@@ -174,6 +174,14 @@ typedef struct {
                   /*         reads v_s instead, on the vector ALU (far slower).     */
   float *v_scale; /* [P]     power of two that keeps v_t inside fp16's range:       */
                   /*         2^(e - 14), e = exponent of max |v_s[p]| (1 if 0)      */
+  double *W;      /* [P, B, r/B, n/B] or NULL.  For tests and debugging: if set,    */
+                  /*         wildcat_compress_kv also writes the Nystrom weights    */
+                  /*         themselves (Alg. 1's return value W = h(K_S,K_S)^-1     */
+                  /*         h(K_S,K), per bin: the diagonal blocks of Alg. 2's W;  */
+                  /*         zero rows in unused slots), which the method never     */
+                  /*         needs as a matrix -- only V_S = W V and w = W 1 are    */
+                  /*         used.  O(n r^2 / B^2) extra work per bin, one thread   */
+                  /*         per key.  No other entry point reads it.               */
 } wildcat_coreset;
 
 /* Library version as major*10000 + minor*100 + patch. */

@@ -43,7 +43,7 @@ class _Coreset(ctypes.Structure):
         ("idx", ctypes.c_void_p), ("r_eff", ctypes.c_void_p), ("k_s", ctypes.c_void_p),
         ("v_s", ctypes.c_void_p), ("w", ctypes.c_void_p), ("v_min", ctypes.c_void_p),
         ("v_max", ctypes.c_void_p), ("tau", ctypes.c_void_p), ("v_t", ctypes.c_void_p),
-        ("v_scale", ctypes.c_void_p),
+        ("v_scale", ctypes.c_void_p), ("W", ctypes.c_void_p),
     ]
 
 
@@ -126,13 +126,15 @@ class Coreset:
     v_t: "torch.Tensor" = None      # [B, Hkv, dv, r64] float16 (bf16 storage only): v_s^T / v_scale, MFMA operand
     v_scale: "torch.Tensor" = None  # [B, Hkv] float32 power of two
     bins: int = 1                   # B of Alg. 2; r_eff and tau are [B, Hkv, bins] when bins > 1
+    W: "torch.Tensor" = None        # [B, Hkv, bins, r/bins, n/bins] float64: debug output of compress_kv(weights=True)
 
     def c_struct(self):
         return _Coreset(self.idx.data_ptr(), self.r_eff.data_ptr() if self.r_eff is not None else None,
                         self.k_s.data_ptr(), self.v_s.data_ptr(), self.w.data_ptr(), self.v_min.data_ptr(),
                         self.v_max.data_ptr(), self.tau.data_ptr() if self.tau is not None else None,
                         self.v_t.data_ptr() if self.v_t is not None else None,
-                        self.v_scale.data_ptr() if self.v_scale is not None else None)
+                        self.v_scale.data_ptr() if self.v_scale is not None else None,
+                        self.W.data_ptr() if self.W is not None else None)
 
 
 def _dtype_code(t):
@@ -248,13 +250,14 @@ def query_radius_static(Q, kv_heads=None, out=None):
 
 
 def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, workspace=None, loop_events=None,
-                bins=1, temperature_n="bin", history="f64", loop="auto", wait_limit=0):
+                bins=1, temperature_n="bin", history="f64", loop="auto", wait_limit=0, weights=False):
     """CompressKV (Alg. 2).  K: [B, Hkv, n, d], V: [B, Hkv, n, dv]; r_q: float64 [B, Hkv] on the device;
     uniforms: optional float64 [B*Hkv, r] on the device (else drawn from `seed`); loop_events: optional pair
     of raw hipEvent_t handles recorded around the RPNys loop; bins: B of Alg. 2 (must divide n and r);
     temperature_n: "bin" (length n/B in the temperature) or "full" (n); history: "f64" (pivots identical to a
     float64 reference) or "f32" (fast mode, see wildcat_history in include/wildcat.h); loop: "auto", "steps" or
-    "wave" (wildcat_loop); wait_limit: see wildcat_opts.  Returns a Coreset."""
+    "wave" (wildcat_loop); wait_limit: see wildcat_opts; weights: also return the Nystrom weights W per bin in
+    Coreset.W (debug output, see wildcat_coreset.W).  Returns a Coreset."""
     import torch
     _need(K, "K", 4)
     _need(V, "V", 4)
@@ -290,6 +293,7 @@ def compress_kv(K, V, r, r_q, seed=0, uniforms=None, beta=None, rank_tol=0.0, wo
              if code == WILDCAT_BF16 else None),
         v_scale=torch.empty((B, H), dtype=torch.float32, device=dev) if code == WILDCAT_BF16 else None,
         bins=bins,
+        W=torch.empty((B, H, bins, r // bins, n // bins), dtype=torch.float64, device=dev) if weights else None,
     )
     o = _opts(B, H, H, n, dv, code, beta, rank_tol, r_q.contiguous(), uniforms, workspace)
     o.bins, o.tau_length, o.history = bins, int(temperature_n == "full"), _history_code(history)

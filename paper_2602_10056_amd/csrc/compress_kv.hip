@@ -1881,6 +1881,30 @@ __global__ void k_gather(const T *__restrict__ K, int32_t *__restrict__ idx, int
   if (threadIdx.x == 0 && bins > 1 && s >= 0) idx[(size_t)pr * r + i] = s + (int32_t)((pr % bins) * n);
 }
 
+// Debug / test output: the Nystrom weights themselves, W = h(K_S,K_S)^-1 h(K_S,K) = L^-T F (Alg. 1's return value;
+// the pass itself only ever forms W V and W 1).  One thread per key solves L^T x = F(:, l) by back substitution, its
+// unknowns kept in the output column it is writing (a thread reads back only what it wrote).  grid (ceil(n / 256), P);
+// W is [P][r][n] with n the keys per bin; rows from r_eff on are zero.
+template <typename H>
+__global__ __launch_bounds__(kThreads) void k_debug_weights(const H *__restrict__ F, const double *__restrict__ L,
+                                                            const int32_t *__restrict__ r_eff, int64_t n, int nblk,
+                                                            int slab, int r, double *__restrict__ W) {
+  const int pr = blockIdx.y;
+  const int64_t l = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (l >= n) return;
+  int re = r_eff[pr];
+  re = re < 0 ? 0 : (re > r ? r : re);
+  const H *Fp = F + ((size_t)pr * nblk + l / slab) * r * slab + l % slab;        // row j: + j * slab
+  const double *Lp = L + (size_t)pr * r * r;
+  double *Wp = W + (size_t)pr * r * n + l;                                       // row j: + j * n
+  for (int j = r - 1; j >= re; --j) Wp[(size_t)j * n] = 0.0;
+  for (int j = re - 1; j >= 0; --j) {
+    double acc = (double)Fp[(size_t)j * slab];
+    for (int k = j + 1; k < re; ++k) acc -= Lp[(size_t)k * r + j] * Wp[(size_t)k * n];
+    Wp[(size_t)j * n] = acc / Lp[(size_t)j * r + j];
+  }
+}
+
 // After the persistent loop: a wait that timed out (never expected) is reported as r_eff = -1 everywhere.
 __global__ void k_check_sync(const int *error, int P, int32_t *r_eff) {
   if (*error)
@@ -2180,6 +2204,11 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   hipLaunchKernelGGL((k_gather<T>), dim3(s.r, P), dim3(64), 0, st, K, out->idx, s.n, s.d, s.r, s.bins,
                      (T *)out->k_s);
   LAUNCH_CHECK();
+  if (out->W) {
+    hipLaunchKernelGGL((k_debug_weights<H>), dim3((unsigned)((s.n + kThreads - 1) / kThreads), P), dim3(kThreads), 0, st, F, L,
+                       out->r_eff, s.n, pl.nblk, pl.slab, s.r, out->W);
+    LAUNCH_CHECK();
+  }
   return WILDCAT_OK;
 }
 

@@ -513,6 +513,45 @@ def test_full_size_config5_long_context():
     print(_full_size(5, heads=[2], prefix_r=48))
 
 
+@pytest.mark.parametrize("cfg,ov,kw", [
+    (1, {}, {}),                                                               # fp32, B = 1, resident loop
+    (2, dict(batch=1, q_heads=2, kv_heads=2, n=1000, r=96), dict(loop="steps")),   # bf16, ragged n, one launch per step
+    (6, dict(q_heads=2, kv_heads=2, n=4096), {}),                              # 16 bins of 256 keys, 4 pivots each
+    (2, dict(batch=1, q_heads=1, kv_heads=1, n=2048, r=64), dict(history="f32")),  # fp32 history rows
+])
+def test_nystrom_weights_themselves_match_the_oracle(cfg, ov, kw):
+    """The return value of Alg. 1, W = h(K_S,K_S)^-1 h(K_S,K), entry by entry (the library's debug output; the pass
+    itself only forms W V and W 1).  The oracle builds W as M R with the explicit inverse of the listing, the library
+    by back substitution with the Cholesky factor."""
+    w = wl.make(cfg, **ov)
+    s = w["shape"]
+    Q, K, V = (to_dev(w[k], s.dtype) for k in ("Q", "K", "V"))
+    u = torch.from_numpy(w["u"]).to(dev())
+    r_q = wc.query_radius(Q, s.kv_heads)
+    cs = wc.compress_kv(K, V, s.r, r_q, uniforms=u, bins=s.bins, weights=True, **kw)
+    torch.cuda.synchronize()
+    Wg = cs.W.cpu().numpy()
+    assert Wg.shape == (s.batch, s.kv_heads, s.bins, s.r // s.bins, s.n // s.bins)
+    tol = 1e-9 if kw.get("history", "f64") == "f64" else 1e-4
+    for b in range(s.batch):
+        for h in range(s.kv_heads):
+            Qg = w["Q"][b, h * s.group:(h + 1) * s.group].astype(np.float64)
+            ocs = wo.compress_kv(w["K"][b, h].astype(np.float64), w["V"][b, h].astype(np.float64),
+                                 float(np.sqrt((Qg * Qg).sum(-1).max())), s.beta, s.r, w["u"][b * s.kv_heads + h],
+                                 bins=s.bins)
+            np.testing.assert_array_equal(cs.idx[b, h].cpu().numpy(), ocs.idx)
+            for bn, rp in enumerate(ocs.rps):
+                k = len(rp.S)
+                assert relmax(Wg[b, h, bn, :k], rp.W) <= tol, (b, h, bn, relmax(Wg[b, h, bn, :k], rp.W))
+                assert not Wg[b, h, bn, k:].any()
+                # and the two quantities the method keeps are what this matrix gives
+                nb = s.n // s.bins
+                Vb = w["V"][b, h, bn * nb:(bn + 1) * nb].astype(np.float64)
+                sl = slice(bn * (s.r // s.bins), bn * (s.r // s.bins) + k)
+                assert relmax(cs.v_s[b, h, sl].cpu().numpy().astype(np.float64), Wg[b, h, bn, :k] @ Vb) <= 1e-5
+                assert relmax(cs.w[b, h, sl].cpu().numpy().astype(np.float64), Wg[b, h, bn, :k].sum(1)) <= 1e-5
+
+
 # ---------------------------------------------------------------------------------- bins (Alg. 2 with B > 1)
 @pytest.mark.parametrize("cfg,ov,kw", [
     (6, dict(q_heads=2, kv_heads=2, n=4096), {}),                               # r/B = 4 pivots in each of 16 bins
