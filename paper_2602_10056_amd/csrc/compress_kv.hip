@@ -630,7 +630,9 @@ struct StepShared {
 // from step to step in `carry`, the residual diagonal is searched in registers, and nothing is polled, published or
 // written for other workgroups (the history rows still go to memory: the Gram pass reads them).  The step's uniform
 // and beta / tau^2 arrive as arguments (u_solo, bt_solo): the caller (k_rpnys_solo) has just computed them itself.
-template <typename T, int KPT, int NC, bool POLL, typename H, bool SOLO = false>
+// LEAN: for loops of a few steps (bins of small rank), where the history stream is nothing and the registers are
+// better spent on occupancy: two history rows in flight instead of eight or twelve, none requested early.
+template <typename T, int KPT, int NC, bool POLL, typename H, bool SOLO = false, bool LEAN = false>
 __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int pr, double *g, double *ksc,
                                           StepShared &sh, const KeyRegs<T, KPT, NC> &kr, double (&pown)[KPT],
                                           const double (&flo)[KPT], int *error, long long spin_limit, int hcn,
@@ -653,8 +655,8 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   // keeps its share of the memory system busy during the part of the step that moves no data. ------------------------
   // Rows in flight per thread: eight 16-byte loads with two keys per thread, twelve narrower ones with one key
   // (those workgroups are small and few, and eight 8-byte loads each would not keep the memory system busy).
-  constexpr int U = KPT == 1 ? 12 : 8;
-  constexpr bool EARLY = POLL && !SOLO;
+  constexpr int U = LEAN ? 2 : (KPT == 1 ? 12 : 8);
+  constexpr bool EARLY = POLL && !SOLO && !LEAN;
   HistVec<KPT, H> early[EARLY ? U : 1];
   bool have_early = false;
   if constexpr (EARLY) {
@@ -978,8 +980,11 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 // bounded: if a limit is hit (it never should be) the error word is set and every workgroup leaves.  With
 // NC > 0 a thread keeps the packed features of its keys in registers for the whole loop, which removes the
 // O(n d) key stream from every step.
-template <typename T, int KPT, int NC, typename H>
-__global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
+// LEAN (see rpnys_step) fits the kernel with its keys in registers into 128 registers, i.e. four workgroups per
+// compute unit: the many bins of a binned long sequence (a few steps each) are then all resident in one launch AND
+// read their keys once instead of once per step.
+template <typename T, int KPT, int NC, typename H, bool LEAN = false>
+__global__ __launch_bounds__(kThreads, (NC == 0 || LEAN) ? 4 : 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
                                                                   int hcn) {
   extern __shared__ double dyn[];
   __shared__ StepShared sh;
@@ -999,7 +1004,7 @@ __global__ __launch_bounds__(kThreads, NC == 0 ? 4 : 2) void k_rpnys_persistent(
                             a.npad, l_glob < a.n);
   int i = 0, rc = 1;
   for (; i < a.r; ++i) {
-    rc = rpnys_step<T, KPT, NC, true, H>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
+    rc = rpnys_step<T, KPT, NC, true, H, false, LEAN>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
     if (rc != 1) break;
   }
   if (rc == 0) {
@@ -1939,9 +1944,14 @@ const void *wave_kernel(const Shape &s, int dpad) {
 
 // The workgroup-per-slab loop kernel: `solo` = problems of one slab, `regs` = keys kept in registers (only where
 // keys_fit_registers says so), nc = chunks of four features.
+constexpr int kLeanRank = 16;                                // loops of at most this many steps take the LEAN kernels
+
 template <typename T, int KPT, typename H>
-const void *loop_kernel(bool solo, bool regs, int nc) {
+const void *loop_kernel(bool solo, bool regs, int nc, bool lean = false) {
   constexpr int regs_per_chunk = KPT * (sizeof(T) == 2 ? 2 : 4);
+  if constexpr (16 * regs_per_chunk <= 64) {                  // (bf16, d <= 64: the keys take at most 64 registers)
+    if (lean && regs && !solo && nc == 16) return (const void *)k_rpnys_persistent<T, KPT, 16, H, true>;
+  }
   if constexpr (32 * regs_per_chunk <= 128) {
     if (regs && nc == 32)
       return solo ? (const void *)k_rpnys_solo<T, KPT, 32, H> : (const void *)k_rpnys_persistent<T, KPT, 32, H>;
@@ -1963,8 +1973,8 @@ int device_caps(const Shape &s, const Plan &pl, DeviceCaps *caps) {
   caps->cus = compute_units();
   caps->occ_regs = caps->occ_stream = 0;
   if (keys_fit_registers(s.dtype, pl.kpt, pl.dpad) &&
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_regs, loop_kernel<T, KPT, H>(solo, true, nc), kThreads,
-                                                   base) != hipSuccess)
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_regs, loop_kernel<T, KPT, H>(solo, true, nc, s.r <= kLeanRank),
+                                                   kThreads, base) != hipSuccess)
     caps->occ_regs = 0;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_stream, loop_kernel<T, KPT, H>(solo, false, nc), kThreads,
                                                    base) != hipSuccess)
@@ -1994,7 +2004,7 @@ LoopPlan plan_loop(const Shape &s, const Plan &pl) {
   }
   if (c.kind == kLoopSteps) return lp;
   const bool solo = c.kind == kLoopSolo;
-  const void *fn = loop_kernel<T, KPT, H>(solo, c.keys_in_regs != 0, pl.dpad / kChunk);
+  const void *fn = loop_kernel<T, KPT, H>(solo, c.keys_in_regs != 0, pl.dpad / kChunk, s.r <= kLeanRank);
   const size_t base = loop_base_lds(s, pl);
   lp.c = c; lp.fn = fn; lp.lds = base;
   // History cache: optional, and only if the kernel stays resident with it.
