@@ -160,6 +160,8 @@ def main():
     ap.add_argument("--cfg", type=int, default=4, help="workload catalogue entry (4 = headline shape)")
     ap.add_argument("--history", choices=("f64", "f32"), default="f64",
                     help="precision of the selection loop's history rows (f32 = the fast mode; default f64)")
+    ap.add_argument("--loop", choices=("auto", "steps"), default="auto",
+                    help="selection loop driver (steps = one launch per step; for profiling the two forms)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-exact", action="store_true")
     ap.add_argument("--sweep-n", action="store_true",
@@ -201,7 +203,7 @@ def main():
         if k is not None:
             marks[k][1].record()
         cs = wc.compress_kv(K, V, s.r, r_q, uniforms=u, workspace=ws, loop_events=ev, bins=s.bins,
-                            history=args.history)
+                            history=args.history, loop=args.loop)
         if k is not None:
             marks[k][2].record()
         wc.wtd_attn(Q, cs, out=out)
@@ -228,7 +230,8 @@ def main():
     loop_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in loop_ev]))
     ph = np.array([[m[i].elapsed_time(m[i + 1]) for i in range(3)] for m in marks]).mean(axis=0)
     P = s.problems
-    plan = wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins, args.history)
+    plan = wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, 1 if s.dtype == "bf16" else 0, s.bins, args.history,
+                        args.loop)
     single = plan["driver"] != 0
     launches = plan["launches"] * (1 if single else s.r // s.bins)
     # with bins the loop is P * B independent problems of n / B keys and r / B steps
