@@ -1872,10 +1872,13 @@ __global__ __launch_bounds__(kThreads) void k_solve_small(const double *__restri
 // K_S = original key rows at the pivots (Alg. 2: recentred pivots plus the mean), zero in unused slots.  Pivot indices
 // were found relative to the bin; once the row is read, the slot's index is rewritten as an index into the head's
 // n * bins keys.  grid (r, P), n = keys per bin.
+// `error` (null unless the loop ran as resident launches): a wait inside the loop that ran out (never expected) is
+// reported here, in the last launch of the pass, as r_eff = -1 for every problem.
 template <typename T>
 __global__ void k_gather(const T *__restrict__ K, int32_t *__restrict__ idx, int64_t n, int d, int r, int bins,
-                         T *__restrict__ k_s) {
+                         T *__restrict__ k_s, const int *__restrict__ error, int32_t *__restrict__ r_eff) {
   const int i = blockIdx.x, pr = blockIdx.y;
+  if (error && i == 0 && threadIdx.x == 0 && *error) r_eff[pr] = -1;
   const int s = idx[(size_t)pr * r + i];
   for (int j = threadIdx.x; j < d; j += blockDim.x) {
     T z;
@@ -1908,12 +1911,6 @@ __global__ __launch_bounds__(kThreads) void k_debug_weights(const H *__restrict_
     for (int k = j + 1; k < re; ++k) acc -= Lp[(size_t)k * r + j] * Wp[(size_t)k * n];
     Wp[(size_t)j * n] = acc / Lp[(size_t)j * r + j];
   }
-}
-
-// After the persistent loop: a wait that timed out (never expected) is reported as r_eff = -1 everywhere.
-__global__ void k_check_sync(const int *error, int P, int32_t *r_eff) {
-  if (*error)
-    for (int p = threadIdx.x; p < P; p += blockDim.x) r_eff[p] = -1;
 }
 
 #define LAUNCH_CHECK()                                   \
@@ -2103,6 +2100,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
   const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
   bool done = false;
+  const int *loop_error = nullptr;                           // set if the loop ran as resident launches (see k_gather)
   const void *fn = lp.fn;
   if (fn && one_slab_form) {
     SoloInit in;
@@ -2129,8 +2127,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
       if (hipLaunchKernel(fn, dim3(pl.nblk, gp), dim3(kThreads), args, lp.lds, st) != hipSuccess) return WILDCAT_EHIP;
     }
     a.pr0 = 0;
-    hipLaunchKernelGGL(k_check_sync, dim3(1), dim3(64), 0, st, err_word, P, out->r_eff);
-    LAUNCH_CHECK();
+    loop_error = err_word;
     done = true;
   }
   if (!done) {
@@ -2212,7 +2209,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     if (rc != WILDCAT_OK) return rc;
   }
   hipLaunchKernelGGL((k_gather<T>), dim3(s.r, P), dim3(64), 0, st, K, out->idx, s.n, s.d, s.r, s.bins,
-                     (T *)out->k_s);
+                     (T *)out->k_s, loop_error, out->r_eff);
   LAUNCH_CHECK();
   if (out->W) {
     hipLaunchKernelGGL((k_debug_weights<H>), dim3((unsigned)((s.n + kThreads - 1) / kThreads), P), dim3(kThreads), 0, st, F, L,

@@ -1083,6 +1083,39 @@ __global__ __launch_bounds__(kThreads) void k_pack_values(const float *__restric
   v_t[((size_t)pr * dv + c) * r64 + j] = *reinterpret_cast<const uint16_t *>(&h);
 }
 
+// Both steps in one launch for small coresets (the binned and image-model shapes, where every launch of a few
+// microseconds counts): one workgroup per problem finds the maximum, then packs.  Same values as the two kernels above.
+__global__ __launch_bounds__(kScaleThreads) void k_scale_and_pack_values(const float *__restrict__ v_s, int r, int r64,
+                                                                         int dv, float *__restrict__ v_scale,
+                                                                         uint16_t *__restrict__ v_t) {
+  __shared__ uint32_t sm[kScaleThreads / kWave];
+  const int pr = blockIdx.x, t = threadIdx.x, count = r * dv;
+  const float *src = v_s + (size_t)pr * count;
+  uint32_t b = 0u;
+  for (int gid = t; gid < count; gid += kScaleThreads) {
+    uint32_t x = __float_as_uint(src[gid]) & 0x7fffffffu;
+    if (x > 0x7f800000u) x = 0u;                            // NaN: ignored
+    b = b > x ? b : x;
+  }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) {
+    const uint32_t o = __shfl_xor(b, off, kWave);
+    b = b > o ? b : o;
+  }
+  if (t % kWave == 0) sm[t / kWave] = b;
+  __syncthreads();
+  b = sm[0];
+  for (int k = 1; k < kScaleThreads / kWave; ++k) b = b > sm[k] ? b : sm[k];
+  const float scale = value_scale(b);
+  if (t == 0) v_scale[pr] = scale;
+  const float inv = 1.0f / scale;                           // exact: a power of two
+  for (int gid = t; gid < r64 * dv; gid += kScaleThreads) {
+    const int c = gid / r64, j = gid % r64;
+    const _Float16 h = (_Float16)(j < r ? src[(size_t)j * dv + c] * inv : 0.0f);   // round to nearest even
+    v_t[((size_t)pr * dv + c) * r64 + j] = *reinterpret_cast<const uint16_t *>(&h);
+  }
+}
+
 template <int D, int DV>
 int launch_mfma2(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
   constexpr int NW = attn_waves<D, DV>();
@@ -1118,6 +1151,11 @@ int launch_simple(const Shape &s, const void *Q, const wildcat_coreset *cs, void
 
 int enqueue_pack_values(int P, int r, int dv, const float *v_s, void *v_t, float *v_scale, hipStream_t stream) {
   const int r64 = (r + 63) / 64 * 64;
+  if ((int64_t)r64 * dv <= 16 * kScaleThreads) {             // at most sixteen elements per thread and phase
+    hipLaunchKernelGGL(k_scale_and_pack_values, dim3(P), dim3(kScaleThreads), 0, stream, v_s, r, r64, dv, v_scale,
+                       (uint16_t *)v_t);
+    return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
+  }
   hipLaunchKernelGGL(k_value_scale, dim3(P), dim3(kScaleThreads), 0, stream, v_s, r * dv, v_scale);
   hipLaunchKernelGGL(k_pack_values, dim3((r64 * dv + kThreads - 1) / kThreads, P), dim3(kThreads), 0, stream, v_s,
                      (const float *)v_scale, r, r64, dv, (uint16_t *)v_t);

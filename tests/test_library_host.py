@@ -175,6 +175,21 @@ def test_loop_plan_honours_the_loop_driver_option_and_small_shapes():
     assert p["driver"] == 1 and p["keys_in_registers"] == 0
 
 
+def test_loop_plan_binned_long_sequence_keeps_keys_in_registers_when_four_workgroups_fit():
+    """128 bins x 8 slabs (workload 6).  With the loop kernel of few-step loops at four workgroups per compute unit
+    all 1024 slabs are resident with their keys in registers; at two per compute unit the plan weighs a second
+    launch (7 us more per step) against re-reading all keys every step (10 us) and splits the bins in two groups."""
+    shape = dict(kv_heads=8, bins=16, dtype=wc.WILDCAT_BF16)
+    p = wc.loop_plan(65536, 64, 64, compute_units=256, occ_resident_keys=4, occ_streamed_keys=4, **shape)
+    assert (p["driver"], p["slabs"], p["problems_per_launch"], p["launches"], p["keys_in_registers"],
+            p["workgroups_per_cu"]) == (1, 8, 128, 1, 1, 4)
+    p = wc.loop_plan(65536, 64, 64, compute_units=256, occ_resident_keys=2, occ_streamed_keys=4, **shape)
+    assert (p["driver"], p["problems_per_launch"], p["launches"], p["keys_in_registers"]) == (1, 64, 2, 1)
+    # ... and streams them where no workgroup with keys in registers fits at all
+    p = wc.loop_plan(65536, 64, 64, compute_units=256, occ_resident_keys=0, occ_streamed_keys=4, **shape)
+    assert (p["driver"], p["launches"], p["keys_in_registers"]) == (1, 1, 0)
+
+
 def test_loop_plan_rejects_bad_arguments():
     lib = wc.load_library()
     o = wc._Opts()
