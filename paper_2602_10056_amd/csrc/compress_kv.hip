@@ -581,12 +581,17 @@ __device__ __forceinline__ void key_chunk(const KeyRegs<T, KPT, NC> &kr, int c, 
 #pragma unroll
   for (int k = 0; k < KPT; ++k) {
     if constexpr (sizeof(T) == 2) {
-      uint32_t lo = __float_as_uint(kr.x[c][k][0]), hi = __float_as_uint(kr.x[c][k][1]);
+      const uint32_t lo = __float_as_uint(kr.x[c][k][0]), hi = __float_as_uint(kr.x[c][k][1]);
       // Opaque to the optimiser on purpose: the widened values are loop-invariant across steps, and hoisting them
-      // out of the step loop would need four times the registers of the packed form.
-      asm volatile("" : "+v"(lo), "+v"(hi));
-      x[k][0] = __uint_as_float(lo << 16); x[k][1] = __uint_as_float(lo & 0xffff0000u);
-      x[k][2] = __uint_as_float(hi << 16); x[k][3] = __uint_as_float(hi & 0xffff0000u);
+      // out of the step loop would need four times the registers of the packed form.  The unpacking instructions
+      // themselves are the opaque statements (an empty statement on a copy of the packed word would cost a move).
+      uint32_t u0, u1, u2, u3;
+      asm volatile("v_lshlrev_b32 %0, 16, %1" : "=v"(u0) : "v"(lo));
+      asm volatile("v_and_b32 %0, 0xffff0000, %1" : "=v"(u1) : "v"(lo));
+      asm volatile("v_lshlrev_b32 %0, 16, %1" : "=v"(u2) : "v"(hi));
+      asm volatile("v_and_b32 %0, 0xffff0000, %1" : "=v"(u3) : "v"(hi));
+      x[k][0] = __uint_as_float(u0); x[k][1] = __uint_as_float(u1);
+      x[k][2] = __uint_as_float(u2); x[k][3] = __uint_as_float(u3);
     } else {
 #pragma unroll
       for (int e = 0; e < kChunk; ++e) {
@@ -870,15 +875,27 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
 #pragma unroll
   for (int k = 0; k < KPT; ++k) dot[k] = 0.0;
   if constexpr (NC > 0) {
+    // The pivot's features for chunk c + 1 are read from LDS before chunk c is worked on (the statement that keeps the
+    // widening of the keys inside the step also keeps the compiler from moving LDS reads across it, so left alone
+    // every chunk would start by waiting out an LDS round trip).
+    double ks_next[kChunk];
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) ks_next[e] = ksc[e];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
+      double ks[kChunk];
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) ks[e] = ks_next[e];
+      if (c + 1 < NC) {
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) ks_next[e] = ksc[(c + 1) * kChunk + e];
+      }
       float x[KPT][kChunk];
       key_chunk<T, KPT, NC>(kr, c, x);
 #pragma unroll
       for (int e = 0; e < kChunk; ++e) {
-        const double ks = ksc[c * kChunk + e];
 #pragma unroll
-        for (int k = 0; k < KPT; ++k) dot[k] = fma((double)x[k][e], ks, dot[k]);
+        for (int k = 0; k < KPT; ++k) dot[k] = fma((double)x[k][e], ks[e], dot[k]);
       }
     }
   } else {
