@@ -345,7 +345,9 @@ def main():
             s6 = w6["shape"]
             Q6, K6, V6 = (torch.from_numpy(w6[k]).to(dev).to(torch.bfloat16).contiguous() for k in ("Q", "K", "V"))
             u6 = torch.from_numpy(w6["u"]).to(dev)
-            ms6 = timed_pass(wc, torch, s6, Q6, K6, V6, u6, args.history, reps=10)
+            # (fifty passes: a pass is a dozen launches of a few microseconds, and over fewer the figure is the
+            # pipeline's fill and drain, not its rate)
+            ms6 = timed_pass(wc, torch, s6, Q6, K6, V6, u6, args.history, reps=50)
             # streaming roof: Q, K and V each read twice (R_Q before the temperature and again in WtdAttn; the key
             # mean before the kernel columns; the value range before the Gram pass) and the output written once
             tensor_bytes = float(s6.batch) * s6.n * 2
