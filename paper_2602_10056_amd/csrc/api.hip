@@ -116,10 +116,11 @@ Plan make_plan(const Shape &s) {
   p.nb0 = (int)(nb0 > 512 ? 512 : nb0);
   // Gram pass: about 1024 workgroups in total, each a whole number of slabs; 512 for the matrix-core form (value
   // widths 64, 128, 256 at r > 16), which runs two workgroups per compute unit and whose partial sums cost a pass
-  // of their own to add up.
+  // of their own to add up, and for ranks up to 8 (k_gram_small8: two workgroups per compute unit as well; the
+  // pass there is a few microseconds, and half as many, longer workgroups leave half as many partial sums).
   int rtiles = (s.r + 127) / 128;
   const bool gram_mfma = s.r > 16 && (s.dv == 64 || s.dv == 128 || s.dv == 256);
-  int want = (gram_mfma ? 512 : 1024) / (s.P * rtiles);
+  int want = ((gram_mfma || s.r <= 8) ? 512 : 1024) / (s.P * rtiles);
   if (want < 1) want = 1;
   if (want > p.nblk) want = p.nblk;
   p.slabs_per_chunk = (p.nblk + want - 1) / want;

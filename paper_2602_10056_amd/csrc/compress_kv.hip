@@ -513,6 +513,7 @@ struct StepArgs {
 // HBM read rate on this part.
 typedef double dbl2 __attribute__((ext_vector_type(2)));
 typedef float flt2 __attribute__((ext_vector_type(2)));
+typedef float flt4 __attribute__((ext_vector_type(4)));
 template <int KPT, typename H>
 struct HistVec;
 template <>
@@ -1687,6 +1688,143 @@ __global__ __launch_bounds__(kThreads) void k_gram_small(const H *__restrict__ F
   }
 }
 
+// The same pass for the common widths (d_v a multiple of 8, at most 512) and r <= 8, arranged for fewer and wider
+// loads: a thread owns EIGHT value columns (one 16-byte load of a bf16 row) of four CONSECUTIVE keys at a time, so the
+// four entries of a row of F it needs are adjacent in memory (two 16-byte loads instead of four 8-byte ones), and two
+// such groups are in flight.  About a third of the load instructions per byte of k_gram_small.  Same partial-sum
+// layout; the sums over key groups associate differently (rounding only).
+template <typename T> struct Value8;
+template <> struct Value8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float *__restrict__ p) {
+    a = reinterpret_cast<const float4 *>(p)[0];
+    b = reinterpret_cast<const float4 *>(p)[1];
+  }
+  __device__ __forceinline__ void widen(double (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+template <> struct Value8<bf16_t> {
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16_t *__restrict__ p) { raw = *reinterpret_cast<const uint4 *>(p); }
+  __device__ __forceinline__ void widen(double (&v)[8]) const {
+    float x[kChunk], y[kChunk];
+    unpack_bf16x4(make_uint2(raw.x, raw.y), x);
+    unpack_bf16x4(make_uint2(raw.z, raw.w), y);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { v[c] = (double)x[c]; v[4 + c] = (double)y[c]; }
+  }
+};
+template <typename H> struct Hist4;                            // four consecutive entries of a row of F
+template <> struct Hist4<double> {
+  dbl2 a, b;
+  __device__ __forceinline__ void load(const double *p) {
+    a = reinterpret_cast<const dbl2 *>(p)[0];
+    b = reinterpret_cast<const dbl2 *>(p)[1];
+  }
+  __device__ __forceinline__ void zero() { a = dbl2{0.0, 0.0}; b = a; }
+  __device__ __forceinline__ double at(int q) const { return q == 0 ? a.x : (q == 1 ? a.y : (q == 2 ? b.x : b.y)); }
+};
+template <> struct Hist4<float> {
+  flt4 a;
+  __device__ __forceinline__ void load(const float *p) { a = *reinterpret_cast<const flt4 *>(p); }
+  __device__ __forceinline__ void zero() { a = flt4{0.f, 0.f, 0.f, 0.f}; }
+  __device__ __forceinline__ double at(int q) const { return (double)a[q]; }
+};
+
+template <typename T, int R, typename H>
+__global__ __launch_bounds__(kThreads) void k_gram_small8(const H *__restrict__ F, const T *__restrict__ V, int64_t n,
+                                                          int nblk, int slab, int r, int dv, int tpr,
+                                                          int64_t chunk_keys, int nchunk, double *__restrict__ gpart) {
+  __shared__ double red[kThreads / kWave][kWave][9];
+  const int t = threadIdx.x, ch = blockIdx.x, pr = blockIdx.z;
+  const int lane = t & (kWave - 1), wv = t / kWave;
+  const int kg = t / tpr, cg = t % tpr, kgs = kThreads / tpr;     // key group, column group (tpr = dv / 8), key groups
+  const int col = 8 * cg;
+  constexpr int G = 2;                                           // groups of four keys in flight per thread
+  double acc[R][8], rs[R];
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    rs[j] = 0.0;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[j][c] = 0.0;
+  }
+  // The chunk's keys [lbeg, lend): whole slabs, or a piece of the only slab; slabs and pieces are multiples of 64
+  // keys, so a group of four keys never straddles either.  F is zero beyond n; V does not exist there.
+  const int64_t lbeg = (int64_t)ch * chunk_keys;
+  const int64_t lend = lbeg + chunk_keys < n ? lbeg + chunk_keys : n;
+  const T *Vp = V + (size_t)pr * n * dv + col;
+  const H *Fp = F + (size_t)pr * nblk * r * slab;
+  for (int64_t l0 = lbeg + 4 * kg; l0 < lend; l0 += (int64_t)G * 4 * kgs) {
+    Value8<T> raw[G][4];
+    Hist4<H> f[G][R];
+    bool ok[G][4];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const int64_t l = l0 + (int64_t)g * 4 * kgs;
+      const bool any = l < lend;
+      const int64_t ls = any ? l : lbeg;                          // (a key that exists: its loads are discarded)
+      const int sb = (int)(ls / slab);
+      const H *Fs = Fp + (size_t)sb * r * slab + (ls - (int64_t)sb * slab);
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        if (any && j < r) f[g][j].load(Fs + (size_t)j * slab);
+        else f[g][j].zero();
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        ok[g][q] = l + q < lend;
+        raw[g][q].load(Vp + (size_t)(ok[g][q] ? l + q : ls) * dv);
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        double v[8];
+        raw[g][q].widen(v);
+        if (!ok[g][q]) {
+#pragma unroll
+          for (int c = 0; c < 8; ++c) v[c] = 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+          const double fj = ok[g][q] ? f[g][j].at(q) : 0.0;
+          rs[j] += fj;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[j][c] = fma(fj, v[c], acc[j][c]);
+        }
+      }
+  }
+  const int dv1 = dv + 1;
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    double x[9];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) x[c] = acc[j][c];
+    x[8] = rs[j];
+    for (int off = tpr; off < kWave; off <<= 1)                   // key groups inside the wavefront
+#pragma unroll
+      for (int c = 0; c < 9; ++c) x[c] += __shfl_xor(x[c], off, kWave);
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 9; ++c) red[wv][lane][c] = x[c];
+    __syncthreads();
+    if (wv == 0 && lane < tpr && j < r) {
+      double *dst = gpart + (((size_t)pr * nchunk + ch) * r + j) * dv1;
+      double tot[9];
+#pragma unroll
+      for (int c = 0; c < 9; ++c) tot[c] = red[0][lane][c];
+      for (int w2 = 1; w2 < kThreads / kWave; ++w2)
+#pragma unroll
+        for (int c = 0; c < 9; ++c) tot[c] += red[w2][lane][c];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) dst[col + c] = tot[c];
+      if (lane == 0) dst[dv] = tot[8];
+    }
+  }
+}
+
 // Gram pass for small bins of small rank (one slab, at most 256 keys, r <= R <= 16: the image-model layer shapes and
 // the many-bin settings).  There a problem is a few dozen keys, and what k_gram_small spends on adding up the partial
 // sums of its threads exceeds the work.  Here a thread owns one value column of one piece of the bin's keys and all R
@@ -2171,6 +2309,16 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     else
       hipLaunchKernelGGL((k_gram_cols<T, 16, H>), grid, dim3(kThreads), (size_t)16 * run * sizeof(double), st, F, V, s.n,
                          pl.slab, s.r, s.dv, tp, (int)pl.chunk_keys, pl.nchunk, gpart);
+  } else if (s.r <= 8 && s.dv % 8 == 0 && (s.dv / 8 & (s.dv / 8 - 1)) == 0 && s.dv <= 512 && pl.slab % 64 == 0 &&
+             pl.chunk_keys % 64 == 0) {
+    const int tpr = s.dv / 8;                                // threads per value row: a power of two, at most 64
+    const dim3 grid(pl.nchunk, 1, P);
+    if (s.r <= 4)
+      hipLaunchKernelGGL((k_gram_small8<T, 4, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
+                         pl.chunk_keys, pl.nchunk, gpart);
+    else
+      hipLaunchKernelGGL((k_gram_small8<T, 8, H>), grid, dim3(kThreads), 0, st, F, V, s.n, pl.nblk, pl.slab, s.r, s.dv, tpr,
+                         pl.chunk_keys, pl.nchunk, gpart);
   } else if (s.r <= 16) {
     int tpr = 1;
     while (tpr * 4 < s.dv) tpr <<= 1;                        // threads per value row (<= 64: dv <= kMaxWidth)
