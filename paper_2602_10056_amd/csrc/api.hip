@@ -112,8 +112,12 @@ Plan make_plan(const Shape &s) {
   p.nblk = (int)((s.n + p.slab - 1) / p.slab);
   p.npad = (int64_t)p.nblk * p.slab;
   p.dpad = (s.d + kChunk - 1) / kChunk * kChunk;
+  // Column statistics and packing: pieces of at least 128 keys, at most 512 per problem and about 2048 in all (with
+  // many problems -- bins -- smaller pieces are workgroups that end before they have a second tile in flight).
   int64_t nb0 = (s.n + 127) / 128;
-  p.nb0 = (int)(nb0 > 512 ? 512 : nb0);
+  const int64_t nb0_cap = 2048 / s.P > 1 ? 2048 / s.P : 1;
+  nb0 = nb0 > 512 ? 512 : nb0;
+  p.nb0 = (int)(nb0 > nb0_cap ? nb0_cap : nb0);
   // Gram pass: about 1024 workgroups in total, each a whole number of slabs; 512 for the matrix-core form (value
   // widths 64, 128, 256 at r > 16), which runs two workgroups per compute unit and whose partial sums cost a pass
   // of their own to add up, and for ranks up to 8 (k_gram_small8: two workgroups per compute unit as well; the

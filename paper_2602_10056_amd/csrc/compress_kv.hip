@@ -215,19 +215,35 @@ __global__ __launch_bounds__(kThreads) void k_pack_stats(const T *__restrict__ K
   for (int e = 0; e < EPP; ++e) ksum[e] = 0.0;
   // Tiles that lie wholly in the padding (rows >= n) are not written: with small bins the padding up to a full
   // slab is many times the data, and every reader of the packed copy skips rows >= n.
-  for (int64_t tile0 = key0; tile0 < key1 && tile0 < n; tile0 += tk) {
-    for (int lr = rk; lr < tk; lr += rpp) {
-      const int64_t row = tile0 + lr;
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (row < n) v = *reinterpret_cast<const uint4 *>(Kpr + (size_t)row * d + jk * EPP);
-      float x[EPP];
-      Piece<T>::unpack(v, x);
+  // A thread's pieces of a tile (tk / rpp of them: at most kPackLoads) are fetched one tile ahead: the next tile's
+  // loads are issued as soon as the current one has been copied to LDS, and fly while it is written out.
+  constexpr int kPackLoads = 8;
+  uint4 cur[kPackLoads];                                 // piece q of a thread: tile row rk + q rpp (if < tk)
+  auto fetch = [&](int64_t tile0) {
 #pragma unroll
-      for (int e = 0; e < EPP; ++e) ksum[e] += (double)x[e];
-      uint2 *dst = reinterpret_cast<uint2 *>(tile + (size_t)lr * rowb + jk * 16);
-      dst[0] = make_uint2(v.x, v.y);
-      dst[1] = make_uint2(v.z, v.w);
+    for (int q = 0; q < kPackLoads; ++q) {
+      const int lr = rk + q * rpp;
+      const int64_t row = tile0 + lr;
+      cur[q] = make_uint4(0u, 0u, 0u, 0u);
+      if (lr < tk && row < n) cur[q] = *reinterpret_cast<const uint4 *>(Kpr + (size_t)row * d + jk * EPP);
     }
+  };
+  if (key0 < key1 && key0 < n) fetch(key0);
+  for (int64_t tile0 = key0; tile0 < key1 && tile0 < n; tile0 += tk) {
+#pragma unroll
+    for (int q = 0; q < kPackLoads; ++q) {
+      const int lr = rk + q * rpp;
+      if (lr < tk) {
+        float x[EPP];
+        Piece<T>::unpack(cur[q], x);
+#pragma unroll
+        for (int e = 0; e < EPP; ++e) ksum[e] += (double)x[e];
+        uint2 *dst = reinterpret_cast<uint2 *>(tile + (size_t)lr * rowb + jk * 16);
+        dst[0] = make_uint2(cur[q].x, cur[q].y);
+        dst[1] = make_uint2(cur[q].z, cur[q].w);
+      }
+    }
+    if (tile0 + tk < key1 && tile0 + tk < n) fetch(tile0 + tk);
     __syncthreads();
     for (int item = t; item < nc * tk; item += kThreads) {
       const int l = item % tk, c = item / tk;
