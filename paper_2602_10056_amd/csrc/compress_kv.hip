@@ -653,7 +653,8 @@ struct StepShared {
 // written for other workgroups (the history rows still go to memory: the Gram pass reads them).  The step's uniform
 // and beta / tau^2 arrive as arguments (u_solo, bt_solo): the caller (k_rpnys_solo) has just computed them itself.
 // LEAN: for loops of a few steps (bins of small rank), where the history stream is nothing and the registers are
-// better spent on occupancy: two history rows in flight instead of eight or twelve, none requested early.
+// better spent on occupancy: one history row in flight instead of eight or twelve, none requested early, the pivot's
+// features not read ahead.
 template <typename T, int KPT, int NC, bool POLL, typename H, bool SOLO = false, bool LEAN = false>
 __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int pr, double *g, double *ksc,
                                           StepShared &sh, const KeyRegs<T, KPT, NC> &kr, double (&pown)[KPT],
@@ -677,7 +678,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   // keeps its share of the memory system busy during the part of the step that moves no data. ------------------------
   // Rows in flight per thread: eight 16-byte loads with two keys per thread, twelve narrower ones with one key
   // (those workgroups are small and few, and eight 8-byte loads each would not keep the memory system busy).
-  constexpr int U = LEAN ? 2 : (KPT == 1 ? 12 : 8);
+  constexpr int U = LEAN ? 1 : (KPT == 1 ? 12 : 8);
   constexpr bool EARLY = POLL && !SOLO && !LEAN;
   HistVec<KPT, H> early[EARLY ? U : 1];
   bool have_early = false;
@@ -903,9 +904,15 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
       double ks[kChunk];
 #pragma unroll
       for (int e = 0; e < kChunk; ++e) ks[e] = ks_next[e];
-      if (c + 1 < NC) {
+      if (c + 1 < NC && !LEAN) {
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) ks_next[e] = ksc[(c + 1) * kChunk + e];
+      }
+      if constexpr (LEAN) {                                    // (no registers to spare for reading ahead: every
+        if (c > 0) {                                           // spilled register costs more than the LDS round trip)
+#pragma unroll
+          for (int e = 0; e < kChunk; ++e) ks[e] = ksc[c * kChunk + e];
+        }
       }
       float x[KPT][kChunk];
       key_chunk<T, KPT, NC>(kr, c, x);
