@@ -568,6 +568,36 @@ def test_binned_shrunk_configs(cfg, ov, kw):
     print(cfg, check_against_oracle(w, out, cs, **kw))
 
 
+@pytest.mark.parametrize("cfg,ov,kw", [
+    (6, dict(q_heads=2, kv_heads=2, n=300 * 4, r=5 * 4, bins=4), {}),                       # ragged bins of 300 keys, 5 pivots, bf16
+    (6, dict(q_heads=2, kv_heads=2, n=1000 * 2, r=8 * 2, bins=2), dict(history="f32")),     # 8 pivots, fp32 history rows
+    (1, dict(n=2048, r=16, bins=2), {}),                                                    # fp32 storage, 8 pivots per bin
+    (7, dict(batch=2, n=2048, r=12, bins=4), {}),                                           # d_v = 256, m != n, 3 pivots per bin of 512 keys
+    (2, dict(batch=1, q_heads=2, kv_heads=2, n=1536, r=7), {}),                             # no bins, rank 7
+])
+def test_small_rank_gram_pass_with_wide_loads(cfg, ov, kw):
+    """Ranks of at most 8 per bin on bins of more than 256 keys: the Gram pass runs as k_gram_small8 (eight value
+    columns and four consecutive keys per thread).  Every bin against the oracle."""
+    w = wl.make(cfg, **ov)
+    out, cs = run_gpu(w, **kw)
+    if kw.get("history") == "f32":
+        ocs_ok = 0
+        s = w["shape"]
+        for b in range(s.batch):
+            for h in range(s.kv_heads):
+                Qg = w["Q"][b, h * s.group:(h + 1) * s.group].astype(np.float64)
+                ocs = wo.compress_kv(w["K"][b, h].astype(np.float64), w["V"][b, h].astype(np.float64),
+                                     float(np.sqrt((Qg * Qg).sum(-1).max())), s.beta, s.r, w["u"][b * s.kv_heads + h],
+                                     bins=s.bins)
+                if np.array_equal(cs.idx[b, h].cpu().numpy(), ocs.idx):      # fast mode: pivots are not guaranteed
+                    ocs_ok += 1
+                    assert relmax(cs.v_s[b, h].cpu().numpy().astype(np.float64), ocs.V_S) <= 1e-4
+                    assert relmax(cs.w[b, h].cpu().numpy().astype(np.float64), ocs.w) <= 1e-4
+        assert ocs_ok >= 1
+    else:
+        print(cfg, check_against_oracle(w, out, cs))
+
+
 def test_binned_rank_exhaustion_leaves_holes_that_add_nothing():
     """Every bin's keys take q = 3 distinct values but get 8 slots: each bin stops after <= 3 pivots, the other slots
     stay empty (in the middle of the coreset), and the result is exact attention over all keys."""
