@@ -248,9 +248,12 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 // costs several per cent of the output range.  fp16 carries 11 bits at the same MFMA rate.  Its narrow exponent is
 // handled by construction: P lies in (0, 2^8] with the row maximum >= 1 (see below), and v_t stores V_S^T divided
 // by a per-problem power of two (coreset field v_scale) that is multiplied back in the epilogue.  The normaliser
-// sum_s P_s w_s is accumulated in fp32 on the vector ALU from the unrounded P.
+// sum_s P_s w_s is accumulated in fp32 on the vector ALU from the unrounded P: with weights of both signs it can be
+// hundreds of times smaller than its terms, and P rounded to half precision then costs a tenth of the output range
+// on the long-context workload (measured, with the sum taken on the matrix unit from the rounded P and the weights
+// in three half-precision parts).
 //
-// Workgroup = NW wavefronts (eight, or four for the narrow instantiation), each owning 32 queries; at least two
+// Workgroup = NW wavefronts (eight), each owning 32 queries; two
 // waves per SIMD, so that one wave's exp/convert work overlaps another's MFMAs.  Key tiles of 64 are
 // double-buffered in LDS.  While tile t is computed, the global loads of tile t+2 fly into a few staging
 // registers (each wave fetches 1 KB pieces: lane i holds bytes 16 i .. 16 i + 15); at the start of tile t+1 they
@@ -260,9 +263,9 @@ __global__ __launch_bounds__(kThreads) void k_wtd_attn_simple(const T *__restric
 // the compiler turns every wait for an LDS operand into a wait for ALL outstanding LDS reads, which rules out
 // requesting operands ahead of the MFMAs that use them.)  One barrier per tile.
 //
-// Rows are not padded; bank conflicts are avoided by permuting the 16-byte pieces of a row:
-// piece p of row q is stored in slot p ^ ((q / rows_per_256B) % pieces_per_row).  Sixteen consecutive rows
-// then put the same logical piece into sixteen different 16-byte bank groups.
+// LDS rows are padded by one 16-byte piece (key rows 2 d + 16 bytes, value-column rows 144): sixteen consecutive
+// rows then put the same piece into sixteen different 16-byte bank groups, and a lane's operand addresses are one
+// base plus compile-time offsets.
 //
 // The running maximum is only a reference point for exp(): any reference within 2^8 of the true row maximum
 // keeps every exponential in range, and a change of reference multiplies numerator and normaliser of a row
@@ -286,13 +289,10 @@ __device__ __forceinline__ float pair_sum(float x) {
   return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
 }
 
-// Wavefronts per workgroup.  Eight (a wave fetches half as many pieces per tile and each tile serves twice the
-// queries) unless the narrow instantiation's registers allow three waves per SIMD, which four-wave groups can fill.
-#ifndef WILDCAT_ATTN_NW_NARROW
-#define WILDCAT_ATTN_NW_NARROW 4
-#endif
+// Wavefronts per workgroup: eight, two per SIMD (against four, a wave fetches half as many pieces per tile and each
+// tile serves twice the queries).
 template <int D, int DV>
-constexpr int attn_waves() { return D == 64 && DV == 64 ? WILDCAT_ATTN_NW_NARROW : 8; }
+constexpr int attn_waves() { return 8; }
 
 
 // A 64-key tile of an item: item = (batch*head, query tile) pair, pr its coreset, re the number of filled slots,
@@ -313,17 +313,21 @@ struct AttnCtx {
   int64_t m;
   int r, r64, q_heads, group, kv_heads, qtiles, total_items, stride;
   float scale_log2;
-  int wv, l, g, c32, krow_sw, vrow_sw;
+  int wv, l, g, c32;
+  uint32_t kst, vst;          // byte offsets of this lane's first piece in the key / value tile of an LDS buffer
+  uint32_t kop, vop;          // ... of its MFMA operands: row c32 of the key (value) tile, piece g
   // per-lane byte offsets of this wave's tile loads from the tile's first key row / first value column entry
   // (fixed for the whole kernel; the tile's own address is wave-uniform and stays in scalar registers)
-  uint32_t krow[kKT * (D / 8) / 64 / NW], kcol[kKT * (D / 8) / 64 / NW];   // row, byte in row
-  uint32_t voff[DV * (kKT / 8) / 64 / NW];
+  // this lane's piece 0: key row and byte in the row; byte offset in the value tile (piece e: KROWS_PER_LOAD rows,
+  // VROWS_PER_LOAD value columns further on)
+  uint32_t krow, kcol, voff;
   // This wave's small piece of a tile (all wave-uniform): CW floats at sm_base + pr * sm_stride + k0 * sm_tile,
   // stored at byte sm_dst of the buffer (the second 64, where CW = 128, at sm_dst2).  Wave 0 carries the tile's 64
   // weights, waves 1 .. CLOADS CW entries of v_min | v_max each (so every buffer holds the clip vectors of its
   // tile's problem); the other waves load the weights too and drop them into a spare corner, which keeps the tile
   // code free of branches.
   const float *sm_base;
+  const float *sm_cap;        // entries of v_min are stored as min(v_min, v_max): sm_cap = the matching entries of v_max; else = sm_base
   int sm_stride, sm_tile, sm_dst, sm_dst2;
   // state: the tile being computed and the one after it, whose data is in the staging registers (or on its way)
   TilePos cur, nxt;
@@ -338,9 +342,7 @@ struct AttnCtx {
 template <int D, int DV, int NW>
 struct AttnGeom {
   static constexpr int KPPR = D / 8;                     // 16-byte pieces per key row
-  static constexpr int KRP = KPPR >= 16 ? 1 : 16 / KPPR; // key rows per 256 bytes
   static constexpr int VPPR = kKT / 8;                   // 16-byte pieces per value-column row (= 8)
-  static constexpr int VRP = 16 / VPPR;                  // value rows per 256 bytes (= 2)
   static constexpr int KLOADS = kKT * KPPR / 64 / NW;    // wave-wide 1 KB loads of the key tile per wave
   static constexpr int VLOADS = DV * VPPR / 64 / NW;     // ... of the value tile
   static constexpr int CW = 2 * DV / 64 <= NW - 1 ? 64 : 128;   // clip entries a wave carries per tile
@@ -348,9 +350,13 @@ struct AttnGeom {
   static_assert(KLOADS * NW * 64 == kKT * KPPR && VLOADS * NW * 64 == DV * VPPR, "tiles must split evenly");
   static_assert(DV % 32 == 0 && CLOADS <= NW - 1, "clip vectors are loaded by waves 1 .. CLOADS");
   // One LDS buffer (bytes): key tile | value tile | weights | clip vectors (v_min | v_max)
+  static constexpr int KROWB = 2 * D + 16;               // bytes of a key row in LDS (padded by one piece)
+  static constexpr int VROWB = 2 * kKT + 16;             // bytes of a value-column row in LDS (padded likewise)
+  static constexpr int KROWS_PER_LOAD = NW * 64 / KPPR;  // key rows (value rows) that the workgroup's pieces e and e + 1 lie apart
+  static constexpr int VROWS_PER_LOAD = NW * 64 / VPPR;
   static constexpr int OFF_K = 0;
-  static constexpr int OFF_V = OFF_K + kKT * D * 2;
-  static constexpr int OFF_W = OFF_V + DV * kKT * 2;
+  static constexpr int OFF_V = OFF_K + kKT * KROWB;
+  static constexpr int OFF_W = OFF_V + DV * VROWB;
   static constexpr int OFF_C = OFF_W + kKT * 4;
   static constexpr int OFF_SPARE = OFF_C + 2 * DV * 4;     // where waves without a small piece of their own write
   static constexpr int BYTES = OFF_SPARE + 512;
@@ -397,13 +403,16 @@ __device__ __forceinline__ void attn_stage_tile(AttnCtx<D, DV, NW> &c, const Til
   const char *vtile = reinterpret_cast<const char *>(c.Vt + (size_t)p.pr * DV * c.r64 + p.k0);
 #pragma unroll
   for (int e = 0; e < G::KLOADS; ++e)
-    c.stage[e] = *reinterpret_cast<const u32x4 *>(ktile + (min(c.krow[e], last) * (2 * D) + c.kcol[e]));
+    c.stage[e] = *reinterpret_cast<const u32x4 *>(ktile + (min(c.krow + e * G::KROWS_PER_LOAD, last) * (2 * D) + c.kcol));
 #pragma unroll
-  for (int e = 0; e < G::VLOADS; ++e) c.stage[G::KLOADS + e] = *reinterpret_cast<const u32x4 *>(vtile + c.voff[e]);
-  const float *small = c.sm_base + (size_t)p.pr * c.sm_stride + p.k0 * c.sm_tile;
+  for (int e = 0; e < G::VLOADS; ++e)
+    c.stage[G::KLOADS + e] =
+        *reinterpret_cast<const u32x4 *>(vtile + (size_t)e * G::VROWS_PER_LOAD * c.r64 * 2 + c.voff);
+  const size_t so = (size_t)p.pr * c.sm_stride + p.k0 * c.sm_tile;
+  const float *small = c.sm_base + so, *cap = c.sm_cap + so;
   const uint32_t j = min((uint32_t)c.l, c.sm_tile ? last : 63u);
-  c.stage_small = small[j];
-  if constexpr (G::CW == 128) c.stage_small2 = small[c.sm_tile ? j : j + 64];
+  c.stage_small = fminf(small[j], cap[j]);
+  if constexpr (G::CW == 128) c.stage_small2 = fminf(small[c.sm_tile ? j : j + 64], cap[c.sm_tile ? j : j + 64]);
 }
 
 // Stores the staged tile into LDS buffer `wr`: piece e of wave wv is bytes (e NW + wv) 1024 .. + 1023 of the key
@@ -413,10 +422,10 @@ __device__ __forceinline__ void attn_store_tile(const AttnCtx<D, DV, NW> &c, cha
   using G = AttnGeom<D, DV, NW>;
 #pragma unroll
   for (int e = 0; e < G::KLOADS; ++e)
-    *reinterpret_cast<u32x4 *>(wr + G::OFF_K + (e * NW + c.wv) * 1024 + c.l * 16) = c.stage[e];
+    *reinterpret_cast<u32x4 *>(wr + G::OFF_K + e * (G::KROWS_PER_LOAD * G::KROWB) + c.kst) = c.stage[e];
 #pragma unroll
   for (int e = 0; e < G::VLOADS; ++e)
-    *reinterpret_cast<u32x4 *>(wr + G::OFF_V + (e * NW + c.wv) * 1024 + c.l * 16) = c.stage[G::KLOADS + e];
+    *reinterpret_cast<u32x4 *>(wr + G::OFF_V + e * (G::VROWS_PER_LOAD * G::VROWB) + c.vst) = c.stage[G::KLOADS + e];
   reinterpret_cast<float *>(wr + c.sm_dst)[c.l] = c.stage_small;
   if constexpr (G::CW == 128) reinterpret_cast<float *>(wr + c.sm_dst2)[c.l] = c.stage_small2;
 }
@@ -441,9 +450,9 @@ template <int D, int DV, int NW>
 __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__restrict__ rd, char *__restrict__ wr,
                                           char *__restrict__ ob) {
   using G = AttnGeom<D, DV, NW>;
-  const uint16_t *lkr = reinterpret_cast<const uint16_t *>(rd + G::OFF_K);
-  const uint16_t *lvr = reinterpret_cast<const uint16_t *>(rd + G::OFF_V);
-  const float *lwr = reinterpret_cast<const float *>(rd + G::OFF_W);
+  const char *lkr = rd + G::OFF_K + c.kop;                    // this lane's operand row of the first 32 keys, piece g
+  const char *lvr = rd + G::OFF_V + c.vop;                    // ... of the first 32 value columns
+  const float *lwr = reinterpret_cast<const float *>(rd + G::OFF_W) + 8 * c.g;   // weights of keys 8 g ..
   const int g = c.g, c32 = c.c32;
   const bool last_tile = c.cur.k0 + kKT >= c.cur.re;         // then c.nxt is tile 0 of the workgroup's next item
   const bool more = c.nxt.item < c.total_items;
@@ -462,8 +471,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
   // requests each pair right before the MFMAs that need it and then waits out the LDS latency eight times).
   constexpr int KB = D / 16;
   auto k_operand = [&](int kb, int mt) {
-    const int slot = (2 * kb + g) ^ c.krow_sw;
-    return *reinterpret_cast<const bf16x8 *>(&lkr[(32 * mt + c32) * D + slot * 8]);
+    return *reinterpret_cast<const bf16x8 *>(lkr + 32 * mt * G::KROWB + 32 * kb);
   };
   bf16x8 ka[3][2];
 #pragma unroll
@@ -508,7 +516,9 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
     for (int v = 0; v < 16; ++v) mx = fmaxf(mx, st[mt][v]);
   mx = pair_max(mx) * c.scale_log2;
   const bool jump = mx > c.mref + kRescaleSlack;
-  if (__builtin_amdgcn_ballot_w64(jump) != 0) {
+  if (c.cur.k0 == 0) {
+    c.mref = mx;                                             // first tile of an item: sums and accumulators are zero
+  } else if (__builtin_amdgcn_ballot_w64(jump) != 0) {
     const float alpha = jump ? __builtin_amdgcn_exp2f(c.mref - mx) : 1.0f;
     c.mref = jump ? mx : c.mref;
     c.den *= alpha;
@@ -529,7 +539,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
     for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(st[mt][v], c.scale_log2, nm));
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const float4 wv4 = *reinterpret_cast<const float4 *>(&lwr[32 * mt + 16 * (q / 2) + 8 * g + 4 * (q % 2)]);
+      const float4 wv4 = *reinterpret_cast<const float4 *>(&lwr[32 * mt + 16 * (q / 2) + 4 * (q % 2)]);
       dl = fmaf(p[4 * q + 0], wv4.x, dl);
       dl = fmaf(p[4 * q + 1], wv4.y, dl);
       dl = fmaf(p[4 * q + 2], wv4.z, dl);
@@ -552,7 +562,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
   for (int kb = 0; kb < 4; ++kb) {
 #pragma unroll
     for (int i = 0; i < DV / 32; ++i) {
-      const f16x8 av = *reinterpret_cast<const f16x8 *>(&lvr[(32 * i + c32) * kKT + ((2 * kb + g) ^ c.vrow_sw) * 8]);
+      const f16x8 av = *reinterpret_cast<const f16x8 *>(lvr + 32 * i * G::VROWB + 32 * kb);
       c.acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, pf[kb], c.acc[i], 0, 0, 0);
     }
   }
@@ -579,13 +589,14 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
           const int i = 2 * h + ii, col = 32 * i + 8 * q + 4 * g;
           const float4 lo = *reinterpret_cast<const float4 *>(&clip[col]);
           const float4 hi = *reinterpret_cast<const float4 *>(&clip[DV + col]);
+          // inv = 0 where the guard fails (the accumulators are finite: P <= 2^8, |v_t| < 2^15).  The lower bounds
+          // in LDS are min(v_min, v_max), so the median of three is min(max(o, v_min), v_max) for any bounds.
           floatx4 o = {c.acc[i][4 * q + 0] * inv, c.acc[i][4 * q + 1] * inv, c.acc[i][4 * q + 2] * inv,
                        c.acc[i][4 * q + 3] * inv};
-          if (!ok) o = {0.f, 0.f, 0.f, 0.f};
-          o[0] = fminf(fmaxf(o[0], lo.x), hi.x);
-          o[1] = fminf(fmaxf(o[1], lo.y), hi.y);
-          o[2] = fminf(fmaxf(o[2], lo.z), hi.z);
-          o[3] = fminf(fmaxf(o[3], lo.w), hi.w);
+          o[0] = __builtin_amdgcn_fmed3f(o[0], lo.x, hi.x);
+          o[1] = __builtin_amdgcn_fmed3f(o[1], lo.y, hi.y);
+          o[2] = __builtin_amdgcn_fmed3f(o[2], lo.z, hi.z);
+          o[3] = __builtin_amdgcn_fmed3f(o[3], lo.w, hi.w);
           const bf16x4 ob4 = __builtin_convertvector(o, bf16x4);
           *reinterpret_cast<uint2 *>(mine + c32 * G::OROWB + (col - 64 * h) * 2) = *reinterpret_cast<const uint2 *>(&ob4);
         }
@@ -616,7 +627,7 @@ __device__ __forceinline__ bool attn_tile(AttnCtx<D, DV, NW> &c, const char *__r
 }
 
 template <int D, int DV, int NW>
-__global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void k_wtd_attn_mfma2(
+__global__ __launch_bounds__(NW * 64, 1) void k_wtd_attn_mfma2(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ Ks, const uint16_t *__restrict__ Vt,
     const float *__restrict__ vscale, const float *__restrict__ w, const float *__restrict__ vmin,
     const float *__restrict__ vmax, const int32_t *__restrict__ r_eff, bf16_t *__restrict__ out, int64_t m, int r,
@@ -633,27 +644,30 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void k_wtd_attn_mfma2(
   const int t = threadIdx.x;
   c.wv = __builtin_amdgcn_readfirstlane(t / kWave);          // wave-uniform: keep it in a scalar register
   c.l = t % kWave; c.g = c.l / 32; c.c32 = c.l % 32;
-  c.krow_sw = (c.c32 / G::KRP) % G::KPPR;          // slot permutation of this lane's operand rows
-  c.vrow_sw = (c.c32 / G::VRP) % G::VPPR;
-#pragma unroll
-  for (int e = 0; e < G::KLOADS; ++e) {      // LDS piece (e NW + wv) 64 + l holds key row `row`, logical piece `slot ^ ...`
-    const int idx = (e * NW + c.wv) * 64 + c.l, row = idx / G::KPPR, slot = idx % G::KPPR;
-    c.krow[e] = (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1);      // LDS row `row` holds key pi(row), see attn_tile
-    c.kcol[e] = (slot ^ ((row / G::KRP) % G::KPPR)) * 16;
+  c.kop = c.c32 * G::KROWB + c.g * 16;
+  c.vop = c.c32 * G::VROWB + c.g * 16;
+  {                                           // piece wv 64 + l of the key tile: piece `slot` of LDS row `row`
+    const int idx = c.wv * 64 + c.l, row = idx / G::KPPR, slot = idx % G::KPPR;
+    // LDS row `row` holds key pi(row), see attn_tile; pi commutes with steps of KROWS_PER_LOAD rows
+    static_assert(G::KROWS_PER_LOAD % 16 == 0, "the row permutation acts on bits 2 and 3");
+    c.krow = (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1);
+    c.kcol = slot * 16;
+    c.kst = row * G::KROWB + slot * 16;
   }
-#pragma unroll
-  for (int e = 0; e < G::VLOADS; ++e) {
-    const int idx = (e * NW + c.wv) * 64 + c.l, row = idx / G::VPPR, slot = idx % G::VPPR;
-    c.voff[e] = (uint32_t)(row * r64 + (slot ^ ((row / G::VRP) % G::VPPR)) * 8) * 2;
+  {
+    const int idx = c.wv * 64 + c.l, row = idx / G::VPPR, slot = idx % G::VPPR;
+    c.voff = (uint32_t)(row * r64 + slot * 8) * 2;
+    c.vst = row * G::VROWB + slot * 16;
   }
 
   static_assert(DV % G::CW == 0, "a wave's clip entries lie in v_min or in v_max, not across");
   if (c.wv >= 1 && c.wv <= G::CLOADS) {
     const int q = c.wv - 1;                                   // entries CW q .. CW q + CW - 1 of v_min | v_max
     c.sm_base = q < DV / G::CW ? vmin + G::CW * q : vmax + (G::CW * q - DV);
+    c.sm_cap = q < DV / G::CW ? vmax + G::CW * q : c.sm_base;
     c.sm_stride = DV; c.sm_tile = 0; c.sm_dst = G::OFF_C + 4 * G::CW * q; c.sm_dst2 = c.sm_dst + 256;
   } else {
-    c.sm_base = w;
+    c.sm_base = c.sm_cap = w;
     c.sm_stride = r; c.sm_tile = 1; c.sm_dst = c.wv == 0 ? G::OFF_W : G::OFF_SPARE; c.sm_dst2 = G::OFF_SPARE + 256;
   }
   // An item is one (batch*head, query tile) pair; this workgroup takes items blockIdx.x, + gridDim.x, ...
@@ -1123,8 +1137,7 @@ int launch_mfma2(const Shape &s, const void *Q, const wildcat_coreset *cs, void 
   const int64_t qtiles = (s.m + NW * 32 - 1) / (NW * 32);
   const int64_t total = qtiles * s.batch * s.q_heads;
   if (total > INT32_MAX) return WILDCAT_EUNSUPPORTED;
-  // Persistent grid: as many workgroups as fit on the device at once (two per compute unit by the launch bounds,
-  // three where the registers of the narrower instantiations allow it).
+  // Persistent grid: as many workgroups as fit on the device at once.
   int occ = 0;
   const int per_cu = (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void *)k_wtd_attn_mfma2<D, DV, NW>,
                                                                    NW * 64, 0) == hipSuccess && occ >= 1) ? occ : 8 / NW;
