@@ -163,6 +163,8 @@ Plan make_plan(const Shape &s) {
   p.off_vmaxpart = take(P * p.nb0 * (size_t)s.dv * 4);
   p.off_u = take(P * r * 8);
   p.off_sync = take(4);
+  // pivot records of the resident loop (problems of several slabs only)
+  p.off_mail = take(p.nblk > 1 ? P * mail_words(s.r, p.dpad) * 8 : 0);
   // Resident launches are an option for every loop of at least two steps (how many problems share a launch is
   // decided against the device, see choose_loop); a problem of one slab takes its single-launch form at any rank.
   p.persistent = p.nblk == 1 || s.r >= 2;

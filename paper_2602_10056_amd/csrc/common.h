@@ -15,6 +15,15 @@ constexpr int kMaxWidth = 256;      // largest key / value width d, dv
 constexpr int kMaxRank = 2048;      // largest coreset size r (the core solve keeps 8 columns of r doubles in LDS)
 constexpr int kChunk = 4;           // keys are re-packed as [d/4][n][4] for coalesced per-key access
 
+// Pivot records (resident loop): the record of step i holds i + dpad + 4 doubles -- g_0 .. g_{i-1}, k_s - kbar,
+// p_s, <kbar, k_s - kbar>, two spare -- and the records of a problem lie one after the other.  A word that has not
+// been written yet holds the all-ones pattern (k_init_p fills them; no arithmetic produces that NaN, and widening a
+// narrower NaN leaves low zero bits), so every word says for itself whether it has arrived.
+__host__ __device__ inline size_t mail_offset(int i, int dpad) { return (size_t)i * (i - 1) / 2 + (size_t)i * (dpad + 4); }
+__host__ __device__ inline size_t mail_words(int r, int dpad) { return mail_offset(r, dpad); }
+constexpr long long kMailEmpty = -1;
+
+
 // ---- resolved options -------------------------------------------------------------------------
 struct Shape {
   int batch, q_heads, kv_heads, group, P;
@@ -58,7 +67,7 @@ struct Plan {
   int64_t chunk_keys;  // keys per chunk: slabs_per_chunk * slab, or a piece of the bin (gram_cols)
   bool gram_cols;      // small bins of small rank: the Gram pass runs as k_gram_cols
   size_t off_kbar, off_kp, off_d0, off_p, off_bsum, off_scal, off_F, off_L, off_gpart, off_g,
-      off_mpart, off_vminpart, off_vmaxpart, off_u, off_sync;
+      off_mpart, off_vminpart, off_vmaxpart, off_u, off_sync, off_mail;
   bool persistent;  // the selection loop may run as resident launches (see choose_loop); false: one launch per step
   size_t total;
 };

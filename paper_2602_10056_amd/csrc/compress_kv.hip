@@ -455,7 +455,8 @@ __global__ __launch_bounds__(kThreads) void k_init_p(int64_t n, int64_t npad, in
                                                      double *__restrict__ p0, double *__restrict__ bsum0,
                                                      int32_t *__restrict__ idx, int32_t *__restrict__ r_eff,
                                                      double *__restrict__ u_gen, unsigned long long seed,
-                                                     int *__restrict__ sync_error) {
+                                                     int *__restrict__ sync_error, long long *__restrict__ mail,
+                                                     long long mail_per_problem) {
   __shared__ double sm[kThreads / kWave];
   __shared__ double s_beta_tau;
   const int t = threadIdx.x, b = blockIdx.x, pr = blockIdx.y;
@@ -487,6 +488,9 @@ __global__ __launch_bounds__(kThreads) void k_init_p(int64_t n, int64_t npad, in
   double *bs = bsum0 + (size_t)pr * r * nblk;               // [r][nblk]: row 0 = initial sums, the rest unpublished
   if (t == 0) bs[b] = tot;
   for (int i = 1 + t; i < r; i += kThreads) bs[(size_t)i * nblk + b] = -1.0;
+  if (mail)                                                  // pivot records of the resident loop: nothing has arrived
+    for (long long w = (long long)b * kThreads + t; w < mail_per_problem; w += (long long)nblk * kThreads)
+      mail[(size_t)pr * mail_per_problem + w] = kMailEmpty;
   if (b == 0) {
     for (int i = t; i < r; i += kThreads) {
       idx[(size_t)pr * r + i] = -1;
@@ -520,6 +524,7 @@ struct StepArgs {
   int32_t *idx, *r_eff;
   int64_t n, npad;
   int P, nblk, r, dpad;
+  double *mail;           // [P][mail_words(r, dpad)] pivot records of the resident loop (see rpnys_step, section 3)
   int pr0;                // first problem of this launch (resident loop: the problems run in groups)
   int absent;             // test hook of the give-up path: every workgroup but slab 0 of a problem leaves at once
 };
@@ -621,7 +626,7 @@ __device__ __forceinline__ void key_chunk(const KeyRegs<T, KPT, NC> &kr, int c, 
 }
 
 // Device-coherent accesses for the few values one workgroup writes and another reads within the persistent
-// launch (slab sums, p, history rows): such stores are written through to memory and such loads bypass the
+// launch (slab sums, pivot records, history rows): such stores are written through to memory and such loads bypass the
 // non-coherent caches, so no cache-wide write-back or invalidate is needed between steps.
 __device__ __forceinline__ void st_dev(double *p, double v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -639,7 +644,8 @@ __device__ __forceinline__ float ld_dev(const float *p) {
 struct StepShared {
   double sm[kThreads / kWave];
   int smi[kThreads / kWave];
-  double s_base, s_ps;
+  double s_base, s_ps, s_cb;
+  uint32_t kraw[128];       // the pivot's packed features, handed over by the thread that keeps them in registers
 };
 
 // Returns 1 after a step, 0 (state untouched) when the residual mass is exhausted, -1 if a bounded wait for another
@@ -703,8 +709,12 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     // nothing to collect
   } else if constexpr (POLL) {
     // The slab sums double as arrival flags: a slot holds -1 until its workgroup has finished the previous step
-    // (and its p and history row have completed), so polling them is the synchronisation between steps, and the
-    // successful poll already has the values.  Bounded: gives up after spin_limit rounds.
+    // (whatever else the others need of that step travels in the pivot's record, section 3), so polling them is
+    // the synchronisation between steps, and the successful poll already has the values.  Bounded: gives up after
+    // spin_limit rounds, or when another workgroup has (the error word is looked at on every sixteenth round only:
+    // its load is a trip through memory of its own).  The two barriers of a round also pace the polling: waves that
+    // poll on their own, without them, were measured to slow the whole loop down by 5 % (they crowd the very cache
+    // lines the awaited stores go to).
     long long spins = 0;
     while (true) {
       int ok = 1;
@@ -715,7 +725,8 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
         loc += v;
       }
       if (__syncthreads_and(ok)) break;
-      if (++spins > spin_limit || __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+      if (++spins > spin_limit ||
+          ((spins & 15) == 0 && __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
         if (t == 0) __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         spins = -1;
       }
@@ -769,51 +780,124 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     bstar = bstar < 0 ? 0 : (bstar >= a.nblk ? a.nblk - 1 : bstar);   // only non-finite input can get here
   }
 
-  // ---- 3. the index inside that slab ---------------------------------------------------------------
-  const double *ps = pin + (size_t)bstar * SLAB;
-  double pv[KPT];
-  loc = 0.0;
-#pragma unroll
-  for (int k = 0; k < KPT; ++k) { pv[k] = SOLO ? pown[k] : ld_dev(ps + l_loc + k); loc += pv[k]; }
-  double tot2;
-  inc = block_incl_scan(loc, sh.sm, &tot2);
-  excl = __shfl_up(inc, 1, kWave);
-  if (lane == 0) {
-    excl = 0.0;
-    for (int k = 0; k < t / kWave; ++k) excl += sh.sm[k];
-  }
-  cand = INT_MAX;
-  last_pos = -1;
-  {
-    double run = base + excl;
-#pragma unroll
-    for (int k = 0; k < KPT; ++k) {
-      const double nxt = run + pv[k];
-      if (nxt > target && cand == INT_MAX) cand = l_loc + k;
-      if (pv[k] > 0.0) last_pos = l_loc + k;
-      run = nxt;
-    }
-  }
-  int s_loc = block_reduce<int>(cand, sh.smi, MinOp());
-  if (s_loc == INT_MAX) s_loc = block_reduce<int>(last_pos, sh.smi, MaxOp());
-  if (s_loc < 0) s_loc = 0;                                          // non-finite input only
-  if (s_loc / KPT == t) sh.s_ps = pv[s_loc % KPT];
-  const int64_t s_glob = (int64_t)bstar * SLAB + s_loc;
-
-  // ---- 4. broadcast data of the pivot: its history column g_j = F_j(s) and k_s - kbar ------------------
-  const H *Fs = reinterpret_cast<const H *>(a.F) + ((size_t)pr * a.nblk + bstar) * a.r * SLAB + s_loc;
-  for (int j = t; j < i; j += kThreads)
-    g[j] = SOLO && j < hcn ? (double)hc[(size_t)j * SLAB + s_loc] : (double)ld_dev(Fs + (size_t)j * SLAB);
+  // ---- 3. the pivot: its index inside that slab, its history column g_j = F_j(s) and k_s - kbar ---------------
+  // Resident loop (RECORD): only the workgroup of slab bstar searches -- the slab's residual diagonal is in its own
+  // registers, the first hcn history rows in its LDS -- and it leaves the pivot's record in memory for the other
+  // slabs of the problem, which wait for it instead of repeating the search: nobody reads another slab's p or
+  // history, so p never goes to memory and a step is published without waiting for its stores to complete
+  // (measured on 512-step loops of 64 slabs: 2 us per step).  Not in the LEAN form: in loops of a few steps over
+  // bins of a few slabs every slab searching for itself, all at once, was measured 1 us per step faster than
+  // seven waiting for the eighth.
+  constexpr bool RECORD = POLL && !LEAN;
   const int nc = a.dpad / kChunk;
   const T *Kp = reinterpret_cast<const T *>(a.Kp) + (size_t)pr * nc * a.npad * kChunk;
-  double cbp = 0.0;
-  if (t < a.dpad) {
-    const double kb = a.kbar[(size_t)pr * a.dpad + t];
-    const double v = (double)to_float(Kp[((size_t)(t / kChunk) * a.npad + s_glob) * kChunk + (t % kChunk)]) - kb;
-    ksc[t] = v;
-    cbp = kb * v;
+  int64_t s_glob = -1;
+  double cb;
+  if (RECORD && b != bstar) {
+    const double *rec = a.mail + (size_t)pr * mail_words(a.r, a.dpad) + mail_offset(i, a.dpad);
+    const int nw = i + a.dpad + 2;
+    long long spins = 0;
+    while (true) {
+      int ok = 1;
+      for (int w = t; w < nw; w += kThreads) {
+        const double v = ld_dev(rec + w);
+        ok &= __double_as_longlong(v) != kMailEmpty;
+        if (w < i) g[w] = v;
+        else if (w < i + a.dpad) ksc[w - i] = v;
+        else if (w == i + a.dpad) sh.s_ps = v;
+        else sh.s_cb = v;
+      }
+      if (__syncthreads_and(ok)) break;                      // also publishes g, ksc, s_ps, s_cb to the workgroup
+      if (++spins > spin_limit ||
+          ((spins & 15) == 0 && __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+        if (t == 0) __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        spins = -1;
+      }
+      if (__syncthreads_or(spins < 0)) return -1;
+      __builtin_amdgcn_s_sleep(1);
+    }
+    cb = sh.s_cb;
+  } else {
+    // (resident loop) rows of this slab's history beyond the LDS cache are read back from memory below, by other
+    // threads than wrote them: every thread's stores of the earlier steps have completed before the barriers of
+    // the scan that follows
+    if constexpr (RECORD) __builtin_amdgcn_s_waitcnt(0x0F70);
+    const double *ps = pin + (size_t)bstar * SLAB;
+    double pv[KPT];
+    loc = 0.0;
+#pragma unroll
+    for (int k = 0; k < KPT; ++k) { pv[k] = (SOLO || RECORD) ? pown[k] : ld_dev(ps + l_loc + k); loc += pv[k]; }
+    double tot2;
+    inc = block_incl_scan(loc, sh.sm, &tot2);
+    excl = __shfl_up(inc, 1, kWave);
+    if (lane == 0) {
+      excl = 0.0;
+      for (int k = 0; k < t / kWave; ++k) excl += sh.sm[k];
+    }
+    cand = INT_MAX;
+    last_pos = -1;
+    {
+      double run = base + excl;
+#pragma unroll
+      for (int k = 0; k < KPT; ++k) {
+        const double nxt = run + pv[k];
+        if (nxt > target && cand == INT_MAX) cand = l_loc + k;
+        if (pv[k] > 0.0) last_pos = l_loc + k;
+        run = nxt;
+      }
+    }
+    int s_loc = block_reduce<int>(cand, sh.smi, MinOp());
+    if (s_loc == INT_MAX) s_loc = block_reduce<int>(last_pos, sh.smi, MaxOp());
+    if (s_loc < 0) s_loc = 0;                                          // non-finite input only
+    // (resident loop with the keys in registers: the pivot's features come from the registers of the thread that
+    // owns it, through LDS, instead of from memory -- the same bits, one trip through memory less on the path
+    // that every other slab of the problem is waiting for)
+    constexpr bool FROM_REGS = RECORD && NC > 0;
+    if (s_loc / KPT == t) {
+      sh.s_ps = pv[s_loc % KPT];
+      if constexpr (FROM_REGS) {
+        constexpr int WPC = sizeof(T) == 2 ? 2 : 4;           // 32-bit words per chunk of four features
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+          for (int k = 0; k < KPT; ++k)
+            if (k == s_loc % KPT) {
+#pragma unroll
+              for (int e = 0; e < WPC; ++e) sh.kraw[c * WPC + e] = __float_as_uint(kr.x[c][k][e]);
+            }
+      }
+    }
+    s_glob = (int64_t)bstar * SLAB + s_loc;
+    if constexpr (FROM_REGS) __syncthreads();
+
+    const H *Fs = reinterpret_cast<const H *>(a.F) + ((size_t)pr * a.nblk + bstar) * a.r * SLAB + s_loc;
+    for (int j = t; j < i; j += kThreads)
+      g[j] = (SOLO || RECORD) && j < hcn ? (double)hc[(size_t)j * SLAB + s_loc] : (double)ld_dev(Fs + (size_t)j * SLAB);
+    double cbp = 0.0;
+    if (t < a.dpad) {
+      const double kb = a.kbar[(size_t)pr * a.dpad + t];
+      double v;
+      if constexpr (FROM_REGS) {
+        if constexpr (sizeof(T) == 2) {
+          const uint32_t wd = sh.kraw[t / 2];
+          v = (double)__uint_as_float((t & 1) ? (wd & 0xffff0000u) : (wd << 16)) - kb;
+        } else {
+          v = (double)__uint_as_float(sh.kraw[t]) - kb;
+        }
+      } else {
+        v = (double)to_float(Kp[((size_t)(t / kChunk) * a.npad + s_glob) * kChunk + (t % kChunk)]) - kb;
+      }
+      ksc[t] = v;
+      cbp = kb * v;
+    }
+    cb = block_sum(cbp, sh.sm);                    // <kbar, k_s - kbar>; also publishes g, ksc, s_ps
+    if constexpr (RECORD) {
+      double *rec = a.mail + (size_t)pr * mail_words(a.r, a.dpad) + mail_offset(i, a.dpad);
+      const int nw = i + a.dpad + 2;
+      for (int w = t; w < nw; w += kThreads)
+        st_dev(rec + w, w < i ? g[w] : w < i + a.dpad ? ksc[w - i] : w == i + a.dpad ? sh.s_ps : cb);
+    }
   }
-  const double cb = block_sum(cbp, sh.sm);       // <kbar, k_s - kbar>; also publishes g, ksc, s_ps
   const double inv = 1.0 / sqrt(sh.s_ps);
   const double beta_tau = SOLO ? bt_solo : a.scal[(size_t)pr * 8 + 2];
 
@@ -953,7 +1037,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     if (l >= a.n) { pn = 0.0; f = 0.0; }
     st_dev(Fb + (size_t)i * SLAB + l_loc + k, (H)f);
     fkeep[k] = f;
-    if constexpr (!SOLO) st_dev(pout + l, pn);
+    if constexpr (!SOLO && !(POLL && !LEAN)) st_dev(pout + l, pn);   // (RECORD: nobody else reads it, see section 3)
     pown[k] = pn;
     psum += pn;
   }
@@ -966,9 +1050,13 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     *carry = tot;
     __syncthreads();                                         // the cached row is complete before the next step reads it
   } else {
-    if constexpr (POLL) __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this thread's p and history stores have completed
-    __syncthreads();
-    if (t == 0 && i + 1 < a.r) st_dev(bs_next + b, tot);     // publishes the sum and, with it, the whole step
+    // (LEAN: the other slabs read this one's p and history row, which must have completed: vmcnt(0))
+    if constexpr (POLL && LEAN) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();                                         // the cached row is complete before the next step reads it
+    // Publishes the sum and, with it, the step.  RECORD: the other slabs need nothing else of this one: its history rows
+    // are read back only by its own threads (section 5: each thread its own entries) and by its own search
+    // (section 3, which waits for the stores first), and by the Gram pass after the launch.
+    if (t == 0 && i + 1 < a.r) st_dev(bs_next + b, tot);
   }
 
   // ---- 8. bookkeeping by the slab that owns the pivot -----------------------------------------------------
@@ -1016,7 +1104,7 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 
 // Driver 2: the whole loop in one launch for the problems a.pr0 .. a.pr0 + gridDim.y - 1.  Requires all
 // nblk * gridDim.y workgroups to fit on the device at once (the host sizes the groups against the kernel's occupancy).  The workgroups of one problem synchronise after every step through
-// the slab sums themselves (see POLL above); the values that cross workgroups (p, slab sums, history rows) are
+// the slab sums themselves (see POLL above); the values that cross workgroups (slab sums, pivot records) are
 // stored and loaded device-coherently (st_dev / ld_dev), so no cache-wide fence is needed.  Every wait is
 // bounded: if a limit is hit (it never should be) the error word is set and every workgroup leaves.  With
 // NC > 0 a thread keeps the packed features of its keys in registers for the whole loop, which removes the
@@ -2266,7 +2354,9 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     LAUNCH_CHECK();
     hipLaunchKernelGGL((k_init_p<KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, s.n, pl.npad, pl.nblk, s.r, s.rank_tol,
                        s.bins, tau_n, s.beta, o->r_q, scal, out->tau, d0, p, bsum, out->idx, out->r_eff,
-                       o->uniforms ? (double *)nullptr : u_gen, (unsigned long long)seed, (int *)(ws + pl.off_sync));
+                       o->uniforms ? (double *)nullptr : u_gen, (unsigned long long)seed, (int *)(ws + pl.off_sync),
+                       lp.c.kind == kLoopResident ? (long long *)(ws + pl.off_mail) : (long long *)nullptr,
+                       (long long)mail_words(s.r, pl.dpad));
     LAUNCH_CHECK();
   }
 
@@ -2274,7 +2364,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   a.Kp = Kp; a.kbar = kbar; a.scal = scal; a.floor = d0; a.u = o->uniforms ? o->uniforms : u_gen;
   a.p = p; a.bsum = bsum; a.F = F; a.L = L; a.idx = out->idx; a.r_eff = out->r_eff;
   a.n = s.n; a.npad = pl.npad; a.P = P; a.nblk = pl.nblk; a.r = s.r; a.dpad = pl.dpad;
-  a.pr0 = 0; a.absent = 0;
+  a.pr0 = 0; a.absent = 0; a.mail = (double *)(ws + pl.off_mail);
   if (o->ev_loop_begin && hipEventRecord((hipEvent_t)o->ev_loop_begin, st) != hipSuccess) return WILDCAT_EHIP;
   const size_t step_lds = (size_t)(s.r + pl.dpad) * sizeof(double);
   bool done = false;
