@@ -142,7 +142,10 @@ typedef struct {
                      /* 2000000.  Negative: a hook for testing the give-up path -- every */
                      /* workgroup but the first of each problem leaves at once, the      */
                      /* first gives up at its first unanswered poll, and the call        */
-                     /* reports r_eff = -1 (all kernels still end normally).             */
+                     /* reports r_eff = -1 (all kernels still end normally).  -2: the    */
+                     /* same test for the second wait of a step: the workgroup that has  */
+                     /* found the pivot leaves before handing it over, and the others    */
+                     /* give up at their first unanswered poll for it.                   */
 } wildcat_opts;
 
 /* The compressed cache: output of CompressKV, input of WtdAttn.  All buffers are

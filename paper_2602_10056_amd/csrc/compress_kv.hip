@@ -526,7 +526,8 @@ struct StepArgs {
   int P, nblk, r, dpad;
   double *mail;           // [P][mail_words(r, dpad)] pivot records of the resident loop (see rpnys_step, section 3)
   int pr0;                // first problem of this launch (resident loop: the problems run in groups)
-  int absent;             // test hook of the give-up path: every workgroup but slab 0 of a problem leaves at once
+  int absent;             // test hooks of the give-up paths.  1: every workgroup but slab 0 of a problem leaves at
+                          // once; 2: the workgroup that has found the pivot leaves before handing its record over
 };
 
 // History loads are streaming: each entry is read once per step and the working set (hundreds of MB)
@@ -892,6 +893,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     }
     cb = block_sum(cbp, sh.sm);                    // <kbar, k_s - kbar>; also publishes g, ksc, s_ps
     if constexpr (RECORD) {
+      if (a.absent == 2) return -1;                // (test hook) the others wait for a record that never comes
       double *rec = a.mail + (size_t)pr * mail_words(a.r, a.dpad) + mail_offset(i, a.dpad);
       const int nw = i + a.dpad + 2;
       for (int w = t; w < nw; w += kThreads)
@@ -1119,7 +1121,7 @@ __global__ __launch_bounds__(kThreads, (NC == 0 || LEAN) ? 4 : 2) void k_rpnys_p
   __shared__ StepShared sh;
   constexpr int SLAB = kThreads * KPT;
   const int t = threadIdx.x, b = blockIdx.x, pr = a.pr0 + blockIdx.y;
-  if (a.absent && b > 0) return;                             // (test hook) as if this workgroup never became resident
+  if (a.absent == 1 && b > 0) return;                        // (test hook) as if this workgroup never became resident
   const int64_t l_glob = (int64_t)b * SLAB + t * KPT;
   const int nc = a.dpad / kChunk;
   double pown[KPT], flo[KPT];
@@ -2382,7 +2384,7 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
   } else if (fn) {
     int *err_word = (int *)(ws + pl.off_sync);
     long long spin_limit = s.wait_limit > 0 ? s.wait_limit : 0;   // polls of about a microsecond each
-    a.absent = s.wait_limit < 0;
+    a.absent = s.wait_limit == -2 ? 2 : s.wait_limit < 0;
     int hcn = lp.hcn;
     // Ordinary launches, one per group of problems, back to back on the stream: a group was sized against the
     // device's capacity (choose_loop), so on an otherwise idle device every workgroup of a launch is resident at

@@ -412,6 +412,22 @@ def test_bounded_wait_gives_up_and_reports_it():
     check_against_oracle(w, out2, cs2)
 
 
+def test_bounded_wait_for_the_pivot_record_gives_up_and_reports_it():
+    """The second wait of a step of the resident loop (for the pivot's record), forced from the host (wait_limit = -2:
+    the workgroup that has found the pivot leaves before handing it over): the others give up at their first
+    unanswered poll, every kernel ends normally, r_eff = -1 everywhere, and the next ordinary call is unaffected."""
+    w = wl.make(4, q_heads=4, kv_heads=2, n=4096, r=64)
+    s = w["shape"]
+    p = wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv)
+    assert p["driver"] == 1 and p["slabs"] > 1
+    out, cs = run_gpu(w, wait_limit=-2)
+    assert torch.all(cs.r_eff == -1)
+    assert out.shape == (s.batch, s.q_heads, s.m, s.dv)
+    out2, cs2 = run_gpu(w)
+    assert torch.all(cs2.r_eff == s.r)
+    check_against_oracle(w, out2, cs2)
+
+
 # ---------------------------------------------------------------------------------- rank tolerance (Alg. 1, last lines)
 def _near_duplicate_keys(bins):
     """Keys = 9 prototypes plus noise whose size varies from key to key over 2.5 decades: after a prototype is
