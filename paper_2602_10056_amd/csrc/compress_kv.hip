@@ -662,7 +662,7 @@ struct StepShared {
 // LEAN: for loops of a few steps (bins of small rank), where the history stream is nothing and the registers are
 // better spent on occupancy: one history row in flight instead of eight or twelve, none requested early, the pivot's
 // features not read ahead.
-template <typename T, int KPT, int NC, bool POLL, typename H, bool SOLO = false, bool LEAN = false>
+template <typename T, int KPT, int NC, bool POLL, typename H, bool SOLO = false, bool LEAN = false, bool HANDOVER = true>
 __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int pr, double *g, double *ksc,
                                           StepShared &sh, const KeyRegs<T, KPT, NC> &kr, double (&pown)[KPT],
                                           const double (&flo)[KPT], int *error, long long spin_limit, int hcn,
@@ -786,10 +786,10 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
   // registers, the first hcn history rows in its LDS -- and it leaves the pivot's record in memory for the other
   // slabs of the problem, which wait for it instead of repeating the search: nobody reads another slab's p or
   // history, so p never goes to memory and a step is published without waiting for its stores to complete
-  // (measured on 512-step loops of 64 slabs: 2 us per step).  Not in the LEAN form: in loops of a few steps over
-  // bins of a few slabs every slab searching for itself, all at once, was measured 1 us per step faster than
-  // seven waiting for the eighth.
-  constexpr bool RECORD = POLL && !LEAN;
+  // (measured on 512-step loops of 64 slabs: 2 us per step).  Not in the LEAN form and not for problems of a few
+  // slabs (HANDOVER false, chosen by the host): there every slab searching for itself, all at once, was measured
+  // faster than all but one waiting for that one (1 us per step with 8 slabs, 0.8 with 4, 0.2 with 16).
+  constexpr bool RECORD = POLL && !LEAN && HANDOVER;
   const int nc = a.dpad / kChunk;
   const T *Kp = reinterpret_cast<const T *>(a.Kp) + (size_t)pr * nc * a.npad * kChunk;
   int64_t s_glob = -1;
@@ -1039,7 +1039,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     if (l >= a.n) { pn = 0.0; f = 0.0; }
     st_dev(Fb + (size_t)i * SLAB + l_loc + k, (H)f);
     fkeep[k] = f;
-    if constexpr (!SOLO && !(POLL && !LEAN)) st_dev(pout + l, pn);   // (RECORD: nobody else reads it, see section 3)
+    if constexpr (!SOLO && !(POLL && !LEAN && HANDOVER)) st_dev(pout + l, pn);   // (RECORD: nobody else reads it, see section 3)
     pown[k] = pn;
     psum += pn;
   }
@@ -1052,8 +1052,8 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     *carry = tot;
     __syncthreads();                                         // the cached row is complete before the next step reads it
   } else {
-    // (LEAN: the other slabs read this one's p and history row, which must have completed: vmcnt(0))
-    if constexpr (POLL && LEAN) __builtin_amdgcn_s_waitcnt(0x0F70);
+    // (not RECORD: the other slabs read this one's p and history row, which must have completed: vmcnt(0))
+    if constexpr (POLL && (LEAN || !HANDOVER)) __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();                                         // the cached row is complete before the next step reads it
     // Publishes the sum and, with it, the step.  RECORD: the other slabs need nothing else of this one: its history rows
     // are read back only by its own threads (section 5: each thread its own entries) and by its own search
@@ -1114,7 +1114,7 @@ __global__ __launch_bounds__(kThreads) void k_step(StepArgs a, int i) {
 // LEAN (see rpnys_step) fits the kernel with its keys in registers into 128 registers, i.e. four workgroups per
 // compute unit: the many bins of a binned long sequence (a few steps each) are then all resident in one launch AND
 // read their keys once instead of once per step.
-template <typename T, int KPT, int NC, typename H, bool LEAN = false>
+template <typename T, int KPT, int NC, typename H, bool LEAN = false, bool HANDOVER = true>
 __global__ __launch_bounds__(kThreads, (NC == 0 || LEAN) ? 4 : 2) void k_rpnys_persistent(StepArgs a, int *error, long long spin_limit,
                                                                   int hcn) {
   extern __shared__ double dyn[];
@@ -1135,7 +1135,7 @@ __global__ __launch_bounds__(kThreads, (NC == 0 || LEAN) ? 4 : 2) void k_rpnys_p
                             a.npad, l_glob < a.n);
   int i = 0, rc = 1;
   for (; i < a.r; ++i) {
-    rc = rpnys_step<T, KPT, NC, true, H, false, LEAN>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
+    rc = rpnys_step<T, KPT, NC, true, H, false, LEAN, HANDOVER>(a, i, b, pr, dyn, dyn + a.r, sh, kr, pown, flo, error, spin_limit, hcn);
     if (rc != 1) break;
   }
   if (rc == 0) {
@@ -2210,22 +2210,27 @@ const void *wave_kernel(const Shape &s, int dpad) {
 // The workgroup-per-slab loop kernel: `solo` = problems of one slab, `regs` = keys kept in registers (only where
 // keys_fit_registers says so), nc = chunks of four features.
 constexpr int kLeanRank = 16;                                // loops of at most this many steps take the LEAN kernels
+constexpr int kHandoverSlabs = 24;                           // problems of at least this many slabs hand the pivot over (rpnys_step, section 3)
+
+template <typename T, int KPT, int NC, typename H>
+const void *resident_kernel(bool handover) {
+  return handover ? (const void *)k_rpnys_persistent<T, KPT, NC, H, false, true>
+                  : (const void *)k_rpnys_persistent<T, KPT, NC, H, false, false>;
+}
 
 template <typename T, int KPT, typename H>
-const void *loop_kernel(bool solo, bool regs, int nc, bool lean = false) {
+const void *loop_kernel(bool solo, bool regs, int nc, bool lean = false, bool handover = true) {
   constexpr int regs_per_chunk = KPT * (sizeof(T) == 2 ? 2 : 4);
   if constexpr (16 * regs_per_chunk <= 64) {                  // (bf16, d <= 64: the keys take at most 64 registers)
     if (lean && regs && !solo && nc == 16) return (const void *)k_rpnys_persistent<T, KPT, 16, H, true>;
   }
   if constexpr (32 * regs_per_chunk <= 128) {
-    if (regs && nc == 32)
-      return solo ? (const void *)k_rpnys_solo<T, KPT, 32, H> : (const void *)k_rpnys_persistent<T, KPT, 32, H>;
+    if (regs && nc == 32) return solo ? (const void *)k_rpnys_solo<T, KPT, 32, H> : resident_kernel<T, KPT, 32, H>(handover);
   }
   if constexpr (16 * regs_per_chunk <= 128) {
-    if (regs && nc == 16)
-      return solo ? (const void *)k_rpnys_solo<T, KPT, 16, H> : (const void *)k_rpnys_persistent<T, KPT, 16, H>;
+    if (regs && nc == 16) return solo ? (const void *)k_rpnys_solo<T, KPT, 16, H> : resident_kernel<T, KPT, 16, H>(handover);
   }
-  return solo ? (const void *)k_rpnys_solo<T, KPT, 0, H> : (const void *)k_rpnys_persistent<T, KPT, 0, H>;
+  return solo ? (const void *)k_rpnys_solo<T, KPT, 0, H> : resident_kernel<T, KPT, 0, H>(handover);
 }
 
 inline size_t loop_base_lds(const Shape &s, const Plan &pl) { return (size_t)((s.r + pl.dpad + 1) & ~1) * sizeof(double); }
@@ -2238,10 +2243,12 @@ int device_caps(const Shape &s, const Plan &pl, DeviceCaps *caps) {
   caps->cus = compute_units();
   caps->occ_regs = caps->occ_stream = 0;
   if (keys_fit_registers(s.dtype, pl.kpt, pl.dpad) &&
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_regs, loop_kernel<T, KPT, H>(solo, true, nc, s.r <= kLeanRank),
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_regs, loop_kernel<T, KPT, H>(solo, true, nc, s.r <= kLeanRank,
+                                                                                        pl.nblk >= kHandoverSlabs),
                                                    kThreads, base) != hipSuccess)
     caps->occ_regs = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_stream, loop_kernel<T, KPT, H>(solo, false, nc), kThreads,
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&caps->occ_stream,
+                                                   loop_kernel<T, KPT, H>(solo, false, nc, false, pl.nblk >= kHandoverSlabs), kThreads,
                                                    base) != hipSuccess)
     caps->occ_stream = 0;
   (void)hipGetLastError();                                   // a failed query must not be reported by a later launch check
@@ -2269,7 +2276,7 @@ LoopPlan plan_loop(const Shape &s, const Plan &pl) {
   }
   if (c.kind == kLoopSteps) return lp;
   const bool solo = c.kind == kLoopSolo;
-  const void *fn = loop_kernel<T, KPT, H>(solo, c.keys_in_regs != 0, pl.dpad / kChunk, s.r <= kLeanRank);
+  const void *fn = loop_kernel<T, KPT, H>(solo, c.keys_in_regs != 0, pl.dpad / kChunk, s.r <= kLeanRank, pl.nblk >= kHandoverSlabs);
   const size_t base = loop_base_lds(s, pl);
   lp.c = c; lp.fn = fn; lp.lds = base;
   // History cache: optional, and only if the kernel stays resident with it.
@@ -2357,7 +2364,8 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     hipLaunchKernelGGL((k_init_p<KPT>), dim3(pl.nblk, P), dim3(kThreads), 0, st, s.n, pl.npad, pl.nblk, s.r, s.rank_tol,
                        s.bins, tau_n, s.beta, o->r_q, scal, out->tau, d0, p, bsum, out->idx, out->r_eff,
                        o->uniforms ? (double *)nullptr : u_gen, (unsigned long long)seed, (int *)(ws + pl.off_sync),
-                       lp.c.kind == kLoopResident ? (long long *)(ws + pl.off_mail) : (long long *)nullptr,
+                       lp.c.kind == kLoopResident && pl.nblk >= kHandoverSlabs ? (long long *)(ws + pl.off_mail)
+                                                                              : (long long *)nullptr,
                        (long long)mail_words(s.r, pl.dpad));
     LAUNCH_CHECK();
   }

@@ -372,6 +372,29 @@ def test_both_loop_drivers_agree():
     check_against_oracle(w, o2, c2)
 
 
+@pytest.mark.parametrize("cfg,kw,history", [
+    (1, dict(n=8192, r=40, q_heads=2, kv_heads=2), "f64"),            # fp32 keys kept in registers (d = 64)
+    (1, dict(n=8192, r=40, q_heads=2, kv_heads=2, d=48), "f64"),      # fp32 keys streamed (width not 64 or 128)
+    (4, dict(n=8192, r=40, q_heads=2, kv_heads=2), "f32"),            # bf16 keys in registers, fp32 history
+    (2, dict(batch=1, n=65536, r=24, q_heads=8, kv_heads=8), "f64"),  # two keys per thread, 128 slabs
+])
+def test_resident_loop_that_hands_the_pivot_over_equals_the_per_step_loop(cfg, kw, history):
+    """Problems of many slabs: only the slab that holds the draw searches it and hands the pivot's record to the others
+    (history column, centred key from the owning thread's registers or from the packed copy).  Same bits as the loop
+    with one launch per step, in which every slab searches for itself, for every storage and history type; pivots and
+    weights equal the oracle's."""
+    w = wl.make(cfg, **kw)
+    s = w["shape"]
+    p = wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv, wc.WILDCAT_BF16 if s.dtype == "bf16" else wc.WILDCAT_F32, 1, history)
+    assert p["driver"] == 1 and p["slabs"] >= 24, p
+    o1, c1 = run_gpu(w, history=history)
+    o2, c2 = run_gpu(w, history=history, loop="steps")
+    for a, b in ((c1.idx, c2.idx), (c1.r_eff, c2.r_eff), (c1.k_s, c2.k_s), (c1.w, c2.w), (c1.v_s, c2.v_s), (o1, o2)):
+        assert torch.equal(a, b)
+    if history == "f64":
+        check_against_oracle(w, o1, c1, heads=[0])
+
+
 def test_problems_in_groups_equal_one_launch_per_step():
     """Long contexts: the problems of a call are independent, so when their slabs cannot all be resident at once with
     the keys in registers the resident loop runs them in groups, one launch per group.  On a shape that this device
@@ -416,10 +439,10 @@ def test_bounded_wait_for_the_pivot_record_gives_up_and_reports_it():
     """The second wait of a step of the resident loop (for the pivot's record), forced from the host (wait_limit = -2:
     the workgroup that has found the pivot leaves before handing it over): the others give up at their first
     unanswered poll, every kernel ends normally, r_eff = -1 everywhere, and the next ordinary call is unaffected."""
-    w = wl.make(4, q_heads=4, kv_heads=2, n=4096, r=64)
+    w = wl.make(4, q_heads=4, kv_heads=2, n=8192, r=64)
     s = w["shape"]
     p = wc.loop_plan(s.n, s.d, s.r, s.batch, s.kv_heads, s.dv)
-    assert p["driver"] == 1 and p["slabs"] > 1
+    assert p["driver"] == 1 and p["slabs"] >= 24                # enough slabs for the form that hands the pivot over
     out, cs = run_gpu(w, wait_limit=-2)
     assert torch.all(cs.r_eff == -1)
     assert out.shape == (s.batch, s.q_heads, s.m, s.dv)
