@@ -646,7 +646,6 @@ struct StepShared {
   double sm[kThreads / kWave];
   int smi[kThreads / kWave];
   double s_base, s_ps, s_cb;
-  uint32_t kraw[128];       // the pivot's packed features, handed over by the thread that keeps them in registers
 };
 
 // Returns 1 after a step, 0 (state untouched) when the residual mass is exhausted, -1 if a bounded wait for another
@@ -850,26 +849,8 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     int s_loc = block_reduce<int>(cand, sh.smi, MinOp());
     if (s_loc == INT_MAX) s_loc = block_reduce<int>(last_pos, sh.smi, MaxOp());
     if (s_loc < 0) s_loc = 0;                                          // non-finite input only
-    // (resident loop with the keys in registers: the pivot's features come from the registers of the thread that
-    // owns it, through LDS, instead of from memory -- the same bits, one trip through memory less on the path
-    // that every other slab of the problem is waiting for)
-    constexpr bool FROM_REGS = RECORD && NC > 0;
-    if (s_loc / KPT == t) {
-      sh.s_ps = pv[s_loc % KPT];
-      if constexpr (FROM_REGS) {
-        constexpr int WPC = sizeof(T) == 2 ? 2 : 4;           // 32-bit words per chunk of four features
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-#pragma unroll
-          for (int k = 0; k < KPT; ++k)
-            if (k == s_loc % KPT) {
-#pragma unroll
-              for (int e = 0; e < WPC; ++e) sh.kraw[c * WPC + e] = __float_as_uint(kr.x[c][k][e]);
-            }
-      }
-    }
+    if (s_loc / KPT == t) sh.s_ps = pv[s_loc % KPT];
     s_glob = (int64_t)bstar * SLAB + s_loc;
-    if constexpr (FROM_REGS) __syncthreads();
 
     const H *Fs = reinterpret_cast<const H *>(a.F) + ((size_t)pr * a.nblk + bstar) * a.r * SLAB + s_loc;
     for (int j = t; j < i; j += kThreads)
@@ -877,17 +858,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     double cbp = 0.0;
     if (t < a.dpad) {
       const double kb = a.kbar[(size_t)pr * a.dpad + t];
-      double v;
-      if constexpr (FROM_REGS) {
-        if constexpr (sizeof(T) == 2) {
-          const uint32_t wd = sh.kraw[t / 2];
-          v = (double)__uint_as_float((t & 1) ? (wd & 0xffff0000u) : (wd << 16)) - kb;
-        } else {
-          v = (double)__uint_as_float(sh.kraw[t]) - kb;
-        }
-      } else {
-        v = (double)to_float(Kp[((size_t)(t / kChunk) * a.npad + s_glob) * kChunk + (t % kChunk)]) - kb;
-      }
+      const double v = (double)to_float(Kp[((size_t)(t / kChunk) * a.npad + s_glob) * kChunk + (t % kChunk)]) - kb;
       ksc[t] = v;
       cbp = kb * v;
     }

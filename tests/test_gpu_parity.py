@@ -380,7 +380,7 @@ def test_both_loop_drivers_agree():
 ])
 def test_resident_loop_that_hands_the_pivot_over_equals_the_per_step_loop(cfg, kw, history):
     """Problems of many slabs: only the slab that holds the draw searches it and hands the pivot's record to the others
-    (history column, centred key from the owning thread's registers or from the packed copy).  Same bits as the loop
+    (history column, centred key, p_s).  Same bits as the loop
     with one launch per step, in which every slab searches for itself, for every storage and history type; pivots and
     weights equal the oracle's."""
     w = wl.make(cfg, **kw)
