@@ -123,15 +123,36 @@ __device__ __forceinline__ void from_float(float v, bf16_t *dst) {   // round to
 // ---- deterministic workgroup reductions / scans over kThreads threads ------------------------------------
 // All take one value per thread and combine in a fixed order, so results do not depend on timing.
 
-__device__ __forceinline__ double wave_incl_scan(double v) {
-  const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    double o = __shfl_up(v, off, kWave);
-    if (lane >= off) v += o;
-  }
+// The cross-lane steps are data-parallel-primitive moves (shifts inside rows of 16 lanes, then lane 15 of a row
+// broadcast to the next row and lane 31 to the upper half): they stay inside the vector unit, where a shuffle goes
+// through the LDS crossbar and costs a round trip per step -- six to twelve of them per scan or reduction, several
+// scans and reductions per step of the selection loop.
+//   dpp_move<CTRL, ROWS>(fill, x): lane l receives x of the lane CTRL names, or `fill` where that lane does not exist
+//   or l's row is not in the row mask ROWS.
+constexpr int kDppRowShr = 0x110, kDppWaveShr1 = 0x138, kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
+template <int CTRL, int ROWS = 0xf>
+__device__ __forceinline__ int dpp_move(int fill, int x) {
+  return __builtin_amdgcn_update_dpp(fill, x, CTRL, ROWS, 0xf, false);
+}
+template <int CTRL, int ROWS = 0xf>
+__device__ __forceinline__ double dpp_move(double fill, double x) {
+  const int lo = __builtin_amdgcn_update_dpp(__double2loint(fill), __double2loint(x), CTRL, ROWS, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(__double2hiint(fill), __double2hiint(x), CTRL, ROWS, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+// Inclusive scan of a wavefront under an associative op with identity `id` (lane l: op over lanes 0 .. l).
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_incl_scan_op(T v, T id, Op op) {
+  v = op(v, dpp_move<kDppRowShr + 1>(id, v));
+  v = op(v, dpp_move<kDppRowShr + 2>(id, v));
+  v = op(v, dpp_move<kDppRowShr + 4>(id, v));
+  v = op(v, dpp_move<kDppRowShr + 8>(id, v));
+  v = op(v, dpp_move<kDppRowBcast15, 0xa>(id, v));           // rows 1 and 3 take the total of the row below
+  v = op(v, dpp_move<kDppRowBcast31, 0xc>(id, v));           // rows 2 and 3 take the total of the lower half
   return v;
 }
+struct AddOp { template <typename T> __device__ T operator()(T a, T b) const { return a + b; } };
+__device__ __forceinline__ double wave_incl_scan(double v) { return wave_incl_scan_op(v, 0.0, AddOp()); }
 
 // Inclusive scan across the workgroup; *total receives the sum of all values.  `sm` is >= 4 doubles of LDS.
 __device__ __forceinline__ double block_incl_scan(double v, double *sm, double *total) {
@@ -157,13 +178,18 @@ __device__ __forceinline__ double block_sum(double v, double *sm) {
   return tot;
 }
 
+// (min or max: the value itself serves as the fill of the scan -- combining a value with itself changes nothing)
 template <typename T, typename Op>
 __device__ __forceinline__ T block_reduce(T v, T *sm, Op op) {
   const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
-#pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) v = op(v, __shfl_xor(v, off, kWave));
+  v = op(v, dpp_move<kDppRowShr + 1>(v, v));
+  v = op(v, dpp_move<kDppRowShr + 2>(v, v));
+  v = op(v, dpp_move<kDppRowShr + 4>(v, v));
+  v = op(v, dpp_move<kDppRowShr + 8>(v, v));
+  v = op(v, dpp_move<kDppRowBcast15, 0xa>(v, v));
+  v = op(v, dpp_move<kDppRowBcast31, 0xc>(v, v));            // lane 63 now holds the wavefront's result
   __syncthreads();
-  if (lane == 0) sm[wv] = v;
+  if (lane == kWave - 1) sm[wv] = v;
   __syncthreads();
   T out = sm[0];
 #pragma unroll

@@ -741,7 +741,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     mass = *carry;
   } else {
     inc = block_incl_scan(loc, sh.sm, &mass);
-    excl = __shfl_up(inc, 1, kWave);               // exclusive prefix = inclusive prefix of thread t-1
+    excl = dpp_move<kDppWaveShr1>(0.0, inc);       // exclusive prefix = inclusive prefix of thread t-1
     if (lane == 0) {
       excl = 0.0;
       for (int k = 0; k < t / kWave; ++k) excl += sh.sm[k];
@@ -829,7 +829,7 @@ __device__ __forceinline__ int rpnys_step(const StepArgs &a, int i, int b, int p
     for (int k = 0; k < KPT; ++k) { pv[k] = (SOLO || RECORD) ? pown[k] : ld_dev(ps + l_loc + k); loc += pv[k]; }
     double tot2;
     inc = block_incl_scan(loc, sh.sm, &tot2);
-    excl = __shfl_up(inc, 1, kWave);
+    excl = dpp_move<kDppWaveShr1>(0.0, inc);
     if (lane == 0) {
       excl = 0.0;
       for (int k = 0; k < t / kWave; ++k) excl += sh.sm[k];
