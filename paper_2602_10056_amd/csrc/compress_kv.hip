@@ -1239,16 +1239,18 @@ __device__ __forceinline__ void wave_sync_lds() {            // LDS written by o
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
 }
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
-}
 __device__ __forceinline__ double lane_value(double v, int lane) {      // lane: the same in every lane
   const long long b = __double_as_longlong(v);
   const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, lane);
   const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)b >> 32), lane);
   return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+// Reductions over the wavefront, in every lane: a scan on data-parallel-primitive moves leaves the result in the last
+// lane, from where it is read into a scalar register.
+__device__ __forceinline__ double wave_sum(double v) { return lane_value(wave_incl_scan(v), kWave - 1); }
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_reduce_idem(T v, Op op) {             // op(x, x) = x: minimum or maximum
+  return wave_incl_scan_op(v, v, op);                                   // (the value itself as fill; result in lane 63)
 }
 
 template <typename T, int KW, int DP, typename H>
@@ -1306,8 +1308,7 @@ __global__ __launch_bounds__(kThreads, KW * DP <= 64 ? 2 : 1) void k_rpnys_wave(
     if (l0 + k >= a.n) sq[k] = 0.0;
     mx = fmax(mx, sq[k]);
   }
-#pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) mx = fmax(mx, __shfl_xor(mx, off, kWave));
+  mx = lane_value(wave_reduce_idem(mx, MaxOp()), kWave - 1);
   double tau, beta_tau, rk;
   temperature(mx, in.r_q[pr / in.bins], in.tau_n, in.beta, &tau, &beta_tau, &rk);   // every lane, same value
   if (lane == 0) {
@@ -1347,14 +1348,8 @@ __global__ __launch_bounds__(kThreads, KW * DP <= 64 ? 2 : 1) void k_rpnys_wave(
     double loc = 0.0;
 #pragma unroll
     for (int k = 0; k < KW; ++k) loc += p[k];
-    double inc = loc;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const double up = __shfl_up(inc, off, kWave);
-      if (lane >= off) inc += up;
-    }
-    double run = __shfl_up(inc, 1, kWave);
-    if (lane == 0) run = 0.0;
+    const double inc = wave_incl_scan(loc);
+    double run = dpp_move<kDppWaveShr1>(0.0, inc);           // exclusive prefix (lane 0: the fill, 0)
     int cand = INT_MAX, last_pos = -1;
 #pragma unroll
     for (int k = 0; k < KW; ++k) {
@@ -1363,14 +1358,10 @@ __global__ __launch_bounds__(kThreads, KW * DP <= 64 ? 2 : 1) void k_rpnys_wave(
       if (p[k] > 0.0) last_pos = l0 + k;
       run = nxt;
     }
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-      cand = min(cand, __shfl_xor(cand, off, kWave));
-      last_pos = max(last_pos, __shfl_xor(last_pos, off, kWave));
-    }
+    cand = __builtin_amdgcn_readlane(wave_reduce_idem(cand, MinOp()), kWave - 1);
+    last_pos = __builtin_amdgcn_readlane(wave_reduce_idem(last_pos, MaxOp()), kWave - 1);
     int s_loc = cand == INT_MAX ? last_pos : cand;
     if (s_loc < 0) s_loc = 0;                                // non-finite input only
-    s_loc = __builtin_amdgcn_readfirstlane(s_loc);
     const int owner = s_loc / KW;
     const bool second = KW == 2 && (s_loc % KW) != 0;
     const double p_s0 = lane_value(p[0], owner), p_s1 = lane_value(p[KW - 1], owner);
