@@ -11,6 +11,8 @@
 //   k_wtd_attn_decode   the same arithmetic at decode shape (few queries per head): the key tiles are dealt out to
 //                       the waves of a workgroup, operands straight from memory.
 //   k_wtd_attn_mfma_f32 fp32 storage (d / dv of 64 / 64, 64 / 256, 128 / 128) on v_mfma_f32_32x32x2_f32.
+//   k_wtd_attn_f32_split  the same at few queries in all (dv <= 128): the waves of a workgroup share one block of 32
+//                       queries and split its key tiles, operands straight from memory.
 //   k_wtd_attn_simple   any storage type / width, fp32 arithmetic on the vector ALU (what the MFMA kernels do
 //                       not cover).
 //   k_qnorm_max(_vec), k_radius_final   the query radius R_Q;   k_value_scale, k_pack_values   the packed values.
@@ -1022,10 +1024,168 @@ __global__ __launch_bounds__(NWF * 64) void k_wtd_attn_mfma_f32(
   }
 }
 
+
+// Few queries in all (the image-model layer shapes: a few thousand queries per head, a handful of heads): 32 queries
+// per wavefront leave most SIMDs without a wave and the others with one, which waits out every load and every MFMA
+// chain.  Here a workgroup still owns one block of 32 queries, but its NS wavefronts share out the key tiles of the
+// coreset (tile wv, wv + NS, ...), each with its own running reference, normaliser and accumulators, and combine them
+// through LDS at the end -- as the bf16 decode kernel does.  No tile is used by two waves of a workgroup, so nothing
+// is staged in LDS: a lane reads its MFMA operands straight from memory (the coreset is small and stays in the L2),
+// in the same arrangement as the kernel above.  Same arithmetic per tile; the tiles are summed in another order.
+// grid (ceil(m / 32), batch * q_heads); dynamic LDS NS x (DV / 2) x 64 floats.
+template <int D, int DV, int NS>
+__global__ __launch_bounds__(NS * 64) void k_wtd_attn_f32_split(
+    const float *__restrict__ Q, const float *__restrict__ Ks, const float *__restrict__ Vs,
+    const float *__restrict__ w, const float *__restrict__ vmin, const float *__restrict__ vmax,
+    const int32_t *__restrict__ r_eff, float *__restrict__ out, int64_t m, int r, int q_heads, int group,
+    float scale_log2) {
+  constexpr int NR = DV / 32 * 16;                            // accumulator registers per lane
+  static_assert(NR % (4 * NS) == 0, "every wave finishes whole groups of four columns");
+  __shared__ float s_ref[NS][64], s_den[NS][64];
+  extern __shared__ float s_acc[];                            // [NS][NR][64]
+  const int t = threadIdx.x, wv = t / kWave, l = t % kWave, g = l / 32, c32 = l % 32;
+  const int bh = blockIdx.y, b = bh / q_heads, hq = bh % q_heads;
+  const int pr = b * (q_heads / group) + hq / group;
+  const int re = r_eff ? max(min(r_eff[pr], r), 1) : r;
+  const int64_t q0 = (int64_t)blockIdx.x * 32;
+  const int64_t qrow = q0 + c32 < m ? q0 + c32 : m - 1;
+  float qf[D / 2];                                            // this lane's half of its query row: features 8 t + 4 g + u
+  {
+    const float4 *src = reinterpret_cast<const float4 *>(Q + ((size_t)bh * m + qrow) * D + 4 * g);
+#pragma unroll
+    for (int tt = 0; tt < D / 8; ++tt) {
+      const float4 v = src[2 * tt];
+      qf[4 * tt + 0] = v.x; qf[4 * tt + 1] = v.y; qf[4 * tt + 2] = v.z; qf[4 * tt + 3] = v.w;
+    }
+  }
+  floatx16 acc[DV / 32];
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+  float mrun = -INFINITY, den = 0.0f;
+  const float *Kp = Ks + (size_t)pr * r * D, *Vp = Vs + (size_t)pr * r * DV, *wp = w + (size_t)pr * r;
+
+  for (int k0 = wv * kFT; k0 < re; k0 += NS * kFT) {
+    // ---- S^T = K Q^T: A operand = key k0 + c32 (clamped; masked below), features 8 t + 4 g .. + 3 ------------------
+    const float *krow = Kp + (size_t)min(k0 + c32, re - 1) * D + 4 * g;
+    floatx16 st;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) st[v] = 0.0f;
+#pragma unroll
+    for (int tt = 0; tt < D / 8; ++tt) {
+      const float4 a = *reinterpret_cast<const float4 *>(krow + 8 * tt);
+      st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, qf[4 * tt + 0], st, 0, 0, 0);
+      st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, qf[4 * tt + 1], st, 0, 0, 0);
+      st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, qf[4 * tt + 2], st, 0, 0, 0);
+      st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, qf[4 * tt + 3], st, 0, 0, 0);
+    }
+    // register v <-> key k0 + 8 (v / 4) + 4 g + v % 4
+    float wk[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int key = k0 + 8 * (v / 4) + 4 * g + (v % 4);
+      wk[v] = wp[min(key, re - 1)];
+      st[v] = key < re ? st[v] * scale_log2 : -INFINITY;
+      mx = fmaxf(mx, st[v]);
+    }
+    mx = pair_max(mx);
+    const float mnew = fmaxf(mrun, mx);                       // finite: key k0 exists
+    const float alpha = __builtin_amdgcn_exp2f(mrun - mnew);
+    mrun = mnew;
+    float dl = 0.0f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      st[v] = __builtin_amdgcn_exp2f(st[v] - mnew);           // 0 for the masked keys
+      dl = fmaf(st[v], wk[v], dl);
+    }
+    den = den * alpha + dl;
+#pragma unroll
+    for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][v] *= alpha;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float *vrow = Vp + (size_t)min(k0 + 8 * (v / 4) + 4 * g + (v % 4), re - 1) * DV + c32;
+#pragma unroll
+      for (int i = 0; i < DV / 32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32 * i], st[v], acc[i], 0, 0, 0);
+    }
+  }
+
+  // ---- combine the waves' partial results: common reference = the largest one (wave 0 always has a tile) ----------
+  s_ref[wv][l] = mrun;
+  __syncthreads();
+  float mall = s_ref[0][l];
+#pragma unroll
+  for (int k = 1; k < NS; ++k) mall = fmaxf(mall, s_ref[k][l]);
+  const float sc = __builtin_amdgcn_exp2f(mrun - mall);       // 0 for a wave without tiles
+  s_den[wv][l] = den * sc;
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s_acc[((size_t)wv * NR + 16 * i + v) * 64 + l] = acc[i][v] * sc;
+  __syncthreads();
+  float dsum = 0.0f;
+#pragma unroll
+  for (int k = 0; k < NS; ++k) dsum += s_den[k][l];
+  const float dn = pair_sum(dsum);
+  const bool ok = dn > 0.0f;
+  const float inv = ok ? 1.0f / dn : 0.0f;
+  // wave wv finishes accumulator registers [R wv, R (wv + 1)): register 16 i + v <-> column 32 i + 8 (v / 4) + 4 g + v % 4
+  constexpr int R = NR / NS;
+  if (q0 + c32 < m) {
+    float *orow = out + ((size_t)bh * m + q0 + c32) * DV;
+#pragma unroll
+    for (int q4 = 0; q4 < R / 4; ++q4) {
+      const int reg = R * wv + 4 * q4, i = reg / 16, v = reg % 16, col = 32 * i + 8 * (v / 4) + 4 * g;
+      const float4 lo = *reinterpret_cast<const float4 *>(vmin + (size_t)pr * DV + col);
+      const float4 hi = *reinterpret_cast<const float4 *>(vmax + (size_t)pr * DV + col);
+      float o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float a = 0.0f;
+#pragma unroll
+        for (int k = 0; k < NS; ++k) a += s_acc[((size_t)k * NR + reg + e) * 64 + l];
+        o[e] = ok ? a * inv : 0.0f;
+      }
+      float4 res;
+      res.x = fminf(fmaxf(o[0], lo.x), hi.x);
+      res.y = fminf(fmaxf(o[1], lo.y), hi.y);
+      res.z = fminf(fmaxf(o[2], lo.z), hi.z);
+      res.w = fminf(fmaxf(o[3], lo.w), hi.w);
+      *reinterpret_cast<float4 *>(orow + col) = res;
+    }
+  }
+}
+
+template <int D, int DV, int NS>
+int launch_f32_split(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out, float scale) {
+  const size_t lds = (size_t)NS * (DV / 2) * 64 * sizeof(float);
+  const void *fn = (const void *)k_wtd_attn_f32_split<D, DV, NS>;
+  if (lds + 2 * NS * 64 * sizeof(float) > 64 * 1024 &&
+      hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    return WILDCAT_EHIP;
+  hipLaunchKernelGGL((k_wtd_attn_f32_split<D, DV, NS>), dim3((unsigned)((s.m + 31) / 32), (unsigned)(s.batch * s.q_heads)),
+                     dim3(NS * 64), lds, s.stream, (const float *)Q, (const float *)cs->k_s, cs->v_s, cs->w, cs->v_min,
+                     cs->v_max, cs->r_eff, (float *)out, s.m, s.r, s.q_heads, s.group, scale);
+  return hipGetLastError() == hipSuccess ? WILDCAT_OK : WILDCAT_EHIP;
+}
+
 template <int D, int DV>
 int launch_mfma_f32(const Shape &s, const void *Q, const wildcat_coreset *cs, void *out) {
   const float scale = (float)(s.beta * (double)kLog2e);
   const int64_t heads = (int64_t)s.batch * s.q_heads;
+  // Few queries in all and a coreset of several tiles: the waves of a workgroup share out the tiles (see above).
+  if constexpr (DV <= 128) {
+    const int64_t waves = (s.m + 31) / 32 * heads;            // at 32 queries per wave
+    const int tiles = (s.r + kFT - 1) / kFT;
+    if (waves < 8 * (int64_t)compute_units() && tiles >= 2) {
+      if (tiles >= 6) return launch_f32_split<D, DV, 8>(s, Q, cs, out, scale);
+      if (tiles >= 3) return launch_f32_split<D, DV, 4>(s, Q, cs, out, scale);
+      return launch_f32_split<D, DV, 2>(s, Q, cs, out, scale);
+    }
+  }
   // 128 queries per workgroup where that still gives every compute unit two workgroups, else 64
   const bool wide = (s.m + 127) / 128 * heads >= 2 * (int64_t)compute_units();
   if (wide) {

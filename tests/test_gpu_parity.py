@@ -206,6 +206,32 @@ def test_wtd_attn_fp32_many_queries_grouped_heads_and_unfilled_slots():
         assert relmax(out[0, h], ref) <= TOL_OUT["f32"], h
 
 
+@pytest.mark.parametrize("d,dv,m,r,r_short", [(64, 64, 97, 40, 33), (64, 64, 1000, 70, 41), (128, 128, 500, 200, 129),
+                                              (64, 64, 31, 448, 300), (128, 128, 3136, 224, 224)])
+def test_wtd_attn_fp32_few_queries_split_over_key_tiles(d, dv, m, r, r_short):
+    """fp32 storage with too few query blocks to fill the chip: the waves of a workgroup share a query block and split
+    its key tiles (two, four or eight ways by the tile count), then merge their partial sums.  Ragged query count,
+    ragged last key tile, one head whose coreset stops short of r, two query heads per kv head."""
+    rng = np.random.default_rng(1000 + r)
+    Q = rng.standard_normal((1, 4, m, d)).astype(np.float32)
+    KS = rng.standard_normal((1, 2, r, d)).astype(np.float32)
+    VS = (rng.standard_normal((1, 2, r, dv)) + 0.5).astype(np.float32)
+    wts = rng.uniform(0.5, 1.5, (1, 2, r)).astype(np.float32)
+    r_eff = np.array([[r, r_short]], np.int32)
+    KS[0, 1, r_short:] = 0; VS[0, 1, r_short:] = 0; wts[0, 1, r_short:] = 0
+    vmin, vmax = VS.min(axis=2), VS.max(axis=2)
+    cs = wc.Coreset(idx=torch.zeros((1, 2, r), dtype=torch.int32, device=dev()), r_eff=torch.from_numpy(r_eff).to(dev()),
+                    k_s=to_dev(KS, "f32"), v_s=to_dev(VS, "f32"), w=to_dev(wts, "f32"), v_min=to_dev(vmin, "f32"),
+                    v_max=to_dev(vmax, "f32"), tau=None)
+    out = wc.wtd_attn(to_dev(Q, "f32"), cs).cpu().numpy()
+    beta = 1.0 / np.sqrt(d)
+    for h in range(4):
+        p, re = h // 2, int(r_eff[0, h // 2])
+        ref = wo.wtd_attn(Q[0, h].astype(np.float64), KS[0, p, :re].astype(np.float64), VS[0, p, :re].astype(np.float64),
+                          wts[0, p, :re].astype(np.float64), vmin[0, p], vmax[0, p], beta)
+        assert relmax(out[0, h], ref) <= TOL_OUT["f32"], h
+
+
 @pytest.mark.parametrize("dtype,d,m", [("f32", 64, 200), ("bf16", 64, 200), ("bf16", 128, 200), ("bf16", 64, 600),
                                        ("bf16", 128, 600)])
 def test_wtd_attn_guard_clip_and_oracle_coreset(dtype, d, m):
