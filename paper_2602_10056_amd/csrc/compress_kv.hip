@@ -127,15 +127,16 @@ __global__ __launch_bounds__(kFinalThreads) void k_col_final(const double *__res
       mn = fminf(mn, smn[q * lpr + cc]);
       mx = fmaxf(mx, smx[q * lpr + cc]);
     }
-    if (cc < dpad) {
-      const double mean = acc / ((double)n * (double)bins);
-      for (int b = 0; b < bins; ++b) kbar[((size_t)head * bins + b) * dpad + cc] = mean;
-    }
     if (cc < dv) {
       vmin[(size_t)head * dv + cc] = mn;
       vmax[(size_t)head * dv + cc] = mx;
     }
   }
+  __syncthreads();                                           // (sd is read above by the threads of rr == 0 only)
+  if (rr == 0 && cc < dpad) sd[cc] = acc / ((double)n * (double)bins);
+  __syncthreads();
+  for (int e = t; e < bins * dpad; e += kFinalThreads)       // one copy of the mean per bin, written by everybody
+    kbar[(size_t)head * bins * dpad + e] = sd[e % dpad];
   for (int b = t; b < bins; b += kFinalThreads) scal[((size_t)head * bins + b) * 8] = 0ull;
 }
 
