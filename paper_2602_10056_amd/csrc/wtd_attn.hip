@@ -1034,7 +1034,7 @@ __global__ __launch_bounds__(NWF * 64) void k_wtd_attn_mfma_f32(
 // in the same arrangement as the kernel above.  Same arithmetic per tile; the tiles are summed in another order.
 // grid (ceil(m / 32), batch * q_heads); dynamic LDS NS x (DV / 2) x 64 floats.
 template <int D, int DV, int NS>
-__global__ __launch_bounds__(NS * 64) void k_wtd_attn_f32_split(
+__global__ __launch_bounds__(NS * 64, 2) void k_wtd_attn_f32_split(
     const float *__restrict__ Q, const float *__restrict__ Ks, const float *__restrict__ Vs,
     const float *__restrict__ w, const float *__restrict__ vmin, const float *__restrict__ vmax,
     const int32_t *__restrict__ r_eff, float *__restrict__ out, int64_t m, int r, int q_heads, int group,
@@ -1043,7 +1043,7 @@ __global__ __launch_bounds__(NS * 64) void k_wtd_attn_f32_split(
   static_assert(NR % (4 * NS) == 0, "every wave finishes whole groups of four columns");
   __shared__ float s_ref[NS][64], s_den[NS][64];
   extern __shared__ float s_acc[];                            // [NS][NR][64]
-  const int t = threadIdx.x, wv = t / kWave, l = t % kWave, g = l / 32, c32 = l % 32;
+  const int t = threadIdx.x, wv = __builtin_amdgcn_readfirstlane(t / kWave), l = t % kWave, g = l / 32, c32 = l % 32;
   const int bh = blockIdx.y, b = bh / q_heads, hq = bh % q_heads;
   const int pr = b * (q_heads / group) + hq / group;
   const int re = r_eff ? max(min(r_eff[pr], r), 1) : r;
@@ -1066,27 +1066,80 @@ __global__ __launch_bounds__(NS * 64) void k_wtd_attn_f32_split(
   float mrun = -INFINITY, den = 0.0f;
   const float *Kp = Ks + (size_t)pr * r * D, *Vp = Vs + (size_t)pr * r * DV, *wp = w + (size_t)pr * r;
 
-  for (int k0 = wv * kFT; k0 < re; k0 += NS * kFT) {
-    // ---- S^T = K Q^T: A operand = key k0 + c32 (clamped; masked below), features 8 t + 4 g .. + 3 ------------------
+  // Where the registers allow it (PF: d = d_v = 64) a wave keeps its loads a tile ahead of its MFMAs: the values and
+  // weights of its next tile are requested before the current tile's score product, the keys of the next tile right
+  // after it, so after the first tile nothing waits for memory (the scheduling barriers keep the requests there).
+  constexpr bool PF = D <= 64 && DV <= 64;
+  auto load_keys = [&](int k0, float4 (&ka)[D / 8]) {
     const float *krow = Kp + (size_t)min(k0 + c32, re - 1) * D + 4 * g;
+#pragma unroll
+    for (int tt = 0; tt < D / 8; ++tt) ka[tt] = *reinterpret_cast<const float4 *>(krow + 8 * tt);
+  };
+  auto load_values = [&](int k0, float (&vv)[PF ? 16 : 1][PF ? DV / 32 : 1], float (&ww)[16]) {
+    if constexpr (PF) {
+      if (k0 + kFT <= re) {
+        // a whole tile: one pointer per lane and compile-time offsets from it (k0 is the same in every lane)
+        const float *vl = Vp + (size_t)k0 * DV + (4 * g * DV + c32), *wl = wp + k0 + 4 * g;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          ww[v] = wl[8 * (v / 4) + (v % 4)];
+#pragma unroll
+          for (int i = 0; i < DV / 32; ++i) vv[v][i] = vl[(8 * (v / 4) + (v % 4)) * DV + 32 * i];
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const unsigned key = (unsigned)min(k0 + 8 * (v / 4) + 4 * g + (v % 4), re - 1);
+          ww[v] = wp[key];
+#pragma unroll
+          for (int i = 0; i < DV / 32; ++i) vv[v][i] = Vp[key * (unsigned)DV + (unsigned)(c32 + 32 * i)];
+        }
+      }
+    }
+  };
+  float4 ka[D / 8];
+  float vn[PF ? 16 : 1][PF ? DV / 32 : 1], wn[16];
+  if (PF && wv * kFT < re) {
+    load_keys(wv * kFT, ka);
+    load_values(wv * kFT, vn, wn);
+  }
+  for (int k0 = wv * kFT; k0 < re; k0 += NS * kFT) {
+    float wk[16];
+    float va[PF ? 16 : 1][PF ? DV / 32 : 1];
+    if constexpr (PF) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        wk[v] = wn[v];
+#pragma unroll
+        for (int i = 0; i < DV / 32; ++i) va[v][i] = vn[v][i];
+      }
+      if (k0 + NS * kFT < re) load_values(k0 + NS * kFT, vn, wn);
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
+      load_keys(k0, ka);
+    }
+    // ---- S^T = K Q^T: A operand = key k0 + c32 (clamped; masked below), features 8 t + 4 g .. + 3 ------------------
     floatx16 st;
 #pragma unroll
     for (int v = 0; v < 16; ++v) st[v] = 0.0f;
 #pragma unroll
     for (int tt = 0; tt < D / 8; ++tt) {
-      const float4 a = *reinterpret_cast<const float4 *>(krow + 8 * tt);
+      const float4 a = ka[tt];
       st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, qf[4 * tt + 0], st, 0, 0, 0);
       st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, qf[4 * tt + 1], st, 0, 0, 0);
       st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, qf[4 * tt + 2], st, 0, 0, 0);
       st = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, qf[4 * tt + 3], st, 0, 0, 0);
     }
+    if constexpr (PF) {
+      if (k0 + NS * kFT < re) load_keys(k0 + NS * kFT, ka);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // register v <-> key k0 + 8 (v / 4) + 4 g + v % 4
-    float wk[16];
     float mx = -INFINITY;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int key = k0 + 8 * (v / 4) + 4 * g + (v % 4);
-      wk[v] = wp[min(key, re - 1)];
+      if constexpr (!PF) wk[v] = wp[min(key, re - 1)];
       st[v] = key < re ? st[v] * scale_log2 : -INFINITY;
       mx = fmaxf(mx, st[v]);
     }
@@ -1107,9 +1160,14 @@ __global__ __launch_bounds__(NS * 64) void k_wtd_attn_f32_split(
       for (int v = 0; v < 16; ++v) acc[i][v] *= alpha;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const float *vrow = Vp + (size_t)min(k0 + 8 * (v / 4) + 4 * g + (v % 4), re - 1) * DV + c32;
+      if constexpr (PF) {
 #pragma unroll
-      for (int i = 0; i < DV / 32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32 * i], st[v], acc[i], 0, 0, 0);
+        for (int i = 0; i < DV / 32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[v][i], st[v], acc[i], 0, 0, 0);
+      } else {
+        const float *vrow = Vp + (size_t)min(k0 + 8 * (v / 4) + 4 * g + (v % 4), re - 1) * DV + c32;
+#pragma unroll
+        for (int i = 0; i < DV / 32; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(vrow[32 * i], st[v], acc[i], 0, 0, 0);
+      }
     }
   }
 
@@ -1178,11 +1236,20 @@ int launch_mfma_f32(const Shape &s, const void *Q, const wildcat_coreset *cs, vo
   const int64_t heads = (int64_t)s.batch * s.q_heads;
   // Few queries in all and a coreset of several tiles: the waves of a workgroup share out the tiles (see above).
   if constexpr (DV <= 128) {
-    const int64_t waves = (s.m + 31) / 32 * heads;            // at 32 queries per wave
+    const int64_t blocks = (s.m + 31) / 32 * heads;           // blocks of 32 queries
     const int tiles = (s.r + kFT - 1) / kFT;
-    if (waves < 8 * (int64_t)compute_units() && tiles >= 2) {
-      if (tiles >= 6) return launch_f32_split<D, DV, 8>(s, Q, cs, out, scale);
-      if (tiles >= 3) return launch_f32_split<D, DV, 4>(s, Q, cs, out, scale);
+    const int64_t cus = compute_units();
+    if (blocks < 8 * cus && tiles >= 2) {
+      // As many waves per block as there are tiles to share out, but not so many that the workgroups no longer run
+      // all at once (two waves per SIMD, i.e. eight per compute unit, and the merge buffer in LDS): a second round of
+      // workgroups costs more than longer chains of tiles per wave.
+      auto one_round = [&](int ns) {
+        const int64_t lds = (int64_t)ns * (DV / 2) * 256 + ns * 512 + 1024;
+        const int64_t by_regs = 8 / ns, by_lds = 160 * 1024 / lds;
+        return blocks <= (by_regs < by_lds ? by_regs : by_lds) * cus;
+      };
+      if (tiles >= 6 && one_round(8)) return launch_f32_split<D, DV, 8>(s, Q, cs, out, scale);
+      if (tiles >= 3 && one_round(4)) return launch_f32_split<D, DV, 4>(s, Q, cs, out, scale);
       return launch_f32_split<D, DV, 2>(s, Q, cs, out, scale);
     }
   }
