@@ -921,7 +921,7 @@ __global__ __launch_bounds__(NWF * 64) void k_wtd_attn_mfma_f32(
   // issued right after tile t has been stored to LDS, so they fly during the MFMAs of tile t.
   constexpr int NT = NWF * 64, KR = kFT * (D / 4) / NT, VR = kFT * (DV / 4) / NT;
   static_assert(KR * NT == kFT * (D / 4) && VR * NT == kFT * (DV / 4), "tiles must split evenly");
-  constexpr bool PREFETCH = DV <= 128;
+  constexpr bool PREFETCH = DV <= 128 || NWF >= 4;          // (staging registers per thread shrink with the workgroup)
   float4 kreg[KR], vreg[VR];
   float wreg = 0.0f;
   auto fetch = [&](int k0) {
@@ -1254,7 +1254,7 @@ int launch_mfma_f32(const Shape &s, const void *Q, const wildcat_coreset *cs, vo
     }
   }
   // 128 queries per workgroup where that still gives every compute unit two workgroups, else 64
-  const bool wide = (s.m + 127) / 128 * heads >= 2 * (int64_t)compute_units();
+  const bool wide = DV == 256 || (s.m + 127) / 128 * heads >= 2 * (int64_t)compute_units();
   if (wide) {
     hipLaunchKernelGGL((k_wtd_attn_mfma_f32<D, DV, 4>), dim3((unsigned)((s.m + 127) / 128), (unsigned)heads), dim3(256),
                        0, s.stream, (const float *)Q, (const float *)cs->k_s, cs->v_s, cs->w, cs->v_min, cs->v_max,
