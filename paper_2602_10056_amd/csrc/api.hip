@@ -126,6 +126,7 @@ Plan make_plan(const Shape &s) {
   const bool gram_mfma = s.r > 16 && (s.dv == 64 || s.dv == 128 || s.dv == 256);
   int want = ((gram_mfma || s.r <= 8) ? 512 : 1024) / (s.P * rtiles);
   if (want < 1) want = 1;
+  const int want_pieces = want;                              // (before the slab count caps it: k_gram_cols cuts inside the slab)
   if (want > p.nblk) want = p.nblk;
   p.slabs_per_chunk = (p.nblk + want - 1) / want;
   p.nchunk = (p.nblk + p.slabs_per_chunk - 1) / p.slabs_per_chunk;
@@ -137,9 +138,10 @@ Plan make_plan(const Shape &s) {
     // many keys; a workgroup takes 256 / (columns rounded up to a power of two >= 64) consecutive pieces.
     int tp = 64;
     while (tp < s.dv) tp <<= 1;
-    const int pieces = want * (kThreads / tp);
+    const int pieces = want_pieces * (kThreads / tp);
     int64_t ck = (s.n + pieces - 1) / pieces;
     ck = (ck + 15) / 16 * 16;
+    if (ck < 32 && s.n >= 32) ck = 32;                       // (every piece costs a partial result of r (d_v + 1) doubles)
     p.chunk_keys = ck;
     p.nchunk = (int)((s.n + ck - 1) / ck);
   }

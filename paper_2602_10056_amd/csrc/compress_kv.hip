@@ -2074,7 +2074,22 @@ __global__ __launch_bounds__(kThreads) void k_solve_small(const double *__restri
   double g[kSolveSmall];
 #pragma unroll
   for (int j = 0; j < kSolveSmall; ++j) g[j] = 0.0;
-  for (int ch = 0; ch < nchunk; ++ch) {                       // chunk order per entry; the rows' loads are independent
+  int ch = 0;
+  for (; ch + 2 <= nchunk; ch += 2) {                         // chunk order per entry; two chunks' loads in flight
+    double x[2][kSolveSmall];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const double *gp = gpart + ((size_t)pr * nchunk + ch + q) * r * dv1 + c;
+#pragma unroll
+      for (int j = 0; j < kSolveSmall; ++j) x[q][j] = j < re ? gp[(size_t)j * dv1] : 0.0;
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int j = 0; j < kSolveSmall; ++j)
+        if (j < re) g[j] += x[q][j];
+  }
+  for (; ch < nchunk; ++ch) {
     const double *gp = gpart + ((size_t)pr * nchunk + ch) * r * dv1 + c;
 #pragma unroll
     for (int j = 0; j < kSolveSmall; ++j)
