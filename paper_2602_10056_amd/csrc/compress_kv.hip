@@ -79,11 +79,13 @@ __global__ __launch_bounds__(kThreads) void k_col_stats(const T *__restrict__ K,
   }
 }
 
-// pass 2: grid = heads, 1024 threads.  The mean of Alg. 2 and the value range of Alg. 4 belong to the whole head:
-// they are combined over the `bins` consecutive problems of the head in a fixed order (thread (rr, cc) takes
-// partials rr, rr + rif, ... of column cc -- eight loads in flight at a time -- then the rif partial results are
-// added in turn), and kbar is written once per bin so that later kernels index it by problem.  n = keys per bin.
-// Clears the R_K^2 accumulators of the head's bins.
+// pass 2.  The mean of Alg. 2 and the value range of Alg. 4 belong to the whole head: they are combined over the
+// `bins` consecutive problems of the head in a fixed order -- logical thread (rr, cc) of kFinalThreads / lpr x lpr
+// takes partials rr, rr + rif, ... of column cc, eight loads in flight at a time, then the rif partial results are
+// added in turn -- and kbar is written once per bin so that later kernels index it by problem.  n = keys per bin.
+// The lpr columns are dealt out to gridDim.y workgroups of kFinalThreads / gridDim.y threads (a slice of lpr /
+// gridDim.y columns each, every thread doing what its logical thread does: the same bits whatever the slicing), so
+// that several compute units share the reading.  grid (heads, slices).  Clears the R_K^2 accumulators of the head's bins.
 constexpr int kFinalThreads = 1024;
 
 __global__ __launch_bounds__(kFinalThreads) void k_col_final(const double *__restrict__ mpart,
@@ -95,8 +97,9 @@ __global__ __launch_bounds__(kFinalThreads) void k_col_final(const double *__res
                                                              unsigned long long *__restrict__ scal) {
   __shared__ double sd[kFinalThreads];
   __shared__ float smn[kFinalThreads], smx[kFinalThreads];
-  const int t = threadIdx.x, head = blockIdx.x;
-  const int rif = kFinalThreads / lpr, rr = t / lpr, cc = t % lpr;
+  const int t = threadIdx.x, head = blockIdx.x, nthr = blockDim.x;
+  const int lprs = lpr / gridDim.y, c0 = blockIdx.y * lprs;   // this workgroup's columns: c0 .. c0 + lprs - 1
+  const int rif = kFinalThreads / lpr, rr = t / lprs, cl = t % lprs, cc = c0 + cl;
   const size_t part0 = (size_t)head * bins * nb0;
   const int nparts = bins * nb0;
   double acc = 0.0;
@@ -123,9 +126,9 @@ __global__ __launch_bounds__(kFinalThreads) void k_col_final(const double *__res
   __syncthreads();
   if (rr == 0) {
     for (int q = 1; q < rif; ++q) {
-      acc += sd[q * lpr + cc];
-      mn = fminf(mn, smn[q * lpr + cc]);
-      mx = fmaxf(mx, smx[q * lpr + cc]);
+      acc += sd[q * lprs + cl];
+      mn = fminf(mn, smn[q * lprs + cl]);
+      mx = fmaxf(mx, smx[q * lprs + cl]);
     }
     if (cc < dv) {
       vmin[(size_t)head * dv + cc] = mn;
@@ -133,11 +136,14 @@ __global__ __launch_bounds__(kFinalThreads) void k_col_final(const double *__res
     }
   }
   __syncthreads();                                           // (sd is read above by the threads of rr == 0 only)
-  if (rr == 0 && cc < dpad) sd[cc] = acc / ((double)n * (double)bins);
+  if (rr == 0) sd[cl] = acc / ((double)n * (double)bins);
   __syncthreads();
-  for (int e = t; e < bins * dpad; e += kFinalThreads)       // one copy of the mean per bin, written by everybody
-    kbar[(size_t)head * bins * dpad + e] = sd[e % dpad];
-  for (int b = t; b < bins; b += kFinalThreads) scal[((size_t)head * bins + b) * 8] = 0ull;
+  for (int e = t; e < bins * lprs; e += nthr) {              // one copy of the mean per bin, written by everybody
+    const int b = e / lprs, c = c0 + e % lprs;
+    if (c < dpad) kbar[((size_t)head * bins + b) * dpad + c] = sd[e % lprs];
+  }
+  if (blockIdx.y == 0)
+    for (int b = t; b < bins; b += nthr) scal[((size_t)head * bins + b) * 8] = 0ull;
 }
 
 // --------------------------------------------------------------------------------------------
@@ -2329,8 +2335,9 @@ int run_compress(const Shape &s, const Plan &pl, const T *K, const T *V, const w
     hipLaunchKernelGGL((k_pack<T>), dim3((unsigned)packs, P), dim3(kThreads), 0, st, K, s.n, pl.npad, s.d, pl.dpad, Kp);
     LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(k_col_final, dim3(P / s.bins), dim3(kFinalThreads), 0, st, mpart, vminpart, vmaxpart, s.n, s.dv, pl.dpad,
-                     nparts, s.bins, lpr, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
+  const int slices = lpr >= 64 ? 4 : 1;                       // (lpr is a power of two, at most kFinalThreads)
+  hipLaunchKernelGGL(k_col_final, dim3(P / s.bins, slices), dim3(kFinalThreads / slices), 0, st, mpart, vminpart, vmaxpart,
+                     s.n, s.dv, pl.dpad, nparts, s.bins, lpr, kbar, out->v_min, out->v_max, (unsigned long long *)scal);
   LAUNCH_CHECK();
   const LoopPlan lp = plan_loop<T, KPT, H>(s, pl);
   const bool one_slab_form = lp.c.kind == kLoopSolo || lp.c.kind == kLoopWave;   // these also do the work of k_sqnorm, k_init_p
